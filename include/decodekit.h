@@ -1,0 +1,223 @@
+/*
+ * decodekit - the continuous-batching decode step of a decoder-only
+ * transformer on one MI355X (gfx950), behind a C ABI.
+ *
+ * One call of dk_decode_step is the body of the paper's continuous-batching
+ * loop (Algorithm 1, "generate one token for all active requests"): every one
+ * of the B active sequences advances by one token against its own KV cache.
+ * The KV cache is a pool of fixed-size blocks addressed through per-sequence
+ * block tables; sequences that resumed from the same cached prompt prefix (the
+ * KV state and start position returned by the paper's text prefix cache
+ * lookup, Algorithm 2) name the same physical blocks for that prefix.
+ *
+ * Conventions
+ *   - Every function returns a dk_status (0 = DK_OK, negative = error).  After
+ *     an error, dk_last_error() gives a text for the calling thread.  Nothing
+ *     throws or aborts across this boundary.
+ *   - "device pointer" = memory of the current HIP device, allocated and
+ *     freed by the caller (e.g. a torch tensor).  The library never allocates
+ *     or frees device memory; it keeps non-owning pointers.  Handles returned
+ *     by dk_create_* are small host objects freed by dk_destroy_*.
+ *   - Kernels are enqueued on the HIP stream passed as `hip_stream`
+ *     (a hipStream_t cast to void*; NULL = the default stream).  No call
+ *     synchronises the device; outputs are valid once the caller has
+ *     synchronised that stream.
+ *   - bf16 = upper 16 bits of an IEEE float32.  Matrices are row-major
+ *     W[out][in] and act as y = W x.
+ */
+#ifndef DECODEKIT_H
+#define DECODEKIT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef int32_t dk_status;
+enum {
+    DK_OK = 0,
+    DK_E_INVALID_ARG = -1,
+    DK_E_POOL_EXHAUSTED = -2,
+    DK_E_BAD_BLOCK = -3,
+    DK_E_WORKSPACE_TOO_SMALL = -4,
+    DK_E_UNSUPPORTED_SHAPE = -5,
+    DK_E_HIP = -6
+};
+
+/* Limits of this build (dk_create_model / dk_decode_step reject beyond). */
+#define DK_MAX_BATCH 64
+#define DK_MAX_EXPERTS 256
+
+/*
+ * Shape of the decoder.  The paper delegates the model forward to its model
+ * library; the shapes are those of the model families it benchmarks (Table 1).
+ *   head_dim    64 or 128;  n_q_heads a multiple of n_kv_heads (group <= 8)
+ *   hidden, ffn, expert_ffn, n_q_heads*head_dim: multiples of 8
+ *   qk_norm     1: RMSNorm over head_dim of every q and k head before the
+ *               rotary embedding (gains g_q, g_k shared by all heads)
+ *   n_experts   0 = dense SwiGLU MLP of width ffn; >0 = mixture of n_experts
+ *               SwiGLU experts of width expert_ffn, top_k chosen per token by
+ *               a softmax router (ties to the lower index), the chosen
+ *               probabilities renormalised to sum to one
+ *   tie_lm_head informational (the caller passes the same pointer twice)
+ */
+typedef struct dk_model_config {
+    int32_t n_layers, hidden, n_q_heads, n_kv_heads, head_dim, ffn, vocab;
+    int32_t qk_norm, n_experts, top_k, expert_ffn, tie_lm_head;
+    double rms_eps, rope_theta;
+} dk_model_config;
+
+/* Device pointers to one layer's bf16 weights (caller-owned). */
+typedef struct dk_layer_weights {
+    const void *g_attn;   /* [hidden]            gain of the pre-attention norm */
+    const void *w_qkv;    /* [(nq+2nkv)*d, hidden]  q rows, then k rows, then v */
+    const void *g_q;      /* [head_dim] or NULL  (qk_norm)                      */
+    const void *g_k;      /* [head_dim] or NULL                                 */
+    const void *w_o;      /* [hidden, nq*d]                                     */
+    const void *g_mlp;    /* [hidden]            gain of the pre-MLP norm       */
+    const void *w_gate;   /* dense [ffn, hidden];  MoE [E, expert_ffn, hidden]  */
+    const void *w_up;     /* same shape as w_gate                               */
+    const void *w_down;   /* dense [hidden, ffn];  MoE [E, hidden, expert_ffn]  */
+    const void *w_router; /* [E, hidden] or NULL                                */
+} dk_layer_weights;
+
+typedef struct dk_weight_ptrs {
+    const void *embed;    /* device, bf16 [vocab, hidden]                       */
+    const void *lm_head;  /* device, bf16 [vocab, hidden] (may equal embed)     */
+    const void *g_final;  /* device, bf16 [hidden]                              */
+    const dk_layer_weights *layers; /* HOST array of n_layers entries; copied   */
+} dk_weight_ptrs;
+
+typedef struct dk_kv_pool dk_kv_pool;
+typedef struct dk_model dk_model;
+
+/* Text of the last error on this thread; valid until the next call here. */
+const char *dk_last_error(void);
+
+/* Library version string and the GPU architecture its kernels were built for. */
+const char *dk_version(void);
+
+/* ---------------------------------------------------------------- KV pool --
+ *
+ * Layout (part of this ABI): a dense bf16 array
+ *     pool[layer][block][kv][kv_head][slot][dim]      kv: 0 = K, 1 = V
+ * i.e. element offset
+ *     ((((layer*num_blocks + block)*2 + kv)*n_kv_heads + head)*block_size + slot)*head_dim + dim
+ * so one (block, K|V, head) tile is a contiguous run of block_size*head_dim
+ * elements.  Cached K is stored after q/k-norm and rotary embedding.  A
+ * sequence's cache grows by one token per decode step (the paper's per-request
+ * KV cache, background section on unified memory) and is never copied.
+ */
+
+/* Bytes of device memory a pool of num_blocks blocks needs.  Host only. */
+dk_status dk_kv_pool_bytes(const dk_model_config *cfg, int32_t num_blocks, int32_t block_size,
+                           size_t *out_bytes);
+
+/* Wraps caller-owned device memory `dev_mem` (>= dk_kv_pool_bytes) as a pool.
+ * All blocks start free.  block_size must be 16.  Host only (dev_mem is not
+ * touched). */
+dk_status dk_create_kv_pool(const dk_model_config *cfg, int32_t num_blocks, int32_t block_size,
+                            void *dev_mem, size_t dev_bytes, dk_kv_pool **out);
+dk_status dk_destroy_kv_pool(dk_kv_pool *pool);
+
+/* Host-side block accounting.  alloc: takes a free block (lowest id first),
+ * refcount 1, DK_E_POOL_EXHAUSTED if none.  alloc_id: takes that specific
+ * block if free (lets a caller place blocks in its own order), DK_E_BAD_BLOCK
+ * if out of range or in use.  retain: refcount+1 on a block in use - this is
+ * how a second sequence shares a cached prefix block.  release: refcount-1,
+ * the block returns to the free list at 0.  refcount: current count (0 =
+ * free).  A block with refcount > 1 must not be an append target; the
+ * caller gives each sequence a private block for its growing tail. */
+dk_status dk_kv_alloc_block(dk_kv_pool *pool, int32_t *out_block_id);
+dk_status dk_kv_alloc_block_id(dk_kv_pool *pool, int32_t block_id);
+dk_status dk_kv_retain_block(dk_kv_pool *pool, int32_t block_id);
+dk_status dk_kv_release_block(dk_kv_pool *pool, int32_t block_id);
+dk_status dk_kv_refcount(const dk_kv_pool *pool, int32_t block_id, int32_t *out_refcount);
+dk_status dk_kv_free_blocks(const dk_kv_pool *pool, int32_t *out_free);
+
+/* Element offset of (layer, block, kv, head, slot, dim) in the pool.  Host only. */
+dk_status dk_kv_offset(const dk_kv_pool *pool, int32_t layer, int32_t block, int32_t kv,
+                       int32_t head, int32_t slot, int32_t dim, int64_t *out_offset);
+
+/* Checks, on HOST copies of the tables, what a decode step over them needs:
+ * every block id on positions 0..seq_lens[b] is in range and in use, and the
+ * append target block of every sequence has refcount 1 and is not another
+ * row's append target.  DK_E_BAD_BLOCK names the offender in dk_last_error. */
+dk_status dk_kv_validate_tables(const dk_kv_pool *pool, const int32_t *h_block_tables,
+                                int32_t max_blocks_per_seq, const int32_t *h_seq_lens, int32_t B);
+
+/* Writes one token's K and V for every sequence into one layer of the pool,
+ * at logical position seq_lens[b] through the block table (used to load
+ * contexts and by tests; dk_decode_step appends by itself).
+ *   d_block_tables  device int32 [B][max_blocks_per_seq]
+ *   d_seq_lens      device int32 [B]
+ *   d_k, d_v        device bf16 [B][n_kv_heads][head_dim], stored bit for bit */
+dk_status dk_append_kv(dk_kv_pool *pool, int32_t layer, const int32_t *d_block_tables,
+                       int32_t max_blocks_per_seq, const int32_t *d_seq_lens, int32_t B,
+                       const void *d_k, const void *d_v, void *hip_stream);
+
+/* ------------------------------------------------------------------ model -- */
+
+/* Validates the shape and records the weight pointers (not dereferenced
+ * here).  DK_E_UNSUPPORTED_SHAPE for shapes outside the limits above. */
+dk_status dk_create_model(const dk_model_config *cfg, const dk_weight_ptrs *weights,
+                          dk_model **out);
+dk_status dk_destroy_model(dk_model *model);
+
+/* Bytes of device scratch a decode step needs for batches up to max_B whose
+ * block tables are at most max_blocks_per_seq wide.  Host only. */
+dk_status dk_workspace_bytes(const dk_model *model, int32_t max_B, int32_t max_blocks_per_seq,
+                             size_t *out_bytes);
+
+/* dk_decode_step flags */
+#define DK_STEP_ADVANCE 1u /* after the step: d_tokens[b] = next token, d_seq_lens[b] += 1 */
+
+/*
+ * One decode step for B sequences (Algorithm 1's per-iteration token
+ * generation, batched; rows do not interact).
+ *
+ * For each row b, with T = d_seq_lens[b] tokens already cached: embeds
+ * d_tokens[b]; per layer: RMSNorm, q/k/v projection, optional q/k head norm,
+ * half-split rotary embedding at position T, stores k and v (rounded to bf16,
+ * nearest even) at position T through the block table, grouped-query
+ * attention over positions 0..T, output projection + residual, RMSNorm,
+ * SwiGLU MLP or expert mixture + residual; final RMSNorm, lm_head, and the
+ * greedy next token (lowest index among equal maxima).
+ *
+ *   d_block_tables  device int32 [B][max_blocks_per_seq]; entries up to index
+ *                   T/block_size must be valid blocks of `pool`, the last of
+ *                   them private to row b (see dk_kv_validate_tables)
+ *   d_seq_lens      device int32 [B]; T < max_blocks_per_seq*block_size
+ *   d_tokens        device int32 [B], each in [0, vocab)
+ *   d_workspace     device scratch >= dk_workspace_bytes(model, B, max_blocks_per_seq),
+ *                   256-byte aligned; contents need not survive between calls
+ *   d_logits        device float32 [B][vocab], or NULL to skip storing logits
+ *   d_next_tokens   device int32 [B]
+ *   flags           0 or DK_STEP_ADVANCE (then d_tokens / d_seq_lens are
+ *                   written; otherwise the step leaves them untouched and the
+ *                   caller advances them)
+ * The block tables are never modified.  Fast arithmetic: bf16 storage, float32
+ * accumulation and float32 residual stream.
+ */
+dk_status dk_decode_step(dk_model *model, dk_kv_pool *pool, const int32_t *d_block_tables,
+                         int32_t max_blocks_per_seq, int32_t *d_seq_lens, int32_t *d_tokens,
+                         int32_t B, void *d_workspace, size_t workspace_bytes, float *d_logits,
+                         int32_t *d_next_tokens, uint32_t flags, void *hip_stream);
+
+/* Algorithmic HBM bytes of one decode step: every dense weight byte once,
+ * every distinct live KV byte once (a shared block counts once), the B
+ * embedding rows and the logits written.  Host only; takes HOST copies of the
+ * tables.  `distinct_experts_per_layer` is a host array of n_layers counts for
+ * MoE models (NULL for dense). */
+dk_status dk_step_algorithmic_bytes(const dk_model *model, const dk_kv_pool *pool,
+                                    const int32_t *h_block_tables, int32_t max_blocks_per_seq,
+                                    const int32_t *h_seq_lens, int32_t B, int32_t with_logits,
+                                    const int32_t *distinct_experts_per_layer,
+                                    uint64_t *out_bytes);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DECODEKIT_H */

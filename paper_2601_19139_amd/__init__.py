@@ -1,0 +1,16 @@
+"""MI355X decode-step library: thin Python binding of the C ABI in
+include/decodekit.h.  Every step of the path runs in the HIP kernels of
+libdecodekit.so; this package only marshals arguments (torch is used for
+device memory and streams).  There is no CPU fallback: importing works
+anywhere, but any call needs the built library and raises if it is missing.
+"""
+from .binding import (  # noqa: F401
+    DecodeKitError, lib, version, last_error,
+    ModelConfig as DkModelConfig, LayerWeights, WeightPtrs,
+    kv_pool_bytes, create_kv_pool, destroy_kv_pool,
+    kv_alloc_block, kv_alloc_block_id, kv_retain_block, kv_release_block, kv_refcount,
+    kv_free_blocks, kv_offset, kv_validate_tables, append_kv,
+    create_model, destroy_model, workspace_bytes, decode_step, step_algorithmic_bytes,
+    STEP_ADVANCE, STATUS,
+)
+from .runtime import DeviceModel, DeviceKV, Decoder  # noqa: F401

@@ -1,0 +1,226 @@
+"""ctypes binding of include/decodekit.h: same names without the dk_ prefix,
+argument marshalling only."""
+import ctypes as C
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libdecodekit.so")
+
+STATUS = {0: "DK_OK", -1: "DK_E_INVALID_ARG", -2: "DK_E_POOL_EXHAUSTED", -3: "DK_E_BAD_BLOCK",
+          -4: "DK_E_WORKSPACE_TOO_SMALL", -5: "DK_E_UNSUPPORTED_SHAPE", -6: "DK_E_HIP"}
+STEP_ADVANCE = 1
+
+
+class DecodeKitError(RuntimeError):
+    def __init__(self, code, text):
+        super().__init__(f"{STATUS.get(code, code)}: {text}")
+        self.code = code
+        self.status = STATUS.get(code, str(code))
+
+
+class ModelConfig(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in (
+        "n_layers", "hidden", "n_q_heads", "n_kv_heads", "head_dim", "ffn", "vocab",
+        "qk_norm", "n_experts", "top_k", "expert_ffn", "tie_lm_head")] + [
+        ("rms_eps", C.c_double), ("rope_theta", C.c_double)]
+
+    @classmethod
+    def from_shape(cls, cfg):
+        """From any object with the fields of workloads.ModelConfig."""
+        return cls(cfg.n_layers, cfg.hidden, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.ffn,
+                   cfg.vocab, int(cfg.qk_norm), cfg.n_experts, cfg.top_k, cfg.expert_ffn,
+                   int(cfg.tie_lm_head), cfg.rms_eps, cfg.rope_theta)
+
+
+LAYER_FIELDS = ("g_attn", "w_qkv", "g_q", "g_k", "w_o", "g_mlp", "w_gate", "w_up", "w_down",
+                "w_router")
+
+
+class LayerWeights(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in LAYER_FIELDS]
+
+
+class WeightPtrs(C.Structure):
+    _fields_ = [("embed", C.c_void_p), ("lm_head", C.c_void_p), ("g_final", C.c_void_p),
+                ("layers", C.POINTER(LayerWeights))]
+
+
+_SIGNATURES = {
+    "dk_last_error": (C.c_char_p, []),
+    "dk_version": (C.c_char_p, []),
+    "dk_kv_pool_bytes": (C.c_int32, [C.POINTER(ModelConfig), C.c_int32, C.c_int32, C.POINTER(C.c_size_t)]),
+    "dk_create_kv_pool": (C.c_int32, [C.POINTER(ModelConfig), C.c_int32, C.c_int32, C.c_void_p,
+                                      C.c_size_t, C.POINTER(C.c_void_p)]),
+    "dk_destroy_kv_pool": (C.c_int32, [C.c_void_p]),
+    "dk_kv_alloc_block": (C.c_int32, [C.c_void_p, C.POINTER(C.c_int32)]),
+    "dk_kv_alloc_block_id": (C.c_int32, [C.c_void_p, C.c_int32]),
+    "dk_kv_retain_block": (C.c_int32, [C.c_void_p, C.c_int32]),
+    "dk_kv_release_block": (C.c_int32, [C.c_void_p, C.c_int32]),
+    "dk_kv_refcount": (C.c_int32, [C.c_void_p, C.c_int32, C.POINTER(C.c_int32)]),
+    "dk_kv_free_blocks": (C.c_int32, [C.c_void_p, C.POINTER(C.c_int32)]),
+    "dk_kv_offset": (C.c_int32, [C.c_void_p] + [C.c_int32] * 6 + [C.POINTER(C.c_int64)]),
+    "dk_kv_validate_tables": (C.c_int32, [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_int32]),
+    "dk_append_kv": (C.c_int32, [C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p, C.c_int32,
+                                 C.c_void_p, C.c_void_p, C.c_void_p]),
+    "dk_create_model": (C.c_int32, [C.POINTER(ModelConfig), C.POINTER(WeightPtrs), C.POINTER(C.c_void_p)]),
+    "dk_destroy_model": (C.c_int32, [C.c_void_p]),
+    "dk_workspace_bytes": (C.c_int32, [C.c_void_p, C.c_int32, C.c_int32, C.POINTER(C.c_size_t)]),
+    "dk_decode_step": (C.c_int32, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p,
+                                   C.c_int32, C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p,
+                                   C.c_uint32, C.c_void_p]),
+    "dk_step_algorithmic_bytes": (C.c_int32, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p,
+                                              C.c_int32, C.c_int32, C.c_void_p, C.POINTER(C.c_uint64)]),
+}
+
+EXPORTS = tuple(_SIGNATURES)
+_LIB = None
+
+
+def lib():
+    """The loaded library.  Raises if it has not been built: there is no
+    fallback path."""
+    global _LIB
+    if _LIB is None:
+        if not os.path.exists(LIB_PATH):
+            raise DecodeKitError(-6, f"{LIB_PATH} is missing; build it with "
+                                     "`python -m paper_2601_19139_amd.build`")
+        L = C.CDLL(LIB_PATH)
+        for name, (res, args) in _SIGNATURES.items():
+            fn = getattr(L, name)
+            fn.restype = res
+            fn.argtypes = args
+        _LIB = L
+    return _LIB
+
+
+def last_error() -> str:
+    return lib().dk_last_error().decode()
+
+
+def version() -> str:
+    return lib().dk_version().decode()
+
+
+def _check(code):
+    if code != 0:
+        raise DecodeKitError(code, last_error())
+
+
+def _ptr(t):
+    """Device (or host) address of a torch tensor / numpy array / int / None."""
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    if hasattr(t, "data_ptr"):
+        return t.data_ptr()
+    return t.ctypes.data
+
+
+def _stream(stream):
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream
+    return stream if isinstance(stream, int) else stream.cuda_stream
+
+
+# ---- pool -----------------------------------------------------------------
+def kv_pool_bytes(cfg: ModelConfig, num_blocks: int, block_size: int) -> int:
+    out = C.c_size_t()
+    _check(lib().dk_kv_pool_bytes(C.byref(cfg), num_blocks, block_size, C.byref(out)))
+    return out.value
+
+
+def create_kv_pool(cfg: ModelConfig, num_blocks: int, block_size: int, dev_mem, dev_bytes: int):
+    out = C.c_void_p()
+    _check(lib().dk_create_kv_pool(C.byref(cfg), num_blocks, block_size, _ptr(dev_mem), dev_bytes,
+                                   C.byref(out)))
+    return out
+
+
+def destroy_kv_pool(pool):
+    _check(lib().dk_destroy_kv_pool(pool))
+
+
+def kv_alloc_block(pool) -> int:
+    out = C.c_int32()
+    _check(lib().dk_kv_alloc_block(pool, C.byref(out)))
+    return out.value
+
+
+def kv_alloc_block_id(pool, block_id: int):
+    _check(lib().dk_kv_alloc_block_id(pool, block_id))
+
+
+def kv_retain_block(pool, block_id: int):
+    _check(lib().dk_kv_retain_block(pool, block_id))
+
+
+def kv_release_block(pool, block_id: int):
+    _check(lib().dk_kv_release_block(pool, block_id))
+
+
+def kv_refcount(pool, block_id: int) -> int:
+    out = C.c_int32()
+    _check(lib().dk_kv_refcount(pool, block_id, C.byref(out)))
+    return out.value
+
+
+def kv_free_blocks(pool) -> int:
+    out = C.c_int32()
+    _check(lib().dk_kv_free_blocks(pool, C.byref(out)))
+    return out.value
+
+
+def kv_offset(pool, layer, block, kv, head, slot, dim) -> int:
+    out = C.c_int64()
+    _check(lib().dk_kv_offset(pool, layer, block, kv, head, slot, dim, C.byref(out)))
+    return out.value
+
+
+def kv_validate_tables(pool, h_block_tables, h_seq_lens):
+    """h_block_tables: host int32 [B, max_blocks] (numpy); h_seq_lens: host int32 [B]."""
+    B, mb = h_block_tables.shape
+    _check(lib().dk_kv_validate_tables(pool, _ptr(h_block_tables), mb, _ptr(h_seq_lens), B))
+
+
+def append_kv(pool, layer, d_block_tables, d_seq_lens, d_k, d_v, stream=None):
+    B, mb = d_block_tables.shape
+    _check(lib().dk_append_kv(pool, layer, _ptr(d_block_tables), mb, _ptr(d_seq_lens), B,
+                              _ptr(d_k), _ptr(d_v), _stream(stream)))
+
+
+# ---- model ----------------------------------------------------------------
+def create_model(cfg: ModelConfig, weights: WeightPtrs):
+    out = C.c_void_p()
+    _check(lib().dk_create_model(C.byref(cfg), C.byref(weights), C.byref(out)))
+    return out
+
+
+def destroy_model(model):
+    _check(lib().dk_destroy_model(model))
+
+
+def workspace_bytes(model, max_B: int, max_blocks_per_seq: int) -> int:
+    out = C.c_size_t()
+    _check(lib().dk_workspace_bytes(model, max_B, max_blocks_per_seq, C.byref(out)))
+    return out.value
+
+
+def decode_step(model, pool, d_block_tables, d_seq_lens, d_tokens, d_workspace, d_logits,
+                d_next_tokens, flags: int = 0, stream=None, workspace_bytes_: int = None):
+    B, mb = d_block_tables.shape
+    nbytes = workspace_bytes_ if workspace_bytes_ is not None else d_workspace.numel() * d_workspace.element_size()
+    _check(lib().dk_decode_step(model, pool, _ptr(d_block_tables), mb, _ptr(d_seq_lens),
+                                _ptr(d_tokens), B, _ptr(d_workspace), nbytes, _ptr(d_logits),
+                                _ptr(d_next_tokens), flags, _stream(stream)))
+
+
+def step_algorithmic_bytes(model, pool, h_block_tables, h_seq_lens, with_logits=True,
+                           distinct_experts_per_layer=None) -> int:
+    B, mb = h_block_tables.shape
+    out = C.c_uint64()
+    _check(lib().dk_step_algorithmic_bytes(model, pool, _ptr(h_block_tables), mb, _ptr(h_seq_lens), B,
+                                           int(with_logits), _ptr(distinct_experts_per_layer),
+                                           C.byref(out)))
+    return out.value

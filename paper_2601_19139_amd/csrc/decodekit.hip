@@ -1,0 +1,620 @@
+// Host side of the decode-step library: handles, argument checks, block
+// accounting, workspace carving and kernel launches.  See include/decodekit.h
+// for the contract of every entry point.
+#include "../../include/decodekit.h"
+
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <set>
+#include <vector>
+
+#include "dk_attention.hip.h"
+#include "dk_gemv.hip.h"
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+dk_status fail(dk_status code, const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof g_err, fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+#define DK_HIP(expr)                                                                        \
+    do {                                                                                    \
+        hipError_t e_ = (expr);                                                             \
+        if (e_ != hipSuccess)                                                               \
+            return fail(DK_E_HIP, "%s: %s", #expr, hipGetErrorString(e_));                  \
+    } while (0)
+
+size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+dk_status check_config(const dk_model_config *c)
+{
+    if (!c) return fail(DK_E_INVALID_ARG, "config is NULL");
+    if (c->n_layers <= 0 || c->hidden <= 0 || c->n_q_heads <= 0 || c->n_kv_heads <= 0 ||
+        c->vocab <= 0)
+        return fail(DK_E_INVALID_ARG, "config has a non-positive dimension");
+    if (c->head_dim != 64 && c->head_dim != 128)
+        return fail(DK_E_UNSUPPORTED_SHAPE, "head_dim %d (64 or 128 supported)", c->head_dim);
+    if (c->n_q_heads % c->n_kv_heads)
+        return fail(DK_E_UNSUPPORTED_SHAPE, "n_q_heads %d is not a multiple of n_kv_heads %d",
+                    c->n_q_heads, c->n_kv_heads);
+    const int G = c->n_q_heads / c->n_kv_heads;
+    if (!(G == 1 || G == 2 || G == 3 || G == 4 || G == 6 || G == 8))
+        return fail(DK_E_UNSUPPORTED_SHAPE, "query group size %d (1,2,3,4,6,8 supported)", G);
+    if (c->hidden % 8) return fail(DK_E_UNSUPPORTED_SHAPE, "hidden %d not a multiple of 8", c->hidden);
+    if (c->n_experts < 0 || c->n_experts > DK_MAX_EXPERTS)
+        return fail(DK_E_UNSUPPORTED_SHAPE, "n_experts %d (at most %d)", c->n_experts, DK_MAX_EXPERTS);
+    if (c->n_experts > 0) {
+        if (c->top_k <= 0 || c->top_k > c->n_experts || c->top_k > 16)
+            return fail(DK_E_INVALID_ARG, "top_k %d with %d experts", c->top_k, c->n_experts);
+        if (c->expert_ffn <= 0 || c->expert_ffn % 8)
+            return fail(DK_E_UNSUPPORTED_SHAPE, "expert_ffn %d not a positive multiple of 8",
+                        c->expert_ffn);
+    } else if (c->ffn <= 0 || c->ffn % 8) {
+        return fail(DK_E_UNSUPPORTED_SHAPE, "ffn %d not a positive multiple of 8", c->ffn);
+    }
+    if (!(c->rms_eps >= 0.0) || !(c->rope_theta > 0.0))
+        return fail(DK_E_INVALID_ARG, "rms_eps / rope_theta out of range");
+    return DK_OK;
+}
+
+}  // namespace
+
+struct dk_kv_pool {
+    dk_model_config cfg;
+    int32_t num_blocks, block_size;
+    uint16_t *mem;
+    std::vector<int32_t> refcount;
+    std::set<int32_t> free_ids;
+};
+
+struct dk_model {
+    dk_model_config cfg;
+    const void *embed, *lm_head, *g_final;
+    std::vector<dk_layer_weights> layers;
+    double inv_freq[64];
+};
+
+namespace {
+
+struct Workspace {
+    size_t x, qkv, attn, act, cs, part, tickets, pmax_val, pmax_idx, total;
+    int chunk_tokens, max_chunks, lm_blocks;
+};
+
+constexpr int kLmRB = 8;  // rows per block of the lm_head GEMV
+
+Workspace carve(const dk_model_config &c, int B, int max_blocks)
+{
+    Workspace w{};
+    const int d = c.head_dim, G = c.n_q_heads / c.n_kv_heads;
+    const size_t qkv_dim = (size_t)(c.n_q_heads + 2 * c.n_kv_heads) * d;
+    const size_t act_dim = c.n_experts ? (size_t)c.top_k * c.expert_ffn : (size_t)c.ffn;
+    // split the context so that rows * kv heads * chunks gives the chip a few
+    // blocks per compute unit
+    const int ctx_max = max_blocks * 16;
+    int want_chunks = (1024 + B * c.n_kv_heads - 1) / (B * c.n_kv_heads);
+    if (want_chunks < 1) want_chunks = 1;
+    int chunk = (ctx_max + want_chunks - 1) / want_chunks;
+    chunk = (chunk + 63) / 64 * 64;
+    if (chunk < 64) chunk = 64;
+    w.chunk_tokens = chunk;
+    w.max_chunks = (ctx_max + chunk - 1) / chunk;
+    w.lm_blocks = (c.vocab + kLmRB - 1) / kLmRB;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
+    w.x = take((size_t)B * c.hidden * 4);
+    w.qkv = take((size_t)B * qkv_dim * 4);
+    w.attn = take((size_t)B * c.n_q_heads * d * 4);
+    w.act = take((size_t)B * act_dim * 4);
+    w.cs = take((size_t)B * (d / 2) * 8);
+    w.part = take((size_t)B * c.n_kv_heads * w.max_chunks * G * (d + 2) * 4);
+    w.tickets = take((size_t)B * c.n_kv_heads * 4);
+    w.pmax_val = take((size_t)B * w.lm_blocks * 4);
+    w.pmax_idx = take((size_t)B * w.lm_blocks * 4);
+    w.total = off;
+    return w;
+}
+
+// ---- GEMV dispatch ----------------------------------------------------------
+template <int NB, int EPI, bool NORM>
+dk_status launch_gemv_nb(const dk::GemvArgs &a, hipStream_t st)
+{
+    constexpr int RB = (EPI == dk::EPI_SWIGLU) ? 4 : 8;
+    const int grid = (a.N + RB - 1) / RB;
+    if (a.K >= 2048)
+        hipLaunchKernelGGL((dk::gemv_kernel<NB, 256, RB, EPI, NORM>), dim3(grid), dim3(256), 0, st, a);
+    else if (a.K >= 1024)
+        hipLaunchKernelGGL((dk::gemv_kernel<NB, 128, RB, EPI, NORM>), dim3(grid), dim3(128), 0, st, a);
+    else
+        hipLaunchKernelGGL((dk::gemv_kernel<NB, 64, RB, EPI, NORM>), dim3(grid), dim3(64), 0, st, a);
+    DK_HIP(hipGetLastError());
+    return DK_OK;
+}
+
+// y[B][N] from x[B][K]; batches above 4 rows are processed four rows at a time.
+template <int EPI, bool NORM>
+dk_status launch_gemv(dk::GemvArgs a, int B, hipStream_t st)
+{
+    const int grid = (a.N + ((EPI == dk::EPI_SWIGLU) ? 4 : 8) - 1) / ((EPI == dk::EPI_SWIGLU) ? 4 : 8);
+    for (int b0 = 0; b0 < B; b0 += 4) {
+        const int nb = std::min(4, B - b0);
+        dk::GemvArgs g = a;
+        g.x = a.x + (size_t)b0 * a.K;
+        g.y = a.y ? a.y + (size_t)b0 * a.N : nullptr;
+        if (a.resid) g.resid = a.resid + (size_t)b0 * a.N;
+        if (a.pmax_val) {
+            g.pmax_val = a.pmax_val + (size_t)b0 * grid;
+            g.pmax_idx = a.pmax_idx + (size_t)b0 * grid;
+        }
+        dk_status s;
+        switch (nb) {
+            case 1: s = launch_gemv_nb<1, EPI, NORM>(g, st); break;
+            case 2: s = launch_gemv_nb<2, EPI, NORM>(g, st); break;
+            case 3: s = launch_gemv_nb<3, EPI, NORM>(g, st); break;
+            default: s = launch_gemv_nb<4, EPI, NORM>(g, st); break;
+        }
+        if (s != DK_OK) return s;
+    }
+    return DK_OK;
+}
+
+template <int D>
+dk_status launch_attention_d(const dk::AttnArgs &a, int G, dim3 grid, hipStream_t st)
+{
+    switch (G) {
+        case 1: hipLaunchKernelGGL((dk::attention_kernel<D, 1>), grid, dim3(256), 0, st, a); break;
+        case 2: hipLaunchKernelGGL((dk::attention_kernel<D, 2>), grid, dim3(256), 0, st, a); break;
+        case 3: hipLaunchKernelGGL((dk::attention_kernel<D, 3>), grid, dim3(256), 0, st, a); break;
+        case 4: hipLaunchKernelGGL((dk::attention_kernel<D, 4>), grid, dim3(256), 0, st, a); break;
+        case 6: hipLaunchKernelGGL((dk::attention_kernel<D, 6>), grid, dim3(256), 0, st, a); break;
+        case 8: hipLaunchKernelGGL((dk::attention_kernel<D, 8>), grid, dim3(256), 0, st, a); break;
+        default: return fail(DK_E_UNSUPPORTED_SHAPE, "query group size %d", G);
+    }
+    DK_HIP(hipGetLastError());
+    return DK_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *dk_last_error(void) { return g_err; }
+
+const char *dk_version(void) { return "decodekit 0.1 (gfx950)"; }
+
+// ------------------------------------------------------------------- pool --
+dk_status dk_kv_pool_bytes(const dk_model_config *cfg, int32_t num_blocks, int32_t block_size,
+                           size_t *out_bytes)
+{
+    dk_status s = check_config(cfg);
+    if (s != DK_OK) return s;
+    if (!out_bytes) return fail(DK_E_INVALID_ARG, "out_bytes is NULL");
+    if (num_blocks <= 0) return fail(DK_E_INVALID_ARG, "num_blocks %d", num_blocks);
+    if (block_size != 16) return fail(DK_E_UNSUPPORTED_SHAPE, "block_size %d (16 supported)", block_size);
+    *out_bytes = (size_t)cfg->n_layers * num_blocks * 2 * cfg->n_kv_heads * block_size *
+                 cfg->head_dim * 2;
+    return DK_OK;
+}
+
+dk_status dk_create_kv_pool(const dk_model_config *cfg, int32_t num_blocks, int32_t block_size,
+                            void *dev_mem, size_t dev_bytes, dk_kv_pool **out)
+{
+    size_t need = 0;
+    dk_status s = dk_kv_pool_bytes(cfg, num_blocks, block_size, &need);
+    if (s != DK_OK) return s;
+    if (!out) return fail(DK_E_INVALID_ARG, "out is NULL");
+    if (!dev_mem) return fail(DK_E_INVALID_ARG, "dev_mem is NULL");
+    if (dev_bytes < need)
+        return fail(DK_E_INVALID_ARG, "pool memory too small: %zu bytes given, %zu needed", dev_bytes, need);
+    if ((uintptr_t)dev_mem % 16) return fail(DK_E_INVALID_ARG, "pool memory must be 16-byte aligned");
+    dk_kv_pool *p = new (std::nothrow) dk_kv_pool;
+    if (!p) return fail(DK_E_INVALID_ARG, "out of host memory");
+    p->cfg = *cfg;
+    p->num_blocks = num_blocks;
+    p->block_size = block_size;
+    p->mem = static_cast<uint16_t *>(dev_mem);
+    p->refcount.assign((size_t)num_blocks, 0);
+    for (int32_t i = 0; i < num_blocks; i++) p->free_ids.insert(i);
+    *out = p;
+    return DK_OK;
+}
+
+dk_status dk_destroy_kv_pool(dk_kv_pool *pool)
+{
+    delete pool;
+    return DK_OK;
+}
+
+dk_status dk_kv_alloc_block(dk_kv_pool *pool, int32_t *out_block_id)
+{
+    if (!pool || !out_block_id) return fail(DK_E_INVALID_ARG, "NULL argument");
+    if (pool->free_ids.empty())
+        return fail(DK_E_POOL_EXHAUSTED, "all %d blocks are in use", pool->num_blocks);
+    const int32_t id = *pool->free_ids.begin();
+    pool->free_ids.erase(pool->free_ids.begin());
+    pool->refcount[(size_t)id] = 1;
+    *out_block_id = id;
+    return DK_OK;
+}
+
+dk_status dk_kv_alloc_block_id(dk_kv_pool *pool, int32_t block_id)
+{
+    if (!pool) return fail(DK_E_INVALID_ARG, "pool is NULL");
+    if (block_id < 0 || block_id >= pool->num_blocks)
+        return fail(DK_E_BAD_BLOCK, "block %d out of range [0,%d)", block_id, pool->num_blocks);
+    if (pool->refcount[(size_t)block_id] != 0)
+        return fail(DK_E_BAD_BLOCK, "block %d is in use", block_id);
+    pool->free_ids.erase(block_id);
+    pool->refcount[(size_t)block_id] = 1;
+    return DK_OK;
+}
+
+dk_status dk_kv_retain_block(dk_kv_pool *pool, int32_t block_id)
+{
+    if (!pool) return fail(DK_E_INVALID_ARG, "pool is NULL");
+    if (block_id < 0 || block_id >= pool->num_blocks)
+        return fail(DK_E_BAD_BLOCK, "block %d out of range [0,%d)", block_id, pool->num_blocks);
+    if (pool->refcount[(size_t)block_id] == 0)
+        return fail(DK_E_BAD_BLOCK, "block %d is free; only a block in use can be shared", block_id);
+    pool->refcount[(size_t)block_id] += 1;
+    return DK_OK;
+}
+
+dk_status dk_kv_release_block(dk_kv_pool *pool, int32_t block_id)
+{
+    if (!pool) return fail(DK_E_INVALID_ARG, "pool is NULL");
+    if (block_id < 0 || block_id >= pool->num_blocks)
+        return fail(DK_E_BAD_BLOCK, "block %d out of range [0,%d)", block_id, pool->num_blocks);
+    if (pool->refcount[(size_t)block_id] == 0)
+        return fail(DK_E_BAD_BLOCK, "block %d is already free", block_id);
+    if (--pool->refcount[(size_t)block_id] == 0) pool->free_ids.insert(block_id);
+    return DK_OK;
+}
+
+dk_status dk_kv_refcount(const dk_kv_pool *pool, int32_t block_id, int32_t *out_refcount)
+{
+    if (!pool || !out_refcount) return fail(DK_E_INVALID_ARG, "NULL argument");
+    if (block_id < 0 || block_id >= pool->num_blocks)
+        return fail(DK_E_BAD_BLOCK, "block %d out of range [0,%d)", block_id, pool->num_blocks);
+    *out_refcount = pool->refcount[(size_t)block_id];
+    return DK_OK;
+}
+
+dk_status dk_kv_free_blocks(const dk_kv_pool *pool, int32_t *out_free)
+{
+    if (!pool || !out_free) return fail(DK_E_INVALID_ARG, "NULL argument");
+    *out_free = (int32_t)pool->free_ids.size();
+    return DK_OK;
+}
+
+dk_status dk_kv_offset(const dk_kv_pool *pool, int32_t layer, int32_t block, int32_t kv,
+                       int32_t head, int32_t slot, int32_t dim, int64_t *out_offset)
+{
+    if (!pool || !out_offset) return fail(DK_E_INVALID_ARG, "NULL argument");
+    const dk_model_config &c = pool->cfg;
+    if (layer < 0 || layer >= c.n_layers || block < 0 || block >= pool->num_blocks || kv < 0 ||
+        kv > 1 || head < 0 || head >= c.n_kv_heads || slot < 0 || slot >= pool->block_size ||
+        dim < 0 || dim >= c.head_dim)
+        return fail(DK_E_INVALID_ARG, "pool coordinate out of range");
+    *out_offset = (((((int64_t)layer * pool->num_blocks + block) * 2 + kv) * c.n_kv_heads + head) *
+                       pool->block_size + slot) * c.head_dim + dim;
+    return DK_OK;
+}
+
+dk_status dk_kv_validate_tables(const dk_kv_pool *pool, const int32_t *bt, int32_t max_blocks,
+                                const int32_t *seq_lens, int32_t B)
+{
+    if (!pool || !bt || !seq_lens) return fail(DK_E_INVALID_ARG, "NULL argument");
+    if (B <= 0 || max_blocks <= 0) return fail(DK_E_INVALID_ARG, "B %d, max_blocks_per_seq %d", B, max_blocks);
+    std::set<int32_t> targets;
+    for (int32_t b = 0; b < B; b++) {
+        const int32_t T = seq_lens[b];
+        if (T < 0 || T / pool->block_size >= max_blocks)
+            return fail(DK_E_INVALID_ARG, "row %d: seq_len %d does not fit %d blocks of %d", b, T,
+                        max_blocks, pool->block_size);
+        const int32_t last = T / pool->block_size;
+        for (int32_t i = 0; i <= last; i++) {
+            const int32_t id = bt[(size_t)b * max_blocks + i];
+            if (id < 0 || id >= pool->num_blocks)
+                return fail(DK_E_BAD_BLOCK, "row %d, table entry %d: block %d out of range [0,%d)", b,
+                            i, id, pool->num_blocks);
+            if (pool->refcount[(size_t)id] == 0)
+                return fail(DK_E_BAD_BLOCK, "row %d, table entry %d: block %d is free", b, i, id);
+        }
+        const int32_t tgt = bt[(size_t)b * max_blocks + last];
+        if (pool->refcount[(size_t)tgt] != 1)
+            return fail(DK_E_BAD_BLOCK, "row %d: append target block %d is shared (refcount %d)", b,
+                        tgt, pool->refcount[(size_t)tgt]);
+        if (!targets.insert(tgt).second)
+            return fail(DK_E_BAD_BLOCK, "row %d: append target block %d is also another row's", b, tgt);
+    }
+    return DK_OK;
+}
+
+dk_status dk_append_kv(dk_kv_pool *pool, int32_t layer, const int32_t *d_block_tables,
+                       int32_t max_blocks, const int32_t *d_seq_lens, int32_t B, const void *d_k,
+                       const void *d_v, void *hip_stream)
+{
+    if (!pool || !d_block_tables || !d_seq_lens || !d_k || !d_v)
+        return fail(DK_E_INVALID_ARG, "NULL argument");
+    if (layer < 0 || layer >= pool->cfg.n_layers) return fail(DK_E_INVALID_ARG, "layer %d", layer);
+    if (B <= 0 || B > DK_MAX_BATCH) return fail(DK_E_INVALID_ARG, "B %d (1..%d)", B, DK_MAX_BATCH);
+    if (max_blocks <= 0) return fail(DK_E_INVALID_ARG, "max_blocks_per_seq %d", max_blocks);
+    dk::AppendArgs a{static_cast<const uint16_t *>(d_k), static_cast<const uint16_t *>(d_v),
+                     pool->mem, d_block_tables, d_seq_lens, max_blocks, pool->num_blocks,
+                     pool->block_size, layer, pool->cfg.n_kv_heads, pool->cfg.head_dim};
+    hipLaunchKernelGGL(dk::append_kv_kernel, dim3(pool->cfg.n_kv_heads, B, 2), dim3(128), 0,
+                       static_cast<hipStream_t>(hip_stream), a);
+    DK_HIP(hipGetLastError());
+    return DK_OK;
+}
+
+// ------------------------------------------------------------------ model --
+dk_status dk_create_model(const dk_model_config *cfg, const dk_weight_ptrs *w, dk_model **out)
+{
+    dk_status s = check_config(cfg);
+    if (s != DK_OK) return s;
+    if (!w || !out) return fail(DK_E_INVALID_ARG, "NULL argument");
+    if (!w->embed || !w->lm_head || !w->g_final || !w->layers)
+        return fail(DK_E_INVALID_ARG, "a top-level weight pointer is NULL");
+    if (cfg->n_experts > 0)
+        return fail(DK_E_UNSUPPORTED_SHAPE, "mixture-of-experts layers are not implemented yet");
+    for (int l = 0; l < cfg->n_layers; l++) {
+        const dk_layer_weights &L = w->layers[l];
+        if (!L.g_attn || !L.w_qkv || !L.w_o || !L.g_mlp || !L.w_gate || !L.w_up || !L.w_down)
+            return fail(DK_E_INVALID_ARG, "layer %d: a weight pointer is NULL", l);
+        if (cfg->qk_norm && (!L.g_q || !L.g_k))
+            return fail(DK_E_INVALID_ARG, "layer %d: qk_norm set but g_q / g_k is NULL", l);
+        if (cfg->n_experts > 0 && !L.w_router)
+            return fail(DK_E_INVALID_ARG, "layer %d: w_router is NULL", l);
+    }
+    dk_model *m = new (std::nothrow) dk_model;
+    if (!m) return fail(DK_E_INVALID_ARG, "out of host memory");
+    m->cfg = *cfg;
+    m->embed = w->embed;
+    m->lm_head = w->lm_head;
+    m->g_final = w->g_final;
+    m->layers.assign(w->layers, w->layers + cfg->n_layers);
+    const int half = cfg->head_dim / 2;
+    for (int i = 0; i < 64; i++)
+        m->inv_freq[i] = i < half ? std::pow(cfg->rope_theta, -2.0 * i / cfg->head_dim) : 0.0;
+    *out = m;
+    return DK_OK;
+}
+
+dk_status dk_destroy_model(dk_model *model)
+{
+    delete model;
+    return DK_OK;
+}
+
+dk_status dk_workspace_bytes(const dk_model *model, int32_t max_B, int32_t max_blocks,
+                             size_t *out_bytes)
+{
+    if (!model || !out_bytes) return fail(DK_E_INVALID_ARG, "NULL argument");
+    if (max_B <= 0 || max_B > DK_MAX_BATCH) return fail(DK_E_INVALID_ARG, "max_B %d (1..%d)", max_B, DK_MAX_BATCH);
+    if (max_blocks <= 0) return fail(DK_E_INVALID_ARG, "max_blocks_per_seq %d", max_blocks);
+    *out_bytes = carve(model->cfg, max_B, max_blocks).total;
+    return DK_OK;
+}
+
+dk_status dk_decode_step(dk_model *model, dk_kv_pool *pool, const int32_t *d_block_tables,
+                         int32_t max_blocks, int32_t *d_seq_lens, int32_t *d_tokens, int32_t B,
+                         void *d_workspace, size_t workspace_bytes, float *d_logits,
+                         int32_t *d_next_tokens, uint32_t flags, void *hip_stream)
+{
+    if (!model || !pool || !d_block_tables || !d_seq_lens || !d_tokens || !d_workspace ||
+        !d_next_tokens)
+        return fail(DK_E_INVALID_ARG, "NULL argument");
+    if (B <= 0 || B > DK_MAX_BATCH) return fail(DK_E_INVALID_ARG, "B %d (1..%d)", B, DK_MAX_BATCH);
+    if (max_blocks <= 0) return fail(DK_E_INVALID_ARG, "max_blocks_per_seq %d", max_blocks);
+    if (flags & ~DK_STEP_ADVANCE) return fail(DK_E_INVALID_ARG, "unknown flags 0x%x", flags);
+    const dk_model_config &c = model->cfg;
+    const dk_model_config &pc = pool->cfg;
+    if (pc.n_layers != c.n_layers || pc.n_kv_heads != c.n_kv_heads || pc.head_dim != c.head_dim)
+        return fail(DK_E_INVALID_ARG, "pool was created for a different model shape");
+    if ((uintptr_t)d_workspace % 256) return fail(DK_E_INVALID_ARG, "workspace must be 256-byte aligned");
+    const Workspace w = carve(c, B, max_blocks);
+    if (workspace_bytes < w.total)
+        return fail(DK_E_WORKSPACE_TOO_SMALL, "workspace %zu bytes, %zu needed", workspace_bytes, w.total);
+
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    char *ws = static_cast<char *>(d_workspace);
+    float *x = reinterpret_cast<float *>(ws + w.x);
+    float *qkv = reinterpret_cast<float *>(ws + w.qkv);
+    float *attn = reinterpret_cast<float *>(ws + w.attn);
+    float *act = reinterpret_cast<float *>(ws + w.act);
+    float2 *cs = reinterpret_cast<float2 *>(ws + w.cs);
+    float *part = reinterpret_cast<float *>(ws + w.part);
+    int *tickets = reinterpret_cast<int *>(ws + w.tickets);
+    float *pmax_val = reinterpret_cast<float *>(ws + w.pmax_val);
+    int *pmax_idx = reinterpret_cast<int *>(ws + w.pmax_idx);
+
+    const int H = c.hidden, d = c.head_dim, nq = c.n_q_heads, nkv = c.n_kv_heads;
+    const int qkv_dim = (nq + 2 * nkv) * d;
+    const float eps = (float)c.rms_eps;
+    dk_status s;
+
+    {
+        dk::EmbedArgs e{};
+        e.embed = static_cast<const uint16_t *>(model->embed);
+        e.tokens = d_tokens;
+        e.seq_lens = d_seq_lens;
+        e.x = x;
+        e.cs = cs;
+        e.tickets = tickets;
+        e.n_tickets = B * nkv;
+        e.H = H;
+        e.half = d / 2;
+        e.V = c.vocab;
+        std::memcpy(e.inv_freq, model->inv_freq, sizeof e.inv_freq);
+        hipLaunchKernelGGL(dk::embed_kernel, dim3(B), dim3(256), 0, st, e);
+        DK_HIP(hipGetLastError());
+    }
+
+    for (int l = 0; l < c.n_layers; l++) {
+        const dk_layer_weights &L = model->layers[(size_t)l];
+        {   // q, k, v = W_qkv * rmsnorm(x)
+            dk::GemvArgs g{};
+            g.W = static_cast<const uint16_t *>(L.w_qkv);
+            g.x = x;
+            g.gain = static_cast<const uint16_t *>(L.g_attn);
+            g.eps = eps;
+            g.y = qkv;
+            g.N = qkv_dim;
+            g.K = H;
+            if ((s = launch_gemv<dk::EPI_STORE, true>(g, B, st)) != DK_OK) return s;
+        }
+        {   // head norm, rotation, append
+            dk::RopeAppendArgs r{};
+            r.qkv = qkv;
+            r.cs = cs;
+            r.g_q = c.qk_norm ? static_cast<const uint16_t *>(L.g_q) : nullptr;
+            r.g_k = c.qk_norm ? static_cast<const uint16_t *>(L.g_k) : nullptr;
+            r.pool = pool->mem;
+            r.block_tables = d_block_tables;
+            r.seq_lens = d_seq_lens;
+            r.max_blocks = max_blocks;
+            r.num_blocks = pool->num_blocks;
+            r.block_size = pool->block_size;
+            r.layer = l;
+            r.nq = nq;
+            r.nkv = nkv;
+            r.d = d;
+            r.eps = eps;
+            hipLaunchKernelGGL(dk::rope_append_kernel, dim3(nq + 2 * nkv, B), dim3(64), 0, st, r);
+            DK_HIP(hipGetLastError());
+        }
+        {   // attention over positions 0..T
+            dk::AttnArgs a{};
+            a.q = qkv;
+            a.pool = pool->mem;
+            a.block_tables = d_block_tables;
+            a.seq_lens = d_seq_lens;
+            a.out = attn;
+            a.part = part;
+            a.tickets = tickets;
+            a.max_blocks = max_blocks;
+            a.num_blocks = pool->num_blocks;
+            a.layer = l;
+            a.nq = nq;
+            a.nkv = nkv;
+            a.chunk_tokens = w.chunk_tokens;
+            a.max_chunks = w.max_chunks;
+            a.q_stride = qkv_dim;
+            a.scale = (float)(1.0 / std::sqrt((double)d));
+            const dim3 grid(w.max_chunks, nkv, B);
+            s = (d == 128) ? launch_attention_d<128>(a, nq / nkv, grid, st)
+                           : launch_attention_d<64>(a, nq / nkv, grid, st);
+            if (s != DK_OK) return s;
+        }
+        {   // x += W_o * attn
+            dk::GemvArgs g{};
+            g.W = static_cast<const uint16_t *>(L.w_o);
+            g.x = attn;
+            g.y = x;
+            g.resid = x;
+            g.N = H;
+            g.K = nq * d;
+            if ((s = launch_gemv<dk::EPI_RESID, false>(g, B, st)) != DK_OK) return s;
+        }
+        {   // act = silu(W_gate * h) * (W_up * h), h = rmsnorm(x)
+            dk::GemvArgs g{};
+            g.W = static_cast<const uint16_t *>(L.w_gate);
+            g.W2 = static_cast<const uint16_t *>(L.w_up);
+            g.x = x;
+            g.gain = static_cast<const uint16_t *>(L.g_mlp);
+            g.eps = eps;
+            g.y = act;
+            g.N = c.ffn;
+            g.K = H;
+            if ((s = launch_gemv<dk::EPI_SWIGLU, true>(g, B, st)) != DK_OK) return s;
+        }
+        {   // x += W_down * act
+            dk::GemvArgs g{};
+            g.W = static_cast<const uint16_t *>(L.w_down);
+            g.x = act;
+            g.y = x;
+            g.resid = x;
+            g.N = H;
+            g.K = c.ffn;
+            if ((s = launch_gemv<dk::EPI_RESID, false>(g, B, st)) != DK_OK) return s;
+        }
+    }
+
+    {   // logits = W_lm * rmsnorm(x); greedy token
+        dk::GemvArgs g{};
+        g.W = static_cast<const uint16_t *>(model->lm_head);
+        g.x = x;
+        g.gain = static_cast<const uint16_t *>(model->g_final);
+        g.eps = eps;
+        g.N = c.vocab;
+        g.K = H;
+        g.pmax_val = pmax_val;
+        g.pmax_idx = pmax_idx;
+        // without a logits buffer the values still need a place to land: reuse is not
+        // possible (B*V floats), so the kernel stores only when asked
+        g.y = d_logits;
+        if ((s = launch_gemv<dk::EPI_STORE, true>(g, B, st)) != DK_OK) return s;
+        dk::ArgmaxArgs am{pmax_val, pmax_idx, w.lm_blocks, d_next_tokens, d_tokens, d_seq_lens,
+                          (flags & DK_STEP_ADVANCE) ? 1 : 0};
+        hipLaunchKernelGGL(dk::argmax_final_kernel, dim3(B), dim3(256), 0, st, am);
+        DK_HIP(hipGetLastError());
+    }
+    return DK_OK;
+}
+
+dk_status dk_step_algorithmic_bytes(const dk_model *model, const dk_kv_pool *pool,
+                                    const int32_t *bt, int32_t max_blocks, const int32_t *seq_lens,
+                                    int32_t B, int32_t with_logits, const int32_t *distinct_experts,
+                                    uint64_t *out_bytes)
+{
+    if (!model || !pool || !bt || !seq_lens || !out_bytes) return fail(DK_E_INVALID_ARG, "NULL argument");
+    if (B <= 0 || max_blocks <= 0) return fail(DK_E_INVALID_ARG, "B %d, max_blocks_per_seq %d", B, max_blocks);
+    const dk_model_config &c = model->cfg;
+    const uint64_t H = (uint64_t)c.hidden, d = (uint64_t)c.head_dim;
+    const uint64_t qd = (uint64_t)c.n_q_heads * d, kvd = (uint64_t)c.n_kv_heads * d;
+    uint64_t per_layer = H * qd + 2 * H * kvd + qd * H;   // q, k, v, o
+    uint64_t bytes = 0;
+    if (c.n_experts > 0) {
+        if (!distinct_experts) return fail(DK_E_INVALID_ARG, "MoE model needs distinct_experts_per_layer");
+        per_layer += (uint64_t)c.n_experts * H;
+        for (int l = 0; l < c.n_layers; l++)
+            bytes += 2 * (uint64_t)distinct_experts[l] * 3 * H * (uint64_t)c.expert_ffn;
+    } else {
+        per_layer += 3 * H * (uint64_t)c.ffn;
+    }
+    bytes += 2 * ((uint64_t)c.n_layers * per_layer + (uint64_t)c.vocab * H);
+    // live KV: every distinct (block, slot) once, including this step's token
+    std::set<int64_t> slots;
+    for (int32_t b = 0; b < B; b++) {
+        const int32_t T = seq_lens[b];
+        if (T < 0 || T / pool->block_size >= max_blocks)
+            return fail(DK_E_INVALID_ARG, "row %d: seq_len %d does not fit the table", b, T);
+        for (int32_t t = 0; t <= T; t++) {
+            const int32_t id = bt[(size_t)b * max_blocks + t / pool->block_size];
+            if (id < 0 || id >= pool->num_blocks)
+                return fail(DK_E_BAD_BLOCK, "row %d: block %d out of range", b, id);
+            slots.insert((int64_t)id * pool->block_size + t % pool->block_size);
+        }
+    }
+    bytes += (uint64_t)slots.size() * (uint64_t)c.n_layers * 2 * kvd * 2;
+    bytes += (uint64_t)B * H * 2;                                   // embedding rows
+    if (with_logits) bytes += (uint64_t)B * (uint64_t)c.vocab * 4;  // logits written
+    *out_bytes = bytes;
+    return DK_OK;
+}
+
+}  // extern "C"

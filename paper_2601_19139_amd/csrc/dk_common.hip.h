@@ -1,0 +1,88 @@
+// Device helpers shared by the decode-step kernels (gfx950, wave64).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace dk {
+
+constexpr int kWave = 64;
+
+// ---- bf16 <-> f32 ---------------------------------------------------------
+// A 32-bit word holds two bf16: element 2i in the low half, 2i+1 in the high.
+__device__ __forceinline__ float bf16lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+__device__ __forceinline__ float bf16_to_f32(uint16_t h) { return __uint_as_float((uint32_t)h << 16); }
+
+// float32 -> bf16, round to nearest, ties to even (NaN stays NaN).
+__device__ __forceinline__ uint16_t f32_to_bf16_rne(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x0040u);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+__device__ __forceinline__ void unpack8(const uint4 &w, float (&f)[8])
+{
+    f[0] = bf16lo(w.x); f[1] = bf16hi(w.x);
+    f[2] = bf16lo(w.y); f[3] = bf16hi(w.y);
+    f[4] = bf16lo(w.z); f[5] = bf16hi(w.z);
+    f[6] = bf16lo(w.w); f[7] = bf16hi(w.w);
+}
+
+// ---- cross-lane reductions with DPP ---------------------------------------
+// dpp_ctrl encodings: quad_perm = perm bits; 0x140 row_mirror; 0x141
+// row_half_mirror; 0x142 row_bcast15; 0x143 row_bcast31.
+template <int CTRL, int ROW_MASK = 0xF>
+__device__ __forceinline__ float dpp_f(float v)
+{
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, ROW_MASK, 0xF, true));
+}
+
+// Sum over each aligned group of 8 lanes; every lane of the group gets it.
+__device__ __forceinline__ float sum8(float v)
+{
+    v += dpp_f<0xB1>(v);   // quad_perm [1,0,3,2]
+    v += dpp_f<0x4E>(v);   // quad_perm [2,3,0,1]
+    v += dpp_f<0x141>(v);  // mirror within 8
+    return v;
+}
+// Sum over each row of 16 lanes; every lane of the row gets it.
+__device__ __forceinline__ float sum16(float v)
+{
+    v = sum8(v);
+    v += dpp_f<0x140>(v);  // mirror within 16
+    return v;
+}
+// Sum over the 64 lanes of the wave; every lane gets it.
+__device__ __forceinline__ float sum64(float v)
+{
+    v = sum16(v);
+    v += __shfl_xor(v, 16);
+    v += __shfl_xor(v, 32);
+    return v;
+}
+__device__ __forceinline__ float max64(float v)
+{
+    v = fmaxf(v, dpp_f<0xB1>(v));
+    v = fmaxf(v, dpp_f<0x4E>(v));
+    v = fmaxf(v, dpp_f<0x141>(v));
+    v = fmaxf(v, dpp_f<0x140>(v));
+    v = fmaxf(v, __shfl_xor(v, 16));
+    v = fmaxf(v, __shfl_xor(v, 32));
+    return v;
+}
+
+__device__ __forceinline__ uint4 ld16(const void *p) { return *reinterpret_cast<const uint4 *>(p); }
+__device__ __forceinline__ float4 ldf4(const float *p) { return *reinterpret_cast<const float4 *>(p); }
+
+// Element offset of the first element of a (layer, block, kv, head) tile of
+// the KV pool: pool[layer][block][kv][head][slot][dim].
+__device__ __forceinline__ int64_t kv_tile_offset(int layer, int num_blocks, int block, int kv,
+                                                  int n_kv_heads, int head, int block_size, int d)
+{
+    return ((((int64_t)layer * num_blocks + block) * 2 + kv) * n_kv_heads + head) *
+           (int64_t)(block_size * d);
+}
+
+}  // namespace dk

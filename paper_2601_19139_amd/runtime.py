@@ -1,0 +1,121 @@
+"""Device-memory plumbing around the C ABI: uploads seeded bf16 bit patterns
+into torch tensors, keeps them alive, and hands their addresses to the library.
+No arithmetic of the decode path happens here."""
+import ctypes as C
+
+import numpy as np
+
+from . import binding as dk
+
+
+def _torch():
+    import torch
+    if not torch.cuda.is_available():
+        raise dk.DecodeKitError(-6, "no HIP device: the decode path has no CPU fallback")
+    return torch
+
+
+def _dev_bf16(bits: np.ndarray):
+    """uint16 bf16 bit patterns (host) -> device tensor of the same bits."""
+    torch = _torch()
+    t = torch.from_numpy(np.ascontiguousarray(bits).view(np.int16))
+    return t.cuda()
+
+
+class DeviceModel:
+    """Weights resident in HBM + the library's model handle.  q, k and v
+    matrices are stored as one [(nq+2nkv)*d, H] matrix (rows q, then k, then v)."""
+
+    def __init__(self, shape, weights: dict):
+        self.shape = shape
+        self.cfg = dk.ModelConfig.from_shape(shape)
+        self.tensors = []
+        keep = self.tensors.append
+
+        def up(a):
+            t = _dev_bf16(a)
+            keep(t)
+            return t.data_ptr()
+
+        embed = up(weights["embed"])
+        lm_head = embed if weights["lm_head"] is weights["embed"] else up(weights["lm_head"])
+        g_final = up(weights["g_final"])
+        self._layers = (dk.LayerWeights * shape.n_layers)()
+        for i, L in enumerate(weights["layers"]):
+            s = self._layers[i]
+            s.g_attn = up(L["g_attn"])
+            s.w_qkv = up(np.concatenate([L["wq"], L["wk"], L["wv"]], axis=0))
+            s.g_q = up(L["g_q"]) if "g_q" in L else None
+            s.g_k = up(L["g_k"]) if "g_k" in L else None
+            s.w_o = up(L["wo"])
+            s.g_mlp = up(L["g_mlp"])
+            s.w_gate = up(L["w_gate"])
+            s.w_up = up(L["w_up"])
+            s.w_down = up(L["w_down"])
+            s.w_router = up(L["w_router"]) if "w_router" in L else None
+        self._ptrs = dk.WeightPtrs(embed, lm_head, g_final, self._layers)
+        self.handle = dk.create_model(self.cfg, self._ptrs)
+
+    def close(self):
+        if self.handle is not None:
+            dk.destroy_model(self.handle)
+            self.handle = None
+
+
+class DeviceKV:
+    """A KV pool in HBM (torch-owned memory) + the library's pool handle, with
+    block ownership mirrored from a block layout (ids, shared prefixes)."""
+
+    def __init__(self, dmodel: DeviceModel, layout, pool_bits: np.ndarray = None):
+        torch = _torch()
+        self.layout = layout
+        nbytes = dk.kv_pool_bytes(dmodel.cfg, layout.num_blocks, layout.block_size)
+        if pool_bits is not None:
+            assert pool_bits.nbytes == nbytes
+            self.mem = _dev_bf16(pool_bits)
+        else:
+            self.mem = torch.zeros(nbytes // 2, dtype=torch.int16, device="cuda")
+        self.handle = dk.create_kv_pool(dmodel.cfg, layout.num_blocks, layout.block_size,
+                                        self.mem, nbytes)
+        # take every block a table names; a block named by several tables is shared
+        for b in range(layout.tables.shape[0]):
+            for bid in layout.tables[b]:
+                bid = int(bid)
+                if bid < 0:
+                    continue
+                if dk.kv_refcount(self.handle, bid) == 0:
+                    dk.kv_alloc_block_id(self.handle, bid)
+                else:
+                    dk.kv_retain_block(self.handle, bid)
+        self.block_tables = torch.from_numpy(np.ascontiguousarray(layout.tables)).cuda()
+
+    def bits(self) -> np.ndarray:
+        return self.mem.cpu().numpy().view(np.uint16)
+
+    def close(self):
+        if self.handle is not None:
+            dk.destroy_kv_pool(self.handle)
+            self.handle = None
+
+
+class Decoder:
+    """Buffers for repeated decode steps of a fixed batch."""
+
+    def __init__(self, dmodel: DeviceModel, dkv: DeviceKV, seq_lens, tokens, want_logits=True):
+        torch = _torch()
+        self.m, self.kv = dmodel, dkv
+        B, mb = dkv.layout.tables.shape
+        self.B = B
+        self.seq_lens = torch.from_numpy(np.ascontiguousarray(seq_lens, dtype=np.int32)).cuda()
+        self.tokens = torch.from_numpy(np.ascontiguousarray(tokens, dtype=np.int32)).cuda()
+        self.next = torch.empty(B, dtype=torch.int32, device="cuda")
+        self.logits = (torch.empty((B, dmodel.shape.vocab), dtype=torch.float32, device="cuda")
+                       if want_logits else None)
+        self.ws_bytes = dk.workspace_bytes(dmodel.handle, B, mb)
+        self.ws = torch.empty(self.ws_bytes + 256, dtype=torch.uint8, device="cuda")
+        self._ws_ptr = (self.ws.data_ptr() + 255) // 256 * 256
+
+    def step(self, flags: int = 0, stream=None):
+        dk.decode_step(self.m.handle, self.kv.handle, self.kv.block_tables, self.seq_lens,
+                       self.tokens, self._ws_ptr, self.logits, self.next, flags, stream,
+                       workspace_bytes_=self.ws_bytes)

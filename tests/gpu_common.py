@@ -1,0 +1,92 @@
+"""Helpers for the GPU parity tests: run the HIP path and the CPU oracle on
+the same seeded inputs and compare."""
+import numpy as np
+
+import workloads as W
+
+
+def rel_l2(got, ref):
+    got = got.astype(np.float64)
+    ref = ref.astype(np.float64)
+    return np.linalg.norm(got - ref, axis=-1) / np.linalg.norm(ref, axis=-1)
+
+
+def bf16_close(a_bits, b_bits):
+    """True where two stored bf16 values agree up to rounding: the float32
+    values they were rounded from differ by at most 1e-4 of the largest
+    magnitude (ten times the measured error of the path), and rounding adds at
+    most one bf16 step (2^-7 relative) on top of that."""
+    a = W.f32_from_bf16_bits(a_bits).astype(np.float64)
+    b = W.f32_from_bf16_bits(b_bits).astype(np.float64)
+    floor = 1e-4 * max(float(np.abs(b).max()), 1e-30)
+    return np.abs(a - b) <= 2.0 ** -7 * np.maximum(np.abs(a), np.abs(b)) + floor
+
+
+def run_both(orc, shape, weights, layout, pool_bits, tokens, steps, teacher_forced=True,
+             want_pool=True, gpu_flags=0):
+    """Runs `steps` decode steps on the GPU and in the oracle.
+
+    teacher_forced: the GPU is fed the oracle's tokens at every step (the graded
+    mode).  Returns a dict of per-step logits / tokens from both and the final
+    pools."""
+    import torch
+    import paper_2601_19139_amd as dk
+    dm = dk.DeviceModel(shape, weights)
+    dkv = dk.DeviceKV(dm, layout, pool_bits)
+    opool = pool_bits.copy()
+    sl = layout.contexts.copy().astype(np.int32)
+    otok = np.asarray(tokens, dtype=np.int32).copy()
+    dec = dk.Decoder(dm, dkv, sl, otok)
+    out = {"gpu_logits": [], "orc_logits": [], "gpu_next": [], "orc_next": []}
+    for s in range(steps):
+        dk.kv_validate_tables(dkv.handle, layout.tables, sl)
+        r = orc.decode_step(shape, weights, opool, layout.block_size, layout.tables, sl, otok)
+        dec.step(flags=gpu_flags)
+        torch.cuda.synchronize()
+        out["gpu_logits"].append(dec.logits.cpu().numpy().copy())
+        out["gpu_next"].append(dec.next.cpu().numpy().copy())
+        out["orc_logits"].append(r["logits"])
+        out["orc_next"].append(r["next"])
+        sl = sl + 1
+        otok = r["next"]
+        if gpu_flags & dk.STEP_ADVANCE:
+            # the kernel advanced its own state (free running)
+            assert np.array_equal(dec.seq_lens.cpu().numpy(), sl)
+            assert np.array_equal(dec.tokens.cpu().numpy(), out["gpu_next"][-1])
+        if teacher_forced or not (gpu_flags & dk.STEP_ADVANCE):
+            dec.seq_lens.copy_(torch.from_numpy(sl))
+            nxt = otok if teacher_forced else out["gpu_next"][-1]
+            dec.tokens.copy_(torch.from_numpy(np.ascontiguousarray(nxt)))
+    if want_pool:
+        out["gpu_pool"] = dkv.bits().reshape(pool_bits.shape)
+        out["orc_pool"] = opool
+    dkv.close()
+    dm.close()
+    return out
+
+
+def check_parity(out, tol=1e-2, min_agree=0.99):
+    """The bar: relative L2 of the logits <= tol for every row of every step
+    (the stated tolerance of the decode path), greedy agreement >= min_agree."""
+    worst, agree, total = 0.0, 0, 0
+    for gl, ol, gn, on in zip(out["gpu_logits"], out["orc_logits"], out["gpu_next"], out["orc_next"]):
+        assert np.all(np.isfinite(gl))
+        worst = max(worst, float(rel_l2(gl, ol).max()))
+        agree += int((gn == on).sum())
+        total += gn.size
+    assert worst <= tol, f"logits relative L2 {worst:.3e} > {tol}"
+    assert agree >= min_agree * total, f"greedy agreement {agree}/{total}"
+    return worst, agree / total
+
+
+def check_pool(out, pool_before, shape, layout, steps):
+    """Appends must land at exactly the oracle's offsets; values may differ by
+    the bf16 rounding of nearly equal float32 numbers (<= 1 step, rarely)."""
+    g, o = out["gpu_pool"], out["orc_pool"]
+    g_changed = g != pool_before
+    o_changed = o != pool_before
+    # every slot the oracle wrote was poison before, so "changed" = "written"
+    assert np.array_equal(g_changed, o_changed), "append addressing differs from the oracle"
+    assert int(o_changed.sum()) == shape.n_layers * layout.tables.shape[0] * 2 * shape.kv_dim * steps
+    assert bf16_close(g[o_changed], o[o_changed]).all(), "appended value differs by more than rounding"
+    assert (g[o_changed] != o[o_changed]).mean() < 0.02

@@ -1,0 +1,203 @@
+"""CPU-side tests of the C ABI: the library loads, exports every symbol the
+header declares, and its host logic (block accounting, argument checks,
+workspace sizing, byte accounting) behaves.  No kernel is launched here."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+import workloads as W
+from workloads.blocktable import layout_for
+import paper_2601_19139_amd as dk
+from paper_2601_19139_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def header_symbols():
+    text = open(os.path.join(ROOT, "include", "decodekit.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(dk_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    L = dk.lib()
+    syms = header_symbols()
+    assert len(syms) >= 19
+    for s in syms:
+        assert hasattr(L, s), s
+    assert sorted(binding.EXPORTS) == syms           # the binding covers the whole header
+    assert "gfx950" in dk.version()
+
+
+def tiny_cfg():
+    return dk.DkModelConfig.from_shape(W.CONFIGS["tiny"])
+
+
+def test_pool_bytes_and_offset_formula():
+    shape = W.CONFIGS["tiny"]
+    cfg = tiny_cfg()
+    nbytes = dk.kv_pool_bytes(cfg, 5, 16)
+    assert nbytes == int(np.prod(W.pool_shape(shape, 5, 16))) * 2
+    pool = dk.create_kv_pool(cfg, 5, 16, 0x1000, nbytes)      # memory is never touched on the host
+    flat = np.arange(nbytes // 2).reshape(W.pool_shape(shape, 5, 16))
+    for idx in [(0, 0, 0, 0, 0, 0), (1, 4, 1, 1, 15, 63), (1, 2, 0, 1, 7, 5), (0, 3, 1, 0, 9, 33)]:
+        assert dk.kv_offset(pool, *idx) == flat[idx]
+    with pytest.raises(dk.DecodeKitError) as e:
+        dk.kv_offset(pool, 2, 0, 0, 0, 0, 0)
+    assert e.value.status == "DK_E_INVALID_ARG"
+    dk.destroy_kv_pool(pool)
+
+
+def test_block_accounting():
+    cfg = tiny_cfg()
+    pool = dk.create_kv_pool(cfg, 4, 16, 0x1000, dk.kv_pool_bytes(cfg, 4, 16))
+    assert dk.kv_free_blocks(pool) == 4
+    a, b = dk.kv_alloc_block(pool), dk.kv_alloc_block(pool)
+    assert (a, b) == (0, 1)
+    dk.kv_alloc_block_id(pool, 3)
+    with pytest.raises(dk.DecodeKitError) as e:
+        dk.kv_alloc_block_id(pool, 3)
+    assert e.value.status == "DK_E_BAD_BLOCK"
+    dk.kv_retain_block(pool, a)                    # a second sequence shares block a
+    assert dk.kv_refcount(pool, a) == 2
+    dk.kv_release_block(pool, a)
+    assert dk.kv_refcount(pool, a) == 1 and dk.kv_free_blocks(pool) == 1
+    dk.kv_release_block(pool, a)
+    assert dk.kv_refcount(pool, a) == 0 and dk.kv_free_blocks(pool) == 2
+    with pytest.raises(dk.DecodeKitError):
+        dk.kv_release_block(pool, a)               # already free
+    with pytest.raises(dk.DecodeKitError):
+        dk.kv_retain_block(pool, a)                # cannot share a free block
+    assert dk.kv_alloc_block(pool) == 0            # lowest free id first
+    assert dk.kv_alloc_block(pool) == 2
+    with pytest.raises(dk.DecodeKitError) as e:
+        dk.kv_alloc_block(pool)
+    assert e.value.status == "DK_E_POOL_EXHAUSTED" and "in use" in str(e.value)
+    with pytest.raises(dk.DecodeKitError) as e:
+        dk.kv_refcount(pool, 4)
+    assert e.value.status == "DK_E_BAD_BLOCK"
+    dk.destroy_kv_pool(pool)
+
+
+def test_validate_tables():
+    wl = W.WORKLOADS["cfg2"]
+    lay = layout_for(wl)
+    cfg = dk.DkModelConfig.from_shape(wl.cfg)
+    pool = dk.create_kv_pool(cfg, lay.num_blocks, 16, 0x1000, dk.kv_pool_bytes(cfg, lay.num_blocks, 16))
+    for b in range(wl.batch):
+        for bid in lay.tables[b]:
+            if bid >= 0:
+                if dk.kv_refcount(pool, int(bid)) == 0:
+                    dk.kv_alloc_block_id(pool, int(bid))
+                else:
+                    dk.kv_retain_block(pool, int(bid))
+    assert dk.kv_free_blocks(pool) == 0
+    assert dk.kv_refcount(pool, int(lay.tables[0, 0])) == 8        # the shared 1024-token prefix
+    dk.kv_validate_tables(pool, lay.tables, lay.contexts)
+    # append into a shared block is refused
+    bad_len = lay.contexts.copy()
+    bad_len[0] = 1000
+    with pytest.raises(dk.DecodeKitError) as e:
+        dk.kv_validate_tables(pool, lay.tables, bad_len)
+    assert e.value.status == "DK_E_BAD_BLOCK" and "shared" in str(e.value)
+    bad = lay.tables.copy()
+    bad[3, 1] = lay.num_blocks
+    with pytest.raises(dk.DecodeKitError) as e:
+        dk.kv_validate_tables(pool, bad, lay.contexts)
+    assert "out of range" in str(e.value)
+    bad = lay.tables.copy()
+    bad[9, int(lay.contexts[9]) // 16] = bad[10, int(lay.contexts[10]) // 16]
+    with pytest.raises(dk.DecodeKitError) as e:
+        dk.kv_validate_tables(pool, bad, lay.contexts)
+    assert "another row" in str(e.value) or "shared" in str(e.value)
+    too_long = lay.contexts.copy()
+    too_long[2] = lay.max_blocks * 16
+    with pytest.raises(dk.DecodeKitError) as e:
+        dk.kv_validate_tables(pool, lay.tables, too_long)
+    assert e.value.status == "DK_E_INVALID_ARG"
+    dk.destroy_kv_pool(pool)
+
+
+def fake_model(shape):
+    cfg = dk.DkModelConfig.from_shape(shape)
+    layers = (dk.LayerWeights * shape.n_layers)()
+    for s in layers:
+        for n in binding.LAYER_FIELDS:
+            setattr(s, n, 0x1000)
+    ptrs = dk.WeightPtrs(0x1000, 0x1000, 0x1000, layers)
+    return cfg, ptrs, layers
+
+
+def test_model_shape_checks_and_workspace():
+    cfg, ptrs, _keep = fake_model(W.CONFIGS["qwen3_8b"])
+    m = dk.create_model(cfg, ptrs)
+    small = dk.workspace_bytes(m, 1, 40)
+    big = dk.workspace_bytes(m, 16, 260)
+    assert 0 < small < big < 64 << 20
+    with pytest.raises(dk.DecodeKitError) as e:
+        dk.workspace_bytes(m, 65, 40)
+    assert e.value.status == "DK_E_INVALID_ARG"
+    # decode_step argument checks fire before any launch
+    pcfg = dk.DkModelConfig.from_shape(W.CONFIGS["tiny"])
+    wrong_pool = dk.create_kv_pool(pcfg, 4, 16, 0x1000, dk.kv_pool_bytes(pcfg, 4, 16))
+    tables = np.zeros((1, 4), dtype=np.int32)
+    with pytest.raises(dk.DecodeKitError) as e:
+        dk.decode_step(m, wrong_pool, tables, 0x1000, 0x1000, 0x1000, None, 0x1000, stream=0,
+                       workspace_bytes_=1 << 30)
+    assert "different model shape" in str(e.value)
+    pool = dk.create_kv_pool(cfg, 4, 16, 0x1000, dk.kv_pool_bytes(cfg, 4, 16))
+    with pytest.raises(dk.DecodeKitError) as e:
+        dk.decode_step(m, pool, tables, 0x1000, 0x1000, 0x1000, None, 0x1000, stream=0,
+                       workspace_bytes_=16)
+    assert e.value.status == "DK_E_WORKSPACE_TOO_SMALL"
+    with pytest.raises(dk.DecodeKitError) as e:
+        dk.decode_step(m, pool, tables, 0x1000, 0x1000, 0x1001, None, 0x1000, stream=0,
+                       workspace_bytes_=1 << 30)
+    assert "aligned" in str(e.value)
+    dk.destroy_model(m)
+    for field, val, status in [("head_dim", 96, "DK_E_UNSUPPORTED_SHAPE"),
+                               ("n_q_heads", 30, "DK_E_UNSUPPORTED_SHAPE"),
+                               ("hidden", 4100, "DK_E_UNSUPPORTED_SHAPE"),
+                               ("n_layers", 0, "DK_E_INVALID_ARG")]:
+        c2, p2, _k2 = fake_model(W.CONFIGS["qwen3_8b"])
+        setattr(c2, field, val)
+        with pytest.raises(dk.DecodeKitError) as e:
+            dk.create_model(c2, p2)
+        assert e.value.status == status, field
+    c3, p3, l3 = fake_model(W.CONFIGS["qwen3_8b"])
+    l3[5].g_q = None
+    with pytest.raises(dk.DecodeKitError) as e:
+        dk.create_model(c3, p3)
+    assert "layer 5" in str(e.value)
+
+
+@pytest.mark.parametrize("wname,expect_gb", [("cfg1", 1.251), ("cfg3", 24.80)])
+def test_algorithmic_bytes_match_the_formula(wname, expect_gb):
+    wl = W.WORKLOADS[wname]
+    lay = layout_for(wl)
+    cfg, ptrs, _keep = fake_model(wl.cfg)
+    m = dk.create_model(cfg, ptrs)
+    pool = dk.create_kv_pool(cfg, lay.num_blocks, 16, 0x1000, dk.kv_pool_bytes(cfg, lay.num_blocks, 16))
+    got = dk.step_algorithmic_bytes(m, pool, lay.tables, lay.contexts, with_logits=False)
+    want = (wl.cfg.dense_weight_bytes()
+            + lay.unique_live_tokens(extra=1) * wl.cfg.kv_bytes_per_token()
+            + wl.batch * wl.cfg.hidden * 2)
+    assert got == want
+    assert abs(got / 1e9 - expect_gb) < 0.01 * expect_gb
+    dk.destroy_model(m)
+    dk.destroy_kv_pool(pool)
+
+
+def test_shared_prefix_counts_once_in_algorithmic_bytes():
+    wl = W.WORKLOADS["cfg2"]
+    lay = layout_for(wl)
+    cfg, ptrs, _keep = fake_model(wl.cfg)
+    m = dk.create_model(cfg, ptrs)
+    pool = dk.create_kv_pool(cfg, lay.num_blocks, 16, 0x1000, dk.kv_pool_bytes(cfg, lay.num_blocks, 16))
+    got = dk.step_algorithmic_bytes(m, pool, lay.tables, lay.contexts, with_logits=False)
+    logical = int(sum(int(t) + 1 for t in lay.contexts))
+    unique = logical - 7 * 1024
+    assert got == wl.cfg.dense_weight_bytes() + unique * wl.cfg.kv_bytes_per_token() + 16 * wl.cfg.hidden * 2

@@ -107,9 +107,30 @@ def layer_tensor_shapes(cfg: ModelConfig):
     return t
 
 
+def normal_bf16_many(seed: int, specs: dict) -> dict:
+    """Several tensors at once: specs maps name -> (shape, std, mean).  Same
+    values as one normal_bf16 call per name; all chunks share the thread pool."""
+    outs, tasks = {}, []
+    for name, (shape, std, mean) in specs.items():
+        n = int(np.prod(shape))
+        res = np.empty(n, dtype=np.uint16)
+        outs[name] = res.reshape(shape)
+        key = _name_key(name)
+        for c in range((n + _CHUNK - 1) // _CHUNK):
+            tasks.append((res, key, c, min(n, (c + 1) * _CHUNK) - c * _CHUNK, std, mean))
+
+    def work(t):
+        res, key, c, m, std, mean = t
+        res[c * _CHUNK: c * _CHUNK + m] = _chunk_normal(seed, key, c, m, std, mean)
+
+    list(_pool().map(work, tasks))
+    return outs
+
+
 def make_layer(cfg: ModelConfig, seed: int, layer: int):
-    return {k: normal_bf16(seed, f"layer{layer}.{k}", shp, std, mean)
-            for k, (shp, std, mean) in layer_tensor_shapes(cfg).items()}
+    specs = {f"layer{layer}.{k}": v for k, v in layer_tensor_shapes(cfg).items()}
+    out = normal_bf16_many(seed, specs)
+    return {k.split(".", 1)[1]: v for k, v in out.items()}
 
 
 def make_weights(cfg: ModelConfig, seed: int = 0, layers=None):
@@ -120,11 +141,18 @@ def make_weights(cfg: ModelConfig, seed: int = 0, layers=None):
     generated (others are None), for models too large to hold at once.
     """
     V, H = cfg.vocab, cfg.hidden
-    w = {"embed": normal_bf16(seed, "embed", (V, H), 0.02)}
-    w["lm_head"] = w["embed"] if cfg.tie_lm_head else normal_bf16(seed, "lm_head", (V, H), 0.02)
-    w["g_final"] = normal_bf16(seed, "g_final", (H,), 0.02, 1.0)
+    specs = {"embed": ((V, H), 0.02, 0.0), "g_final": ((H,), 0.02, 1.0)}
+    if not cfg.tie_lm_head:
+        specs["lm_head"] = ((V, H), 0.02, 0.0)
     want = range(cfg.n_layers) if layers is None else layers
-    w["layers"] = [make_layer(cfg, seed, l) if l in want else None for l in range(cfg.n_layers)]
+    for l in want:
+        for k, v in layer_tensor_shapes(cfg).items():
+            specs[f"layer{l}.{k}"] = v
+    t = normal_bf16_many(seed, specs)
+    w = {"embed": t["embed"], "g_final": t["g_final"]}
+    w["lm_head"] = t["embed"] if cfg.tie_lm_head else t["lm_head"]
+    w["layers"] = [{k: t[f"layer{l}.{k}"] for k in layer_tensor_shapes(cfg)} if l in want else None
+                   for l in range(cfg.n_layers)]
     return w
 
 
