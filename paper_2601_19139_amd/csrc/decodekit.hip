@@ -91,9 +91,11 @@ namespace {
 struct Workspace {
     size_t x, qkv, attn, act, cs, part, tickets, pmax_val, pmax_idx, total;
     int chunk_tokens, max_chunks, lm_blocks;
+    bool defer_merge;   // small problems: the output projection merges the attention chunks
 };
 
-constexpr int kLmRB = 8;  // rows per block of the lm_head GEMV
+constexpr int kLmRB = 8;     // rows per tile of the lm_head GEMV
+constexpr int kLmTiles = 1;  // tiles per block of the lm_head GEMV
 
 Workspace carve(const dk_model_config &c, int B, int max_blocks)
 {
@@ -111,7 +113,25 @@ Workspace carve(const dk_model_config &c, int B, int max_blocks)
     if (chunk < 64) chunk = 64;
     w.chunk_tokens = chunk;
     w.max_chunks = (ctx_max + chunk - 1) / chunk;
-    w.lm_blocks = (c.vocab + kLmRB - 1) / kLmRB;
+    w.defer_merge = false;
+    // With few rows and a short context the chunk partials are a few tens of KB:
+    // the output projection then merges them as it loads its input (at most 8
+    // chunks, one round of loads), which saves the attention kernel a round of
+    // device-wide synchronisation.
+    if (B <= 4) {
+        int chunk8 = ((ctx_max + 7) / 8 + 63) / 64 * 64;
+        if (chunk8 < chunk) chunk8 = chunk;
+        const int n8 = (ctx_max + chunk8 - 1) / chunk8;
+        if ((size_t)B * c.n_q_heads * n8 * (d + 2) * 4 <= (96u << 10) && chunk8 <= 512) {
+            w.defer_merge = true;
+            w.chunk_tokens = chunk8;
+            w.max_chunks = n8;
+        }
+    }
+    {
+        const int rb = ((size_t)c.vocab * c.hidden * 2 < (64u << 20)) ? 2 : kLmRB;
+        w.lm_blocks = (c.vocab + rb * kLmTiles - 1) / (rb * kLmTiles);
+    }
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
     w.x = take((size_t)B * c.hidden * 4);
@@ -128,30 +148,53 @@ Workspace carve(const dk_model_config &c, int B, int max_blocks)
 }
 
 // ---- GEMV dispatch ----------------------------------------------------------
-template <int NB, int EPI, bool NORM>
-dk_status launch_gemv_nb(const dk::GemvArgs &a, hipStream_t st)
+// Rows per block tile.  Small matrices (a few MB, one or two loads per lane)
+// are latency-bound: two rows per block spread them over every compute unit.
+// Large ones (lm_head) stream better with eight rows per block.
+inline bool gemv_small(const dk::GemvArgs &a) { return (size_t)a.N * a.K * 2 < (64u << 20); }
+template <int EPI>
+inline int gemv_rows_per_tile(const dk::GemvArgs &a)
 {
-    constexpr int RB = (EPI == dk::EPI_SWIGLU) ? 4 : 8;
-    const int grid = (a.N + RB - 1) / RB;
+    return gemv_small(a) ? 2 : (EPI == dk::EPI_SWIGLU ? 4 : 8);
+}
+
+template <int NB, int RB, int EPI, bool NORM, bool XATTN>
+dk_status launch_gemv_rb(const dk::GemvArgs &a, hipStream_t st)
+{
+    const int grid = (a.N + RB * a.tiles - 1) / (RB * a.tiles);
     if (a.K >= 2048)
-        hipLaunchKernelGGL((dk::gemv_kernel<NB, 256, RB, EPI, NORM>), dim3(grid), dim3(256), 0, st, a);
+        hipLaunchKernelGGL((dk::gemv_kernel<NB, 256, RB, EPI, NORM, XATTN>), dim3(grid), dim3(256), 0, st, a);
     else if (a.K >= 1024)
-        hipLaunchKernelGGL((dk::gemv_kernel<NB, 128, RB, EPI, NORM>), dim3(grid), dim3(128), 0, st, a);
+        hipLaunchKernelGGL((dk::gemv_kernel<NB, 128, RB, EPI, NORM, XATTN>), dim3(grid), dim3(128), 0, st, a);
     else
-        hipLaunchKernelGGL((dk::gemv_kernel<NB, 64, RB, EPI, NORM>), dim3(grid), dim3(64), 0, st, a);
+        hipLaunchKernelGGL((dk::gemv_kernel<NB, 64, RB, EPI, NORM, XATTN>), dim3(grid), dim3(64), 0, st, a);
     DK_HIP(hipGetLastError());
     return DK_OK;
 }
 
+template <int NB, int EPI, bool NORM, bool XATTN = false>
+dk_status launch_gemv_nb(const dk::GemvArgs &a, hipStream_t st)
+{
+    if (gemv_small(a)) return launch_gemv_rb<NB, 2, EPI, NORM, XATTN>(a, st);
+    return launch_gemv_rb<NB, (EPI == dk::EPI_SWIGLU ? 4 : 8), EPI, NORM, XATTN>(a, st);
+}
+
 // y[B][N] from x[B][K]; batches above 4 rows are processed four rows at a time.
-template <int EPI, bool NORM>
+template <int EPI, bool NORM, bool XATTN = false>
 dk_status launch_gemv(dk::GemvArgs a, int B, hipStream_t st)
 {
-    const int grid = (a.N + ((EPI == dk::EPI_SWIGLU) ? 4 : 8) - 1) / ((EPI == dk::EPI_SWIGLU) ? 4 : 8);
+    static_assert(!XATTN || (EPI == dk::EPI_RESID && !NORM), "partials feed the output projection only");
+    if (a.tiles < 1) a.tiles = 1;
+    const int rows_per_block = gemv_rows_per_tile<EPI>(a) * a.tiles;
+    const int grid = (a.N + rows_per_block - 1) / rows_per_block;
     for (int b0 = 0; b0 < B; b0 += 4) {
         const int nb = std::min(4, B - b0);
         dk::GemvArgs g = a;
         g.x = a.x + (size_t)b0 * a.K;
+        if (XATTN) {
+            g.part = a.part + (size_t)b0 * a.nkv * a.max_chunks * a.group * (a.d + 2);
+            g.seq_lens = a.seq_lens + b0;
+        }
         g.y = a.y ? a.y + (size_t)b0 * a.N : nullptr;
         if (a.resid) g.resid = a.resid + (size_t)b0 * a.N;
         if (a.pmax_val) {
@@ -160,10 +203,10 @@ dk_status launch_gemv(dk::GemvArgs a, int B, hipStream_t st)
         }
         dk_status s;
         switch (nb) {
-            case 1: s = launch_gemv_nb<1, EPI, NORM>(g, st); break;
-            case 2: s = launch_gemv_nb<2, EPI, NORM>(g, st); break;
-            case 3: s = launch_gemv_nb<3, EPI, NORM>(g, st); break;
-            default: s = launch_gemv_nb<4, EPI, NORM>(g, st); break;
+            case 1: s = launch_gemv_nb<1, EPI, NORM, XATTN>(g, st); break;
+            case 2: s = launch_gemv_nb<2, EPI, NORM, XATTN>(g, st); break;
+            case 3: s = launch_gemv_nb<3, EPI, NORM, XATTN>(g, st); break;
+            default: s = launch_gemv_nb<4, EPI, NORM, XATTN>(g, st); break;
         }
         if (s != DK_OK) return s;
     }
@@ -477,29 +520,12 @@ dk_status dk_decode_step(dk_model *model, dk_kv_pool *pool, const int32_t *d_blo
             g.K = H;
             if ((s = launch_gemv<dk::EPI_STORE, true>(g, B, st)) != DK_OK) return s;
         }
-        {   // head norm, rotation, append
-            dk::RopeAppendArgs r{};
-            r.qkv = qkv;
-            r.cs = cs;
-            r.g_q = c.qk_norm ? static_cast<const uint16_t *>(L.g_q) : nullptr;
-            r.g_k = c.qk_norm ? static_cast<const uint16_t *>(L.g_k) : nullptr;
-            r.pool = pool->mem;
-            r.block_tables = d_block_tables;
-            r.seq_lens = d_seq_lens;
-            r.max_blocks = max_blocks;
-            r.num_blocks = pool->num_blocks;
-            r.block_size = pool->block_size;
-            r.layer = l;
-            r.nq = nq;
-            r.nkv = nkv;
-            r.d = d;
-            r.eps = eps;
-            hipLaunchKernelGGL(dk::rope_append_kernel, dim3(nq + 2 * nkv, B), dim3(64), 0, st, r);
-            DK_HIP(hipGetLastError());
-        }
-        {   // attention over positions 0..T
+        {   // head norm, rotation, KV append and attention over positions 0..T
             dk::AttnArgs a{};
-            a.q = qkv;
+            a.qkv = qkv;
+            a.cs = cs;
+            a.g_q = c.qk_norm ? static_cast<const uint16_t *>(L.g_q) : nullptr;
+            a.g_k = c.qk_norm ? static_cast<const uint16_t *>(L.g_k) : nullptr;
             a.pool = pool->mem;
             a.block_tables = d_block_tables;
             a.seq_lens = d_seq_lens;
@@ -513,8 +539,9 @@ dk_status dk_decode_step(dk_model *model, dk_kv_pool *pool, const int32_t *d_blo
             a.nkv = nkv;
             a.chunk_tokens = w.chunk_tokens;
             a.max_chunks = w.max_chunks;
-            a.q_stride = qkv_dim;
+            a.defer_merge = w.defer_merge ? 1 : 0;
             a.scale = (float)(1.0 / std::sqrt((double)d));
+            a.eps = eps;
             const dim3 grid(w.max_chunks, nkv, B);
             s = (d == 128) ? launch_attention_d<128>(a, nq / nkv, grid, st)
                            : launch_attention_d<64>(a, nq / nkv, grid, st);
@@ -528,7 +555,20 @@ dk_status dk_decode_step(dk_model *model, dk_kv_pool *pool, const int32_t *d_blo
             g.resid = x;
             g.N = H;
             g.K = nq * d;
-            if ((s = launch_gemv<dk::EPI_RESID, false>(g, B, st)) != DK_OK) return s;
+            if (w.defer_merge) {
+                g.part = part;
+                g.seq_lens = d_seq_lens;
+                g.chunk_tokens = w.chunk_tokens;
+                g.max_chunks = w.max_chunks;
+                g.max_blocks = max_blocks;
+                g.group = nq / nkv;
+                g.d = d;
+                g.nkv = nkv;
+                s = launch_gemv<dk::EPI_RESID, false, true>(g, B, st);
+            } else {
+                s = launch_gemv<dk::EPI_RESID, false>(g, B, st);
+            }
+            if (s != DK_OK) return s;
         }
         {   // act = silu(W_gate * h) * (W_up * h), h = rmsnorm(x)
             dk::GemvArgs g{};
@@ -564,13 +604,14 @@ dk_status dk_decode_step(dk_model *model, dk_kv_pool *pool, const int32_t *d_blo
         g.K = H;
         g.pmax_val = pmax_val;
         g.pmax_idx = pmax_idx;
+        g.tiles = kLmTiles;
         // without a logits buffer the values still need a place to land: reuse is not
         // possible (B*V floats), so the kernel stores only when asked
         g.y = d_logits;
         if ((s = launch_gemv<dk::EPI_STORE, true>(g, B, st)) != DK_OK) return s;
         dk::ArgmaxArgs am{pmax_val, pmax_idx, w.lm_blocks, d_next_tokens, d_tokens, d_seq_lens,
                           (flags & DK_STEP_ADVANCE) ? 1 : 0};
-        hipLaunchKernelGGL(dk::argmax_final_kernel, dim3(B), dim3(256), 0, st, am);
+        hipLaunchKernelGGL(dk::argmax_final_kernel, dim3(B), dim3(1024), 0, st, am);
         DK_HIP(hipGetLastError());
     }
     return DK_OK;

@@ -43,69 +43,6 @@ __global__ __launch_bounds__(256) void embed_kernel(EmbedArgs a)
         for (int i = tid; i < a.n_tickets; i += 256) a.tickets[i] = 0;
 }
 
-// ---------------------------------------------------------------------------
-// Per head of the fused qkv vector: (q, k) optional RMSNorm over the head,
-// half-split rotation by the step's angle; q is written back in place (f32),
-// k and v are rounded to bf16 and stored at position seq_lens[b] of the
-// sequence through its block table.  One wave per (row, head); lane i owns the
-// rotation pair (i, i + d/2).
-struct RopeAppendArgs {
-    float *qkv;             // [B][(nq+2nkv)*d]
-    const float2 *cs;       // [B][d/2]
-    const uint16_t *g_q, *g_k;  // [d] or null
-    uint16_t *pool;
-    const int *block_tables;
-    const int *seq_lens;
-    int max_blocks, num_blocks, block_size;
-    int layer, nq, nkv, d;
-    float eps;
-};
-
-__global__ __launch_bounds__(64) void rope_append_kernel(RopeAppendArgs a)
-{
-    const int head = blockIdx.x, b = blockIdx.y, lane = threadIdx.x;
-    const int d = a.d, half = d >> 1;
-    const bool act = lane < half;
-    float *v = a.qkv + (int64_t)b * (a.nq + 2 * a.nkv) * d + (int64_t)head * d;
-    float lo = act ? v[lane] : 0.f, hi = act ? v[lane + half] : 0.f;
-    const bool is_q = head < a.nq, is_k = !is_q && head < a.nq + a.nkv;
-    if (is_q || is_k) {
-        const uint16_t *g = is_q ? a.g_q : a.g_k;
-        if (g != nullptr) {
-            float ss = sum64(lo * lo + hi * hi);
-            float inv = rsqrtf(ss / (float)d + a.eps);
-            if (act) {
-                lo = lo * inv * bf16_to_f32(g[lane]);
-                hi = hi * inv * bf16_to_f32(g[lane + half]);
-            }
-        }
-        if (act) {
-            float2 cs = a.cs[b * half + lane];
-            float nlo = lo * cs.x - hi * cs.y;
-            float nhi = hi * cs.x + lo * cs.y;
-            lo = nlo;
-            hi = nhi;
-        }
-    }
-    if (!act) return;
-    if (is_q) {
-        v[lane] = lo;
-        v[lane + half] = hi;
-        return;
-    }
-    // positions / block ids outside the table or pool are clamped: the result
-    // is then meaningless but no access leaves the caller's buffers
-    const int pos = min(max(a.seq_lens[b], 0), a.max_blocks * a.block_size - 1);
-    const int block = min(max(a.block_tables[(int64_t)b * a.max_blocks + pos / a.block_size], 0),
-                          a.num_blocks - 1);
-    const int slot = pos % a.block_size;
-    const int kvh = is_k ? head - a.nq : head - a.nq - a.nkv;
-    uint16_t *dst = a.pool + kv_tile_offset(a.layer, a.num_blocks, block, is_k ? 0 : 1, a.nkv, kvh,
-                                            a.block_size, d) + (int64_t)slot * d;
-    dst[lane] = f32_to_bf16_rne(lo);
-    dst[lane + half] = f32_to_bf16_rne(hi);
-}
-
 // Stand-alone append of caller-provided bf16 K/V rows (bit for bit).
 struct AppendArgs {
     const uint16_t *k, *v;  // [B][nkv][d]
@@ -130,32 +67,78 @@ __global__ __launch_bounds__(128) void append_kv_kernel(AppendArgs a)
 }
 
 // ---------------------------------------------------------------------------
-// Ragged grouped-query decode attention, split over the context.
+// Fused q/k head norm + rotary embedding + KV append + ragged grouped-query
+// decode attention, split over the context.
 //
 // grid = (chunks, kv heads, rows); a block handles `chunk_tokens` consecutive
 // positions of one sequence for one kv head and the G query heads that share
-// it, so every K/V byte is read once for all G heads.  A wave reads a 16-token
-// block tile (contiguous 16*d bf16) with 16-byte lane loads: D/8 lanes span a
-// token, so one load covers 512/D tokens.  Each aligned group of D/8 lanes
-// keeps its own running (max, sum, output) over the tokens it sees; the groups
-// of a wave, the waves of a block and finally the chunks of a sequence are
-// merged with the usual rescaling by exp(max differences).  The last block to
-// finish for a (row, kv head) merges the chunk partials, in chunk order, so
-// results do not depend on timing.
+// it, so every K/V byte is read once for all G heads.
+//
+// Prologue: each aligned group of D/8 lanes holds a whole head (8 dims per
+// lane), so the head RMSNorm is a reduction inside the group and the rotation
+// partner (dim +- D/2) sits D/16 lanes away.  Every block prepares its G query
+// heads this way.  The block that owns the chunk containing the new position T
+// also prepares the new k and v, rounds them to bf16, stores them at position T
+// through the block table, and feeds the rounded values to its own softmax as
+// one more token (so cached positions < T come from the pool, T from registers).
+//
+// Main loop: a wave reads a 16-token block tile (contiguous 16*D bf16) with
+// 16-byte lane loads; one load covers 512/D tokens.  Each lane group keeps its
+// own running (max, sum, output) over the tokens it sees; groups, waves and
+// finally chunks are merged with the usual exp(max difference) rescaling.  The
+// last block to finish for a (row, kv head) merges the chunk partials in chunk
+// order, so results do not depend on timing.  Partials cross compute dies
+// through device-coherent stores and loads (no cache flush is needed then).
 struct AttnArgs {
-    const float *q;          // [B][(nq+2nkv)*d]: q heads first (already rotated)
-    const uint16_t *pool;
+    const float *qkv;        // [B][(nq+2nkv)*d]: raw projections q | k | v
+    const float2 *cs;        // [B][d/2] (cos, sin) at the row's position
+    const uint16_t *g_q, *g_k;  // [d] head-norm gains or null
+    uint16_t *pool;
     const int *block_tables;
     const int *seq_lens;
     float *out;              // [B][nq*d]
     float *part;             // [B][nkv][max_chunks][G][d+2]
-    int *tickets;            // [B*nkv]
+    int *tickets;            // [B*nkv], zero before the launch, zero after
     int max_blocks, num_blocks, layer, nq, nkv;
     int chunk_tokens;        // multiple of 64
     int max_chunks;
-    int q_stride;            // (nq+2nkv)*d
-    float scale;
+    int defer_merge;         // 1: leave the chunk partials for the consumer to merge
+    float scale, eps;
 };
+
+__device__ __forceinline__ void st_coherent(float *p, float v)
+{
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float ld_coherent(const float *p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// One head held as 8 dims per lane by an aligned group of TPR = D/8 lanes:
+// optional RMSNorm over the head (gain g, already loaded), then the half-split
+// rotation by the angles whose (cos, sin) are in cs (already loaded; cs[e]
+// belongs to dim (dl + e) mod D/2).
+template <int D>
+__device__ __forceinline__ void head_norm_rope(float (&h)[8], bool norm, const float (&g)[8],
+                                               float eps, const float2 (&cs)[8], bool upper)
+{
+    constexpr int TPR = D / 8;
+    if (norm) {
+        float ss = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; e++) ss += h[e] * h[e];
+        ss = (TPR == 16) ? sum16(ss) : sum8(ss);
+        const float inv = rsqrtf(ss / (float)D + eps);
+#pragma unroll
+        for (int e = 0; e < 8; e++) h[e] = h[e] * inv * g[e];
+    }
+#pragma unroll
+    for (int e = 0; e < 8; e++) {
+        const float other = __shfl_xor(h[e], TPR / 2);   // element dl+e +- D/2
+        h[e] = upper ? h[e] * cs[e].x + other * cs[e].y : h[e] * cs[e].x - other * cs[e].y;
+    }
+}
 
 template <int D, int G>
 __global__ __launch_bounds__(256) void attention_kernel(AttnArgs a)
@@ -171,22 +154,86 @@ __global__ __launch_bounds__(256) void attention_kernel(AttnArgs a)
 
     const int c = blockIdx.x, j = blockIdx.y, b = blockIdx.z;
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-    // keys to attend to, incl. the new token (clamped to what the table can name)
-    const int T1 = min(max(a.seq_lens[b], 0) + 1, a.max_blocks * BS);
-    const int nact = (T1 + a.chunk_tokens - 1) / a.chunk_tokens;
-    if (c >= nact) return;
-    const int t0 = c * a.chunk_tokens;
-    const int t1 = min(T1, t0 + a.chunk_tokens);
     const int dl = (lane % TPR) * 8;   // this lane's 8 dims
     const int sub = lane / TPR;        // token within a wave load
+    const int q_stride = (a.nq + 2 * a.nkv) * D;
+    const float *row = a.qkv + (int64_t)b * q_stride;
+    const float2 *cs_row = a.cs + (int64_t)b * (D / 2);
+    const int *table = a.block_tables + (int64_t)b * a.max_blocks;
 
+    // Everything that does not depend on the sequence length is requested
+    // before the length is looked at, so the loads overlap: the raw q heads and
+    // the first block-table entry this wave will need (always inside the table).
     float q[G][8];
 #pragma unroll
     for (int g = 0; g < G; g++) {
-        const float *qp = a.q + (int64_t)b * a.q_stride + (int64_t)(j * G + g) * D + dl;
-        float4 lo = ldf4(qp), hi = ldf4(qp + 4);
-        q[g][0] = lo.x * a.scale; q[g][1] = lo.y * a.scale; q[g][2] = lo.z * a.scale; q[g][3] = lo.w * a.scale;
-        q[g][4] = hi.x * a.scale; q[g][5] = hi.y * a.scale; q[g][6] = hi.z * a.scale; q[g][7] = hi.w * a.scale;
+        const float *qp = row + (int64_t)(j * G + g) * D + dl;
+        const float4 lo = ldf4(qp), hi = ldf4(qp + 4);
+        q[g][0] = lo.x; q[g][1] = lo.y; q[g][2] = lo.z; q[g][3] = lo.w;
+        q[g][4] = hi.x; q[g][5] = hi.y; q[g][6] = hi.z; q[g][7] = hi.w;
+    }
+    const bool upper = dl >= D / 2;
+    float2 cs[8];
+    {
+        const float4 *cp = reinterpret_cast<const float4 *>(cs_row + (upper ? dl - D / 2 : dl));
+#pragma unroll
+        for (int e = 0; e < 4; e++) {
+            const float4 t = cp[e];
+            cs[2 * e] = make_float2(t.x, t.y);
+            cs[2 * e + 1] = make_float2(t.z, t.w);
+        }
+    }
+    const bool norm = a.g_q != nullptr;
+    float gq[8], gk[8];
+    if (norm) {
+        unpack8(ld16(a.g_q + dl), gq);
+        unpack8(ld16(a.g_k + dl), gk);
+    } else {
+#pragma unroll
+        for (int e = 0; e < 8; e++) gq[e] = gk[e] = 1.f;
+    }
+    // raw k and v of the new token (only the block owning position T uses them)
+    float kn[8], vn[8];
+    {
+        const float *kp = row + (int64_t)(a.nq + j) * D + dl;
+        const float *vp = row + (int64_t)(a.nq + a.nkv + j) * D + dl;
+        const float4 klo = ldf4(kp), khi = ldf4(kp + 4), vlo = ldf4(vp), vhi = ldf4(vp + 4);
+        kn[0] = klo.x; kn[1] = klo.y; kn[2] = klo.z; kn[3] = klo.w;
+        kn[4] = khi.x; kn[5] = khi.y; kn[6] = khi.z; kn[7] = khi.w;
+        vn[0] = vlo.x; vn[1] = vlo.y; vn[2] = vlo.z; vn[3] = vlo.w;
+        vn[4] = vhi.x; vn[5] = vhi.y; vn[6] = vhi.z; vn[7] = vhi.w;
+    }
+    const int first_blk = c * (a.chunk_tokens / BS) + wv;
+    int phys_next = table[min(first_blk, a.max_blocks - 1)];
+    // T = cached tokens = position of the new token (clamped to what the table can name)
+    const int T = min(max(a.seq_lens[b], 0), a.max_blocks * BS - 1);
+    const int T1 = T + 1;
+    const int nact = (T1 + a.chunk_tokens - 1) / a.chunk_tokens;
+    if (c >= nact) return;
+    const int t0 = c * a.chunk_tokens;
+    const int t1 = min(T, t0 + a.chunk_tokens);   // cached positions [t0, t1) come from the pool
+    const bool owns_new = (c == nact - 1);        // position T itself
+
+    const int blk_end = (t1 + BS - 1) / BS;
+    // the tile after the current one is already in flight while the current is used
+    uint4 kw[NI], vw[NI], kw_n[NI], vw_n[NI];
+    if (first_blk < blk_end) {
+        const int phys = min(max(phys_next, 0), a.num_blocks - 1);
+        const uint16_t *kt = a.pool + kv_tile_offset(a.layer, a.num_blocks, phys, 0, a.nkv, j, BS, D);
+        const uint16_t *vt = kt + (int64_t)a.nkv * BS * D;
+#pragma unroll
+        for (int i = 0; i < NI; i++) {
+            kw_n[i] = ld16(kt + i * 512 + lane * 8);
+            vw_n[i] = ld16(vt + i * 512 + lane * 8);
+        }
+        phys_next = table[min(first_blk + NWV, a.max_blocks - 1)];
+    }
+
+#pragma unroll
+    for (int g = 0; g < G; g++) {
+        head_norm_rope<D>(q[g], norm, gq, a.eps, cs, upper);
+#pragma unroll
+        for (int e = 0; e < 8; e++) q[g][e] *= a.scale;
     }
     float m[G], l[G], o[G][8];
 #pragma unroll
@@ -197,17 +244,56 @@ __global__ __launch_bounds__(256) void attention_kernel(AttnArgs a)
         for (int e = 0; e < 8; e++) o[g][e] = 0.f;
     }
 
-    const int *table = a.block_tables + (int64_t)b * a.max_blocks;
-    const int blk_end = (t1 + BS - 1) / BS;
-    for (int blk = t0 / BS + wv; blk < blk_end; blk += NWV) {
-        const int phys = min(max(table[blk], 0), a.num_blocks - 1);
-        const uint16_t *kt = a.pool + kv_tile_offset(a.layer, a.num_blocks, phys, 0, a.nkv, j, BS, D);
-        const uint16_t *vt = kt + (int64_t)a.nkv * BS * D;
-        uint4 kw[NI], vw[NI];
+    if (owns_new && wv == 0) {
+        // the new token: k (norm, rotation) and v, rounded to bf16, stored, and used
+        head_norm_rope<D>(kn, norm, gk, a.eps, cs, upper);
+        uint32_t kb[4], vb[4];
 #pragma unroll
-        for (int i = 0; i < NI; i++) {
-            kw[i] = ld16(kt + i * 512 + lane * 8);
-            vw[i] = ld16(vt + i * 512 + lane * 8);
+        for (int e = 0; e < 4; e++) {
+            const uint32_t k0 = f32_to_bf16_rne(kn[2 * e]), k1 = f32_to_bf16_rne(kn[2 * e + 1]);
+            const uint32_t v0 = f32_to_bf16_rne(vn[2 * e]), v1 = f32_to_bf16_rne(vn[2 * e + 1]);
+            kb[e] = k0 | (k1 << 16);
+            vb[e] = v0 | (v1 << 16);
+            kn[2 * e] = __uint_as_float(k0 << 16); kn[2 * e + 1] = __uint_as_float(k1 << 16);
+            vn[2 * e] = __uint_as_float(v0 << 16); vn[2 * e + 1] = __uint_as_float(v1 << 16);
+        }
+        if (sub == 0) {
+            const int phys = min(max(table[T / BS], 0), a.num_blocks - 1);
+            uint16_t *kt = a.pool + kv_tile_offset(a.layer, a.num_blocks, phys, 0, a.nkv, j, BS, D) +
+                           (T % BS) * D + dl;
+            uint16_t *vt = kt + (int64_t)a.nkv * BS * D;
+            *reinterpret_cast<uint4 *>(kt) = make_uint4(kb[0], kb[1], kb[2], kb[3]);
+            *reinterpret_cast<uint4 *>(vt) = make_uint4(vb[0], vb[1], vb[2], vb[3]);
+        }
+        // lane group 0 takes the new token into its running softmax
+#pragma unroll
+        for (int g = 0; g < G; g++) {
+            float p = 0.f;
+#pragma unroll
+            for (int e = 0; e < 8; e++) p += q[g][e] * kn[e];
+            p = (TPR == 16) ? sum16(p) : sum8(p);
+            if (sub == 0) {
+                m[g] = p;
+                l[g] = 1.f;
+#pragma unroll
+                for (int e = 0; e < 8; e++) o[g][e] = vn[e];
+            }
+        }
+    }
+
+    for (int blk = first_blk; blk < blk_end; blk += NWV) {
+#pragma unroll
+        for (int i = 0; i < NI; i++) { kw[i] = kw_n[i]; vw[i] = vw_n[i]; }
+        if (blk + NWV < blk_end) {
+            const int phys = min(max(phys_next, 0), a.num_blocks - 1);
+            const uint16_t *kt = a.pool + kv_tile_offset(a.layer, a.num_blocks, phys, 0, a.nkv, j, BS, D);
+            const uint16_t *vt = kt + (int64_t)a.nkv * BS * D;
+#pragma unroll
+            for (int i = 0; i < NI; i++) {
+                kw_n[i] = ld16(kt + i * 512 + lane * 8);
+                vw_n[i] = ld16(vt + i * 512 + lane * 8);
+            }
+            phys_next = table[min(blk + 2 * NWV, a.max_blocks - 1)];
         }
         float s[NI][G];
         bool valid[NI];
@@ -291,38 +377,47 @@ __global__ __launch_bounds__(256) void attention_kernel(AttnArgs a)
             ls += sm_ml[w][g][1] * sc;
             os += sm_o[w][g][dim] * sc;
         }
-        if (nact == 1) {
-            a.out[(int64_t)b * a.nq * D + (int64_t)(j * G + g) * D + dim] = os / ls;
-        } else {
-            float *pp = part + (int64_t)c * (G * (D + 2)) + g * (D + 2);
+        float *pp = part + (int64_t)c * (G * (D + 2)) + g * (D + 2);
+        if (a.defer_merge) {
+            // the next kernel merges the partials while it loads its input
             pp[dim] = os;
             if (dim == 0) { pp[D] = mn; pp[D + 1] = ls; }
+        } else if (nact == 1) {
+            a.out[(int64_t)b * a.nq * D + (int64_t)(j * G + g) * D + dim] = os / ls;
+        } else {
+            st_coherent(pp + dim, os);
+            if (dim == 0) { st_coherent(pp + D, mn); st_coherent(pp + D + 1, ls); }
         }
     }
-    if (nact == 1) return;
+    if (a.defer_merge || nact == 1) return;
 
-    // last block of this (row, kv head) merges the chunk partials
-    __threadfence();
+    // Last block of this (row, kv head) merges the chunk partials.  The partial
+    // stores above are device-coherent and complete (the barrier waits for
+    // them) before the ticket is taken.
     __syncthreads();
-    if (tid == 0) sm_ticket = atomicAdd(&a.tickets[b * a.nkv + j], 1);
+    if (tid == 0)
+        sm_ticket = __hip_atomic_fetch_add(&a.tickets[b * a.nkv + j], 1, __ATOMIC_RELAXED,
+                                           __HIP_MEMORY_SCOPE_AGENT);
     __syncthreads();
     if (sm_ticket != nact - 1) return;
-    __threadfence();
     for (int idx = tid; idx < G * D; idx += 256) {
         const int g = idx / D, dim = idx % D;
-        float mn = -1e30f;
-        for (int cc = 0; cc < nact; cc++)
-            mn = fmaxf(mn, part[(int64_t)cc * (G * (D + 2)) + g * (D + 2) + D]);
-        float ls = 0.f, os = 0.f;
+        const float *pg = part + g * (D + 2);
+        // online merge in chunk order; the loads of different chunks are independent
+        float mn = -1e30f, ls = 0.f, os = 0.f;
         for (int cc = 0; cc < nact; cc++) {
-            const float *pp = part + (int64_t)cc * (G * (D + 2)) + g * (D + 2);
-            const float sc = __expf(pp[D] - mn);
-            ls += pp[D + 1] * sc;
-            os += pp[dim] * sc;
+            const float *pp = pg + (int64_t)cc * (G * (D + 2));
+            const float mc = ld_coherent(pp + D), lc = ld_coherent(pp + D + 1), oc = ld_coherent(pp + dim);
+            const float m2 = fmaxf(mn, mc);
+            const float sa = __expf(mn - m2), sb = __expf(mc - m2);
+            ls = ls * sa + lc * sb;
+            os = os * sa + oc * sb;
+            mn = m2;
         }
         a.out[(int64_t)b * a.nq * D + (int64_t)(j * G + g) * D + dim] = os / ls;
     }
-    if (tid == 0) a.tickets[b * a.nkv + j] = 0;
+    if (tid == 0)
+        __hip_atomic_store(&a.tickets[b * a.nkv + j], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 }  // namespace dk

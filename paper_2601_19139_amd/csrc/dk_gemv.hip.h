@@ -25,13 +25,20 @@ struct GemvArgs {
     int N, K;
     float *pmax_val;       // optional per-block running maximum [NB][gridDim.x]
     int *pmax_idx;
+    int tiles;             // row tiles (of RB rows) a block walks through
+    // XATTN: x is the attention output, given as per-chunk softmax partials
+    // part[b][kv head][chunk][g][d+2] = (unnormalised output[d], max, sum) that
+    // are merged while loading (k = head*d + dim)
+    const float *part;
+    const int *seq_lens;
+    int chunk_tokens, max_chunks, max_blocks, group, d, nkv;
 };
 
 __device__ __forceinline__ float silu_f(float z) { return z / (1.0f + __expf(-z)); }
 
-// BT threads stride over K in 8-element pieces; a block owns RB consecutive rows
-// (EPI_SWIGLU: RB rows of each of the two matrices).
-template <int NB, int BT, int RB, int EPI, bool NORM>
+// BT threads stride over K in 8-element pieces; a block owns `tiles` consecutive
+// tiles of RB rows (EPI_SWIGLU: RB rows of each of the two matrices).
+template <int NB, int BT, int RB, int EPI, bool NORM, bool XATTN = false>
 __global__ __launch_bounds__(BT) void gemv_kernel(GemvArgs a)
 {
     constexpr int NW = BT / kWave;
@@ -40,9 +47,13 @@ __global__ __launch_bounds__(BT) void gemv_kernel(GemvArgs a)
     __shared__ float red[NW][NV];
 
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-    const int row0 = blockIdx.x * RB;
     const int K = a.K, N = a.N;
+    float best = -INFINITY;
+    int best_i = 0x7fffffff;
 
+  for (int tile = 0; tile < a.tiles; tile++) {
+    const int row0 = (blockIdx.x * a.tiles + tile) * RB;
+    if (row0 >= N) break;
     float acc[NM][RB][NB];
     float ssq[NB];
 #pragma unroll
@@ -71,9 +82,50 @@ __global__ __launch_bounds__(BT) void gemv_kernel(GemvArgs a)
         float xv[NB][8];
 #pragma unroll
         for (int b = 0; b < NB; b++) {
-            float4 lo = ldf4(a.x + (int64_t)b * K + k), hi = ldf4(a.x + (int64_t)b * K + k + 4);
-            xv[b][0] = lo.x; xv[b][1] = lo.y; xv[b][2] = lo.z; xv[b][3] = lo.w;
-            xv[b][4] = hi.x; xv[b][5] = hi.y; xv[b][6] = hi.z; xv[b][7] = hi.w;
+            if (XATTN) {
+                // merge the chunk partials of head k/d (in chunk order) for dims k%d .. +8
+                const int d = a.d, h = k / d, dim = k - h * d, stride = a.group * (d + 2);
+                const int T1 = min(max(a.seq_lens[b], 0), a.max_blocks * 16 - 1) + 1;
+                const int nact = (T1 + a.chunk_tokens - 1) / a.chunk_tokens;
+                const float *pg = a.part + ((int64_t)(b * a.nkv + h / a.group) * a.max_chunks) * stride +
+                                  (h % a.group) * (d + 2);
+                float mn = -1e30f, ls = 0.f, os[8];
+#pragma unroll
+                for (int e = 0; e < 8; e++) os[e] = 0.f;
+                // eight chunks per round: their loads are issued together
+                constexpr int MR = 8;
+                for (int c0 = 0; c0 < nact; c0 += MR) {
+                    float2 ml[MR];
+                    float4 lo[MR], hi[MR];
+#pragma unroll
+                    for (int u = 0; u < MR; u++) {
+                        const float *pp = pg + (int64_t)min(c0 + u, nact - 1) * stride;
+                        ml[u] = *reinterpret_cast<const float2 *>(pp + d);
+                        lo[u] = ldf4(pp + dim);
+                        hi[u] = ldf4(pp + dim + 4);
+                    }
+#pragma unroll
+                    for (int u = 0; u < MR; u++) {
+                        if (c0 + u < nact) {
+                            const float m2 = fmaxf(mn, ml[u].x);
+                            const float sa = __expf(mn - m2), sb = __expf(ml[u].x - m2);
+                            ls = ls * sa + ml[u].y * sb;
+                            os[0] = os[0] * sa + lo[u].x * sb; os[1] = os[1] * sa + lo[u].y * sb;
+                            os[2] = os[2] * sa + lo[u].z * sb; os[3] = os[3] * sa + lo[u].w * sb;
+                            os[4] = os[4] * sa + hi[u].x * sb; os[5] = os[5] * sa + hi[u].y * sb;
+                            os[6] = os[6] * sa + hi[u].z * sb; os[7] = os[7] * sa + hi[u].w * sb;
+                            mn = m2;
+                        }
+                    }
+                }
+                const float inv = 1.0f / ls;
+#pragma unroll
+                for (int e = 0; e < 8; e++) xv[b][e] = os[e] * inv;
+            } else {
+                float4 lo = ldf4(a.x + (int64_t)b * K + k), hi = ldf4(a.x + (int64_t)b * K + k + 4);
+                xv[b][0] = lo.x; xv[b][1] = lo.y; xv[b][2] = lo.z; xv[b][3] = lo.w;
+                xv[b][4] = hi.x; xv[b][5] = hi.y; xv[b][6] = hi.z; xv[b][7] = hi.w;
+            }
         }
         if (NORM) {
             float g[8];
@@ -119,8 +171,6 @@ __global__ __launch_bounds__(BT) void gemv_kernel(GemvArgs a)
     }
     __syncthreads();
 
-    float best = -INFINITY;
-    int best_i = 0x7fffffff;
     if (tid < RB * NB) {
         const int r = tid % RB, b = tid / RB;
         const int row = row0 + r;
@@ -146,14 +196,15 @@ __global__ __launch_bounds__(BT) void gemv_kernel(GemvArgs a)
             else if (EPI == EPI_RESID) out = a.resid[(int64_t)b * N + row] + v[0];
             else out = v[0];
             if (a.y != nullptr) a.y[(int64_t)b * N + row] = out;
-            best = out;
-            best_i = row;
+            if (out > best) { best = out; best_i = row; }   // rows ascend: ties keep the lower
         }
     }
+    if (tile + 1 < a.tiles) __syncthreads();   // `red` is reused by the next tile
+  }
     if (a.pmax_val != nullptr && tid < 64) {
         // lanes b*RB .. b*RB+RB-1 hold the RB rows of batch row b: RB <= 16 and a
         // power of two, so a row-of-16 butterfly restricted to RB lanes reduces them
-        static_assert(RB * NB <= 64, "argmax epilogue needs RB*NB <= 64");
+        static_assert(RB * NB <= 64 && (RB & (RB - 1)) == 0, "argmax epilogue needs RB*NB <= 64, RB a power of two");
 #pragma unroll
         for (int off = 1; off < RB; off <<= 1) {
             float ov = __shfl_xor(best, off);
@@ -180,17 +231,27 @@ struct ArgmaxArgs {
     int advance;
 };
 
-__global__ __launch_bounds__(256) void argmax_final_kernel(ArgmaxArgs a)
+__global__ __launch_bounds__(1024) void argmax_final_kernel(ArgmaxArgs a)
 {
-    __shared__ float sv[4];
-    __shared__ int si[4];
+    __shared__ float sv[16];
+    __shared__ int si[16];
     const int b = blockIdx.x, tid = threadIdx.x;
     float best = -INFINITY;
     int best_i = 0x7fffffff;
-    for (int i = tid; i < a.nblk; i += 256) {
-        float v = a.pmax_val[(int64_t)b * a.nblk + i];
-        int ix = a.pmax_idx[(int64_t)b * a.nblk + i];
-        if (v > best || (v == best && ix < best_i)) { best = v; best_i = ix; }
+    const float *pv = a.pmax_val + (int64_t)b * a.nblk;
+    const int *pi = a.pmax_idx + (int64_t)b * a.nblk;
+    for (int i0 = tid; i0 < a.nblk; i0 += 1024 * 8) {
+        float v[8];
+        int ix[8];
+#pragma unroll
+        for (int u = 0; u < 8; u++) {       // independent loads first
+            const int i = i0 + u * 1024;
+            v[u] = i < a.nblk ? pv[i] : -INFINITY;
+            ix[u] = i < a.nblk ? pi[i] : 0x7fffffff;
+        }
+#pragma unroll
+        for (int u = 0; u < 8; u++)
+            if (v[u] > best || (v[u] == best && ix[u] < best_i)) { best = v[u]; best_i = ix[u]; }
     }
 #pragma unroll
     for (int off = 1; off < 64; off <<= 1) {
@@ -201,7 +262,7 @@ __global__ __launch_bounds__(256) void argmax_final_kernel(ArgmaxArgs a)
     if ((tid & 63) == 0) { sv[tid >> 6] = best; si[tid >> 6] = best_i; }
     __syncthreads();
     if (tid == 0) {
-        for (int w = 1; w < 4; w++)
+        for (int w = 1; w < 16; w++)
             if (sv[w] > best || (sv[w] == best && si[w] < best_i)) { best = sv[w]; best_i = si[w]; }
         if (best_i == 0x7fffffff) best_i = 0;   // only if every logit is NaN
         a.next[b] = best_i;
