@@ -14,6 +14,7 @@
 #include <vector>
 
 #include "dk_attention.hip.h"
+#include "dk_gemm.hip.h"
 #include "dk_gemv.hip.h"
 
 namespace {
@@ -90,10 +91,15 @@ namespace {
 
 struct Workspace {
     size_t x, qkv, attn, act, cs, part, tickets, pmax_val, pmax_idx, total;
+    // batched (matrix-core) path: activations as bf16 hi/lo, sum-of-squares partials
+    size_t xhi, xlo, ahi, alo, fhi, flo, ssq;
+    int Bp;             // batch rows padded to a multiple of 16
+    bool batched;
     int chunk_tokens, max_chunks, lm_blocks;
     bool defer_merge;   // small problems: the output projection merges the attention chunks
 };
 
+constexpr int kMaxGemvBatch = 4;  // up to here the vector-ALU GEMV; above, the matrix-core GEMM
 constexpr int kLmRB = 8;     // rows per tile of the lm_head GEMV
 constexpr int kLmTiles = 1;  // tiles per block of the lm_head GEMV
 
@@ -141,6 +147,18 @@ Workspace carve(const dk_model_config &c, int B, int max_blocks)
     w.cs = take((size_t)B * (d / 2) * 8);
     w.part = take((size_t)B * c.n_kv_heads * w.max_chunks * G * (d + 2) * 4);
     w.tickets = take((size_t)B * c.n_kv_heads * 4);
+    w.batched = B > kMaxGemvBatch;
+    w.Bp = (B + 15) / 16 * 16;
+    if (w.batched) {
+        w.lm_blocks = (c.vocab + 15) / 16;
+        w.xhi = take((size_t)w.Bp * c.hidden * 2);
+        w.xlo = take((size_t)w.Bp * c.hidden * 2);
+        w.ahi = take((size_t)w.Bp * c.n_q_heads * d * 2);
+        w.alo = take((size_t)w.Bp * c.n_q_heads * d * 2);
+        w.fhi = take((size_t)w.Bp * act_dim * 2);
+        w.flo = take((size_t)w.Bp * act_dim * 2);
+        w.ssq = take((size_t)((c.hidden + 15) / 16) * dk::kSsqStride * 4);
+    }
     w.pmax_val = take((size_t)B * w.lm_blocks * 4);
     w.pmax_idx = take((size_t)B * w.lm_blocks * 4);
     w.total = off;
@@ -210,6 +228,22 @@ dk_status launch_gemv(dk::GemvArgs a, int B, hipStream_t st)
         }
         if (s != DK_OK) return s;
     }
+    return DK_OK;
+}
+
+// ---- skinny GEMM dispatch (batches of 5..64 rows) ---------------------------
+template <int EPI, bool NORM>
+dk_status launch_gemm(const dk::GemmArgs &a, int Bp, hipStream_t st)
+{
+    const int grid = (a.N + 15) / 16;
+    switch (Bp / 16) {
+        case 1: hipLaunchKernelGGL((dk::skinny_gemm_kernel<1, 8, EPI, NORM>), dim3(grid), dim3(512), 0, st, a); break;
+        case 2: hipLaunchKernelGGL((dk::skinny_gemm_kernel<2, 8, EPI, NORM>), dim3(grid), dim3(512), 0, st, a); break;
+        case 3: hipLaunchKernelGGL((dk::skinny_gemm_kernel<3, 4, EPI, NORM>), dim3(grid), dim3(256), 0, st, a); break;
+        case 4: hipLaunchKernelGGL((dk::skinny_gemm_kernel<4, 4, EPI, NORM>), dim3(grid), dim3(256), 0, st, a); break;
+        default: return fail(DK_E_INVALID_ARG, "batch %d exceeds %d", Bp, DK_MAX_BATCH);
+    }
+    DK_HIP(hipGetLastError());
     return DK_OK;
 }
 
@@ -484,15 +518,22 @@ dk_status dk_decode_step(dk_model *model, dk_kv_pool *pool, const int32_t *d_blo
     int *tickets = reinterpret_cast<int *>(ws + w.tickets);
     float *pmax_val = reinterpret_cast<float *>(ws + w.pmax_val);
     int *pmax_idx = reinterpret_cast<int *>(ws + w.pmax_idx);
+    uint16_t *xhi = reinterpret_cast<uint16_t *>(ws + w.xhi), *xlo = reinterpret_cast<uint16_t *>(ws + w.xlo);
+    uint16_t *ahi = reinterpret_cast<uint16_t *>(ws + w.ahi), *alo = reinterpret_cast<uint16_t *>(ws + w.alo);
+    uint16_t *fhi = reinterpret_cast<uint16_t *>(ws + w.fhi), *flo = reinterpret_cast<uint16_t *>(ws + w.flo);
+    float *ssq = reinterpret_cast<float *>(ws + w.ssq);
 
     const int H = c.hidden, d = c.head_dim, nq = c.n_q_heads, nkv = c.n_kv_heads;
     const int qkv_dim = (nq + 2 * nkv) * d;
     const float eps = (float)c.rms_eps;
+    const bool batched = w.batched;
+    const int ssq_tiles = (H + 15) / 16;   // sum-of-squares partials a residual GEMM leaves
     dk_status s;
+    auto u16 = [](const void *p) { return static_cast<const uint16_t *>(p); };
 
-    {
+    {   // embedding rows, rotary angles, cleared tickets
         dk::EmbedArgs e{};
-        e.embed = static_cast<const uint16_t *>(model->embed);
+        e.embed = u16(model->embed);
         e.tokens = d_tokens;
         e.seq_lens = d_seq_lens;
         e.x = x;
@@ -502,6 +543,12 @@ dk_status dk_decode_step(dk_model *model, dk_kv_pool *pool, const int32_t *d_blo
         e.H = H;
         e.half = d / 2;
         e.V = c.vocab;
+        if (batched) {
+            e.gain = u16(model->layers[0].g_attn);
+            e.xhi = xhi;
+            e.xlo = xlo;
+            e.ssq_out = ssq;
+        }
         std::memcpy(e.inv_freq, model->inv_freq, sizeof e.inv_freq);
         hipLaunchKernelGGL(dk::embed_kernel, dim3(B), dim3(256), 0, st, e);
         DK_HIP(hipGetLastError());
@@ -509,11 +556,25 @@ dk_status dk_decode_step(dk_model *model, dk_kv_pool *pool, const int32_t *d_blo
 
     for (int l = 0; l < c.n_layers; l++) {
         const dk_layer_weights &L = model->layers[(size_t)l];
-        {   // q, k, v = W_qkv * rmsnorm(x)
+        // q, k, v = W_qkv * rmsnorm(x)
+        if (batched) {
+            dk::GemmArgs g{};
+            g.W = u16(L.w_qkv);
+            g.N = qkv_dim;
+            g.K = H;
+            g.B = B;
+            g.xhi = xhi;
+            g.xlo = xlo;
+            g.ssq_in = ssq;
+            g.n_part = (l == 0) ? 1 : ssq_tiles;
+            g.eps = eps;
+            g.y = qkv;
+            if ((s = launch_gemm<dk::GEPI_STORE, true>(g, w.Bp, st)) != DK_OK) return s;
+        } else {
             dk::GemvArgs g{};
-            g.W = static_cast<const uint16_t *>(L.w_qkv);
+            g.W = u16(L.w_qkv);
             g.x = x;
-            g.gain = static_cast<const uint16_t *>(L.g_attn);
+            g.gain = u16(L.g_attn);
             g.eps = eps;
             g.y = qkv;
             g.N = qkv_dim;
@@ -524,12 +585,16 @@ dk_status dk_decode_step(dk_model *model, dk_kv_pool *pool, const int32_t *d_blo
             dk::AttnArgs a{};
             a.qkv = qkv;
             a.cs = cs;
-            a.g_q = c.qk_norm ? static_cast<const uint16_t *>(L.g_q) : nullptr;
-            a.g_k = c.qk_norm ? static_cast<const uint16_t *>(L.g_k) : nullptr;
+            a.g_q = c.qk_norm ? u16(L.g_q) : nullptr;
+            a.g_k = c.qk_norm ? u16(L.g_k) : nullptr;
             a.pool = pool->mem;
             a.block_tables = d_block_tables;
             a.seq_lens = d_seq_lens;
             a.out = attn;
+            if (batched) {
+                a.out_hi = ahi;
+                a.out_lo = alo;
+            }
             a.part = part;
             a.tickets = tickets;
             a.max_blocks = max_blocks;
@@ -547,9 +612,24 @@ dk_status dk_decode_step(dk_model *model, dk_kv_pool *pool, const int32_t *d_blo
                            : launch_attention_d<64>(a, nq / nkv, grid, st);
             if (s != DK_OK) return s;
         }
-        {   // x += W_o * attn
+        // x += W_o * attn
+        if (batched) {
+            dk::GemmArgs g{};
+            g.W = u16(L.w_o);
+            g.N = H;
+            g.K = nq * d;
+            g.B = B;
+            g.xhi = ahi;
+            g.xlo = alo;
+            g.xres = x;
+            g.gain_next = u16(L.g_mlp);
+            g.ohi = xhi;
+            g.olo = xlo;
+            g.ssq_out = ssq;
+            if ((s = launch_gemm<dk::GEPI_RESID, false>(g, w.Bp, st)) != DK_OK) return s;
+        } else {
             dk::GemvArgs g{};
-            g.W = static_cast<const uint16_t *>(L.w_o);
+            g.W = u16(L.w_o);
             g.x = attn;
             g.y = x;
             g.resid = x;
@@ -570,50 +650,92 @@ dk_status dk_decode_step(dk_model *model, dk_kv_pool *pool, const int32_t *d_blo
             }
             if (s != DK_OK) return s;
         }
-        {   // act = silu(W_gate * h) * (W_up * h), h = rmsnorm(x)
+        // act = silu(W_gate * h) * (W_up * h), h = rmsnorm(x);  x += W_down * act
+        if (batched) {
+            dk::GemmArgs g{};
+            g.W = u16(L.w_gate);
+            g.W2 = u16(L.w_up);
+            g.N = c.ffn;
+            g.K = H;
+            g.B = B;
+            g.xhi = xhi;
+            g.xlo = xlo;
+            g.ssq_in = ssq;
+            g.n_part = ssq_tiles;
+            g.eps = eps;
+            g.ohi = fhi;
+            g.olo = flo;
+            if ((s = launch_gemm<dk::GEPI_SWIGLU, true>(g, w.Bp, st)) != DK_OK) return s;
+            dk::GemmArgs h{};
+            h.W = u16(L.w_down);
+            h.N = H;
+            h.K = c.ffn;
+            h.B = B;
+            h.xhi = fhi;
+            h.xlo = flo;
+            h.xres = x;
+            h.gain_next = (l + 1 < c.n_layers) ? u16(model->layers[(size_t)l + 1].g_attn)
+                                               : u16(model->g_final);
+            h.ohi = xhi;
+            h.olo = xlo;
+            h.ssq_out = ssq;
+            if ((s = launch_gemm<dk::GEPI_RESID, false>(h, w.Bp, st)) != DK_OK) return s;
+        } else {
             dk::GemvArgs g{};
-            g.W = static_cast<const uint16_t *>(L.w_gate);
-            g.W2 = static_cast<const uint16_t *>(L.w_up);
+            g.W = u16(L.w_gate);
+            g.W2 = u16(L.w_up);
             g.x = x;
-            g.gain = static_cast<const uint16_t *>(L.g_mlp);
+            g.gain = u16(L.g_mlp);
             g.eps = eps;
             g.y = act;
             g.N = c.ffn;
             g.K = H;
             if ((s = launch_gemv<dk::EPI_SWIGLU, true>(g, B, st)) != DK_OK) return s;
-        }
-        {   // x += W_down * act
-            dk::GemvArgs g{};
-            g.W = static_cast<const uint16_t *>(L.w_down);
-            g.x = act;
-            g.y = x;
-            g.resid = x;
-            g.N = H;
-            g.K = c.ffn;
-            if ((s = launch_gemv<dk::EPI_RESID, false>(g, B, st)) != DK_OK) return s;
+            dk::GemvArgs h{};
+            h.W = u16(L.w_down);
+            h.x = act;
+            h.y = x;
+            h.resid = x;
+            h.N = H;
+            h.K = c.ffn;
+            if ((s = launch_gemv<dk::EPI_RESID, false>(h, B, st)) != DK_OK) return s;
         }
     }
 
-    {   // logits = W_lm * rmsnorm(x); greedy token
+    // logits = W_lm * rmsnorm(x); greedy token
+    if (batched) {
+        dk::GemmArgs g{};
+        g.W = u16(model->lm_head);
+        g.N = c.vocab;
+        g.K = H;
+        g.B = B;
+        g.xhi = xhi;
+        g.xlo = xlo;
+        g.ssq_in = ssq;
+        g.n_part = ssq_tiles;
+        g.eps = eps;
+        g.y = d_logits;
+        g.pmax_val = pmax_val;
+        g.pmax_idx = pmax_idx;
+        if ((s = launch_gemm<dk::GEPI_STORE, true>(g, w.Bp, st)) != DK_OK) return s;
+    } else {
         dk::GemvArgs g{};
-        g.W = static_cast<const uint16_t *>(model->lm_head);
+        g.W = u16(model->lm_head);
         g.x = x;
-        g.gain = static_cast<const uint16_t *>(model->g_final);
+        g.gain = u16(model->g_final);
         g.eps = eps;
         g.N = c.vocab;
         g.K = H;
         g.pmax_val = pmax_val;
         g.pmax_idx = pmax_idx;
         g.tiles = kLmTiles;
-        // without a logits buffer the values still need a place to land: reuse is not
-        // possible (B*V floats), so the kernel stores only when asked
-        g.y = d_logits;
+        g.y = d_logits;   // may be null: then only the running maxima are kept
         if ((s = launch_gemv<dk::EPI_STORE, true>(g, B, st)) != DK_OK) return s;
-        dk::ArgmaxArgs am{pmax_val, pmax_idx, w.lm_blocks, d_next_tokens, d_tokens, d_seq_lens,
-                          (flags & DK_STEP_ADVANCE) ? 1 : 0};
-        hipLaunchKernelGGL(dk::argmax_final_kernel, dim3(B), dim3(1024), 0, st, am);
-        DK_HIP(hipGetLastError());
     }
+    dk::ArgmaxArgs am{pmax_val, pmax_idx, w.lm_blocks, d_next_tokens, d_tokens, d_seq_lens,
+                      (flags & DK_STEP_ADVANCE) ? 1 : 0};
+    hipLaunchKernelGGL(dk::argmax_final_kernel, dim3(B), dim3(1024), 0, st, am);
+    DK_HIP(hipGetLastError());
     return DK_OK;
 }
 

@@ -17,6 +17,11 @@ struct EmbedArgs {
     int *tickets;           // [n_tickets]
     int n_tickets;
     int H, half, V;
+    // batched path (null otherwise): (x * gain) as bf16 hi/lo [.][H] and the
+    // row's sum of x^2 in ssq_out[b], for the first matrix-core GEMM
+    const uint16_t *gain;
+    uint16_t *xhi, *xlo;
+    float *ssq_out;
     double inv_freq[64];    // theta^(-2i/d), i < d/2
 };
 
@@ -26,12 +31,37 @@ __global__ __launch_bounds__(256) void embed_kernel(EmbedArgs a)
     // an out-of-range token id is clamped (reads a valid row) rather than faulting
     const int tok = min(max(a.tokens[b], 0), a.V - 1);
     const uint16_t *row = a.embed + (int64_t)tok * a.H;
+    float ss = 0.f;
     for (int k = tid * 8; k < a.H; k += 256 * 8) {
         float f[8];
         unpack8(ld16(row + k), f);
         float *o = a.x + (int64_t)b * a.H + k;
         *reinterpret_cast<float4 *>(o) = make_float4(f[0], f[1], f[2], f[3]);
         *reinterpret_cast<float4 *>(o + 4) = make_float4(f[4], f[5], f[6], f[7]);
+        if (a.xhi != nullptr) {
+            float g[8];
+            unpack8(ld16(a.gain + k), g);
+            uint32_t hw[4], lw[4];
+#pragma unroll
+            for (int e = 0; e < 4; e++) {
+                ss += f[2 * e] * f[2 * e] + f[2 * e + 1] * f[2 * e + 1];
+                const float v0 = f[2 * e] * g[2 * e], v1 = f[2 * e + 1] * g[2 * e + 1];
+                const uint32_t h0 = f32_to_bf16_rne(v0), h1 = f32_to_bf16_rne(v1);
+                const uint32_t l0 = f32_to_bf16_rne(v0 - __uint_as_float(h0 << 16));
+                const uint32_t l1 = f32_to_bf16_rne(v1 - __uint_as_float(h1 << 16));
+                hw[e] = h0 | (h1 << 16);
+                lw[e] = l0 | (l1 << 16);
+            }
+            *reinterpret_cast<uint4 *>(a.xhi + (int64_t)b * a.H + k) = make_uint4(hw[0], hw[1], hw[2], hw[3]);
+            *reinterpret_cast<uint4 *>(a.xlo + (int64_t)b * a.H + k) = make_uint4(lw[0], lw[1], lw[2], lw[3]);
+        }
+    }
+    if (a.xhi != nullptr) {
+        __shared__ float ssw[4];
+        ss = sum64(ss);
+        if ((tid & 63) == 0) ssw[tid >> 6] = ss;
+        __syncthreads();
+        if (tid == 0) a.ssq_out[b] = ssw[0] + ssw[1] + ssw[2] + ssw[3];
     }
     if (tid < a.half) {
         double ang = (double)a.seq_lens[b] * a.inv_freq[tid];
@@ -96,7 +126,8 @@ struct AttnArgs {
     uint16_t *pool;
     const int *block_tables;
     const int *seq_lens;
-    float *out;              // [B][nq*d]
+    float *out;              // [B][nq*d] float32 result, or
+    uint16_t *out_hi, *out_lo;  // (batched path) the result as bf16 hi/lo [.][nq*d]
     float *part;             // [B][nkv][max_chunks][G][d+2]
     int *tickets;            // [B*nkv], zero before the launch, zero after
     int max_blocks, num_blocks, layer, nq, nkv;
@@ -113,6 +144,17 @@ __device__ __forceinline__ void st_coherent(float *p, float v)
 __device__ __forceinline__ float ld_coherent(const float *p)
 {
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+__device__ __forceinline__ void store_attn_out(const AttnArgs &a, int64_t idx, float v)
+{
+    if (a.out_hi != nullptr) {
+        const uint16_t hi = f32_to_bf16_rne(v);
+        a.out_hi[idx] = hi;
+        a.out_lo[idx] = f32_to_bf16_rne(v - bf16_to_f32(hi));
+    } else {
+        a.out[idx] = v;
+    }
 }
 
 // One head held as 8 dims per lane by an aligned group of TPR = D/8 lanes:
@@ -383,7 +425,7 @@ __global__ __launch_bounds__(256) void attention_kernel(AttnArgs a)
             pp[dim] = os;
             if (dim == 0) { pp[D] = mn; pp[D + 1] = ls; }
         } else if (nact == 1) {
-            a.out[(int64_t)b * a.nq * D + (int64_t)(j * G + g) * D + dim] = os / ls;
+            store_attn_out(a, (int64_t)b * a.nq * D + (int64_t)(j * G + g) * D + dim, os / ls);
         } else {
             st_coherent(pp + dim, os);
             if (dim == 0) { st_coherent(pp + D, mn); st_coherent(pp + D + 1, ls); }
@@ -414,7 +456,7 @@ __global__ __launch_bounds__(256) void attention_kernel(AttnArgs a)
             os = os * sa + oc * sb;
             mn = m2;
         }
-        a.out[(int64_t)b * a.nq * D + (int64_t)(j * G + g) * D + dim] = os / ls;
+        store_attn_out(a, (int64_t)b * a.nq * D + (int64_t)(j * G + g) * D + dim, os / ls);
     }
     if (tid == 0)
         __hip_atomic_store(&a.tickets[b * a.nkv + j], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);

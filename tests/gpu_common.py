@@ -90,3 +90,70 @@ def check_pool(out, pool_before, shape, layout, steps):
     assert int(o_changed.sum()) == shape.n_layers * layout.tables.shape[0] * 2 * shape.kv_dim * steps
     assert bf16_close(g[o_changed], o[o_changed]).all(), "appended value differs by more than rounding"
     assert (g[o_changed] != o[o_changed]).mean() < 0.02
+
+
+def run_sampled(orc, shape, weights, layout, pool_bits, tokens, steps, rows):
+    """Full-size variant: the GPU runs the whole batch, the oracle only the
+    sampled `rows` (rows of a batch do not interact, so a row's result does not
+    depend on which other rows are computed).  Sampled rows are teacher-forced
+    with the oracle's tokens; the others follow the GPU's own tokens.
+
+    Returns per-step logits/tokens of the sampled rows from both sides, the GPU
+    pool, and the oracle pool (which holds only the sampled rows' appends)."""
+    import torch
+    import paper_2601_19139_amd as dk
+    rows = list(rows)
+    dm = dk.DeviceModel(shape, weights)
+    dkv = dk.DeviceKV(dm, layout, pool_bits)
+    opool = pool_bits.copy()
+    sl = layout.contexts.copy().astype(np.int32)
+    tok = np.asarray(tokens, dtype=np.int32).copy()
+    dec = dk.Decoder(dm, dkv, sl, tok)
+    out = {"gpu_logits": [], "orc_logits": [], "gpu_next": [], "orc_next": []}
+    for s in range(steps):
+        dk.kv_validate_tables(dkv.handle, layout.tables, sl)
+        r = orc.decode_step(shape, weights, opool, layout.block_size, layout.tables[rows], sl[rows],
+                            tok[rows])
+        dec.step()
+        torch.cuda.synchronize()
+        g_next = dec.next.cpu().numpy().copy()
+        out["gpu_logits"].append(dec.logits[rows].cpu().numpy().copy())
+        out["gpu_next"].append(g_next[rows])
+        out["orc_logits"].append(r["logits"])
+        out["orc_next"].append(r["next"])
+        sl = sl + 1
+        tok = g_next.copy()
+        tok[rows] = r["next"]
+        dec.seq_lens.copy_(torch.from_numpy(sl))
+        dec.tokens.copy_(torch.from_numpy(tok))
+    out["gpu_pool"] = dkv.bits().reshape(pool_bits.shape)
+    out["orc_pool"] = opool
+    dkv.close()
+    dm.close()
+    return out
+
+
+def check_pool_sampled(out, pool_before, shape, layout, steps, rows):
+    """Addressing for every row against the closed-form slot list (block
+    table entry T // 16, slot T % 16, every layer, K and V, every kv head);
+    values of the sampled rows against the oracle's pool."""
+    g, o = out["gpu_pool"], out["orc_pool"]
+    bs = layout.block_size
+    targets = {}                                     # block -> list of (slot, row)
+    for b, T0 in enumerate(layout.contexts):
+        for s in range(steps):
+            T = int(T0) + s
+            targets.setdefault(int(layout.tables[b, T // bs]), []).append((T % bs, b))
+    untouched = np.ones(layout.num_blocks, dtype=bool)
+    untouched[list(targets)] = False
+    for l in range(shape.n_layers):                  # layer by layer keeps temporaries small
+        assert np.array_equal(g[l][untouched], pool_before[l][untouched]), "a block no row appends to changed"
+        for blk, lst in targets.items():
+            slots = [sl for sl, _ in lst]
+            other = [i for i in range(bs) if i not in slots]
+            assert np.array_equal(g[l, blk][:, :, other, :], pool_before[l, blk][:, :, other, :])
+            for sl_, b in lst:
+                # poisoned beforehand, so a written slot holds no NaN pattern any more
+                assert not np.any(g[l, blk, :, :, sl_, :] == W.BF16_NAN_BITS), "append slot not written"
+                if b in rows:
+                    assert bf16_close(g[l, blk, :, :, sl_, :], o[l, blk, :, :, sl_, :]).all()

@@ -12,7 +12,7 @@ import pytest
 
 import workloads as W
 from workloads.blocktable import layout_for, build_block_tables
-from gpu_common import run_both, check_parity, check_pool, rel_l2
+from gpu_common import run_both, run_sampled, check_parity, check_pool, check_pool_sampled, rel_l2
 
 pytestmark = pytest.mark.gpu
 
@@ -87,6 +87,13 @@ CASES = [
     ("multi_chunk_ragged", variant("tiny", qk_norm=True), [300, 65, 128, 7, 191], 3),
     ("batch7", variant("tiny"), [3, 50, 17, 80, 1, 64, 33], 2),
     ("odd_sizes", variant("tiny", hidden=264, ffn=1000, vocab=1003), [29, 12], 2),
+    # batches above 4 rows take the matrix-core GEMM path (rows padded to 16, 32, 48, 64)
+    ("batch16", variant("tiny", qk_norm=True), [5 + 9 * i for i in range(16)], 2),
+    ("batch5_odd_sizes", variant("tiny", hidden=264, ffn=1000, vocab=1003), [29, 12, 0, 77, 16], 2),
+    ("batch20_d128", variant("tiny", head_dim=128, n_q_heads=8, n_kv_heads=2, qk_norm=True),
+     [3 + 7 * i for i in range(20)], 2),
+    ("batch40", variant("tiny"), [1 + 3 * i for i in range(40)], 1),
+    ("batch64", variant("tiny", qk_norm=True), [(11 * i) % 90 for i in range(64)], 1),
 ]
 
 
@@ -188,3 +195,23 @@ def test_cfg1_full_size(dk, orc):
     print(f"cfg1: worst rel-L2 {worst:.3e}, greedy agreement {agree:.3f}")
     assert worst < TIGHT
     check_pool(out, pool, shape, lay, steps)
+
+
+@pytest.mark.parametrize("wname,rows,steps", [("cfg2", (0, 9, 15), 2), ("cfg3", (3, 12), 2)])
+def test_batch16_full_size_sampled_rows(dk, orc, wname, rows, steps):
+    """The batch-16 workloads at full size (Llama-3.2-3B shape with ragged
+    contexts and a shared 1024-token prefix; Qwen3-8B shape, context 4096):
+    the GPU decodes all 16 rows, the oracle the sampled rows; every logit of
+    those rows is compared, and append addressing is checked for all rows."""
+    wl = W.WORKLOADS[wname]
+    shape, lay = wl.cfg, layout_for(wl)
+    if wl.n_sharers:
+        assert rows[0] < wl.n_sharers <= rows[1]          # a sharer and a non-sharer are sampled
+    weights = W.make_weights(shape, wl.seed_weights)
+    pool = W.fill_kv_pool(shape, lay, wl.seed_kv)
+    tokens = W.initial_tokens(shape, wl.batch, wl.seed_tokens)
+    out = run_sampled(orc, shape, weights, lay, pool, tokens, steps, rows)
+    worst, agree = check_parity(out)
+    print(f"{wname}: worst rel-L2 {worst:.3e}, greedy agreement {agree:.3f} on rows {rows}")
+    assert worst < TIGHT
+    check_pool_sampled(out, pool, shape, lay, steps, rows)
