@@ -151,12 +151,13 @@ Workspace carve(const dk_model_config &c, int B, int max_blocks)
     w.Bp = (B + 15) / 16 * 16;
     if (w.batched) {
         w.lm_blocks = (c.vocab + 15) / 16;
-        w.xhi = take((size_t)w.Bp * c.hidden * 2);
-        w.xlo = take((size_t)w.Bp * c.hidden * 2);
-        w.ahi = take((size_t)w.Bp * c.n_q_heads * d * 2);
-        w.alo = take((size_t)w.Bp * c.n_q_heads * d * 2);
-        w.fhi = take((size_t)w.Bp * act_dim * 2);
-        w.flo = take((size_t)w.Bp * act_dim * 2);
+        auto padded = [](size_t k) { return (k + 127) / 128 * 128; };   // whole K-steps
+        w.xhi = take((size_t)w.Bp * padded(c.hidden) * 2);
+        w.xlo = take((size_t)w.Bp * padded(c.hidden) * 2);
+        w.ahi = take((size_t)w.Bp * padded((size_t)c.n_q_heads * d) * 2);
+        w.alo = take((size_t)w.Bp * padded((size_t)c.n_q_heads * d) * 2);
+        w.fhi = take((size_t)w.Bp * padded(act_dim) * 2);
+        w.flo = take((size_t)w.Bp * padded(act_dim) * 2);
         w.ssq = take((size_t)((c.hidden + 15) / 16) * dk::kSsqStride * 4);
     }
     w.pmax_val = take((size_t)B * w.lm_blocks * 4);
@@ -232,19 +233,52 @@ dk_status launch_gemv(dk::GemvArgs a, int B, hipStream_t st)
 }
 
 // ---- skinny GEMM dispatch (batches of 5..64 rows) ---------------------------
+template <int MT, int KS, int RT, int EPI, bool NORM, bool KALIGNED>
+dk_status launch_gemm_inst(const dk::GemmArgs &a, hipStream_t st)
+{
+    constexpr size_t lds = dk::skinny_gemm_lds_bytes<MT, KS, RT, EPI>();
+    static_assert(lds <= (64u << 10), "dynamic LDS above 64 KB would need a function attribute");
+    const int grid = (a.N + 16 * RT - 1) / (16 * RT);
+    constexpr int PD = 2;   // K-steps in flight per wave (deeper did not measure faster)
+    hipLaunchKernelGGL((dk::skinny_gemm_kernel<MT, KS, RT, PD, EPI, NORM, KALIGNED>), dim3(grid),
+                       dim3(KS * 64), lds, st, a);
+    DK_HIP(hipGetLastError());
+    return DK_OK;
+}
+
+template <int MT, int KS, int RT, int EPI, bool NORM>
+dk_status launch_gemm_cfg(const dk::GemmArgs &a, hipStream_t st)
+{
+    if (a.K % 128 == 0) return launch_gemm_inst<MT, KS, RT, EPI, NORM, true>(a, st);
+    return launch_gemm_inst<MT, KS, RT, EPI, NORM, false>(a, st);
+}
+
+// A wave that handles several 16-row weight tiles per K-step reuses the
+// activation operand it has loaded, which cuts the cache traffic of the
+// activations; it pays when enough blocks remain to fill the chip (measured on
+// the 8B-class shapes: 4 tiles per wave for the lm_head, 2 for the fused q/k/v
+// matrix, 1 for the square-ish projections and the gate/up pair).
 template <int EPI, bool NORM>
 dk_status launch_gemm(const dk::GemmArgs &a, int Bp, hipStream_t st)
 {
-    const int grid = (a.N + 15) / 16;
+    constexpr int NM = (EPI == dk::GEPI_SWIGLU) ? 2 : 1;
+    const int tiles = (a.N + 15) / 16;
     switch (Bp / 16) {
-        case 1: hipLaunchKernelGGL((dk::skinny_gemm_kernel<1, 8, EPI, NORM>), dim3(grid), dim3(512), 0, st, a); break;
-        case 2: hipLaunchKernelGGL((dk::skinny_gemm_kernel<2, 8, EPI, NORM>), dim3(grid), dim3(512), 0, st, a); break;
-        case 3: hipLaunchKernelGGL((dk::skinny_gemm_kernel<3, 4, EPI, NORM>), dim3(grid), dim3(256), 0, st, a); break;
-        case 4: hipLaunchKernelGGL((dk::skinny_gemm_kernel<4, 4, EPI, NORM>), dim3(grid), dim3(256), 0, st, a); break;
+        case 1:
+            if constexpr (NM == 1) {
+                if (tiles >= 4096) return launch_gemm_cfg<1, 8, 4, EPI, NORM>(a, st);
+                if (tiles >= 320) return launch_gemm_cfg<1, 8, 2, EPI, NORM>(a, st);
+            }
+            return launch_gemm_cfg<1, 8, 1, EPI, NORM>(a, st);
+        case 2:
+            if constexpr (NM == 1) {
+                if (tiles >= 1024) return launch_gemm_cfg<2, 8, 2, EPI, NORM>(a, st);
+            }
+            return launch_gemm_cfg<2, 8, 1, EPI, NORM>(a, st);
+        case 3: return launch_gemm_cfg<3, 4, 1, EPI, NORM>(a, st);
+        case 4: return launch_gemm_cfg<4, 4, 1, EPI, NORM>(a, st);
         default: return fail(DK_E_INVALID_ARG, "batch %d exceeds %d", Bp, DK_MAX_BATCH);
     }
-    DK_HIP(hipGetLastError());
-    return DK_OK;
 }
 
 template <int D>

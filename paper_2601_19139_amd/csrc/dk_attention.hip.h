@@ -17,7 +17,7 @@ struct EmbedArgs {
     int *tickets;           // [n_tickets]
     int n_tickets;
     int H, half, V;
-    // batched path (null otherwise): (x * gain) as bf16 hi/lo [.][H] and the
+    // batched path (null otherwise): (x * gain) as bf16 hi/lo in act_offset() order and the
     // row's sum of x^2 in ssq_out[b], for the first matrix-core GEMM
     const uint16_t *gain;
     uint16_t *xhi, *xlo;
@@ -52,8 +52,9 @@ __global__ __launch_bounds__(256) void embed_kernel(EmbedArgs a)
                 hw[e] = h0 | (h1 << 16);
                 lw[e] = l0 | (l1 << 16);
             }
-            *reinterpret_cast<uint4 *>(a.xhi + (int64_t)b * a.H + k) = make_uint4(hw[0], hw[1], hw[2], hw[3]);
-            *reinterpret_cast<uint4 *>(a.xlo + (int64_t)b * a.H + k) = make_uint4(lw[0], lw[1], lw[2], lw[3]);
+            const int64_t oo = act_offset(b, k, (a.H + 127) >> 7);
+            *reinterpret_cast<uint4 *>(a.xhi + oo) = make_uint4(hw[0], hw[1], hw[2], hw[3]);
+            *reinterpret_cast<uint4 *>(a.xlo + oo) = make_uint4(lw[0], lw[1], lw[2], lw[3]);
         }
     }
     if (a.xhi != nullptr) {
@@ -127,7 +128,7 @@ struct AttnArgs {
     const int *block_tables;
     const int *seq_lens;
     float *out;              // [B][nq*d] float32 result, or
-    uint16_t *out_hi, *out_lo;  // (batched path) the result as bf16 hi/lo [.][nq*d]
+    uint16_t *out_hi, *out_lo;  // (batched path) the result as bf16 hi/lo in act_offset() order
     float *part;             // [B][nkv][max_chunks][G][d+2]
     int *tickets;            // [B*nkv], zero before the launch, zero after
     int max_blocks, num_blocks, layer, nq, nkv;
@@ -146,14 +147,16 @@ __device__ __forceinline__ float ld_coherent(const float *p)
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-__device__ __forceinline__ void store_attn_out(const AttnArgs &a, int64_t idx, float v)
+// element k of batch row b of the attention output (k = head*d + dim)
+__device__ __forceinline__ void store_attn_out(const AttnArgs &a, int b, int k, int width, float v)
 {
     if (a.out_hi != nullptr) {
         const uint16_t hi = f32_to_bf16_rne(v);
-        a.out_hi[idx] = hi;
-        a.out_lo[idx] = f32_to_bf16_rne(v - bf16_to_f32(hi));
+        const int64_t oo = act_offset(b, k, (width + 127) >> 7);
+        a.out_hi[oo] = hi;
+        a.out_lo[oo] = f32_to_bf16_rne(v - bf16_to_f32(hi));
     } else {
-        a.out[idx] = v;
+        a.out[(int64_t)b * width + k] = v;
     }
 }
 
@@ -425,7 +428,7 @@ __global__ __launch_bounds__(256) void attention_kernel(AttnArgs a)
             pp[dim] = os;
             if (dim == 0) { pp[D] = mn; pp[D + 1] = ls; }
         } else if (nact == 1) {
-            store_attn_out(a, (int64_t)b * a.nq * D + (int64_t)(j * G + g) * D + dim, os / ls);
+            store_attn_out(a, b, (j * G + g) * D + dim, a.nq * D, os / ls);
         } else {
             st_coherent(pp + dim, os);
             if (dim == 0) { st_coherent(pp + D, mn); st_coherent(pp + D + 1, ls); }
@@ -456,7 +459,7 @@ __global__ __launch_bounds__(256) void attention_kernel(AttnArgs a)
             os = os * sa + oc * sb;
             mn = m2;
         }
-        store_attn_out(a, (int64_t)b * a.nq * D + (int64_t)(j * G + g) * D + dim, os / ls);
+        store_attn_out(a, b, (j * G + g) * D + dim, a.nq * D, os / ls);
     }
     if (tid == 0)
         __hip_atomic_store(&a.tickets[b * a.nkv + j], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);

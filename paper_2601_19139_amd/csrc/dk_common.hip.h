@@ -85,4 +85,16 @@ __device__ __forceinline__ int64_t kv_tile_offset(int layer, int num_blocks, int
            (int64_t)(block_size * d);
 }
 
+// Layout of an activation matrix X[n][k] that feeds the matrix-core GEMM as
+// bf16: stored in the order the MFMA B-operand loads consume it, so that every
+// wave load is one contiguous 1 KB run.  For batch tile t = n/16, K-step
+// ks = k/128 and MFMA sub-step s = (k%128)/32, lane (lg = (k%32)/8, ln = n%16)
+// holds the 8 elements k%8:
+//     offset = (((t*nks + ks)*4 + s)*64 + lg*16 + ln)*8 + k%8,  nks = ceil(K/128)
+__device__ __forceinline__ int64_t act_offset(int n, int k, int nks)
+{
+    const int t = n >> 4, ln = n & 15, ks = k >> 7, s = (k >> 5) & 3, lg = (k >> 3) & 3;
+    return ((((int64_t)t * nks + ks) * 4 + s) * 64 + lg * 16 + ln) * 8 + (k & 7);
+}
+
 }  // namespace dk

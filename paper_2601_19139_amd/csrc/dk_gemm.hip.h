@@ -11,10 +11,12 @@
 // matrix cores have an order of magnitude more throughput than the HBM stream
 // needs, so the second product is free.
 //
-// A block owns 16 weight rows (SWIGLU: 16 rows of each of the two matrices);
-// its KS waves split K in interleaved 128-element steps (a lane loads 64
+// A block owns a group of 16*RT weight rows (SWIGLU: of each of the two
+// matrices); its KS waves split K in interleaved 128-element steps (a lane loads 64
 // contiguous bytes of one row per step, the wave 16 rows x 256 bytes) and add
-// their accumulators through LDS in a fixed order.  With NORM the RMSNorm of
+// their accumulators through LDS in a fixed order.  The activations are stored
+// in the order the B-operand loads consume them (act_offset), so each of those
+// loads is one contiguous 1 KB run per wave.  With NORM the RMSNorm of
 // the input is fused: the producer stored (x * gain) as hi/lo plus per-tile
 // sums of x^2; the scalar 1/rms per batch row is applied in the epilogue.
 #pragma once
@@ -33,20 +35,21 @@ struct GemmArgs {
     const uint16_t *W;       // [N][K]
     const uint16_t *W2;      // GEPI_SWIGLU: the "up" matrix [N][K]
     int N, K, B;             // B valid batch rows (<= 16*MT)
-    const uint16_t *xhi;     // [16*MT][K] bf16, hi part of the input
-    const uint16_t *xlo;     // [16*MT][K] bf16, lo part
+    const uint16_t *xhi;     // hi part of the input, bf16 in act_offset() order
+    const uint16_t *xlo;     // lo part
     // NORM: sum over p < n_part of ssq_in[p][n] = sum_k x[n][k]^2
     const float *ssq_in;
     int n_part;
     float eps;
-    // GEPI_STORE: y[B][N] (may be null), optional running maxima [B][gridDim.x]
+    // GEPI_STORE: y[B][N] (may be null), optional running maxima [B][ceil(N/16)]
     float *y;
     float *pmax_val;
     int *pmax_idx;
-    // GEPI_SWIGLU and GEPI_RESID: result as hi/lo bf16 [16*MT][N] for the next GEMM
+    // GEPI_SWIGLU and GEPI_RESID: result as hi/lo bf16 in act_offset() order (K = N)
+    // for the next GEMM
     uint16_t *ohi, *olo;
     // GEPI_RESID: xres[B][N] += D; the hi/lo output is (xres * gain_next); the
-    // block's sum of xres^2 per batch row goes to ssq_out[blockIdx.x][n]
+    // sum of xres^2 over each 16-row tile and batch row goes to ssq_out[tile][n]
     float *xres;
     const uint16_t *gain_next;  // [N]
     float *ssq_out;
@@ -65,152 +68,245 @@ __device__ __forceinline__ bf16x8_t as_bf16x8(const uint4 &u)
     return c.v;
 }
 
-template <int MT, int KS, int EPI, bool NORM>
+// KALIGNED: K is a multiple of 128 (every real model shape); the K-steps are then
+// whole and the loaded registers feed the MFMAs untouched.
+template <int MT, int KS, int RT, int PD, int EPI, bool NORM, bool KALIGNED>
 __global__ __launch_bounds__(KS * 64) void skinny_gemm_kernel(GemmArgs a)
 {
     constexpr int NM = (EPI == GEPI_SWIGLU) ? 2 : 1;
-    static_assert(KS * NM * MT <= 32, "LDS reduction buffer is limited to 32 KB");
-    __shared__ float red[KS][NM][MT][4][64];
-    __shared__ float ssq_s[KS][64];
+    constexpr int NA = NM * RT;   // weight tiles (accumulator sets) per wave
+    static_assert(KS * NA * MT <= 32, "LDS reduction buffer is limited to 32 KB");
+    extern __shared__ float dyn_lds[];
+    typedef float RedBuf[KS][NA][MT][4][64];
+    RedBuf *red = reinterpret_cast<RedBuf *>(dyn_lds);
+    float (*ssq_s)[64] = reinterpret_cast<float (*)[64]>(dyn_lds + sizeof(RedBuf) / sizeof(float));
 
-    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave index, known to be uniform
     const int ln = lane & 15, lg = lane >> 4;
-    const int r0 = blockIdx.x * 16;
     const int K = a.K, N = a.N;
+    const int nks = (K + 127) >> 7;
+    const int niter = (nks + KS - 1) / KS;   // K-steps per wave and row group
+    const int niter2 = (niter + PD - 1) / PD * PD;   // padded to the pipeline depth
 
-    // sum-of-squares partials of the input rows (independent of the main loop)
-    if (NORM) {
-        float s = 0.f;
-        for (int p = wv; p < a.n_part; p += KS) s += a.ssq_in[(int64_t)p * kSsqStride + lane];
-        ssq_s[wv][lane] = s;
-    }
-
-    f32x4_t acc[NM][MT];
+    f32x4_t acc[NA][MT];
 #pragma unroll
-    for (int m = 0; m < NM; m++)
+    for (int m = 0; m < NA; m++)
 #pragma unroll
         for (int t = 0; t < MT; t++) acc[m][t] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
-    const int wrow = min(r0 + ln, N - 1);   // clamped rows are computed and dropped
-    const uint16_t *wp0 = a.W + (int64_t)wrow * K;
-    const uint16_t *wp1 = (NM == 2) ? a.W2 + (int64_t)wrow * K : nullptr;
-    const int nks = (K + 127) >> 7;
-    const uint4 zero4 = make_uint4(0, 0, 0, 0);
-
-    for (int ks = wv; ks < nks; ks += KS) {
-        const int kb = ks * 128 + lg * 32;
-        uint4 wa[NM][4], bh[MT][4], bl[MT][4];
+    // Software pipeline: PD K-steps are always in flight per wave.  The loop has
+    // no conditional loads and no stores (the compiler can then wait for exactly
+    // the stage it is about to use): every wave runs the same number of steps, a
+    // multiple of PD; a step past the end of K reads clamped (valid, cached)
+    // addresses and is not used.
+    struct Stage {
+        uint4 wa[NA][4], bh[MT][4], bl[MT][4];
+    };
+    int it_i = 0;   // step to issue next
+    auto issue = [&](Stage &st) {
+        const int g = (int)blockIdx.x;
+        const int ks = min(it_i * KS + wv, nks - 1);
+        const int kb = ks * 128 + lg * 8;
+        const uint16_t *wq[NA];
+#pragma unroll
+        for (int m = 0; m < NA; m++) {
+            // tile m: matrix m / RT, rows of group g; rows past the end are clamped
+            const int wrow = min(g * (16 * RT) + 16 * (m % RT) + ln, N - 1);
+            wq[m] = ((m / RT) ? a.W2 : a.W) + (int64_t)wrow * K + kb;
+        }
+        const int64_t xb = ((int64_t)ks * 4 * 64 + lane) * 8;
 #pragma unroll
         for (int s = 0; s < 4; s++) {
-            const int k = kb + s * 8;
-            const bool in = k < K;
-            wa[0][s] = in ? ld16(wp0 + k) : zero4;
-            if (NM == 2) wa[NM - 1][s] = in ? ld16(wp1 + k) : zero4;
+            // aligned K: constant offsets; otherwise clamped into the row
+            const int ko = KALIGNED ? s * 32 : min(kb + s * 32, K - 8) - kb;
+#pragma unroll
+            for (int m = 0; m < NA; m++) st.wa[m][s] = ld16(wq[m] + ko);
 #pragma unroll
             for (int t = 0; t < MT; t++) {
-                const int64_t xo = (int64_t)(t * 16 + ln) * K + k;
-                bh[t][s] = in ? ld16(a.xhi + xo) : zero4;
-                bl[t][s] = in ? ld16(a.xlo + xo) : zero4;
+                const int64_t xo = xb + ((int64_t)t * nks * 4 + s) * 512;
+                st.bh[t][s] = ld16(a.xhi + xo);
+                st.bl[t][s] = ld16(a.xlo + xo);
             }
         }
+        it_i++;
+    };
+    auto consume = [&](Stage &st, int it) {
+        const int ks = it * KS + wv;
+        if (ks >= nks) return;   // a padding step of this wave (uniform branch)
+        if (KALIGNED) {
 #pragma unroll
-        for (int s = 0; s < 4; s++)
+            for (int s = 0; s < 4; s++)
 #pragma unroll
-            for (int m = 0; m < NM; m++)
+                for (int t = 0; t < MT; t++)
+#pragma unroll
+                    for (int m = 0; m < NA; m++) {
+                        acc[m][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                            as_bf16x8(st.wa[m][s]), as_bf16x8(st.bh[t][s]), acc[m][t], 0, 0, 0);
+                        acc[m][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                            as_bf16x8(st.wa[m][s]), as_bf16x8(st.bl[t][s]), acc[m][t], 0, 0, 0);
+                    }
+        } else {
+            const int kb = ks * 128 + lg * 8;
+#pragma unroll
+            for (int s = 0; s < 4; s++) {
+                // past the end of K both operands are zeroed (the padding of the
+                // activation buffer is not initialised)
+                const bool in = kb + s * 32 < K;
+                const uint4 z = make_uint4(0, 0, 0, 0);
 #pragma unroll
                 for (int t = 0; t < MT; t++) {
-                    acc[m][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(wa[m][s]), as_bf16x8(bh[t][s]),
-                                                                        acc[m][t], 0, 0, 0);
-                    acc[m][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(wa[m][s]), as_bf16x8(bl[t][s]),
-                                                                        acc[m][t], 0, 0, 0);
+                    const uint4 h4 = in ? st.bh[t][s] : z, l4 = in ? st.bl[t][s] : z;
+#pragma unroll
+                    for (int m = 0; m < NA; m++) {
+                        const uint4 w4 = in ? st.wa[m][s] : z;
+                        acc[m][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(w4), as_bf16x8(h4),
+                                                                            acc[m][t], 0, 0, 0);
+                        acc[m][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(w4), as_bf16x8(l4),
+                                                                            acc[m][t], 0, 0, 0);
+                    }
                 }
+            }
+        }
+    };
+
+    // Sum-of-squares partials of the input rows: requested before the weight
+    // stream starts and added up after it, so their latency is hidden and the
+    // main loop never waits for them alone.  Wave wv takes partials wv, wv+KS, ...
+    constexpr int SSQ_REGS = 32;
+    float sv[SSQ_REGS];
+    if (NORM) {
+#pragma unroll
+        for (int u = 0; u < SSQ_REGS; u++)
+            sv[u] = a.ssq_in[(int64_t)min(wv + u * KS, a.n_part - 1) * kSsqStride + lane];
     }
 
+    Stage st[PD];
 #pragma unroll
-    for (int m = 0; m < NM; m++)
-#pragma unroll
-        for (int t = 0; t < MT; t++)
-#pragma unroll
-            for (int i = 0; i < 4; i++) red[wv][m][t][i][lane] = acc[m][t][i];
-    __syncthreads();
-    if (wv != 0) return;
+    for (int p = 0; p < PD; p++) issue(st[p]);
 
-    // wave 0: add the K-splits in wave order, then the epilogue.  The lane holds
-    // D[r0 + 4*lg + i][n = 16*t + ln], i = 0..3.
-    float best = -INFINITY;
-    int best_i = 0x7fffffff;
+    const int onks = (N + 127) >> 7;   // K-steps of the GEMM that consumes this output
+    const int n_tiles = (N + 15) >> 4;
+    {
+        for (int it = 0; it + PD < niter2; it += PD) {
 #pragma unroll
-    for (int t = 0; t < MT; t++) {
-        const int n = t * 16 + ln;
-        float v[NM][4];
-#pragma unroll
-        for (int m = 0; m < NM; m++)
-#pragma unroll
-            for (int i = 0; i < 4; i++) {
-                float s = 0.f;
-#pragma unroll
-                for (int w = 0; w < KS; w++) s += red[w][m][t][i][lane];
-                v[m][i] = s;
+            for (int p = 0; p < PD; p++) {
+                consume(st[p], it + p);
+                issue(st[p]);
             }
-        if (NORM) {
-            float s = 0.f;
+        }
 #pragma unroll
-            for (int w = 0; w < KS; w++) s += ssq_s[w][n];
-            const float inv = rsqrtf(s / (float)K + a.eps);
+        for (int p = 0; p < PD; p++) consume(st[p], niter2 - PD + p);
+        if (NORM) {
+            float ss = 0.f;
+#pragma unroll
+            for (int u = 0; u < SSQ_REGS; u++) ss += (wv + u * KS < a.n_part) ? sv[u] : 0.f;
+            for (int p = wv + SSQ_REGS * KS; p < a.n_part; p += KS)   // very wide models only
+                ss += a.ssq_in[(int64_t)p * kSsqStride + lane];
+            ssq_s[wv][lane] = ss;
+        }
+        // K-splits meet in LDS
+        RedBuf &rb = red[0];
+#pragma unroll
+        for (int m = 0; m < NA; m++)
+#pragma unroll
+            for (int t = 0; t < MT; t++)
+#pragma unroll
+                for (int i = 0; i < 4; i++) rb[wv][m][t][i][lane] = acc[m][t][i];
+        __syncthreads();
+        if (wv >= RT) return;
+
+        // Wave rt < RT finishes row tile rt of the group: it adds the K-splits in
+        // wave order, then the epilogue.  The lane holds
+        // D[row0 + 4*lg + i][n = 16*t + ln], i = 0..3.
+        const int rt = wv;
+        const int out_tile = (int)blockIdx.x * RT + rt;
+        const int row0 = out_tile * 16;
+        if (row0 >= N) return;
+        float best = -INFINITY;
+        int best_i = 0x7fffffff;
+#pragma unroll
+        for (int t = 0; t < MT; t++) {
+            const int n = t * 16 + ln;
+            float v[NM][4];
 #pragma unroll
             for (int m = 0; m < NM; m++)
 #pragma unroll
-                for (int i = 0; i < 4; i++) v[m][i] *= inv;
-        }
-        const bool nvalid = n < a.B;
-        const int rr = r0 + 4 * lg;
-        float sq = 0.f;
+                for (int i = 0; i < 4; i++) {
+                    float s = 0.f;
 #pragma unroll
-        for (int i = 0; i < 4; i++) {
-            const int r = rr + i;
-            if (!nvalid || r >= N) continue;
-            if (EPI == GEPI_STORE) {
-                const float out = v[0][i];
-                if (a.y != nullptr) a.y[(int64_t)n * N + r] = out;
-                if (out > best) { best = out; best_i = r; }
-            } else if (EPI == GEPI_SWIGLU) {
-                const float z = v[0][i];
-                const float out = z / (1.0f + __expf(-z)) * v[NM - 1][i];
-                uint16_t hi, lo;
-                split_bf16(out, hi, lo);
-                a.ohi[(int64_t)n * N + r] = hi;
-                a.olo[(int64_t)n * N + r] = lo;
-            } else {
-                const float xn = a.xres[(int64_t)n * N + r] + v[0][i];
-                a.xres[(int64_t)n * N + r] = xn;
-                sq += xn * xn;
-                uint16_t hi, lo;
-                split_bf16(xn * bf16_to_f32(a.gain_next[r]), hi, lo);
-                a.ohi[(int64_t)n * N + r] = hi;
-                a.olo[(int64_t)n * N + r] = lo;
-            }
-        }
-        if (EPI == GEPI_RESID) {
-            // the block's 16 rows of batch row n are spread over the 4 lane groups
-            sq += __shfl_xor(sq, 16);
-            sq += __shfl_xor(sq, 32);
-            if (lg == 0) a.ssq_out[(int64_t)blockIdx.x * kSsqStride + n] = nvalid ? sq : 0.f;
-        }
-        if (EPI == GEPI_STORE && a.pmax_val != nullptr) {
+                    for (int w = 0; w < KS; w++) s += rb[w][m * RT + rt][t][i][lane];
+                    v[m][i] = s;
+                }
+            if (NORM) {
+                float s = 0.f;
 #pragma unroll
-            for (int off = 16; off < 64; off <<= 1) {
-                const float ov = __shfl_xor(best, off);
-                const int oi = __shfl_xor(best_i, off);
-                if (ov > best || (ov == best && oi < best_i)) { best = ov; best_i = oi; }
+                for (int w = 0; w < KS; w++) s += ssq_s[w][n];
+                const float inv = rsqrtf(s / (float)K + a.eps);
+#pragma unroll
+                for (int m = 0; m < NM; m++)
+#pragma unroll
+                    for (int i = 0; i < 4; i++) v[m][i] *= inv;
             }
-            if (lg == 0 && nvalid) {
-                a.pmax_val[(int64_t)n * gridDim.x + blockIdx.x] = best;
-                a.pmax_idx[(int64_t)n * gridDim.x + blockIdx.x] = best_i;
+            const bool nvalid = n < a.B;
+            const int rr = row0 + 4 * lg;
+            float sq = 0.f;
+#pragma unroll
+            for (int i = 0; i < 4; i++) {
+                const int r = rr + i;
+                if (!nvalid || r >= N) continue;
+                if (EPI == GEPI_STORE) {
+                    const float out = v[0][i];
+                    if (a.y != nullptr) a.y[(int64_t)n * N + r] = out;
+                    if (out > best) { best = out; best_i = r; }
+                } else if (EPI == GEPI_SWIGLU) {
+                    const float z = v[0][i];
+                    const float out = z / (1.0f + __expf(-z)) * v[NM - 1][i];
+                    uint16_t hi, lo;
+                    split_bf16(out, hi, lo);
+                    const int64_t oo = act_offset(n, r, onks);
+                    a.ohi[oo] = hi;
+                    a.olo[oo] = lo;
+                } else {
+                    const float xn = a.xres[(int64_t)n * N + r] + v[0][i];
+                    a.xres[(int64_t)n * N + r] = xn;
+                    sq += xn * xn;
+                    uint16_t hi, lo;
+                    split_bf16(xn * bf16_to_f32(a.gain_next[r]), hi, lo);
+                    const int64_t oo = act_offset(n, r, onks);
+                    a.ohi[oo] = hi;
+                    a.olo[oo] = lo;
+                }
             }
-            best = -INFINITY;
-            best_i = 0x7fffffff;
+            if (EPI == GEPI_RESID) {
+                // the tile's 16 rows of batch row n are spread over the 4 lane groups
+                sq += __shfl_xor(sq, 16);
+                sq += __shfl_xor(sq, 32);
+                if (lg == 0) a.ssq_out[(int64_t)out_tile * kSsqStride + n] = nvalid ? sq : 0.f;
+            }
+            if (EPI == GEPI_STORE && a.pmax_val != nullptr) {
+#pragma unroll
+                for (int off = 16; off < 64; off <<= 1) {
+                    const float ov = __shfl_xor(best, off);
+                    const int oi = __shfl_xor(best_i, off);
+                    if (ov > best || (ov == best && oi < best_i)) { best = ov; best_i = oi; }
+                }
+                if (lg == 0 && nvalid) {
+                    a.pmax_val[(int64_t)n * n_tiles + out_tile] = best;
+                    a.pmax_idx[(int64_t)n * n_tiles + out_tile] = best_i;
+                }
+                best = -INFINITY;
+                best_i = 0x7fffffff;
+            }
         }
     }
+}
+
+// Dynamic LDS bytes of a skinny_gemm_kernel instance.
+template <int MT, int KS, int RT, int EPI>
+constexpr size_t skinny_gemm_lds_bytes()
+{
+    return (size_t)KS * ((EPI == GEPI_SWIGLU) ? 2 : 1) * RT * MT * 4 * 64 * 4 + (size_t)KS * 64 * 4;
 }
 
 }  // namespace dk
