@@ -206,6 +206,14 @@ dk_status dk_decode_step(dk_model *model, dk_kv_pool *pool, const int32_t *d_blo
                          int32_t B, void *d_workspace, size_t workspace_bytes, float *d_logits,
                          int32_t *d_next_tokens, uint32_t flags, void *hip_stream);
 
+/* Experts chosen in the most recent decode step that used `d_workspace` with
+ * the same B and max_blocks_per_seq (mixture-of-experts models only): copies
+ * int32 [n_layers][B][top_k], each row in order of decreasing router
+ * probability, to the HOST buffer h_out and synchronises the stream.  Used to
+ * count the distinct experts a step streamed and to compare routing decisions. */
+dk_status dk_step_routing(const dk_model *model, const void *d_workspace, int32_t B,
+                          int32_t max_blocks_per_seq, int32_t *h_out, void *hip_stream);
+
 /* Algorithmic HBM bytes of one decode step: every dense weight byte once,
  * every distinct live KV byte once (a shared block counts once), the B
  * embedding rows and the logits written.  Host only; takes HOST copies of the

@@ -68,6 +68,7 @@ _SIGNATURES = {
     "dk_decode_step": (C.c_int32, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p,
                                    C.c_int32, C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p,
                                    C.c_uint32, C.c_void_p]),
+    "dk_step_routing": (C.c_int32, [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]),
     "dk_step_algorithmic_bytes": (C.c_int32, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p,
                                               C.c_int32, C.c_int32, C.c_void_p, C.POINTER(C.c_uint64)]),
 }
@@ -214,6 +215,14 @@ def decode_step(model, pool, d_block_tables, d_seq_lens, d_tokens, d_workspace, 
     _check(lib().dk_decode_step(model, pool, _ptr(d_block_tables), mb, _ptr(d_seq_lens),
                                 _ptr(d_tokens), B, _ptr(d_workspace), nbytes, _ptr(d_logits),
                                 _ptr(d_next_tokens), flags, _stream(stream)))
+
+
+def step_routing(model, d_workspace, B, max_blocks_per_seq, n_layers, top_k, stream=None):
+    """Experts chosen in the last decode step: numpy int32 [n_layers, B, top_k]."""
+    import numpy as np
+    out = np.empty((n_layers, B, top_k), dtype=np.int32)
+    _check(lib().dk_step_routing(model, _ptr(d_workspace), B, max_blocks_per_seq, _ptr(out), _stream(stream)))
+    return out
 
 
 def step_algorithmic_bytes(model, pool, h_block_tables, h_seq_lens, with_logits=True,

@@ -16,6 +16,7 @@
 #include "dk_attention.hip.h"
 #include "dk_gemm.hip.h"
 #include "dk_gemv.hip.h"
+#include "dk_moe.hip.h"
 
 namespace {
 
@@ -93,6 +94,8 @@ struct Workspace {
     size_t x, qkv, attn, act, cs, part, tickets, pmax_val, pmax_idx, total;
     // batched (matrix-core) path: activations as bf16 hi/lo, sum-of-squares partials
     size_t xhi, xlo, ahi, alo, fhi, flo, ssq;
+    // mixture of experts: routing of every layer, per-row 1/rms, expert outputs
+    size_t topk_idx, topk_w, rinv, yexp;
     int Bp;             // batch rows padded to a multiple of 16
     bool batched;
     int chunk_tokens, max_chunks, lm_blocks;
@@ -124,7 +127,7 @@ Workspace carve(const dk_model_config &c, int B, int max_blocks)
     // the output projection then merges them as it loads its input (at most 8
     // chunks, one round of loads), which saves the attention kernel a round of
     // device-wide synchronisation.
-    if (B <= 4) {
+    if (B <= kMaxGemvBatch && c.n_experts == 0) {   // the vector-ALU path only
         int chunk8 = ((ctx_max + 7) / 8 + 63) / 64 * 64;
         if (chunk8 < chunk) chunk8 = chunk;
         const int n8 = (ctx_max + chunk8 - 1) / chunk8;
@@ -147,7 +150,7 @@ Workspace carve(const dk_model_config &c, int B, int max_blocks)
     w.cs = take((size_t)B * (d / 2) * 8);
     w.part = take((size_t)B * c.n_kv_heads * w.max_chunks * G * (d + 2) * 4);
     w.tickets = take((size_t)B * c.n_kv_heads * 4);
-    w.batched = B > kMaxGemvBatch;
+    w.batched = B > kMaxGemvBatch || c.n_experts > 0;   // expert layers use the matrix-core kernels
     w.Bp = (B + 15) / 16 * 16;
     if (w.batched) {
         w.lm_blocks = (c.vocab + 15) / 16;
@@ -156,8 +159,18 @@ Workspace carve(const dk_model_config &c, int B, int max_blocks)
         w.xlo = take((size_t)w.Bp * padded(c.hidden) * 2);
         w.ahi = take((size_t)w.Bp * padded((size_t)c.n_q_heads * d) * 2);
         w.alo = take((size_t)w.Bp * padded((size_t)c.n_q_heads * d) * 2);
-        w.fhi = take((size_t)w.Bp * padded(act_dim) * 2);
-        w.flo = take((size_t)w.Bp * padded(act_dim) * 2);
+        if (c.n_experts > 0) {
+            const size_t pairs = ((size_t)B * c.top_k + 15) / 16 * 16;   // one activation row per (row, slot)
+            w.fhi = take(pairs * padded((size_t)c.expert_ffn) * 2);
+            w.flo = take(pairs * padded((size_t)c.expert_ffn) * 2);
+            w.topk_idx = take((size_t)c.n_layers * B * c.top_k * 4);
+            w.topk_w = take((size_t)B * c.top_k * 4);
+            w.rinv = take((size_t)B * 4);
+            w.yexp = take((size_t)B * c.top_k * c.hidden * 4);
+        } else {
+            w.fhi = take((size_t)w.Bp * padded(act_dim) * 2);
+            w.flo = take((size_t)w.Bp * padded(act_dim) * 2);
+        }
         w.ssq = take((size_t)((c.hidden + 15) / 16) * dk::kSsqStride * 4);
     }
     w.pmax_val = take((size_t)B * w.lm_blocks * 4);
@@ -480,8 +493,9 @@ dk_status dk_create_model(const dk_model_config *cfg, const dk_weight_ptrs *w, d
     if (!w || !out) return fail(DK_E_INVALID_ARG, "NULL argument");
     if (!w->embed || !w->lm_head || !w->g_final || !w->layers)
         return fail(DK_E_INVALID_ARG, "a top-level weight pointer is NULL");
-    if (cfg->n_experts > 0)
-        return fail(DK_E_UNSUPPORTED_SHAPE, "mixture-of-experts layers are not implemented yet");
+    if (cfg->n_experts > 0 && cfg->hidden > 8192)
+        return fail(DK_E_UNSUPPORTED_SHAPE, "mixture-of-experts layers support hidden <= 8192 (got %d)",
+                    cfg->hidden);
     for (int l = 0; l < cfg->n_layers; l++) {
         const dk_layer_weights &L = w->layers[l];
         if (!L.g_attn || !L.w_qkv || !L.w_o || !L.g_mlp || !L.w_gate || !L.w_up || !L.w_down)
@@ -600,7 +614,7 @@ dk_status dk_decode_step(dk_model *model, dk_kv_pool *pool, const int32_t *d_blo
             g.xhi = xhi;
             g.xlo = xlo;
             g.ssq_in = ssq;
-            g.n_part = (l == 0) ? 1 : ssq_tiles;
+            g.n_part = (l == 0 || c.n_experts > 0) ? 1 : ssq_tiles;   // who wrote the partials
             g.eps = eps;
             g.y = qkv;
             if ((s = launch_gemm<dk::GEPI_STORE, true>(g, w.Bp, st)) != DK_OK) return s;
@@ -685,7 +699,68 @@ dk_status dk_decode_step(dk_model *model, dk_kv_pool *pool, const int32_t *d_blo
             if (s != DK_OK) return s;
         }
         // act = silu(W_gate * h) * (W_up * h), h = rmsnorm(x);  x += W_down * act
-        if (batched) {
+        const uint16_t *gain_after = (l + 1 < c.n_layers) ? u16(model->layers[(size_t)l + 1].g_attn)
+                                                           : u16(model->g_final);
+        if (batched && c.n_experts > 0) {
+            int *topk_idx = reinterpret_cast<int *>(ws + w.topk_idx) + (size_t)l * B * c.top_k;
+            float *topk_w = reinterpret_cast<float *>(ws + w.topk_w);
+            float *rinv = reinterpret_cast<float *>(ws + w.rinv);
+            float *yexp = reinterpret_cast<float *>(ws + w.yexp);
+            dk::RouterArgs r{};
+            r.x = x;
+            r.gain = u16(L.g_mlp);
+            r.w_router = u16(L.w_router);
+            r.eps = eps;
+            r.H = H;
+            r.E = c.n_experts;
+            r.top_k = c.top_k;
+            r.topk_idx = topk_idx;
+            r.topk_w = topk_w;
+            r.rinv = rinv;
+            hipLaunchKernelGGL(dk::moe_router_kernel, dim3(B), dim3(256), 0, st, r);
+            DK_HIP(hipGetLastError());
+            dk::ExpertArgs up{};
+            up.w_a = u16(L.w_gate);
+            up.w_b = u16(L.w_up);
+            up.N = c.expert_ffn;
+            up.K = H;
+            up.B = B;
+            up.top_k = c.top_k;
+            up.topk_idx = topk_idx;
+            up.xhi = xhi;
+            up.xlo = xlo;
+            up.rinv = rinv;
+            up.ohi = fhi;
+            up.olo = flo;
+            hipLaunchKernelGGL((dk::moe_expert_kernel<true, 8>), dim3((c.expert_ffn + 15) / 16, c.n_experts),
+                               dim3(512), 0, st, up);
+            DK_HIP(hipGetLastError());
+            dk::ExpertArgs dn{};
+            dn.w_a = u16(L.w_down);
+            dn.N = H;
+            dn.K = c.expert_ffn;
+            dn.B = B;
+            dn.top_k = c.top_k;
+            dn.topk_idx = topk_idx;
+            dn.xhi = fhi;
+            dn.xlo = flo;
+            dn.y = yexp;
+            hipLaunchKernelGGL((dk::moe_expert_kernel<false, 4>), dim3((H + 15) / 16, c.n_experts),
+                               dim3(256), 0, st, dn);
+            DK_HIP(hipGetLastError());
+            dk::MoeCombineArgs cb{};
+            cb.x = x;
+            cb.y = yexp;
+            cb.topk_w = topk_w;
+            cb.gain_next = gain_after;
+            cb.xhi = xhi;
+            cb.xlo = xlo;
+            cb.ssq_out = ssq;
+            cb.H = H;
+            cb.top_k = c.top_k;
+            hipLaunchKernelGGL(dk::moe_combine_kernel, dim3(B), dim3(256), 0, st, cb);
+            DK_HIP(hipGetLastError());
+        } else if (batched) {
             dk::GemmArgs g{};
             g.W = u16(L.w_gate);
             g.W2 = u16(L.w_up);
@@ -708,8 +783,7 @@ dk_status dk_decode_step(dk_model *model, dk_kv_pool *pool, const int32_t *d_blo
             h.xhi = fhi;
             h.xlo = flo;
             h.xres = x;
-            h.gain_next = (l + 1 < c.n_layers) ? u16(model->layers[(size_t)l + 1].g_attn)
-                                               : u16(model->g_final);
+            h.gain_next = gain_after;
             h.ohi = xhi;
             h.olo = xlo;
             h.ssq_out = ssq;
@@ -746,7 +820,7 @@ dk_status dk_decode_step(dk_model *model, dk_kv_pool *pool, const int32_t *d_blo
         g.xhi = xhi;
         g.xlo = xlo;
         g.ssq_in = ssq;
-        g.n_part = ssq_tiles;
+        g.n_part = c.n_experts > 0 ? 1 : ssq_tiles;
         g.eps = eps;
         g.y = d_logits;
         g.pmax_val = pmax_val;
@@ -770,6 +844,21 @@ dk_status dk_decode_step(dk_model *model, dk_kv_pool *pool, const int32_t *d_blo
                       (flags & DK_STEP_ADVANCE) ? 1 : 0};
     hipLaunchKernelGGL(dk::argmax_final_kernel, dim3(B), dim3(1024), 0, st, am);
     DK_HIP(hipGetLastError());
+    return DK_OK;
+}
+
+dk_status dk_step_routing(const dk_model *model, const void *d_workspace, int32_t B,
+                          int32_t max_blocks, int32_t *h_out, void *hip_stream)
+{
+    if (!model || !d_workspace || !h_out) return fail(DK_E_INVALID_ARG, "NULL argument");
+    if (model->cfg.n_experts <= 0) return fail(DK_E_INVALID_ARG, "the model has no expert layers");
+    if (B <= 0 || B > DK_MAX_BATCH || max_blocks <= 0) return fail(DK_E_INVALID_ARG, "B %d, max_blocks_per_seq %d", B, max_blocks);
+    const Workspace w = carve(model->cfg, B, max_blocks);
+    const size_t bytes = (size_t)model->cfg.n_layers * B * model->cfg.top_k * 4;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    DK_HIP(hipMemcpyAsync(h_out, static_cast<const char *>(d_workspace) + w.topk_idx, bytes,
+                          hipMemcpyDeviceToHost, st));
+    DK_HIP(hipStreamSynchronize(st));
     return DK_OK;
 }
 

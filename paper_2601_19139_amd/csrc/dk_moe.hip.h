@@ -1,0 +1,277 @@
+// Mixture-of-experts MLP: softmax router with top-k selection, expert SwiGLU
+// GEMMs over only the experts that some row selected, and the weighted
+// combination.  Every byte of a selected expert is streamed once per step; an
+// expert nobody selected costs a 128-entry table scan per block and no HBM
+// traffic.
+#pragma once
+#include "dk_common.hip.h"
+#include "dk_gemm.hip.h"
+
+namespace dk {
+
+// ---------------------------------------------------------------------------
+// Router.  One block per batch row: h = rmsnorm(x) * gain, logits = W_r h,
+// probabilities = softmax over all experts, the top_k largest (ties to the
+// lower expert index) renormalised to sum to one.
+struct RouterArgs {
+    const float *x;          // [B][H] residual stream
+    const uint16_t *gain;    // [H]
+    const uint16_t *w_router;  // [E][H]
+    float eps;
+    int H, E, top_k;
+    int *topk_idx;           // [B][top_k] experts in order of decreasing probability
+    float *topk_w;           // [B][top_k] renormalised weights
+    float *rinv;             // [B] 1/rms of the row (the expert GEMMs apply it)
+};
+
+__global__ __launch_bounds__(256) void moe_router_kernel(RouterArgs a)
+{
+    __shared__ float xs[8192];           // x * gain for the row (H <= 8192)
+    __shared__ float red[4];
+    __shared__ float logit[256];
+    const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const float *xr = a.x + (int64_t)b * a.H;
+    float ss = 0.f;
+    for (int k = tid; k < a.H; k += 256) {
+        const float v = xr[k];
+        ss += v * v;
+        xs[k] = v * bf16_to_f32(a.gain[k]);
+    }
+    ss = sum64(ss);
+    if (lane == 0) red[wv] = ss;
+    __syncthreads();
+    const float inv = rsqrtf((red[0] + red[1] + red[2] + red[3]) / (float)a.H + a.eps);
+    if (tid == 0) a.rinv[b] = inv;
+    // wave wv takes experts wv, wv+4, ...; lanes stride over H in 8-element pieces
+    for (int e = wv; e < a.E; e += 4) {
+        const uint16_t *wr = a.w_router + (int64_t)e * a.H;
+        float acc = 0.f;
+        for (int k = lane * 8; k < a.H; k += 512) {
+            float w[8];
+            unpack8(ld16(wr + k), w);
+#pragma unroll
+            for (int i = 0; i < 8; i++) acc += w[i] * xs[k + i];
+        }
+        acc = sum64(acc);
+        if (lane == 0) logit[e] = acc * inv;
+    }
+    __syncthreads();
+    if (wv != 0) return;
+    // softmax over the E logits (lane holds experts lane, lane+64, ...; E <= 256)
+    float p[4];
+    float mx = -INFINITY;
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+        const int e = lane + 64 * i;
+        p[i] = e < a.E ? logit[e] : -INFINITY;
+        mx = fmaxf(mx, p[i]);
+    }
+    mx = max64(mx);
+    float sum = 0.f;
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+        p[i] = (lane + 64 * i < a.E) ? expf(p[i] - mx) : -1.f;   // -1 marks "not an expert"
+        sum += fmaxf(p[i], 0.f);
+    }
+    sum = sum64(sum);
+#pragma unroll
+    for (int i = 0; i < 4; i++)
+        if (p[i] >= 0.f) p[i] /= sum;
+    // top_k by repeated argmax (largest probability, lowest index among equals)
+    float sel_sum = 0.f, my_w = 0.f;
+    int my_e = 0;
+    for (int k = 0; k < a.top_k; k++) {
+        float bv = -1.f;
+        int be = 0x7fffffff;
+#pragma unroll
+        for (int i = 0; i < 4; i++)
+            if (p[i] > bv) { bv = p[i]; be = lane + 64 * i; }   // ascending index: ties keep the lower
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const float ov = __shfl_xor(bv, off);
+            const int oe = __shfl_xor(be, off);
+            if (ov > bv || (ov == bv && oe < be)) { bv = ov; be = oe; }
+        }
+        sel_sum += bv;
+        if (lane == k) { my_w = bv; my_e = be; }
+#pragma unroll
+        for (int i = 0; i < 4; i++)
+            if (lane + 64 * i == be) p[i] = -1.f;   // taken
+    }
+    if (lane < a.top_k) {
+        a.topk_idx[b * a.top_k + lane] = my_e;
+        a.topk_w[b * a.top_k + lane] = my_w / sel_sum;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Expert GEMMs.  grid = (row tiles, experts).  A block first collects, in
+// order, the (row, slot) pairs that selected its expert; none -> it exits.  The
+// pairs become the batch columns of 16x16x32 bf16 MFMAs exactly as in the dense
+// skinny GEMM (activations as bf16 hi + lo in act_offset() order, KS waves
+// splitting K, accumulators added through LDS in wave order).
+//
+// UP:   in  = (x * gain) of batch row `row`            (activation row = row)
+//       out = silu(rinv*Wg x) * (rinv*Wu x) as hi/lo   (activation row = row*top_k + slot)
+// DOWN: in  = the UP output of (row, slot)
+//       out = y[row*top_k + slot][:] = Wd act   (float32; weighted and summed later)
+struct ExpertArgs {
+    const uint16_t *w_a;     // UP: gate [E][Fe][H];  DOWN: down [E][H][Fe]
+    const uint16_t *w_b;     // UP: up   [E][Fe][H]
+    int N, K;                // rows and columns of one expert matrix
+    int B, top_k;
+    const int *topk_idx;     // [B][top_k]
+    const uint16_t *xhi, *xlo;   // input activations (act_offset order)
+    const float *rinv;       // UP: [B]
+    uint16_t *ohi, *olo;     // UP: output activations (act_offset order, K' = N)
+    float *y;                // DOWN: [B*top_k][N]
+};
+
+template <bool UP, int KS>
+__global__ __launch_bounds__(KS * 64) void moe_expert_kernel(ExpertArgs a)
+{
+    constexpr int NM = UP ? 2 : 1;
+    constexpr int MAXCOL = 64 * 16;   // DK_MAX_BATCH rows x up to 16 slots
+    __shared__ float red[KS][NM][4][64];
+    __shared__ int col_row[MAXCOL];   // the pairs that selected this expert: row*top_k + slot
+    __shared__ int ncol_s;
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int ln = lane & 15, lg = lane >> 4;
+    const int e = blockIdx.y;
+    const int r0 = blockIdx.x * 16;
+    const int K = a.K, N = a.N;
+
+    if (wv == 0) {
+        // ordered compaction of the assignment table by one wave
+        int n = 0;
+        const int total = a.B * a.top_k;
+        for (int base = 0; base < total; base += 64) {
+            const int i = base + lane;
+            const bool hit = i < total && a.topk_idx[i] == e;
+            const unsigned long long m = __ballot(hit);
+            if (hit) col_row[n + __popcll(m & ((1ull << lane) - 1))] = i;
+            n += __popcll(m);
+        }
+        if (lane == 0) ncol_s = n;
+    }
+    __syncthreads();
+    const int ncol = ncol_s;
+    if (ncol == 0) return;
+
+    const int wrow = min(r0 + ln, N - 1);
+    const uint16_t *wp0 = a.w_a + ((int64_t)e * N + wrow) * K;
+    const uint16_t *wp1 = UP ? a.w_b + ((int64_t)e * N + wrow) * K : nullptr;
+    const int nks = (K + 127) >> 7;
+    const int onks = (N + 127) >> 7;
+
+    for (int c0 = 0; c0 < ncol; c0 += 16) {   // 16 batch columns per pass
+        // column ln of this pass: pair index, its batch row, its activation row
+        const int pair = col_row[min(c0 + ln, ncol - 1)];
+        const int in_row = UP ? pair / a.top_k : pair;
+        const int64_t xbase = (((int64_t)(in_row >> 4) * nks) * 4 * 64 + lg * 16 + (in_row & 15)) * 8;
+
+        f32x4_t acc[NM];
+#pragma unroll
+        for (int m = 0; m < NM; m++) acc[m] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+        for (int ks = wv; ks < nks; ks += KS) {
+            const int kb = ks * 128 + lg * 8;
+#pragma unroll
+            for (int s = 0; s < 4; s++) {
+                const bool in = kb + s * 32 < K;
+                const int kc = min(kb + s * 32, K - 8);
+                const uint4 z = make_uint4(0, 0, 0, 0);
+                const int64_t xo = xbase + ((int64_t)ks * 4 + s) * 512;
+                const uint4 h4 = in ? ld16(a.xhi + xo) : z, l4 = in ? ld16(a.xlo + xo) : z;
+                const uint4 w0 = in ? ld16(wp0 + kc) : z;
+                acc[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(w0), as_bf16x8(h4), acc[0], 0, 0, 0);
+                acc[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(w0), as_bf16x8(l4), acc[0], 0, 0, 0);
+                if (UP) {
+                    const uint4 w1 = in ? ld16(wp1 + kc) : z;
+                    acc[NM - 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(w1), as_bf16x8(h4),
+                                                                          acc[NM - 1], 0, 0, 0);
+                    acc[NM - 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(w1), as_bf16x8(l4),
+                                                                          acc[NM - 1], 0, 0, 0);
+                }
+            }
+        }
+#pragma unroll
+        for (int m = 0; m < NM; m++)
+#pragma unroll
+            for (int i = 0; i < 4; i++) red[wv][m][i][lane] = acc[m][i];
+        __syncthreads();
+        if (wv == 0 && c0 + ln < ncol) {
+            // lane holds D[r0 + 4*lg + i][column ln]
+            float v[NM][4];
+#pragma unroll
+            for (int m = 0; m < NM; m++)
+#pragma unroll
+                for (int i = 0; i < 4; i++) {
+                    float s = 0.f;
+#pragma unroll
+                    for (int w = 0; w < KS; w++) s += red[w][m][i][lane];
+                    v[m][i] = s;
+                }
+            const float inv = UP ? a.rinv[in_row] : 1.f;
+#pragma unroll
+            for (int i = 0; i < 4; i++) {
+                const int r = r0 + 4 * lg + i;
+                if (r >= N) continue;
+                if (UP) {
+                    const float z = v[0][i] * inv;
+                    const float out = z / (1.0f + __expf(-z)) * (v[NM - 1][i] * inv);
+                    uint16_t hi, lo;
+                    split_bf16(out, hi, lo);
+                    const int64_t oo = act_offset(pair, r, onks);
+                    a.ohi[oo] = hi;
+                    a.olo[oo] = lo;
+                } else {
+                    a.y[(int64_t)pair * N + r] = v[0][i];
+                }
+            }
+        }
+        __syncthreads();   // `red` is reused by the next pass
+    }
+}
+
+// ---------------------------------------------------------------------------
+// x[b] += sum_k w[b][k] * y[b*top_k + k]   (k in the router's order), then the
+// input of the next matrix-core GEMM: (x * next gain) as hi/lo and the row's
+// sum of squares.  One block per batch row.
+struct MoeCombineArgs {
+    float *x;                // [B][H]
+    const float *y;          // [B*top_k][H]
+    const float *topk_w;     // [B][top_k]
+    const uint16_t *gain_next;  // [H]
+    uint16_t *xhi, *xlo;
+    float *ssq_out;          // [.] entry b = sum_k x[b][k]^2
+    int H, top_k;
+};
+
+__global__ __launch_bounds__(256) void moe_combine_kernel(MoeCombineArgs a)
+{
+    __shared__ float red[4];
+    const int b = blockIdx.x, tid = threadIdx.x;
+    const int nks = (a.H + 127) >> 7;
+    float ss = 0.f;
+    for (int k = tid; k < a.H; k += 256) {
+        float acc = 0.f;
+        for (int j = 0; j < a.top_k; j++)
+            acc += a.topk_w[b * a.top_k + j] * a.y[((int64_t)b * a.top_k + j) * a.H + k];
+        const float xn = a.x[(int64_t)b * a.H + k] + acc;
+        a.x[(int64_t)b * a.H + k] = xn;
+        ss += xn * xn;
+        uint16_t hi, lo;
+        split_bf16(xn * bf16_to_f32(a.gain_next[k]), hi, lo);
+        const int64_t oo = act_offset(b, k, nks);
+        a.xhi[oo] = hi;
+        a.xlo[oo] = lo;
+    }
+    ss = sum64(ss);
+    if ((tid & 63) == 0) red[tid >> 6] = ss;
+    __syncthreads();
+    if (tid == 0) a.ssq_out[b] = red[0] + red[1] + red[2] + red[3];
+}
+
+}  // namespace dk

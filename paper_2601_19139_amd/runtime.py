@@ -115,6 +115,12 @@ class Decoder:
         self.ws = torch.empty(self.ws_bytes + 256, dtype=torch.uint8, device="cuda")
         self._ws_ptr = (self.ws.data_ptr() + 255) // 256 * 256
 
+    def routing(self):
+        """Experts chosen in the last step, int32 [n_layers, B, top_k] (MoE models)."""
+        shape = self.m.shape
+        return dk.step_routing(self.m.handle, self._ws_ptr, self.B, self.kv.layout.tables.shape[1],
+                               shape.n_layers, shape.top_k)
+
     def step(self, flags: int = 0, stream=None):
         dk.decode_step(self.m.handle, self.kv.handle, self.kv.block_tables, self.seq_lens,
                        self.tokens, self._ws_ptr, self.logits, self.next, flags, stream,

@@ -37,12 +37,17 @@ def run_both(orc, shape, weights, layout, pool_bits, tokens, steps, teacher_forc
     sl = layout.contexts.copy().astype(np.int32)
     otok = np.asarray(tokens, dtype=np.int32).copy()
     dec = dk.Decoder(dm, dkv, sl, otok)
-    out = {"gpu_logits": [], "orc_logits": [], "gpu_next": [], "orc_next": []}
+    out = {"gpu_logits": [], "orc_logits": [], "gpu_next": [], "orc_next": [],
+           "gpu_experts": [], "orc_experts": []}
     for s in range(steps):
         dk.kv_validate_tables(dkv.handle, layout.tables, sl)
-        r = orc.decode_step(shape, weights, opool, layout.block_size, layout.tables, sl, otok)
+        r = orc.decode_step(shape, weights, opool, layout.block_size, layout.tables, sl, otok,
+                            want_trace=bool(shape.n_experts))
         dec.step(flags=gpu_flags)
         torch.cuda.synchronize()
+        if shape.n_experts:
+            out["gpu_experts"].append(dec.routing())
+            out["orc_experts"].append(r["experts"])
         out["gpu_logits"].append(dec.logits.cpu().numpy().copy())
         out["gpu_next"].append(dec.next.cpu().numpy().copy())
         out["orc_logits"].append(r["logits"])

@@ -72,6 +72,11 @@ CONFIGS = {
     "qwen3_30b_a3b": ModelConfig("qwen3_30b_a3b", 48, 2048, 32, 4, 128, 0, 151936,
                                  rope_theta=1e6, qk_norm=True,
                                  n_experts=128, top_k=8, expert_ffn=768),
+    # The 30B-A3B shape cut to 4 layers: every kernel runs at its real size while
+    # weights stay at 5 GB (the 48-layer model is 61 GB).
+    "qwen3_30b_a3b_l4": ModelConfig("qwen3_30b_a3b_l4", 4, 2048, 32, 4, 128, 0, 151936,
+                                    rope_theta=1e6, qk_norm=True,
+                                    n_experts=128, top_k=8, expert_ffn=768),
     # Not a benchmark shape: a few-layer MoE small enough for the oracle.
     "tiny_moe": ModelConfig("tiny_moe", 2, 256, 4, 2, 64, 0, 1024,
                             qk_norm=True, n_experts=8, top_k=2, expert_ffn=96),
@@ -109,5 +114,7 @@ WORKLOADS = {
     "cfg3": Workload("cfg3", "qwen3_8b", 16, 16, 64, contexts=(4096,) * 16),
     "cfg4": Workload("cfg4", "qwen3_30b_a3b", 16, 16, 32, context_range=(256, 4096),
                      shared_prefix=2048, n_sharers=8),
+    "cfg4_l4": Workload("cfg4_l4", "qwen3_30b_a3b_l4", 16, 16, 32, context_range=(256, 4096),
+                        shared_prefix=2048, n_sharers=8),
     "cfg0_moe": Workload("cfg0_moe", "tiny_moe", 3, 16, 4, contexts=(33, 16, 5)),
 }
