@@ -173,6 +173,22 @@ dk_status dk_workspace_bytes(const dk_model *model, int32_t max_B, int32_t max_b
 
 /* dk_decode_step flags */
 #define DK_STEP_ADVANCE 1u /* after the step: d_tokens[b] = next token, d_seq_lens[b] += 1 */
+#define DK_STEP_PROFILE 2u /* time every kernel of the step with its own start/stop events;
+                              the call then synchronises the stream before it returns and
+                              adds the times to the totals dk_profile_read returns */
+
+/* Kernel classes of a profiled step. */
+enum {
+    DK_K_EMBED = 0,      /* embedding rows, rotary angles                         */
+    DK_K_GEMV,           /* weight-streaming GEMV (batches up to 4 rows)          */
+    DK_K_GEMM,           /* weight-streaming skinny GEMM on the matrix cores      */
+    DK_K_ATTENTION,      /* head norm + rotation + KV append + paged attention    */
+    DK_K_MOE_ROUTER,
+    DK_K_MOE_EXPERT,
+    DK_K_MOE_COMBINE,
+    DK_K_ARGMAX,
+    DK_K_COUNT
+};
 
 /*
  * One decode step for B sequences (Algorithm 1's per-iteration token
@@ -195,9 +211,9 @@ dk_status dk_workspace_bytes(const dk_model *model, int32_t max_B, int32_t max_b
  *                   256-byte aligned; contents need not survive between calls
  *   d_logits        device float32 [B][vocab], or NULL to skip storing logits
  *   d_next_tokens   device int32 [B]
- *   flags           0 or DK_STEP_ADVANCE (then d_tokens / d_seq_lens are
- *                   written; otherwise the step leaves them untouched and the
- *                   caller advances them)
+ *   flags           0, DK_STEP_ADVANCE (then d_tokens / d_seq_lens are written;
+ *                   otherwise the step leaves them untouched and the caller
+ *                   advances them) and/or DK_STEP_PROFILE
  * The block tables are never modified.  Fast arithmetic: bf16 storage, float32
  * accumulation and float32 residual stream.
  */
@@ -205,6 +221,11 @@ dk_status dk_decode_step(dk_model *model, dk_kv_pool *pool, const int32_t *d_blo
                          int32_t max_blocks_per_seq, int32_t *d_seq_lens, int32_t *d_tokens,
                          int32_t B, void *d_workspace, size_t workspace_bytes, float *d_logits,
                          int32_t *d_next_tokens, uint32_t flags, void *hip_stream);
+
+/* Totals of all profiled steps of `model` so far: out_ms[DK_K_COUNT] kernel
+ * execution time in milliseconds per class, out_launches[DK_K_COUNT] launches
+ * per class.  reset != 0 clears the totals.  Host only. */
+dk_status dk_profile_read(dk_model *model, double *out_ms, int64_t *out_launches, int32_t reset);
 
 /* Experts chosen in the most recent decode step that used `d_workspace` with
  * the same B and max_blocks_per_seq (mixture-of-experts models only): copies

@@ -9,6 +9,8 @@ LIB_PATH = os.path.join(_HERE, "libdecodekit.so")
 STATUS = {0: "DK_OK", -1: "DK_E_INVALID_ARG", -2: "DK_E_POOL_EXHAUSTED", -3: "DK_E_BAD_BLOCK",
           -4: "DK_E_WORKSPACE_TOO_SMALL", -5: "DK_E_UNSUPPORTED_SHAPE", -6: "DK_E_HIP"}
 STEP_ADVANCE = 1
+STEP_PROFILE = 2
+KERNEL_CLASSES = ("embed", "gemv", "gemm", "attention", "moe_router", "moe_expert", "moe_combine", "argmax")
 
 
 class DecodeKitError(RuntimeError):
@@ -68,6 +70,7 @@ _SIGNATURES = {
     "dk_decode_step": (C.c_int32, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p,
                                    C.c_int32, C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p,
                                    C.c_uint32, C.c_void_p]),
+    "dk_profile_read": (C.c_int32, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32]),
     "dk_step_routing": (C.c_int32, [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]),
     "dk_step_algorithmic_bytes": (C.c_int32, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p,
                                               C.c_int32, C.c_int32, C.c_void_p, C.POINTER(C.c_uint64)]),
@@ -215,6 +218,15 @@ def decode_step(model, pool, d_block_tables, d_seq_lens, d_tokens, d_workspace, 
     _check(lib().dk_decode_step(model, pool, _ptr(d_block_tables), mb, _ptr(d_seq_lens),
                                 _ptr(d_tokens), B, _ptr(d_workspace), nbytes, _ptr(d_logits),
                                 _ptr(d_next_tokens), flags, _stream(stream)))
+
+
+def profile_read(model, reset=True):
+    """Per kernel class: (milliseconds, launches) summed over the profiled steps."""
+    n = len(KERNEL_CLASSES)
+    ms = (C.c_double * n)()
+    cnt = (C.c_int64 * n)()
+    _check(lib().dk_profile_read(model, ms, cnt, int(reset)))
+    return {k: (ms[i], cnt[i]) for i, k in enumerate(KERNEL_CLASSES)}
 
 
 def step_routing(model, d_workspace, B, max_blocks_per_seq, n_layers, top_k, stream=None):

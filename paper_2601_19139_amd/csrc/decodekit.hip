@@ -4,6 +4,7 @@
 #include "../../include/decodekit.h"
 
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 
 #include <cmath>
 #include <cstdarg>
@@ -39,6 +40,44 @@ dk_status fail(dk_status code, const char *fmt, ...)
     } while (0)
 
 size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// Per-kernel timing of a profiled step: every launch carries a start and a stop
+// event (the dispatch's own timestamps, not the gaps between launches).
+struct Profiler {
+    struct Pending { int cls; hipEvent_t e0, e1; };
+    std::vector<hipEvent_t> free_events;
+    std::vector<Pending> pending;
+    double ms[DK_K_COUNT] = {};
+    int64_t launches[DK_K_COUNT] = {};
+    bool take(int cls, hipEvent_t *e0, hipEvent_t *e1)
+    {
+        hipEvent_t ev[2];
+        for (auto &e : ev) {
+            if (!free_events.empty()) { e = free_events.back(); free_events.pop_back(); }
+            else if (hipEventCreate(&e) != hipSuccess) return false;
+        }
+        *e0 = ev[0];
+        *e1 = ev[1];
+        pending.push_back({cls, ev[0], ev[1]});
+        return true;
+    }
+    ~Profiler()
+    {
+        for (auto &p : pending) { (void)hipEventDestroy(p.e0); (void)hipEventDestroy(p.e1); }
+        for (auto e : free_events) (void)hipEventDestroy(e);
+    }
+};
+thread_local Profiler *g_prof = nullptr;   // set for the duration of a profiled step
+
+// Launch through here so that a profiled step can time each kernel.
+#define DK_LAUNCH(cls, kernel, grid, block, lds, st, ...)                                      \
+    do {                                                                                       \
+        hipEvent_t e0_, e1_;                                                                   \
+        if (g_prof != nullptr && g_prof->take(cls, &e0_, &e1_))                                \
+            hipExtLaunchKernelGGL(kernel, grid, block, lds, st, e0_, e1_, 0, __VA_ARGS__);     \
+        else                                                                                   \
+            hipLaunchKernelGGL(kernel, grid, block, lds, st, __VA_ARGS__);                     \
+    } while (0)
 
 dk_status check_config(const dk_model_config *c)
 {
@@ -86,6 +125,7 @@ struct dk_model {
     const void *embed, *lm_head, *g_final;
     std::vector<dk_layer_weights> layers;
     double inv_freq[64];
+    Profiler prof;
 };
 
 namespace {
@@ -195,11 +235,11 @@ dk_status launch_gemv_rb(const dk::GemvArgs &a, hipStream_t st)
 {
     const int grid = (a.N + RB * a.tiles - 1) / (RB * a.tiles);
     if (a.K >= 2048)
-        hipLaunchKernelGGL((dk::gemv_kernel<NB, 256, RB, EPI, NORM, XATTN>), dim3(grid), dim3(256), 0, st, a);
+        DK_LAUNCH(DK_K_GEMV, (dk::gemv_kernel<NB, 256, RB, EPI, NORM, XATTN>), dim3(grid), dim3(256), 0, st, a);
     else if (a.K >= 1024)
-        hipLaunchKernelGGL((dk::gemv_kernel<NB, 128, RB, EPI, NORM, XATTN>), dim3(grid), dim3(128), 0, st, a);
+        DK_LAUNCH(DK_K_GEMV, (dk::gemv_kernel<NB, 128, RB, EPI, NORM, XATTN>), dim3(grid), dim3(128), 0, st, a);
     else
-        hipLaunchKernelGGL((dk::gemv_kernel<NB, 64, RB, EPI, NORM, XATTN>), dim3(grid), dim3(64), 0, st, a);
+        DK_LAUNCH(DK_K_GEMV, (dk::gemv_kernel<NB, 64, RB, EPI, NORM, XATTN>), dim3(grid), dim3(64), 0, st, a);
     DK_HIP(hipGetLastError());
     return DK_OK;
 }
@@ -253,8 +293,8 @@ dk_status launch_gemm_inst(const dk::GemmArgs &a, hipStream_t st)
     static_assert(lds <= (64u << 10), "dynamic LDS above 64 KB would need a function attribute");
     const int grid = (a.N + 16 * RT - 1) / (16 * RT);
     constexpr int PD = 2;   // K-steps in flight per wave (deeper did not measure faster)
-    hipLaunchKernelGGL((dk::skinny_gemm_kernel<MT, KS, RT, PD, EPI, NORM, KALIGNED>), dim3(grid),
-                       dim3(KS * 64), lds, st, a);
+    DK_LAUNCH(DK_K_GEMM, (dk::skinny_gemm_kernel<MT, KS, RT, PD, EPI, NORM, KALIGNED>), dim3(grid),
+              dim3(KS * 64), lds, st, a);
     DK_HIP(hipGetLastError());
     return DK_OK;
 }
@@ -298,12 +338,12 @@ template <int D>
 dk_status launch_attention_d(const dk::AttnArgs &a, int G, dim3 grid, hipStream_t st)
 {
     switch (G) {
-        case 1: hipLaunchKernelGGL((dk::attention_kernel<D, 1>), grid, dim3(256), 0, st, a); break;
-        case 2: hipLaunchKernelGGL((dk::attention_kernel<D, 2>), grid, dim3(256), 0, st, a); break;
-        case 3: hipLaunchKernelGGL((dk::attention_kernel<D, 3>), grid, dim3(256), 0, st, a); break;
-        case 4: hipLaunchKernelGGL((dk::attention_kernel<D, 4>), grid, dim3(256), 0, st, a); break;
-        case 6: hipLaunchKernelGGL((dk::attention_kernel<D, 6>), grid, dim3(256), 0, st, a); break;
-        case 8: hipLaunchKernelGGL((dk::attention_kernel<D, 8>), grid, dim3(256), 0, st, a); break;
+        case 1: DK_LAUNCH(DK_K_ATTENTION, (dk::attention_kernel<D, 1>), grid, dim3(256), 0, st, a); break;
+        case 2: DK_LAUNCH(DK_K_ATTENTION, (dk::attention_kernel<D, 2>), grid, dim3(256), 0, st, a); break;
+        case 3: DK_LAUNCH(DK_K_ATTENTION, (dk::attention_kernel<D, 3>), grid, dim3(256), 0, st, a); break;
+        case 4: DK_LAUNCH(DK_K_ATTENTION, (dk::attention_kernel<D, 4>), grid, dim3(256), 0, st, a); break;
+        case 6: DK_LAUNCH(DK_K_ATTENTION, (dk::attention_kernel<D, 6>), grid, dim3(256), 0, st, a); break;
+        case 8: DK_LAUNCH(DK_K_ATTENTION, (dk::attention_kernel<D, 8>), grid, dim3(256), 0, st, a); break;
         default: return fail(DK_E_UNSUPPORTED_SHAPE, "query group size %d", G);
     }
     DK_HIP(hipGetLastError());
@@ -535,10 +575,59 @@ dk_status dk_workspace_bytes(const dk_model *model, int32_t max_B, int32_t max_b
     return DK_OK;
 }
 
+static dk_status decode_step_impl(dk_model *model, dk_kv_pool *pool, const int32_t *d_block_tables,
+                                  int32_t max_blocks, int32_t *d_seq_lens, int32_t *d_tokens, int32_t B,
+                                  void *d_workspace, size_t workspace_bytes, float *d_logits,
+                                  int32_t *d_next_tokens, uint32_t flags, void *hip_stream);
+
 dk_status dk_decode_step(dk_model *model, dk_kv_pool *pool, const int32_t *d_block_tables,
                          int32_t max_blocks, int32_t *d_seq_lens, int32_t *d_tokens, int32_t B,
                          void *d_workspace, size_t workspace_bytes, float *d_logits,
                          int32_t *d_next_tokens, uint32_t flags, void *hip_stream)
+{
+    if (!model) return fail(DK_E_INVALID_ARG, "NULL argument");
+    if (!(flags & DK_STEP_PROFILE))
+        return decode_step_impl(model, pool, d_block_tables, max_blocks, d_seq_lens, d_tokens, B,
+                                d_workspace, workspace_bytes, d_logits, d_next_tokens, flags, hip_stream);
+    // profiled step: every launch carries its own start/stop events; the stream
+    // is synchronised afterwards and the times are added to the model's totals
+    Profiler &p = model->prof;
+    g_prof = &p;
+    const dk_status s = decode_step_impl(model, pool, d_block_tables, max_blocks, d_seq_lens, d_tokens,
+                                         B, d_workspace, workspace_bytes, d_logits, d_next_tokens,
+                                         flags & ~DK_STEP_PROFILE, hip_stream);
+    g_prof = nullptr;
+    hipError_t e = hipStreamSynchronize(static_cast<hipStream_t>(hip_stream));
+    for (auto &q : p.pending) {
+        float ms = 0.f;
+        if (e == hipSuccess && hipEventElapsedTime(&ms, q.e0, q.e1) == hipSuccess) {
+            p.ms[q.cls] += ms;
+            p.launches[q.cls] += 1;
+        }
+        p.free_events.push_back(q.e0);
+        p.free_events.push_back(q.e1);
+    }
+    p.pending.clear();
+    if (s != DK_OK) return s;
+    if (e != hipSuccess) return fail(DK_E_HIP, "hipStreamSynchronize: %s", hipGetErrorString(e));
+    return DK_OK;
+}
+
+dk_status dk_profile_read(dk_model *model, double *out_ms, int64_t *out_launches, int32_t reset)
+{
+    if (!model || !out_ms || !out_launches) return fail(DK_E_INVALID_ARG, "NULL argument");
+    for (int i = 0; i < DK_K_COUNT; i++) {
+        out_ms[i] = model->prof.ms[i];
+        out_launches[i] = model->prof.launches[i];
+        if (reset) { model->prof.ms[i] = 0.0; model->prof.launches[i] = 0; }
+    }
+    return DK_OK;
+}
+
+static dk_status decode_step_impl(dk_model *model, dk_kv_pool *pool, const int32_t *d_block_tables,
+                                  int32_t max_blocks, int32_t *d_seq_lens, int32_t *d_tokens, int32_t B,
+                                  void *d_workspace, size_t workspace_bytes, float *d_logits,
+                                  int32_t *d_next_tokens, uint32_t flags, void *hip_stream)
 {
     if (!model || !pool || !d_block_tables || !d_seq_lens || !d_tokens || !d_workspace ||
         !d_next_tokens)
@@ -598,7 +687,7 @@ dk_status dk_decode_step(dk_model *model, dk_kv_pool *pool, const int32_t *d_blo
             e.ssq_out = ssq;
         }
         std::memcpy(e.inv_freq, model->inv_freq, sizeof e.inv_freq);
-        hipLaunchKernelGGL(dk::embed_kernel, dim3(B), dim3(256), 0, st, e);
+        DK_LAUNCH(DK_K_EMBED, dk::embed_kernel, dim3(B), dim3(256), 0, st, e);
         DK_HIP(hipGetLastError());
     }
 
@@ -717,7 +806,7 @@ dk_status dk_decode_step(dk_model *model, dk_kv_pool *pool, const int32_t *d_blo
             r.topk_idx = topk_idx;
             r.topk_w = topk_w;
             r.rinv = rinv;
-            hipLaunchKernelGGL(dk::moe_router_kernel, dim3(B), dim3(256), 0, st, r);
+            DK_LAUNCH(DK_K_MOE_ROUTER, dk::moe_router_kernel, dim3(B), dim3(256), 0, st, r);
             DK_HIP(hipGetLastError());
             dk::ExpertArgs up{};
             up.w_a = u16(L.w_gate);
@@ -732,8 +821,8 @@ dk_status dk_decode_step(dk_model *model, dk_kv_pool *pool, const int32_t *d_blo
             up.rinv = rinv;
             up.ohi = fhi;
             up.olo = flo;
-            hipLaunchKernelGGL((dk::moe_expert_kernel<true, 8>), dim3((c.expert_ffn + 15) / 16, c.n_experts),
-                               dim3(512), 0, st, up);
+            DK_LAUNCH(DK_K_MOE_EXPERT, (dk::moe_expert_kernel<true, 8>), dim3((c.expert_ffn + 15) / 16, c.n_experts),
+                      dim3(512), 0, st, up);
             DK_HIP(hipGetLastError());
             dk::ExpertArgs dn{};
             dn.w_a = u16(L.w_down);
@@ -745,8 +834,8 @@ dk_status dk_decode_step(dk_model *model, dk_kv_pool *pool, const int32_t *d_blo
             dn.xhi = fhi;
             dn.xlo = flo;
             dn.y = yexp;
-            hipLaunchKernelGGL((dk::moe_expert_kernel<false, 4>), dim3((H + 15) / 16, c.n_experts),
-                               dim3(256), 0, st, dn);
+            DK_LAUNCH(DK_K_MOE_EXPERT, (dk::moe_expert_kernel<false, 4>), dim3((H + 15) / 16, c.n_experts),
+                      dim3(256), 0, st, dn);
             DK_HIP(hipGetLastError());
             dk::MoeCombineArgs cb{};
             cb.x = x;
@@ -758,7 +847,7 @@ dk_status dk_decode_step(dk_model *model, dk_kv_pool *pool, const int32_t *d_blo
             cb.ssq_out = ssq;
             cb.H = H;
             cb.top_k = c.top_k;
-            hipLaunchKernelGGL(dk::moe_combine_kernel, dim3(B), dim3(256), 0, st, cb);
+            DK_LAUNCH(DK_K_MOE_COMBINE, dk::moe_combine_kernel, dim3(B), dim3(256), 0, st, cb);
             DK_HIP(hipGetLastError());
         } else if (batched) {
             dk::GemmArgs g{};
@@ -842,7 +931,7 @@ dk_status dk_decode_step(dk_model *model, dk_kv_pool *pool, const int32_t *d_blo
     }
     dk::ArgmaxArgs am{pmax_val, pmax_idx, w.lm_blocks, d_next_tokens, d_tokens, d_seq_lens,
                       (flags & DK_STEP_ADVANCE) ? 1 : 0};
-    hipLaunchKernelGGL(dk::argmax_final_kernel, dim3(B), dim3(1024), 0, st, am);
+    DK_LAUNCH(DK_K_ARGMAX, dk::argmax_final_kernel, dim3(B), dim3(1024), 0, st, am);
     DK_HIP(hipGetLastError());
     return DK_OK;
 }
