@@ -15,6 +15,7 @@
 #include <vector>
 
 #include "dk_attention.hip.h"
+#include "dk_attention_mfma.hip.h"
 #include "dk_gemm.hip.h"
 #include "dk_gemv.hip.h"
 #include "dk_moe.hip.h"
@@ -135,7 +136,7 @@ struct Workspace {
     // batched (matrix-core) path: activations as bf16 hi/lo, sum-of-squares partials
     size_t xhi, xlo, ahi, alo, fhi, flo, ssq;
     // mixture of experts: routing of every layer, per-row 1/rms, expert outputs
-    size_t topk_idx, topk_w, rinv, yexp;
+    size_t topk_idx, topk_w, rinv, yexp, rlogits;
     int Bp;             // batch rows padded to a multiple of 16
     bool batched;
     int chunk_tokens, max_chunks, lm_blocks;
@@ -146,6 +147,14 @@ constexpr int kMaxGemvBatch = 4;  // up to here the vector-ALU GEMV; above, the 
 constexpr int kLmRB = 8;     // rows per tile of the lm_head GEMV
 constexpr int kLmTiles = 1;  // tiles per block of the lm_head GEMV
 
+// The matrix-core attention kernel pays off once the group of query heads that
+// share a kv head is large (the vector-ALU kernel's multiply-adds grow with it).
+bool attention_uses_mfma(const dk_model_config &c, int B)
+{
+    const bool batched = B > kMaxGemvBatch || c.n_experts > 0;
+    return batched && c.n_q_heads / c.n_kv_heads >= 4;
+}
+
 Workspace carve(const dk_model_config &c, int B, int max_blocks)
 {
     Workspace w{};
@@ -155,7 +164,11 @@ Workspace carve(const dk_model_config &c, int B, int max_blocks)
     // split the context so that rows * kv heads * chunks gives the chip a few
     // blocks per compute unit
     const int ctx_max = max_blocks * 16;
-    int want_chunks = (1024 + B * c.n_kv_heads - 1) / (B * c.n_kv_heads);
+    // measured on 8B-class shapes: the matrix-core kernel (query groups of 4 and
+    // more) runs best with about two blocks per compute unit, the vector-ALU one
+    // with about four
+    const int want_blocks = attention_uses_mfma(c, B) ? 512 : 1024;
+    int want_chunks = (want_blocks + B * c.n_kv_heads - 1) / (B * c.n_kv_heads);
     if (want_chunks < 1) want_chunks = 1;
     int chunk = (ctx_max + want_chunks - 1) / want_chunks;
     chunk = (chunk + 63) / 64 * 64;
@@ -207,6 +220,7 @@ Workspace carve(const dk_model_config &c, int B, int max_blocks)
             w.topk_w = take((size_t)B * c.top_k * 4);
             w.rinv = take((size_t)B * 4);
             w.yexp = take((size_t)B * c.top_k * c.hidden * 4);
+            w.rlogits = take((size_t)B * c.n_experts * 4);
         } else {
             w.fhi = take((size_t)w.Bp * padded(act_dim) * 2);
             w.flo = take((size_t)w.Bp * padded(act_dim) * 2);
@@ -334,18 +348,25 @@ dk_status launch_gemm(const dk::GemmArgs &a, int Bp, hipStream_t st)
     }
 }
 
+// mfma: the matrix-core inner loop (batched path); otherwise the vector-ALU one
 template <int D>
-dk_status launch_attention_d(const dk::AttnArgs &a, int G, dim3 grid, hipStream_t st)
+dk_status launch_attention_d(const dk::AttnArgs &a, int G, dim3 grid, bool mfma, hipStream_t st)
 {
+#define DK_ATTN_CASE(g)                                                                              \
+    case g:                                                                                          \
+        if (mfma) DK_LAUNCH(DK_K_ATTENTION, (dk::attention_mfma_kernel<D, g>), grid, dim3(256), 0, st, a); \
+        else DK_LAUNCH(DK_K_ATTENTION, (dk::attention_kernel<D, g>), grid, dim3(256), 0, st, a);     \
+        break;
     switch (G) {
-        case 1: DK_LAUNCH(DK_K_ATTENTION, (dk::attention_kernel<D, 1>), grid, dim3(256), 0, st, a); break;
-        case 2: DK_LAUNCH(DK_K_ATTENTION, (dk::attention_kernel<D, 2>), grid, dim3(256), 0, st, a); break;
-        case 3: DK_LAUNCH(DK_K_ATTENTION, (dk::attention_kernel<D, 3>), grid, dim3(256), 0, st, a); break;
-        case 4: DK_LAUNCH(DK_K_ATTENTION, (dk::attention_kernel<D, 4>), grid, dim3(256), 0, st, a); break;
-        case 6: DK_LAUNCH(DK_K_ATTENTION, (dk::attention_kernel<D, 6>), grid, dim3(256), 0, st, a); break;
-        case 8: DK_LAUNCH(DK_K_ATTENTION, (dk::attention_kernel<D, 8>), grid, dim3(256), 0, st, a); break;
+        DK_ATTN_CASE(1)
+        DK_ATTN_CASE(2)
+        DK_ATTN_CASE(3)
+        DK_ATTN_CASE(4)
+        DK_ATTN_CASE(6)
+        DK_ATTN_CASE(8)
         default: return fail(DK_E_UNSUPPORTED_SHAPE, "query group size %d", G);
     }
+#undef DK_ATTN_CASE
     DK_HIP(hipGetLastError());
     return DK_OK;
 }
@@ -703,7 +724,8 @@ static dk_status decode_step_impl(dk_model *model, dk_kv_pool *pool, const int32
             g.xhi = xhi;
             g.xlo = xlo;
             g.ssq_in = ssq;
-            g.n_part = (l == 0 || c.n_experts > 0) ? 1 : ssq_tiles;   // who wrote the partials
+            // who wrote the partials: the embedding (1), the expert combine, or a residual GEMM
+            g.n_part = (l == 0) ? 1 : (c.n_experts > 0) ? (H + 1023) / 1024 : ssq_tiles;
             g.eps = eps;
             g.y = qkv;
             if ((s = launch_gemm<dk::GEPI_STORE, true>(g, w.Bp, st)) != DK_OK) return s;
@@ -745,8 +767,9 @@ static dk_status decode_step_impl(dk_model *model, dk_kv_pool *pool, const int32
             a.scale = (float)(1.0 / std::sqrt((double)d));
             a.eps = eps;
             const dim3 grid(w.max_chunks, nkv, B);
-            s = (d == 128) ? launch_attention_d<128>(a, nq / nkv, grid, st)
-                           : launch_attention_d<64>(a, nq / nkv, grid, st);
+            const bool use_mfma = attention_uses_mfma(c, B);
+            s = (d == 128) ? launch_attention_d<128>(a, nq / nkv, grid, use_mfma, st)
+                           : launch_attention_d<64>(a, nq / nkv, grid, use_mfma, st);
             if (s != DK_OK) return s;
         }
         // x += W_o * attn
@@ -803,10 +826,13 @@ static dk_status decode_step_impl(dk_model *model, dk_kv_pool *pool, const int32
             r.H = H;
             r.E = c.n_experts;
             r.top_k = c.top_k;
+            r.logits = reinterpret_cast<float *>(ws + w.rlogits);
             r.topk_idx = topk_idx;
             r.topk_w = topk_w;
             r.rinv = rinv;
-            DK_LAUNCH(DK_K_MOE_ROUTER, dk::moe_router_kernel, dim3(B), dim3(256), 0, st, r);
+            DK_LAUNCH(DK_K_MOE_ROUTER, dk::moe_router_logits_kernel, dim3((c.n_experts + 7) / 8, B), dim3(256),
+                      0, st, r);
+            DK_LAUNCH(DK_K_MOE_ROUTER, dk::moe_router_select_kernel, dim3(B), dim3(64), 0, st, r);
             DK_HIP(hipGetLastError());
             dk::ExpertArgs up{};
             up.w_a = u16(L.w_gate);
@@ -847,7 +873,7 @@ static dk_status decode_step_impl(dk_model *model, dk_kv_pool *pool, const int32
             cb.ssq_out = ssq;
             cb.H = H;
             cb.top_k = c.top_k;
-            DK_LAUNCH(DK_K_MOE_COMBINE, dk::moe_combine_kernel, dim3(B), dim3(256), 0, st, cb);
+            DK_LAUNCH(DK_K_MOE_COMBINE, dk::moe_combine_kernel, dim3((H + 1023) / 1024, B), dim3(256), 0, st, cb);
             DK_HIP(hipGetLastError());
         } else if (batched) {
             dk::GemmArgs g{};
@@ -909,7 +935,7 @@ static dk_status decode_step_impl(dk_model *model, dk_kv_pool *pool, const int32
         g.xhi = xhi;
         g.xlo = xlo;
         g.ssq_in = ssq;
-        g.n_part = c.n_experts > 0 ? 1 : ssq_tiles;
+        g.n_part = c.n_experts > 0 ? (H + 1023) / 1024 : ssq_tiles;
         g.eps = eps;
         g.y = d_logits;
         g.pmax_val = pmax_val;

@@ -10,53 +10,73 @@
 namespace dk {
 
 // ---------------------------------------------------------------------------
-// Router.  One block per batch row: h = rmsnorm(x) * gain, logits = W_r h,
-// probabilities = softmax over all experts, the top_k largest (ties to the
-// lower expert index) renormalised to sum to one.
+// Router, in two small kernels.
+//   logits: grid (ceil(E/8), B), 256 threads.  Each block normalises its row
+//           (h = rmsnorm(x) * gain, recomputed per block: the row is a few KB)
+//           and computes 8 router logits, two per wave.
+//   select: grid (B), one wave.  Softmax over all experts, the top_k largest
+//           probabilities (ties to the lower expert index) renormalised to sum
+//           to one.
 struct RouterArgs {
     const float *x;          // [B][H] residual stream
     const uint16_t *gain;    // [H]
     const uint16_t *w_router;  // [E][H]
     float eps;
     int H, E, top_k;
+    float *logits;           // [B][E]
     int *topk_idx;           // [B][top_k] experts in order of decreasing probability
     float *topk_w;           // [B][top_k] renormalised weights
     float *rinv;             // [B] 1/rms of the row (the expert GEMMs apply it)
 };
 
-__global__ __launch_bounds__(256) void moe_router_kernel(RouterArgs a)
+__global__ __launch_bounds__(256) void moe_router_logits_kernel(RouterArgs a)
 {
     __shared__ float xs[8192];           // x * gain for the row (H <= 8192)
     __shared__ float red[4];
-    __shared__ float logit[256];
-    const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int b = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const float *xr = a.x + (int64_t)b * a.H;
     float ss = 0.f;
-    for (int k = tid; k < a.H; k += 256) {
-        const float v = xr[k];
-        ss += v * v;
-        xs[k] = v * bf16_to_f32(a.gain[k]);
+    for (int k = tid * 4; k < a.H; k += 1024) {
+        const float4 v = ldf4(xr + k);
+        const uint2 gw = *reinterpret_cast<const uint2 *>(a.gain + k);
+        ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+        xs[k] = v.x * bf16lo(gw.x);
+        xs[k + 1] = v.y * bf16hi(gw.x);
+        xs[k + 2] = v.z * bf16lo(gw.y);
+        xs[k + 3] = v.w * bf16hi(gw.y);
     }
     ss = sum64(ss);
     if (lane == 0) red[wv] = ss;
     __syncthreads();
     const float inv = rsqrtf((red[0] + red[1] + red[2] + red[3]) / (float)a.H + a.eps);
-    if (tid == 0) a.rinv[b] = inv;
-    // wave wv takes experts wv, wv+4, ...; lanes stride over H in 8-element pieces
-    for (int e = wv; e < a.E; e += 4) {
-        const uint16_t *wr = a.w_router + (int64_t)e * a.H;
-        float acc = 0.f;
-        for (int k = lane * 8; k < a.H; k += 512) {
-            float w[8];
-            unpack8(ld16(wr + k), w);
+    if (blockIdx.x == 0 && tid == 0) a.rinv[b] = inv;
+    // wave wv: experts 8*blockIdx.x + 2*wv, +1; lanes stride over H in 8-element pieces
+    const int e0 = blockIdx.x * 8 + wv * 2;
+    const uint16_t *w0 = a.w_router + (int64_t)min(e0, a.E - 1) * a.H;
+    const uint16_t *w1 = a.w_router + (int64_t)min(e0 + 1, a.E - 1) * a.H;
+    float acc0 = 0.f, acc1 = 0.f;
+    for (int k = lane * 8; k < a.H; k += 512) {
+        float f0[8], f1[8];
+        unpack8(ld16(w0 + k), f0);
+        unpack8(ld16(w1 + k), f1);
 #pragma unroll
-            for (int i = 0; i < 8; i++) acc += w[i] * xs[k + i];
+        for (int i = 0; i < 8; i++) {
+            acc0 += f0[i] * xs[k + i];
+            acc1 += f1[i] * xs[k + i];
         }
-        acc = sum64(acc);
-        if (lane == 0) logit[e] = acc * inv;
     }
-    __syncthreads();
-    if (wv != 0) return;
+    acc0 = sum64(acc0);
+    acc1 = sum64(acc1);
+    if (lane == 0) {
+        if (e0 < a.E) a.logits[(int64_t)b * a.E + e0] = acc0 * inv;
+        if (e0 + 1 < a.E) a.logits[(int64_t)b * a.E + e0 + 1] = acc1 * inv;
+    }
+}
+
+__global__ __launch_bounds__(64) void moe_router_select_kernel(RouterArgs a)
+{
+    const int b = blockIdx.x, lane = threadIdx.x;
+    const float *logit = a.logits + (int64_t)b * a.E;
     // softmax over the E logits (lane holds experts lane, lane+64, ...; E <= 256)
     float p[4];
     float mx = -INFINITY;
@@ -237,41 +257,53 @@ __global__ __launch_bounds__(KS * 64) void moe_expert_kernel(ExpertArgs a)
 
 // ---------------------------------------------------------------------------
 // x[b] += sum_k w[b][k] * y[b*top_k + k]   (k in the router's order), then the
-// input of the next matrix-core GEMM: (x * next gain) as hi/lo and the row's
-// sum of squares.  One block per batch row.
+// input of the next matrix-core GEMM: (x * next gain) as hi/lo and the sum of
+// squares of the block's columns.  grid = (ceil(H/1024), B): a block covers
+// 1024 columns of one row, four per thread.
 struct MoeCombineArgs {
     float *x;                // [B][H]
     const float *y;          // [B*top_k][H]
     const float *topk_w;     // [B][top_k]
     const uint16_t *gain_next;  // [H]
     uint16_t *xhi, *xlo;
-    float *ssq_out;          // [.] entry b = sum_k x[b][k]^2
+    float *ssq_out;          // [gridDim.x][kSsqStride]: entry [blockIdx.x][b]
     int H, top_k;
 };
 
 __global__ __launch_bounds__(256) void moe_combine_kernel(MoeCombineArgs a)
 {
     __shared__ float red[4];
-    const int b = blockIdx.x, tid = threadIdx.x;
+    const int b = blockIdx.y, tid = threadIdx.x;
     const int nks = (a.H + 127) >> 7;
+    const int k = blockIdx.x * 1024 + tid * 4;
     float ss = 0.f;
-    for (int k = tid; k < a.H; k += 256) {
-        float acc = 0.f;
-        for (int j = 0; j < a.top_k; j++)
-            acc += a.topk_w[b * a.top_k + j] * a.y[((int64_t)b * a.top_k + j) * a.H + k];
-        const float xn = a.x[(int64_t)b * a.H + k] + acc;
-        a.x[(int64_t)b * a.H + k] = xn;
-        ss += xn * xn;
-        uint16_t hi, lo;
-        split_bf16(xn * bf16_to_f32(a.gain_next[k]), hi, lo);
-        const int64_t oo = act_offset(b, k, nks);
-        a.xhi[oo] = hi;
-        a.xlo[oo] = lo;
+    if (k < a.H) {
+        float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int j = 0; j < a.top_k; j++) {
+            const float w = a.topk_w[b * a.top_k + j];
+            const float4 v = ldf4(a.y + ((int64_t)b * a.top_k + j) * a.H + k);
+            acc.x += w * v.x; acc.y += w * v.y; acc.z += w * v.z; acc.w += w * v.w;
+        }
+        float4 xn = ldf4(a.x + (int64_t)b * a.H + k);
+        xn.x += acc.x; xn.y += acc.y; xn.z += acc.z; xn.w += acc.w;
+        *reinterpret_cast<float4 *>(a.x + (int64_t)b * a.H + k) = xn;
+        ss = xn.x * xn.x + xn.y * xn.y + xn.z * xn.z + xn.w * xn.w;
+        const uint2 gw = *reinterpret_cast<const uint2 *>(a.gain_next + k);
+        uint16_t h[4], l[4];
+        split_bf16(xn.x * bf16lo(gw.x), h[0], l[0]);
+        split_bf16(xn.y * bf16hi(gw.x), h[1], l[1]);
+        split_bf16(xn.z * bf16lo(gw.y), h[2], l[2]);
+        split_bf16(xn.w * bf16hi(gw.y), h[3], l[3]);
+        const int64_t oo = act_offset(b, k, nks);   // 4 consecutive k stay inside one 8-element piece
+        *reinterpret_cast<uint2 *>(a.xhi + oo) = make_uint2((uint32_t)h[0] | ((uint32_t)h[1] << 16),
+                                                            (uint32_t)h[2] | ((uint32_t)h[3] << 16));
+        *reinterpret_cast<uint2 *>(a.xlo + oo) = make_uint2((uint32_t)l[0] | ((uint32_t)l[1] << 16),
+                                                            (uint32_t)l[2] | ((uint32_t)l[3] << 16));
     }
     ss = sum64(ss);
     if ((tid & 63) == 0) red[tid >> 6] = ss;
     __syncthreads();
-    if (tid == 0) a.ssq_out[b] = red[0] + red[1] + red[2] + red[3];
+    if (tid == 0) a.ssq_out[(int64_t)blockIdx.x * kSsqStride + b] = red[0] + red[1] + red[2] + red[3];
 }
 
 }  // namespace dk
