@@ -21,6 +21,11 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
 
+# HBM bytes per launch from rocprofv3 FETCH_SIZE + WRITE_SIZE (scaled by a plain copy
+# kernel: x2.0 and x1.0 to KiB), see profiles/decode_step_cfg1_hbm_counters.md.
+# Quoted only while the library reports the kernel revision they were taken on.
+MEASURED_TRAFFIC = {("cfg1", "gemv"): ("gemv r3", 10805373)}
+
 
 def cpu_baseline(shape, weights, layout, pool_bits, tokens, budget_s=12.0, max_steps=64, max_rows=2):
     """The CPU oracle, as it stands, on a bounded sample of the same workload:
@@ -141,6 +146,10 @@ def main():
     dom = kernels[dominant]
     dom_bytes_per_launch = class_bytes.get(dominant, 0) / dom["launches_per_step"]
     achieved = dom_bytes_per_launch / (dom["avg_us"] * 1e-6) / 1e9
+    traffic = None
+    rev, measured = MEASURED_TRAFFIC.get((wl.name, dominant), (None, None))
+    if rev is not None and rev in dk.version():
+        traffic = measured
 
     out = {
         "metric": "aggregate_decode_tok_per_s",
@@ -163,7 +172,7 @@ def main():
         # the kernel class that takes most of the step; achieved = its algorithmic
         # bytes per launch / its mean launch duration (start/stop events per launch)
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
                      "kernel": dominant, "launches_per_step": dom["launches_per_step"],
                      "avg_launch_us": dom["avg_us"],
                      "algorithmic_bytes_per_launch": int(dom_bytes_per_launch)},

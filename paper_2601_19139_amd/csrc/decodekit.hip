@@ -377,7 +377,9 @@ extern "C" {
 
 const char *dk_last_error(void) { return g_err; }
 
-const char *dk_version(void) { return "decodekit 0.1 (gfx950)"; }
+// The kernel revisions change whenever a kernel's memory behaviour changes; the
+// benchmark quotes stored counter measurements only for a matching revision.
+const char *dk_version(void) { return "decodekit 0.2 (gfx950; gemv r3, gemm r6, attention r5, moe r2)"; }
 
 // ------------------------------------------------------------------- pool --
 dk_status dk_kv_pool_bytes(const dk_model_config *cfg, int32_t num_blocks, int32_t block_size,
