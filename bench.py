@@ -58,6 +58,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=16)
     ap.add_argument("--workload", default="cfg1")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--kernel-per-stage", action="store_true",
+                    help="never take the single persistent kernel (small batches of small dense models)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU; --gpus must be 1", file=sys.stderr)
@@ -86,6 +88,8 @@ def main():
     d_tok0 = dec.tokens.clone()
     span = wl.steps                              # tokens of growth the block tables have room for
 
+    path_flag = dk.STEP_NO_FUSED if args.kernel_per_stage else 0
+
     def restart():
         dec.seq_lens.copy_(d_ctx0)
         dec.tokens.copy_(d_tok0)
@@ -94,7 +98,7 @@ def main():
         for i in range(n):
             if i % span == 0:
                 restart()                        # back to the initial context (tables are sized for `span` steps)
-            dec.step(flags=dk.STEP_ADVANCE)      # greedy: the step feeds its token to the next one
+            dec.step(flags=dk.STEP_ADVANCE | path_flag)   # greedy: the step feeds its token to the next one
 
     run(args.warmup)
     torch.cuda.synchronize()
@@ -115,7 +119,7 @@ def main():
     dk.profile_read(dm.handle, reset=True)
     restart()
     for _ in range(prof_steps):
-        dec.step(flags=dk.STEP_ADVANCE | dk.STEP_PROFILE)
+        dec.step(flags=dk.STEP_ADVANCE | dk.STEP_PROFILE | path_flag)
     prof = dk.profile_read(dm.handle, reset=True)
 
     # algorithmic bytes of a step at the mean context of the timed steps
@@ -134,7 +138,8 @@ def main():
     expert_bytes = int(distinct.sum()) * shape.expert_bytes() if distinct is not None else 0
     router_bytes = shape.n_layers * shape.n_experts * shape.hidden * 2
     class_bytes = {"gemv": shape.dense_weight_bytes() - router_bytes, "gemm": shape.dense_weight_bytes() - router_bytes,
-                   "attention": kv_bytes, "moe_expert": expert_bytes, "moe_router": router_bytes}
+                   "attention": kv_bytes, "moe_expert": expert_bytes, "moe_router": router_bytes,
+                   "fused_step": alg_bytes}      # the persistent kernel is the whole step
     step_dev_s = dev_ms * 1e-3 / args.steps
     achieved_step = alg_bytes / step_dev_s / 1e9
     kernels = {}

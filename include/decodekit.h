@@ -173,6 +173,8 @@ dk_status dk_workspace_bytes(const dk_model *model, int32_t max_B, int32_t max_b
 
 /* dk_decode_step flags */
 #define DK_STEP_ADVANCE 1u /* after the step: d_tokens[b] = next token, d_seq_lens[b] += 1 */
+#define DK_STEP_NO_FUSED 4u /* do not use the single persistent step kernel even where it
+                               applies (batches of 1-2 rows of small dense models) */
 #define DK_STEP_PROFILE 2u /* time every kernel of the step with its own start/stop events;
                               the call then synchronises the stream before it returns and
                               adds the times to the totals dk_profile_read returns */
@@ -187,6 +189,7 @@ enum {
     DK_K_MOE_EXPERT,
     DK_K_MOE_COMBINE,
     DK_K_ARGMAX,
+    DK_K_FUSED_STEP,     /* the whole step as one persistent kernel               */
     DK_K_COUNT
 };
 
@@ -208,7 +211,12 @@ enum {
  *   d_seq_lens      device int32 [B]; T < max_blocks_per_seq*block_size
  *   d_tokens        device int32 [B], each in [0, vocab)
  *   d_workspace     device scratch >= dk_workspace_bytes(model, B, max_blocks_per_seq),
- *                   256-byte aligned; contents need not survive between calls
+ *                   256-byte aligned.  Between the steps of one model the caller
+ *                   must leave it alone: the persistent step kernel (batches of
+ *                   1-2 rows of small dense models) keeps hand-over buffers in it
+ *                   that one step prepares for the next.  A workspace that was
+ *                   overwritten, or is used with this model for the first time
+ *                   after other use, must be announced with dk_workspace_reset.
  *   d_logits        device float32 [B][vocab], or NULL to skip storing logits
  *   d_next_tokens   device int32 [B]
  *   flags           0, DK_STEP_ADVANCE (then d_tokens / d_seq_lens are written;
@@ -226,6 +234,19 @@ dk_status dk_decode_step(dk_model *model, dk_kv_pool *pool, const int32_t *d_blo
  * execution time in milliseconds per class, out_launches[DK_K_COUNT] launches
  * per class.  reset != 0 clears the totals.  Host only. */
 dk_status dk_profile_read(dk_model *model, double *out_ms, int64_t *out_launches, int32_t reset);
+
+/* Declares the workspace contents of `model` lost: the next decode step
+ * re-initialises what it needs.  Host only. */
+dk_status dk_workspace_reset(dk_model *model);
+
+/* The persistent step kernel bounds every wait it does; if a wait ever ran out
+ * (its blocks were not all resident, e.g. on a GPU shared with other work) the
+ * step's results are invalid and this reports it: out[0] = serial number of the
+ * last step that gave up (0 = none), out[1] = waits that ran out since the
+ * workspace was first used.  Synchronises the stream.  DK_E_INVALID_ARG if the
+ * workspace has not been used by a persistent step of `model`. */
+dk_status dk_fused_status(const dk_model *model, const void *d_workspace, uint32_t *out,
+                          void *hip_stream);
 
 /* Experts chosen in the most recent decode step that used `d_workspace` with
  * the same B and max_blocks_per_seq (mixture-of-experts models only): copies

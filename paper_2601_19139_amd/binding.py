@@ -10,7 +10,8 @@ STATUS = {0: "DK_OK", -1: "DK_E_INVALID_ARG", -2: "DK_E_POOL_EXHAUSTED", -3: "DK
           -4: "DK_E_WORKSPACE_TOO_SMALL", -5: "DK_E_UNSUPPORTED_SHAPE", -6: "DK_E_HIP"}
 STEP_ADVANCE = 1
 STEP_PROFILE = 2
-KERNEL_CLASSES = ("embed", "gemv", "gemm", "attention", "moe_router", "moe_expert", "moe_combine", "argmax")
+STEP_NO_FUSED = 4
+KERNEL_CLASSES = ("embed", "gemv", "gemm", "attention", "moe_router", "moe_expert", "moe_combine", "argmax", "fused_step")
 
 
 class DecodeKitError(RuntimeError):
@@ -70,6 +71,8 @@ _SIGNATURES = {
     "dk_decode_step": (C.c_int32, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p,
                                    C.c_int32, C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p,
                                    C.c_uint32, C.c_void_p]),
+    "dk_workspace_reset": (C.c_int32, [C.c_void_p]),
+    "dk_fused_status": (C.c_int32, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
     "dk_profile_read": (C.c_int32, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32]),
     "dk_step_routing": (C.c_int32, [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]),
     "dk_step_algorithmic_bytes": (C.c_int32, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p,
@@ -218,6 +221,17 @@ def decode_step(model, pool, d_block_tables, d_seq_lens, d_tokens, d_workspace, 
     _check(lib().dk_decode_step(model, pool, _ptr(d_block_tables), mb, _ptr(d_seq_lens),
                                 _ptr(d_tokens), B, _ptr(d_workspace), nbytes, _ptr(d_logits),
                                 _ptr(d_next_tokens), flags, _stream(stream)))
+
+
+def workspace_reset(model):
+    _check(lib().dk_workspace_reset(model))
+
+
+def fused_status(model, d_workspace, stream=None):
+    """(serial of the last persistent step that gave up waiting or 0, waits that ran out so far)."""
+    out = (C.c_uint32 * 2)()
+    _check(lib().dk_fused_status(model, _ptr(d_workspace), out, _stream(stream)))
+    return out[0], out[1]
 
 
 def profile_read(model, reset=True):

@@ -16,6 +16,7 @@
 
 #include "dk_attention.hip.h"
 #include "dk_attention_mfma.hip.h"
+#include "dk_fused.hip.h"
 #include "dk_gemm.hip.h"
 #include "dk_gemv.hip.h"
 #include "dk_moe.hip.h"
@@ -127,6 +128,13 @@ struct dk_model {
     std::vector<dk_layer_weights> layers;
     double inv_freq[64];
     Profiler prof;
+    // persistent step kernel: the workspace whose buffer sets hold the "not
+    // written yet" pattern, which of the two sets the next step uses, step serial
+    const void *fused_ws = nullptr;
+    size_t fused_ws_bytes = 0;
+    int fused_parity = 0;
+    unsigned fused_serial = 0;
+    int n_cus = 0;
 };
 
 namespace {
@@ -137,6 +145,11 @@ struct Workspace {
     size_t xhi, xlo, ahi, alo, fhi, flo, ssq;
     // mixture of experts: routing of every layer, per-row 1/rms, expert outputs
     size_t topk_idx, topk_w, rinv, yexp, rlogits;
+    // persistent step kernel: two buffer sets + status words
+    size_t fused_sets, fused_status;
+    long long fused_set_floats;
+    int fused_chunks;
+    bool fused;
     int Bp;             // batch rows padded to a multiple of 16
     bool batched;
     int chunk_tokens, max_chunks, lm_blocks;
@@ -146,6 +159,25 @@ struct Workspace {
 constexpr int kMaxGemvBatch = 4;  // up to here the vector-ALU GEMV; above, the matrix-core GEMM
 constexpr int kLmRB = 8;     // rows per tile of the lm_head GEMV
 constexpr int kLmTiles = 1;  // tiles per block of the lm_head GEMV
+
+// The persistent step kernel is compiled for a few shape classes: (head_dim,
+// query group, 512-element pieces of hidden / nq*d / ffn).  Returns the index of
+// the smallest class that fits, or -1.
+constexpr int kFusedBlocks = 256;   // one per compute unit of an MI355X
+struct FusedClass { int d, g, ksh, ksq, ksf; };
+constexpr FusedClass kFusedClasses[] = {{64, 2, 1, 1, 2}, {128, 2, 2, 4, 6}};
+int fused_variant(const dk_model_config &c, int B)
+{
+    if (B > 2 || c.n_experts > 0 || c.n_layers > dk::kFusedMaxLayers) return -1;
+    const int g = c.n_q_heads / c.n_kv_heads;
+    for (int i = 0; i < (int)(sizeof kFusedClasses / sizeof kFusedClasses[0]); i++) {
+        const FusedClass &k = kFusedClasses[i];
+        if (k.d == c.head_dim && k.g == g && c.hidden <= 512 * k.ksh &&
+            c.n_q_heads * c.head_dim <= 512 * k.ksq && c.ffn <= 512 * k.ksf)
+            return i;
+    }
+    return -1;
+}
 
 // The matrix-core attention kernel pays off once the group of query heads that
 // share a kv head is large (the vector-ALU kernel's multiply-adds grow with it).
@@ -229,6 +261,14 @@ Workspace carve(const dk_model_config &c, int B, int max_blocks)
     }
     w.pmax_val = take((size_t)B * w.lm_blocks * 4);
     w.pmax_idx = take((size_t)B * w.lm_blocks * 4);
+    w.fused = fused_variant(c, B) >= 0;
+    if (w.fused) {
+        w.fused_chunks = (ctx_max + dk::kFusedChunk - 1) / dk::kFusedChunk;
+        w.fused_set_floats = dk::fused_layout(c.n_layers, B, c.hidden, c.n_q_heads, c.n_kv_heads, d, c.ffn,
+                                              w.fused_chunks, kFusedBlocks).total;
+        w.fused_sets = take((size_t)2 * w.fused_set_floats * 4);
+        w.fused_status = take(64);
+    }
     w.total = off;
     return w;
 }
@@ -371,6 +411,89 @@ dk_status launch_attention_d(const dk::AttnArgs &a, int G, dim3 grid, bool mfma,
     return DK_OK;
 }
 
+template <int NB, int D, int G, int KSH, int KSQ, int KSF>
+dk_status launch_fused_inst(const dk::FusedArgs &a, hipStream_t st)
+{
+    DK_LAUNCH(DK_K_FUSED_STEP, (dk::fused_step_kernel<NB, D, G, KSH, KSQ, KSF>), dim3(kFusedBlocks),
+              dim3(dk::kFusedThreads), 0, st, a);
+    DK_HIP(hipGetLastError());
+    return DK_OK;
+}
+
+// The whole step as one persistent kernel (see dk_fused.hip.h).  Returns
+// DK_E_UNSUPPORTED_SHAPE (without setting an error text) when the device cannot
+// keep one block per compute unit resident; the caller then takes the ordinary path.
+dk_status launch_fused(dk_model *model, dk_kv_pool *pool, const Workspace &w, char *ws,
+                       const int32_t *d_block_tables, int32_t max_blocks, int32_t *d_seq_lens,
+                       int32_t *d_tokens, int32_t B, float *d_logits, int32_t *d_next, bool advance,
+                       hipStream_t st)
+{
+    const dk_model_config &c = model->cfg;
+    if (model->n_cus == 0) {
+        int dev = 0, n = 0;
+        DK_HIP(hipGetDevice(&dev));
+        DK_HIP(hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev));
+        model->n_cus = n;
+    }
+    if (model->n_cus < kFusedBlocks) return DK_E_UNSUPPORTED_SHAPE;   // blocks could not all be resident
+    float *sets = reinterpret_cast<float *>(ws + w.fused_sets);
+    unsigned *status = reinterpret_cast<unsigned *>(ws + w.fused_status);
+    if (model->fused_ws != ws || model->fused_ws_bytes != w.total) {
+        // first use of this workspace (or another batch shape): both sets to "not written yet"
+        hipLaunchKernelGGL(dk::fused_fill_kernel, dim3(1024), dim3(256), 0, st,
+                           reinterpret_cast<uint32_t *>(sets), 2 * w.fused_set_floats, status);
+        DK_HIP(hipGetLastError());
+        model->fused_ws = ws;
+        model->fused_ws_bytes = w.total;
+        model->fused_parity = 0;
+    }
+    dk::FusedArgs a{};
+    a.L = c.n_layers;
+    a.H = c.hidden;
+    a.nq = c.n_q_heads;
+    a.nkv = c.n_kv_heads;
+    a.F = c.ffn;
+    a.V = c.vocab;
+    a.B = B;
+    a.eps = (float)c.rms_eps;
+    a.scale = (float)(1.0 / std::sqrt((double)c.head_dim));
+    a.embed = static_cast<const uint16_t *>(model->embed);
+    a.lm_head = static_cast<const uint16_t *>(model->lm_head);
+    a.g_final = static_cast<const uint16_t *>(model->g_final);
+    a.tokens = d_tokens;
+    a.seq_lens = d_seq_lens;
+    a.block_tables = d_block_tables;
+    a.max_blocks = max_blocks;
+    a.num_blocks = pool->num_blocks;
+    a.pool = pool->mem;
+    a.logits = d_logits;
+    a.next = d_next;
+    a.advance = advance ? 1 : 0;
+    a.set = sets + (size_t)model->fused_parity * w.fused_set_floats;
+    a.other_set = sets + (size_t)(model->fused_parity ^ 1) * w.fused_set_floats;
+    a.set_floats = w.fused_set_floats;
+    a.nchunks = w.fused_chunks;
+    a.status = status;
+    model->fused_serial = model->fused_serial + 1 == 0 ? 1 : model->fused_serial + 1;
+    a.serial = model->fused_serial;
+    std::memcpy(a.inv_freq, model->inv_freq, sizeof a.inv_freq);
+    for (int l = 0; l < c.n_layers; l++) {
+        const dk_layer_weights &L = model->layers[(size_t)l];
+        auto u16 = [](const void *p) { return static_cast<const uint16_t *>(p); };
+        a.layers[l] = dk::FusedLayer{u16(L.g_attn), u16(L.w_qkv), c.qk_norm ? u16(L.g_q) : nullptr,
+                                     c.qk_norm ? u16(L.g_k) : nullptr, u16(L.w_o), u16(L.g_mlp),
+                                     u16(L.w_gate), u16(L.w_up), u16(L.w_down)};
+    }
+    model->fused_parity ^= 1;
+    const int v = fused_variant(c, B);
+    dk_status s = DK_E_UNSUPPORTED_SHAPE;
+    if (v == 0 && B == 1) s = launch_fused_inst<1, 64, 2, 1, 1, 2>(a, st);
+    else if (v == 0 && B == 2) s = launch_fused_inst<2, 64, 2, 1, 1, 2>(a, st);
+    else if (v == 1 && B == 1) s = launch_fused_inst<1, 128, 2, 2, 4, 6>(a, st);
+    else if (v == 1 && B == 2) s = launch_fused_inst<2, 128, 2, 2, 4, 6>(a, st);
+    return s;
+}
+
 }  // namespace
 
 extern "C" {
@@ -379,7 +502,7 @@ const char *dk_last_error(void) { return g_err; }
 
 // The kernel revisions change whenever a kernel's memory behaviour changes; the
 // benchmark quotes stored counter measurements only for a matching revision.
-const char *dk_version(void) { return "decodekit 0.2 (gfx950; gemv r3, gemm r6, attention r5, moe r2)"; }
+const char *dk_version(void) { return "decodekit 0.3 (gfx950; gemv r3, gemm r6, attention r5, moe r2, fused r1)"; }
 
 // ------------------------------------------------------------------- pool --
 dk_status dk_kv_pool_bytes(const dk_model_config *cfg, int32_t num_blocks, int32_t block_size,
@@ -657,7 +780,7 @@ static dk_status decode_step_impl(dk_model *model, dk_kv_pool *pool, const int32
         return fail(DK_E_INVALID_ARG, "NULL argument");
     if (B <= 0 || B > DK_MAX_BATCH) return fail(DK_E_INVALID_ARG, "B %d (1..%d)", B, DK_MAX_BATCH);
     if (max_blocks <= 0) return fail(DK_E_INVALID_ARG, "max_blocks_per_seq %d", max_blocks);
-    if (flags & ~DK_STEP_ADVANCE) return fail(DK_E_INVALID_ARG, "unknown flags 0x%x", flags);
+    if (flags & ~(DK_STEP_ADVANCE | DK_STEP_NO_FUSED)) return fail(DK_E_INVALID_ARG, "unknown flags 0x%x", flags);
     const dk_model_config &c = model->cfg;
     const dk_model_config &pc = pool->cfg;
     if (pc.n_layers != c.n_layers || pc.n_kv_heads != c.n_kv_heads || pc.head_dim != c.head_dim)
@@ -669,6 +792,11 @@ static dk_status decode_step_impl(dk_model *model, dk_kv_pool *pool, const int32
 
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     char *ws = static_cast<char *>(d_workspace);
+    if (w.fused && !(flags & DK_STEP_NO_FUSED)) {
+        const dk_status fs = launch_fused(model, pool, w, ws, d_block_tables, max_blocks, d_seq_lens, d_tokens,
+                                          B, d_logits, d_next_tokens, (flags & DK_STEP_ADVANCE) != 0, st);
+        if (fs != DK_E_UNSUPPORTED_SHAPE) return fs;   // otherwise: the ordinary path below
+    }
     float *x = reinterpret_cast<float *>(ws + w.x);
     float *qkv = reinterpret_cast<float *>(ws + w.qkv);
     float *attn = reinterpret_cast<float *>(ws + w.attn);
@@ -961,6 +1089,27 @@ static dk_status decode_step_impl(dk_model *model, dk_kv_pool *pool, const int32
                       (flags & DK_STEP_ADVANCE) ? 1 : 0};
     DK_LAUNCH(DK_K_ARGMAX, dk::argmax_final_kernel, dim3(B), dim3(1024), 0, st, am);
     DK_HIP(hipGetLastError());
+    return DK_OK;
+}
+
+dk_status dk_workspace_reset(dk_model *model)
+{
+    if (!model) return fail(DK_E_INVALID_ARG, "model is NULL");
+    model->fused_ws = nullptr;
+    model->fused_ws_bytes = 0;
+    return DK_OK;
+}
+
+dk_status dk_fused_status(const dk_model *model, const void *d_workspace, uint32_t *out, void *hip_stream)
+{
+    if (!model || !d_workspace || !out) return fail(DK_E_INVALID_ARG, "NULL argument");
+    if (model->fused_ws != d_workspace)
+        return fail(DK_E_INVALID_ARG, "this workspace has not been used by a persistent step of the model");
+    // the status words sit at the end of the workspace layout the last step used
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    DK_HIP(hipMemcpyAsync(out, static_cast<const char *>(d_workspace) + model->fused_ws_bytes - 256, 8,
+                          hipMemcpyDeviceToHost, st));
+    DK_HIP(hipStreamSynchronize(st));
     return DK_OK;
 }
 

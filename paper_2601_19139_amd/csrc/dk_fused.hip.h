@@ -1,0 +1,828 @@
+// One decode step as a single persistent kernel, for small batches of small
+// dense models, where a step is a chain of ~5 tiny dependent stages per layer
+// and the chip would otherwise spend its time at kernel boundaries.
+//
+// One block per compute unit stays resident for the whole step and walks through
+// every stage of every layer.  A stage's weights do not depend on the previous
+// stage, so each block requests its slice of the NEXT stage's weights before it
+// waits for that stage's input: the HBM latency of the weight stream is hidden
+// behind the hand-over.  The hand-over itself needs no barrier and no flag:
+//
+//   * every activation buffer of the step (per layer: q|k|v, attention partials,
+//     the two residual vectors, the MLP activations) has its own place in a
+//     set of buffers that holds a "not written yet" bit pattern (a NaN that no
+//     arithmetic produces) when the step starts;
+//   * producers write results with device-coherent stores; consumers read with
+//     device-coherent loads and simply re-read until no element is the pattern
+//     (the 8 compute dies do not share an L2, so ordinary loads could be stale);
+//   * there are two sets; a step uses one and refills the other with the
+//     pattern for the next step (the kernel boundary between steps orders that).
+//
+// Every wait is bounded: after a spin limit a block raises an abort word tagged
+// with the step's serial number, and every waiter that sees it stops waiting, so
+// the kernel always terminates (with an error the host can read) even if
+// blocks were not co-resident.
+//
+// Work split: the rows of a matrix are divided evenly over the blocks and, in a
+// block, over its 4 waves; a wave owns whole rows (lanes stride K in 16-byte
+// pieces) so no cross-wave reduction is needed.  Attention: one block per
+// (row, kv head, 64-token chunk) with the K/V tiles requested ahead as well;
+// the block of a sequence's first chunk collects the other chunks' partials and
+// publishes the finished attention output, which the output projection awaits.
+#pragma once
+#include "dk_attention.hip.h"
+
+namespace dk {
+
+constexpr uint32_t kNotYet = 0x7FFFFFFFu;   // "not written yet"
+constexpr int kFusedThreads = 256;
+constexpr int kFusedWaves = 4;
+constexpr int kFusedMaxLayers = 40;
+constexpr int kFusedChunk = 64;             // tokens per attention work item
+constexpr int kFusedMergeRound = 12;        // chunk partials the collecting block awaits at a time
+constexpr int kFusedWaveTiles = kFusedChunk / (16 * kFusedWaves);   // 16-token K/V tiles per wave
+constexpr int kFusedSpinLimit = 1 << 16;    // polls before a block gives up (each ~1 us)
+
+struct FusedLayer {
+    const uint16_t *g_attn, *w_qkv, *g_q, *g_k, *w_o, *g_mlp, *w_gate, *w_up, *w_down;
+};
+
+struct FusedArgs {
+    int L, H, nq, nkv, F, V, B;
+    float eps, scale;
+    const uint16_t *embed, *lm_head, *g_final;
+    int *tokens, *seq_lens;
+    const int *block_tables;
+    int max_blocks, num_blocks;
+    uint16_t *pool;
+    float *logits;         // [B][V] or null
+    int *next;             // [B]
+    int advance;
+    float *set;            // this step's buffers (all "not yet")
+    float *other_set;      // refilled with the pattern during this step
+    long long set_floats;
+    int nchunks;           // attention chunks per sequence the buffers have room for
+    unsigned *status;      // [0] abort tag, [1] number of timeouts ever
+    unsigned serial;       // this step's tag (never 0)
+    double inv_freq[64];
+    FusedLayer layers[kFusedMaxLayers];
+};
+
+// offsets (in floats) inside a buffer set
+struct FusedLayout {
+    long long qkv, part, attn, xmid, act, xout, per_layer, amax, total;
+};
+__host__ __device__ inline FusedLayout fused_layout(int L, int B, int H, int nq, int nkv, int d, int F,
+                                                   int nchunks, int nblocks)
+{
+    FusedLayout o;
+    const long long qkv_dim = (long long)(nq + 2 * nkv) * d;
+    o.qkv = 0;
+    o.part = o.qkv + B * qkv_dim;
+    o.attn = o.part + (long long)B * nq * nchunks * (d + 2);
+    o.xmid = o.attn + (long long)B * nq * d;
+    o.act = o.xmid + (long long)B * H;
+    o.xout = o.act + (long long)B * F;
+    o.per_layer = o.xout + (long long)B * H;
+    o.amax = o.per_layer * L;
+    o.total = o.amax + 2LL * nblocks * B;
+    return o;
+}
+
+__device__ __forceinline__ uint32_t ldc_u32(const void *p)
+{
+    return __hip_atomic_load(static_cast<const uint32_t *>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void stc_f32(float *p, float v)
+{
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Bounded wait shared by every hand-over: `ready` is this thread's verdict on
+// the elements it just loaded.  Returns true when the whole block may stop
+// polling (everything arrived, or the step was aborted).
+struct Waiter {
+    unsigned *status;
+    unsigned serial;
+    int spins;
+    bool aborted;
+    unsigned *slots;   // LDS [2][kFusedWaves]: the waves' verdicts, double-buffered so one barrier per poll suffices
+    int phase;
+    __device__ __forceinline__ bool done(bool ready)
+    {
+        const int wv = threadIdx.x >> 6;
+        const bool wave_ok = __all(ready);
+        if ((threadIdx.x & 63) == 0) slots[phase * kFusedWaves + wv] = wave_ok;
+        __syncthreads();
+        const unsigned *sl = slots + phase * kFusedWaves;
+        const bool ok = (sl[0] & sl[1] & sl[2] & sl[3]) != 0;
+        phase ^= 1;
+        if (ok) return true;
+        spins++;
+        if ((spins & 63) == 0 || spins > kFusedSpinLimit) {
+            bool stop = ldc_u32(status) == serial;
+            if (spins > kFusedSpinLimit && !stop) {
+                if (threadIdx.x == 0) {
+                    __hip_atomic_store(status, serial, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    atomicAdd(status + 1, 1u);
+                }
+                stop = true;
+            }
+            if (__syncthreads_or(stop)) { aborted = true; return true; }
+        }
+        __builtin_amdgcn_s_sleep(1);
+        return false;
+    }
+};
+
+// Loads x[NB][K] (device-coherent, re-reading until complete) into LDS as
+// x * gain (or x) and returns 1/rms per row when NORM.
+template <int NB, bool NORM>
+__device__ __forceinline__ void stage_input(const float *src, int K, const uint16_t *gain, float eps,
+                                            float *xs /*[NB][K]*/, float (&rinv)[NB], float *red /*[4][NB]*/,
+                                            Waiter &w)
+{
+    const int tid = threadIdx.x;
+    constexpr int MAXE = 16;   // elements per thread per row: K <= 4096
+    uint32_t v[NB][MAXE];
+    float gn[MAXE];
+#pragma unroll
+    for (int e = 0; e < MAXE; e++) {
+        const int k = e * kFusedThreads + tid;
+        gn[e] = (NORM && k < K) ? bf16_to_f32(gain[k]) : 1.f;   // on its way during the wait
+    }
+    w.spins = 0;
+    for (;;) {
+        bool ready = true;
+#pragma unroll
+        for (int b = 0; b < NB; b++)
+#pragma unroll
+            for (int e = 0; e < MAXE; e++) {
+                const int k = e * kFusedThreads + tid;
+                v[b][e] = k < K ? ldc_u32(src + (long long)b * K + k) : 0u;
+                ready = ready && v[b][e] != kNotYet;
+            }
+        if (w.done(ready)) break;
+    }
+    float ss[NB];
+#pragma unroll
+    for (int b = 0; b < NB; b++) {
+        ss[b] = 0.f;
+#pragma unroll
+        for (int e = 0; e < MAXE; e++) {
+            const int k = e * kFusedThreads + tid;
+            if (k < K) {
+                const float x = __uint_as_float(v[b][e]);
+                ss[b] += x * x;
+                xs[b * K + k] = NORM ? x * gn[e] : x;
+            }
+        }
+    }
+    if (NORM) {
+#pragma unroll
+        for (int b = 0; b < NB; b++) {
+            const float s = sum64(ss[b]);
+            if ((tid & 63) == 0) red[(tid >> 6) * NB + b] = s;
+        }
+    }
+    __syncthreads();
+    if (NORM) {
+#pragma unroll
+        for (int b = 0; b < NB; b++)
+            rinv[b] = rsqrtf((red[b] + red[NB + b] + red[2 * NB + b] + red[3 * NB + b]) / (float)K + eps);
+    }
+}
+
+// The rows [r0, r1) of a matrix that a wave owns: rows of the block split over
+// its waves, rows of the matrix split over the blocks.
+__device__ __forceinline__ void block_rows(int N, int &b0, int &n)
+{
+    const int nb = gridDim.x, blk = blockIdx.x;
+    b0 = (int)((long long)N * blk / nb);
+    n = (int)((long long)N * (blk + 1) / nb) - b0;
+}
+__device__ __forceinline__ void wave_rows(int N, int wv, int &r0, int &r1)
+{
+    int b0, n;
+    block_rows(N, b0, n);
+    r0 = b0 + n * wv / kFusedWaves;
+    r1 = b0 + n * (wv + 1) / kFusedWaves;
+}
+
+// Weights of up to RW rows x KS 512-element pieces, one 16-byte piece per lane.
+template <int RW, int KS>
+struct RowRegs {
+    uint4 w[RW][KS];
+};
+template <int RW, int KS>
+__device__ __forceinline__ void load_rows(RowRegs<RW, KS> &r, const uint16_t *W, int K, int row0, int row_end,
+                                          int lane)
+{
+#pragma unroll
+    for (int i = 0; i < RW; i++)
+#pragma unroll
+        for (int s = 0; s < KS; s++) {
+            const int k = s * 512 + lane * 8;
+            // rows / pieces outside the matrix read a valid address and are not used
+            const int row = min(row0 + i, row_end - 1);
+            r.w[i][s] = ld16(W + (long long)max(row, 0) * K + min(k, K - 8));
+        }
+}
+// acc[i][b] = sum_k W[row0+i][k] * xs[b][k]   (all lanes get the sums)
+template <int NB, int RW, int KS>
+__device__ __forceinline__ void dot_rows(const RowRegs<RW, KS> &r, const float *xs, int K, int lane,
+                                         float (&acc)[RW][NB])
+{
+#pragma unroll
+    for (int i = 0; i < RW; i++)
+#pragma unroll
+        for (int b = 0; b < NB; b++) acc[i][b] = 0.f;
+#pragma unroll
+    for (int s = 0; s < KS; s++) {
+        const int k = s * 512 + lane * 8;
+        if (k < K) {
+            float xv[NB][8];
+#pragma unroll
+            for (int b = 0; b < NB; b++) {
+                const float4 lo = *reinterpret_cast<const float4 *>(xs + b * K + k);
+                const float4 hi = *reinterpret_cast<const float4 *>(xs + b * K + k + 4);
+                xv[b][0] = lo.x; xv[b][1] = lo.y; xv[b][2] = lo.z; xv[b][3] = lo.w;
+                xv[b][4] = hi.x; xv[b][5] = hi.y; xv[b][6] = hi.z; xv[b][7] = hi.w;
+            }
+#pragma unroll
+            for (int i = 0; i < RW; i++) {
+                float wf[8];
+                unpack8(r.w[i][s], wf);
+#pragma unroll
+                for (int b = 0; b < NB; b++)
+#pragma unroll
+                    for (int e = 0; e < 8; e++) acc[i][b] += wf[e] * xv[b][e];
+            }
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < RW; i++)
+#pragma unroll
+        for (int b = 0; b < NB; b++) acc[i][b] = sum64(acc[i][b]);
+}
+
+// A block hands a stage's result over with ONE coalesced store: the waves put
+// their rows into LDS (`sm_y`, [NB][kFusedMaxBlockRows]) and, after a barrier,
+// thread b*n + r stores element (batch row b, block row r).  Scattered 4-byte
+// stores from 1024 waves made the hand-over measurably slower.
+constexpr int kFusedMaxBlockRows = 64;
+
+// sm_y[b][row - b0] = scale_b * W[row] . xs[b] for the wave's rows; the first RW
+// rows come from `pre` (requested before the input was awaited).
+template <int NB, int RW, int KS>
+__device__ __forceinline__ void gemv_rows(RowRegs<RW, KS> &pre, const uint16_t *W, int K, int r0, int r1, int b0,
+                                          const float *xs, const float (&scale)[NB], float *sm_y, int lane)
+{
+    for (int rb = r0; rb < r1; rb += RW) {
+        if (rb != r0) load_rows<RW, KS>(pre, W, K, rb, r1, lane);
+        float acc[RW][NB];
+        dot_rows<NB, RW, KS>(pre, xs, K, lane, acc);
+        float v = 0.f;
+#pragma unroll
+        for (int i = 0; i < RW; i++)
+#pragma unroll
+            for (int b = 0; b < NB; b++)
+                if (lane == i * NB + b) v = acc[i][b] * scale[b];
+        const int li = lane / NB, lb = lane - li * NB;
+        if (lane < RW * NB && rb + li < r1) sm_y[lb * kFusedMaxBlockRows + rb + li - b0] = v;
+    }
+}
+
+// The block's n rows starting at b0, for every batch row: out[b][b0 + r] = sm_y[b][r] + rv.
+template <int NB>
+__device__ __forceinline__ void publish_rows(float *out, int N, int b0, int n, const float *sm_y, float rv)
+{
+    __syncthreads();
+    const int tid = threadIdx.x;
+    if (tid < n * NB) {
+        const int b = tid / n, r = tid - b * n;
+        stc_f32(out + (long long)b * N + b0 + r, sm_y[b * kFusedMaxBlockRows + r] + rv);
+    }
+}
+
+template <int NB, int D, int G, int KSH, int KSQ, int KSF>
+__global__ __launch_bounds__(kFusedThreads) void fused_step_kernel(FusedArgs a)
+{
+    constexpr int BS = 16, TPR = D / 8, TPW = 64 / TPR, NI = BS / TPW;
+    constexpr int RW_H = (KSH <= 2) ? 4 : 2;      // rows per wave in flight, K = H
+    constexpr int RW_GU = (KSH <= 2) ? 3 : 1;     // gate and up: two matrices
+    constexpr int RW_Q = (KSQ <= 2) ? 4 : 2;      // K = nq*d
+    constexpr int RW_F = (KSF <= 2) ? 4 : 2;      // K = F
+    constexpr int MAXK = 512 * (KSF > KSQ ? (KSF > KSH ? KSF : KSH) : (KSQ > KSH ? KSQ : KSH));
+    __shared__ float xs[NB * MAXK];
+    __shared__ float red[kFusedWaves * NB];
+    __shared__ float sm_o[kFusedWaves][G][D];
+    __shared__ float sm_ml[kFusedWaves][G][2];
+    __shared__ float sm_qkv[(G + 2) * D];
+    __shared__ unsigned wslots[2 * kFusedWaves];
+    __shared__ float sm_y[NB * kFusedMaxBlockRows];
+    static_assert(G * D <= kFusedThreads, "one thread per element of a kv head's query group");
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int blk = blockIdx.x, nblk = gridDim.x;
+    const int H = a.H, F = a.F, V = a.V, QD = a.nq * D, QKV = (a.nq + 2 * a.nkv) * D;
+    const FusedLayout lay = fused_layout(a.L, NB, H, a.nq, a.nkv, D, F, a.nchunks, nblk);
+    Waiter w{a.status, a.serial, 0, false, wslots, 0};
+
+    // refill the other buffer set for the next step
+    {
+        uint32_t *o = reinterpret_cast<uint32_t *>(a.other_set);
+        const long long per = (a.set_floats + nblk - 1) / nblk;
+        const long long lo = per * blk, hi = min(a.set_floats, lo + per);
+        for (long long i = lo + tid; i < hi; i += kFusedThreads) o[i] = kNotYet;
+    }
+
+    // sequence state of the step (constant until the very end)
+    int T[NB], nact[NB];
+#pragma unroll
+    for (int b = 0; b < NB; b++) {
+        T[b] = min(max(a.seq_lens[b], 0), a.max_blocks * BS - 1);
+        nact[b] = min((T[b] + 1 + kFusedChunk - 1) / kFusedChunk, a.nchunks);
+    }
+
+    // ---- stage 0: x0 = embedding rows, straight into LDS; q|k|v weights ahead ----
+    int r0, r1, qkv_b0, qkv_n, h_b0, h_n, f_b0, f_n;
+    wave_rows(QKV, wv, r0, r1);
+    block_rows(QKV, qkv_b0, qkv_n);
+    block_rows(H, h_b0, h_n);
+    block_rows(F, f_b0, f_n);
+    RowRegs<RW_H, KSH> pre_h;
+    load_rows<RW_H, KSH>(pre_h, a.layers[0].w_qkv, H, r0, r1, lane);
+    float rinv[NB], ones[NB];
+#pragma unroll
+    for (int b = 0; b < NB; b++) ones[b] = 1.f;
+    {
+        float ss[NB];
+#pragma unroll
+        for (int b = 0; b < NB; b++) {
+            ss[b] = 0.f;
+            const int tok = min(max(a.tokens[b], 0), V - 1);
+            for (int k = tid; k < H; k += kFusedThreads) {
+                const float x = bf16_to_f32(a.embed[(long long)tok * H + k]);
+                ss[b] += x * x;
+                xs[b * H + k] = x * bf16_to_f32(a.layers[0].g_attn[k]);
+            }
+            const float s = sum64(ss[b]);
+            if (lane == 0) red[wv * NB + b] = s;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int b = 0; b < NB; b++)
+            rinv[b] = rsqrtf((red[b] + red[NB + b] + red[2 * NB + b] + red[3 * NB + b]) / (float)H + a.eps);
+    }
+
+    // rotary (cos, sin) of this block's attention row, computed once per step
+    const int dl = (lane % TPR) * 8, sub = lane / TPR;
+    const bool upper = dl >= D / 2;
+    const int items = NB * a.nkv * a.nchunks;
+    float2 cs[8];
+    int cs_row = -1;
+
+    for (int l = 0; l < a.L; l++) {
+        const FusedLayer &Lw = a.layers[l];
+        float *base = a.set + lay.per_layer * l;
+        float *b_qkv = base + lay.qkv, *b_part = base + lay.part, *b_attn = base + lay.attn, *b_xmid = base + lay.xmid;
+        float *b_act = base + lay.act, *b_xout = base + lay.xout;
+        const float *x_in = l ? a.set + lay.per_layer * (l - 1) + lay.xout : nullptr;   // layer 0: embedding
+
+        // ---- q|k|v = W_qkv rmsnorm(x) ------------------------------------------------
+        gemv_rows<NB, RW_H, KSH>(pre_h, Lw.w_qkv, H, r0, r1, qkv_b0, xs, rinv, sm_y, lane);
+        publish_rows<NB>(b_qkv, QKV, qkv_b0, qkv_n, sm_y, 0.f);
+        // ---- attention: request the K/V tiles, then wait for q|k|v --------------------
+        RowRegs<RW_Q, KSQ> pre_q;
+        int q0, q1;
+        wave_rows(H, wv, q0, q1);
+        load_rows<RW_Q, KSQ>(pre_q, Lw.w_o, QD, q0, q1, lane);
+        // the residual of the element this thread will publish: the layer's input, which is
+        // the embedding row (layer 0) or the previous x_out (complete: the block consumed it)
+        float rv_o = 0.f;
+        if (tid < h_n * NB) {
+            const int b = tid / h_n, r = tid - b * h_n;
+            if (l == 0) {
+                const int tok = min(max(a.tokens[b], 0), V - 1);
+                rv_o = bf16_to_f32(a.embed[(long long)tok * H + h_b0 + r]);
+            } else {
+                rv_o = __uint_as_float(ldc_u32(x_in + (long long)b * H + h_b0 + r));
+            }
+        }
+        for (int item = blk; item < items; item += nblk) {
+            const int c = item % a.nchunks, j = (item / a.nchunks) % a.nkv, b = item / (a.nchunks * a.nkv);
+            if (c >= nact[b]) continue;
+            const int *table = a.block_tables + (long long)b * a.max_blocks;
+            const int t0 = c * kFusedChunk, t1 = min(T[b], t0 + kFusedChunk);
+            const bool owns_new = (c == nact[b] - 1);
+            const bool norm = Lw.g_q != nullptr;
+            float gq[8], gk[8];
+            if (norm) {
+                unpack8(ld16(Lw.g_q + dl), gq);
+                unpack8(ld16(Lw.g_k + dl), gk);
+            } else {
+#pragma unroll
+                for (int e = 0; e < 8; e++) gq[e] = gk[e] = 1.f;
+            }
+            // this wave's tiles: t0/16 + wv (+ 4, + 8 ... when a chunk has more tiles than waves)
+            uint4 kw[kFusedWaveTiles][NI], vw[kFusedWaveTiles][NI];
+#pragma unroll
+            for (int u = 0; u < kFusedWaveTiles; u++) {
+                const int tb = min(t0 / BS + wv + u * kFusedWaves, a.max_blocks - 1);
+                const int phys = min(max(table[tb], 0), a.num_blocks - 1);
+                const uint16_t *kt = a.pool + kv_tile_offset(l, a.num_blocks, phys, 0, a.nkv, j, BS, D);
+                const uint16_t *vt = kt + (long long)a.nkv * BS * D;
+#pragma unroll
+                for (int i = 0; i < NI; i++) {
+                    kw[u][i] = ld16(kt + i * 512 + lane * 8);
+                    vw[u][i] = ld16(vt + i * 512 + lane * 8);
+                }
+            }
+            if (cs_row != b) {
+                cs_row = b;
+#pragma unroll
+                for (int e = 0; e < 8; e++) {
+                    const int i = (upper ? dl - D / 2 : dl) + e;
+                    double s_, c_;
+                    sincos((double)T[b] * a.inv_freq[i], &s_, &c_);
+                    cs[e] = make_float2((float)c_, (float)s_);
+                }
+            }
+            // wait for this (row, kv head)'s q heads and new k, v: each word is fetched once per block
+            {
+                constexpr int NW = (G + 2) * D, PE = (NW + kFusedThreads - 1) / kFusedThreads;
+                const float *rowp = b_qkv + (long long)b * QKV;
+                const float *src[PE];
+                uint32_t got[PE];
+#pragma unroll
+                for (int e = 0; e < PE; e++) {
+                    const int idx = e * kFusedThreads + tid;
+                    const int part = idx / D, dim = idx - part * D;   // part: G query heads, then k, then v
+                    const int head = part < G ? j * G + part : (part == G ? a.nq + j : a.nq + a.nkv + j);
+                    src[e] = idx < NW ? rowp + (long long)head * D + dim : nullptr;
+                }
+                w.spins = 0;
+                for (;;) {
+                    bool ready = true;
+#pragma unroll
+                    for (int e = 0; e < PE; e++) {
+                        got[e] = src[e] ? ldc_u32(src[e]) : 0u;
+                        ready = ready && got[e] != kNotYet;
+                    }
+                    if (w.done(ready)) break;
+                }
+#pragma unroll
+                for (int e = 0; e < PE; e++)
+                    if (src[e]) sm_qkv[e * kFusedThreads + tid] = __uint_as_float(got[e]);
+                __syncthreads();
+            }
+            float q[G][8], kn[8], vn[8];
+#pragma unroll
+            for (int e = 0; e < 8; e++) {
+#pragma unroll
+                for (int g = 0; g < G; g++) q[g][e] = sm_qkv[g * D + dl + e];
+                kn[e] = sm_qkv[G * D + dl + e];
+                vn[e] = sm_qkv[(G + 1) * D + dl + e];
+            }
+#pragma unroll
+            for (int g = 0; g < G; g++) {
+                head_norm_rope<D>(q[g], norm, gq, a.eps, cs, upper);
+#pragma unroll
+                for (int e = 0; e < 8; e++) q[g][e] *= a.scale;
+            }
+            float m[G], lsum[G], o[G][8];
+#pragma unroll
+            for (int g = 0; g < G; g++) {
+                m[g] = -1e30f;
+                lsum[g] = 0.f;
+#pragma unroll
+                for (int e = 0; e < 8; e++) o[g][e] = 0.f;
+            }
+            if (owns_new && wv == 0) {
+                head_norm_rope<D>(kn, norm, gk, a.eps, cs, upper);
+                uint32_t kb[4], vb[4];
+#pragma unroll
+                for (int e = 0; e < 4; e++) {
+                    const uint32_t k0 = f32_to_bf16_rne(kn[2 * e]), k1 = f32_to_bf16_rne(kn[2 * e + 1]);
+                    const uint32_t v0 = f32_to_bf16_rne(vn[2 * e]), v1 = f32_to_bf16_rne(vn[2 * e + 1]);
+                    kb[e] = k0 | (k1 << 16);
+                    vb[e] = v0 | (v1 << 16);
+                    kn[2 * e] = __uint_as_float(k0 << 16); kn[2 * e + 1] = __uint_as_float(k1 << 16);
+                    vn[2 * e] = __uint_as_float(v0 << 16); vn[2 * e + 1] = __uint_as_float(v1 << 16);
+                }
+                if (sub == 0) {
+                    const int phys = min(max(table[T[b] / BS], 0), a.num_blocks - 1);
+                    uint16_t *kt = a.pool + kv_tile_offset(l, a.num_blocks, phys, 0, a.nkv, j, BS, D) +
+                                   (T[b] % BS) * D + dl;
+                    uint16_t *vt = kt + (long long)a.nkv * BS * D;
+                    *reinterpret_cast<uint4 *>(kt) = make_uint4(kb[0], kb[1], kb[2], kb[3]);
+                    *reinterpret_cast<uint4 *>(vt) = make_uint4(vb[0], vb[1], vb[2], vb[3]);
+                }
+#pragma unroll
+                for (int g = 0; g < G; g++) {
+                    float p = 0.f;
+#pragma unroll
+                    for (int e = 0; e < 8; e++) p += q[g][e] * kn[e];
+                    p = (TPR == 16) ? sum16(p) : sum8(p);
+                    if (sub == 0) {
+                        m[g] = p;
+                        lsum[g] = 1.f;
+#pragma unroll
+                        for (int e = 0; e < 8; e++) o[g][e] = vn[e];
+                    }
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < kFusedWaveTiles; u++) {
+                const int tile = t0 / BS + wv + u * kFusedWaves;
+                float s[NI][G];
+                bool valid[NI];
+#pragma unroll
+                for (int i = 0; i < NI; i++) {
+                    valid[i] = (tile * BS + i * TPW + sub) < t1;
+                    float kf[8];
+                    unpack8(kw[u][i], kf);
+#pragma unroll
+                    for (int g = 0; g < G; g++) {
+                        float p = 0.f;
+#pragma unroll
+                        for (int e = 0; e < 8; e++) p += q[g][e] * kf[e];
+                        p = (TPR == 16) ? sum16(p) : sum8(p);
+                        s[i][g] = valid[i] ? p : -1e30f;
+                    }
+                }
+#pragma unroll
+                for (int g = 0; g < G; g++) {
+                    float mn = m[g];
+#pragma unroll
+                    for (int i = 0; i < NI; i++) mn = fmaxf(mn, s[i][g]);
+                    const float alpha = __expf(m[g] - mn);
+                    m[g] = mn;
+                    lsum[g] *= alpha;
+#pragma unroll
+                    for (int e = 0; e < 8; e++) o[g][e] *= alpha;
+                }
+#pragma unroll
+                for (int i = 0; i < NI; i++) {
+                    float vf[8];
+                    unpack8(vw[u][i], vf);
+#pragma unroll
+                    for (int g = 0; g < G; g++) {
+                        const float p = valid[i] ? __expf(s[i][g] - m[g]) : 0.f;
+                        lsum[g] += p;
+#pragma unroll
+                        for (int e = 0; e < 8; e++) o[g][e] += valid[i] ? p * vf[e] : 0.f;
+                    }
+                }
+            }
+            // merge the token groups of the wave, then the waves
+#pragma unroll
+            for (int off = TPR; off < 64; off <<= 1) {
+#pragma unroll
+                for (int g = 0; g < G; g++) {
+                    const float om = __shfl_xor(m[g], off), ol = __shfl_xor(lsum[g], off);
+                    const float mn = fmaxf(m[g], om);
+                    const float sa = __expf(m[g] - mn), sb = __expf(om - mn);
+                    lsum[g] = lsum[g] * sa + ol * sb;
+#pragma unroll
+                    for (int e = 0; e < 8; e++) {
+                        const float oo = __shfl_xor(o[g][e], off);
+                        o[g][e] = o[g][e] * sa + oo * sb;
+                    }
+                    m[g] = mn;
+                }
+            }
+            if (lane < TPR) {
+#pragma unroll
+                for (int g = 0; g < G; g++) {
+#pragma unroll
+                    for (int e = 0; e < 8; e++) sm_o[wv][g][dl + e] = o[g][e];
+                    if (lane == 0) { sm_ml[wv][g][0] = m[g]; sm_ml[wv][g][1] = lsum[g]; }
+                }
+            }
+            __syncthreads();
+            // thread (g, dim) owns one element of the chunk's result
+            const bool has = tid < G * D;
+            const int g_ = has ? tid / D : 0, dim = has ? tid - g_ * D : 0;
+            float mn = sm_ml[0][g_][0];
+#pragma unroll
+            for (int ww = 1; ww < kFusedWaves; ww++) mn = fmaxf(mn, sm_ml[ww][g_][0]);
+            float ls = 0.f, os = 0.f;
+#pragma unroll
+            for (int ww = 0; ww < kFusedWaves; ww++) {
+                const float sc = __expf(sm_ml[ww][g_][0] - mn);
+                ls += sm_ml[ww][g_][1] * sc;
+                os += sm_o[ww][g_][dim] * sc;
+            }
+            float *pg = b_part + (((long long)b * a.nkv + j) * a.nchunks) * (G * (D + 2)) + g_ * (D + 2);
+            if (c != 0) {
+                // a later chunk: hand the partial to the block of chunk 0
+                if (has) {
+                    float *pp = pg + (long long)c * (G * (D + 2));
+                    stc_f32(pp + dim, os);
+                    if (dim == 0) { stc_f32(pp + D, mn); stc_f32(pp + D + 1, ls); }
+                }
+            } else {
+                // chunk 0 collects the other chunks of its (row, kv head) in order and
+                // publishes the finished attention output
+                for (int c0 = 1; c0 < nact[b]; c0 += kFusedMergeRound) {
+                    uint32_t um[kFusedMergeRound], ul[kFusedMergeRound], uo[kFusedMergeRound];
+                    w.spins = 0;
+                    for (;;) {
+                        bool ready = true;
+#pragma unroll
+                        for (int u = 0; u < kFusedMergeRound; u++) {
+                            um[u] = ul[u] = uo[u] = 0u;
+                            if (has && c0 + u < nact[b]) {
+                                const float *pp = pg + (long long)(c0 + u) * (G * (D + 2));
+                                um[u] = ldc_u32(pp + D);
+                                ul[u] = ldc_u32(pp + D + 1);
+                                uo[u] = ldc_u32(pp + dim);
+                                ready = ready && um[u] != kNotYet && ul[u] != kNotYet && uo[u] != kNotYet;
+                            }
+                        }
+                        if (w.done(ready)) break;
+                    }
+#pragma unroll
+                    for (int u = 0; u < kFusedMergeRound; u++)
+                        if (has && c0 + u < nact[b]) {
+                            const float mc = __uint_as_float(um[u]), lc = __uint_as_float(ul[u]);
+                            const float oc = __uint_as_float(uo[u]);
+                            const float m2 = fmaxf(mn, mc);
+                            const float sa = __expf(mn - m2), sb = __expf(mc - m2);
+                            ls = ls * sa + lc * sb;
+                            os = os * sa + oc * sb;
+                            mn = m2;
+                        }
+                }
+                if (has) stc_f32(b_attn + (long long)b * QD + (long long)(j * G + g_) * D + dim, os / ls);
+            }
+            __syncthreads();   // sm_o / sm_ml / sm_qkv are rewritten by the block's next item
+        }
+        // ---- x_mid = x + W_o attn -------------------------------------------------------------
+        {
+            float dummy[NB];
+            stage_input<NB, false>(b_attn, QD, nullptr, a.eps, xs, dummy, red, w);
+            gemv_rows<NB, RW_Q, KSQ>(pre_q, Lw.w_o, QD, q0, q1, h_b0, xs, ones, sm_y, lane);
+            publish_rows<NB>(b_xmid, H, h_b0, h_n, sm_y, rv_o);
+        }
+        // ---- act = silu(W_g h) * (W_u h), h = rmsnorm(x_mid) ----------------------------
+        {
+            int f0, f1;
+            wave_rows(F, wv, f0, f1);
+            RowRegs<RW_GU, KSH> pg, pu;
+            load_rows<RW_GU, KSH>(pg, Lw.w_gate, H, f0, f1, lane);
+            load_rows<RW_GU, KSH>(pu, Lw.w_up, H, f0, f1, lane);
+            __syncthreads();   // xs is about to be overwritten
+            stage_input<NB, true>(b_xmid, H, Lw.g_mlp, a.eps, xs, rinv, red, w);
+            for (int rb = f0; rb < f1; rb += RW_GU) {
+                if (rb != f0) {
+                    load_rows<RW_GU, KSH>(pg, Lw.w_gate, H, rb, f1, lane);
+                    load_rows<RW_GU, KSH>(pu, Lw.w_up, H, rb, f1, lane);
+                }
+                float ag[RW_GU][NB], au[RW_GU][NB];
+                dot_rows<NB, RW_GU, KSH>(pg, xs, H, lane, ag);
+                dot_rows<NB, RW_GU, KSH>(pu, xs, H, lane, au);
+                float v = 0.f;
+#pragma unroll
+                for (int i = 0; i < RW_GU; i++)
+#pragma unroll
+                    for (int b = 0; b < NB; b++)
+                        if (lane == i * NB + b) {
+                            const float z = ag[i][b] * rinv[b];
+                            v = z / (1.0f + __expf(-z)) * (au[i][b] * rinv[b]);
+                        }
+                const int li = lane / NB, lb = lane - li * NB;
+                if (lane < RW_GU * NB && rb + li < f1) sm_y[lb * kFusedMaxBlockRows + rb + li - f_b0] = v;
+            }
+            publish_rows<NB>(b_act, F, f_b0, f_n, sm_y, 0.f);
+        }
+        // ---- x_out = x_mid + W_d act ------------------------------------------------------
+        {
+            int d0, d1;
+            wave_rows(H, wv, d0, d1);
+            RowRegs<RW_F, KSF> pd;
+            load_rows<RW_F, KSF>(pd, Lw.w_down, F, d0, d1, lane);
+            float rv_d = 0.f;
+            if (tid < h_n * NB) {
+                const int b = tid / h_n, r = tid - b * h_n;
+                rv_d = __uint_as_float(ldc_u32(b_xmid + (long long)b * H + h_b0 + r));
+            }
+            __syncthreads();
+            float dummy[NB];
+            stage_input<NB, false>(b_act, F, nullptr, a.eps, xs, dummy, red, w);
+            gemv_rows<NB, RW_F, KSF>(pd, Lw.w_down, F, d0, d1, h_b0, xs, ones, sm_y, lane);
+            publish_rows<NB>(b_xout, H, h_b0, h_n, sm_y, rv_d);
+        }
+        // ---- next layer's q|k|v weights ahead, then its input --------------------------------
+        if (l + 1 < a.L) {
+            load_rows<RW_H, KSH>(pre_h, a.layers[l + 1].w_qkv, H, r0, r1, lane);
+            __syncthreads();
+            stage_input<NB, true>(b_xout, H, a.layers[l + 1].g_attn, a.eps, xs, rinv, red, w);
+        }
+    }
+
+    // ---- logits = W_lm rmsnorm(x); per-block maxima; block 0 picks the tokens ------------------
+    {
+        int v0, v1;
+        wave_rows(V, wv, v0, v1);
+        RowRegs<RW_H, KSH> pl;
+        load_rows<RW_H, KSH>(pl, a.lm_head, H, v0, v1, lane);
+        __syncthreads();
+        const float *x_last = a.set + lay.per_layer * (a.L - 1) + lay.xout;
+        stage_input<NB, true>(x_last, H, a.g_final, a.eps, xs, rinv, red, w);
+        float best[NB];
+        int best_i[NB];
+#pragma unroll
+        for (int b = 0; b < NB; b++) { best[b] = -INFINITY; best_i[b] = 0x7fffffff; }
+        for (int rb = v0; rb < v1; rb += RW_H) {
+            RowRegs<RW_H, KSH> nxt;
+            const bool more = rb + RW_H < v1;
+            if (more) load_rows<RW_H, KSH>(nxt, a.lm_head, H, rb + RW_H, v1, lane);   // next rows in flight
+            float acc[RW_H][NB];
+            dot_rows<NB, RW_H, KSH>(pl, xs, H, lane, acc);
+#pragma unroll
+            for (int i = 0; i < RW_H; i++)
+#pragma unroll
+                for (int b = 0; b < NB; b++) {
+                    const float v = acc[i][b] * rinv[b];
+                    if (rb + i < v1) {
+                        if (v > best[b]) { best[b] = v; best_i[b] = rb + i; }   // rows ascend: ties keep the lower
+                        if (a.logits != nullptr && lane == i * NB + b) a.logits[(long long)b * V + rb + i] = v;
+                    }
+                }
+            if (more) pl = nxt;
+        }
+        // block maximum per row of the batch: waves own ascending row ranges
+        __syncthreads();
+        float *sv = xs;                       // reuse LDS: [wave][b] values and indices
+        int *si = reinterpret_cast<int *>(xs + kFusedWaves * NB);
+        if (lane == 0) {
+#pragma unroll
+            for (int b = 0; b < NB; b++) { sv[wv * NB + b] = best[b]; si[wv * NB + b] = best_i[b]; }
+        }
+        __syncthreads();
+        float *amax = a.set + lay.amax;
+        if (tid < NB) {
+            float bv = sv[tid];
+            int bi = si[tid];
+            for (int ww = 1; ww < kFusedWaves; ww++)
+                if (sv[ww * NB + tid] > bv) { bv = sv[ww * NB + tid]; bi = si[ww * NB + tid]; }
+            stc_f32(amax + 2 * ((long long)blk * NB + tid), bv);
+            // a block without rows reports index -1 (0x7fffffff would read as "not yet")
+            stc_f32(amax + 2 * ((long long)blk * NB + tid) + 1, __int_as_float(bi == 0x7fffffff ? -1 : bi));
+        }
+        if (blk != 0) return;
+        // block 0: all per-block maxima (blocks own ascending row ranges)
+        for (int b = 0; b < NB; b++) {
+            float bv = -INFINITY;
+            int bi = 0x7fffffff;
+            w.spins = 0;
+            for (;;) {
+                bool ready = true;
+                bv = -INFINITY;
+                bi = 0x7fffffff;
+                for (int i = tid; i < nblk; i += kFusedThreads) {
+                    const uint32_t uv = ldc_u32(amax + 2 * ((long long)i * NB + b));
+                    const uint32_t ui = ldc_u32(amax + 2 * ((long long)i * NB + b) + 1);
+                    ready = ready && uv != kNotYet && ui != kNotYet;
+                    const float v = __uint_as_float(uv);
+                    const int ix = (int)ui;
+                    if (ix >= 0 && (v > bv || (v == bv && ix < bi))) { bv = v; bi = ix; }
+                }
+                if (w.done(ready)) break;
+            }
+#pragma unroll
+            for (int off = 1; off < 64; off <<= 1) {
+                const float ov = __shfl_xor(bv, off);
+                const int oi = __shfl_xor(bi, off);
+                if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
+            }
+            __syncthreads();
+            if (lane == 0) { sv[wv] = bv; si[wv] = bi; }
+            __syncthreads();
+            if (tid == 0) {
+                for (int ww = 1; ww < kFusedWaves; ww++)
+                    if (sv[ww] > bv || (sv[ww] == bv && si[ww] < bi)) { bv = sv[ww]; bi = si[ww]; }
+                if (bi == 0x7fffffff) bi = 0;
+                a.next[b] = bi;
+                if (a.advance) {
+                    a.tokens[b] = bi;
+                    a.seq_lens[b] += 1;
+                }
+            }
+        }
+    }
+}
+
+// Fills both buffer sets with the "not written yet" pattern (first use of a workspace).
+__global__ __launch_bounds__(256) void fused_fill_kernel(uint32_t *p, long long n, unsigned *status)
+{
+    const long long i0 = (long long)blockIdx.x * 256 + threadIdx.x, stride = (long long)gridDim.x * 256;
+    for (long long i = i0; i < n; i += stride) p[i] = kNotYet;
+    if (i0 == 0) { status[0] = 0; status[1] = 0; }
+}
+
+}  // namespace dk

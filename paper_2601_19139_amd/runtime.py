@@ -115,6 +115,14 @@ class Decoder:
         self.ws = torch.empty(self.ws_bytes + 256, dtype=torch.uint8, device="cuda")
         self._ws_ptr = (self.ws.data_ptr() + 255) // 256 * 256
 
+    def fused_status(self):
+        """(serial of the last persistent step that gave up waiting, waits that ran out) or None
+        when no persistent step has used this decoder's workspace."""
+        try:
+            return dk.fused_status(self.m.handle, self._ws_ptr)
+        except dk.DecodeKitError:
+            return None
+
     def routing(self):
         """Experts chosen in the last step, int32 [n_layers, B, top_k] (MoE models)."""
         shape = self.m.shape

@@ -62,6 +62,7 @@ def run_both(orc, shape, weights, layout, pool_bits, tokens, steps, teacher_forc
             dec.seq_lens.copy_(torch.from_numpy(sl))
             nxt = otok if teacher_forced else out["gpu_next"][-1]
             dec.tokens.copy_(torch.from_numpy(np.ascontiguousarray(nxt)))
+    out["fused_status"] = dec.fused_status()
     if want_pool:
         out["gpu_pool"] = dkv.bits().reshape(pool_bits.shape)
         out["orc_pool"] = opool
@@ -73,6 +74,8 @@ def run_both(orc, shape, weights, layout, pool_bits, tokens, steps, teacher_forc
 def check_parity(out, tol=1e-2, min_agree=0.99):
     """The bar: relative L2 of the logits <= tol for every row of every step
     (the stated tolerance of the decode path), greedy agreement >= min_agree."""
+    # the persistent step kernel (when it ran) must never have given up a wait
+    assert out.get("fused_status") in (None, (0, 0)), f"persistent step kernel timed out: {out['fused_status']}"
     worst, agree, total = 0.0, 0, 0
     for gl, ol, gn, on in zip(out["gpu_logits"], out["orc_logits"], out["gpu_next"], out["orc_next"]):
         assert np.all(np.isfinite(gl))

@@ -109,6 +109,32 @@ def test_shapes_and_edges(dk, orc, name, shape, contexts, steps):
     check_pool(out, pool, shape, lay, steps)
 
 
+@pytest.mark.parametrize("wname,steps", [("cfg0", 8), ("cfg1", 4)])
+def test_persistent_and_kernel_per_stage_paths_agree(dk, orc, wname, steps):
+    """Batches of 1-2 rows of the small dense shapes run as one persistent
+    kernel; the same step as a chain of kernels (DK_STEP_NO_FUSED) must pass the
+    same parity bars and give the same tokens."""
+    wl = W.WORKLOADS[wname]
+    shape, lay = wl.cfg, layout_for(wl)
+    weights = W.make_weights(shape, wl.seed_weights)
+    pool = W.fill_kv_pool(shape, lay, wl.seed_kv)
+    tokens = W.initial_tokens(shape, wl.batch, wl.seed_tokens)
+    fused = run_both(orc, shape, weights, lay, pool, tokens, steps)
+    chain = run_both(orc, shape, weights, lay, pool, tokens, steps, gpu_flags=dk.STEP_NO_FUSED)
+    assert fused["fused_status"] == (0, 0), "the persistent kernel did not run (or gave up a wait)"
+    assert chain["fused_status"] is None
+    for out in (fused, chain):
+        worst, agree = check_parity(out)
+        assert worst < TIGHT and agree == 1.0
+        check_pool(out, pool, shape, lay, steps)
+    for a, b in zip(fused["gpu_logits"], chain["gpu_logits"]):
+        assert rel_l2(a, b).max() < 5e-5          # each is ~1e-5 from the oracle
+    # the persistent kernel repeats bit for bit
+    again = run_both(orc, shape, weights, lay, pool, tokens, steps)
+    for a, b in zip(fused["gpu_logits"], again["gpu_logits"]):
+        assert np.array_equal(a, b)
+
+
 def test_shared_prefix_blocks(dk, orc):
     shape = variant("tiny", qk_norm=True)
     ctx = [100, 70, 65, 90, 20]
