@@ -135,6 +135,32 @@ def test_persistent_and_kernel_per_stage_paths_agree(dk, orc, wname, steps):
         assert np.array_equal(a, b)
 
 
+FUSED_CASES = [
+    # contexts around the 64-token attention chunks of the persistent kernel, for both of its
+    # shape classes (head_dim 64 and 128, query groups of 2), one and two rows
+    ("d64_chunk_edges", variant("tiny", qk_norm=True), [63, 64], 3),
+    ("d64_one_row_long", variant("tiny"), [700], 2),
+    ("d64_empty_and_long", variant("tiny", qk_norm=True), [0, 830], 2),
+    ("d128_chunk_edges", variant("tiny", head_dim=128, n_q_heads=4, n_kv_heads=2, qk_norm=True), [127, 65], 3),
+    ("d128_one_row", variant("tiny", head_dim=128, n_q_heads=4, n_kv_heads=2), [129], 2),
+    ("d128_wide", variant("tiny", head_dim=128, n_q_heads=16, n_kv_heads=8, hidden=1024, ffn=3072, vocab=2000,
+                          qk_norm=True), [1, 513], 2),
+]
+
+
+@pytest.mark.parametrize("name,shape,contexts,steps", FUSED_CASES, ids=[c[0] for c in FUSED_CASES])
+def test_persistent_kernel_edges(dk, orc, name, shape, contexts, steps):
+    lay = build_block_tables(contexts, 16, steps, seed=23)
+    weights = W.make_weights(shape, 6)
+    pool = W.fill_kv_pool(shape, lay, 7)
+    tokens = W.initial_tokens(shape, len(contexts), 8)
+    out = run_both(orc, shape, weights, lay, pool, tokens, steps)
+    assert out["fused_status"] == (0, 0), "the persistent kernel did not run (or gave up a wait)"
+    worst, agree = check_parity(out)
+    assert worst < TIGHT and agree == 1.0, (name, worst, agree)
+    check_pool(out, pool, shape, lay, steps)
+
+
 def test_shared_prefix_blocks(dk, orc):
     shape = variant("tiny", qk_norm=True)
     ctx = [100, 70, 65, 90, 20]
