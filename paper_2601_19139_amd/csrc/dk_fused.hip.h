@@ -311,8 +311,10 @@ __global__ __launch_bounds__(kFusedThreads) void fused_step_kernel(FusedArgs a)
     constexpr int BS = 16, TPR = D / 8, TPW = 64 / TPR, NI = BS / TPW;
     constexpr int RW_H = (KSH <= 2) ? 4 : 2;      // rows per wave in flight, K = H
     constexpr int RW_GU = (KSH <= 2) ? 3 : 1;     // gate and up: two matrices
-    constexpr int RW_Q = (KSQ <= 2) ? 4 : 2;      // K = nq*d
-    constexpr int RW_F = (KSF <= 2) ? 4 : 2;      // K = F
+    // the output projection and the down projection have `hidden` rows: at most one per wave
+    // (hidden <= 512 * KSH <= 1024 = blocks * waves for every shape class)
+    constexpr int RW_Q = 1, RW_F = 1;
+    static_assert(KSH <= 2, "a wave owns at most one row of a hidden-sized output");
     constexpr int MAXK = 512 * (KSF > KSQ ? (KSF > KSH ? KSF : KSH) : (KSQ > KSH ? KSQ : KSH));
     __shared__ float xs[NB * MAXK];
     __shared__ float red[kFusedWaves * NB];
@@ -728,8 +730,12 @@ __global__ __launch_bounds__(kFusedThreads) void fused_step_kernel(FusedArgs a)
     {
         int v0, v1;
         wave_rows(V, wv, v0, v1);
-        RowRegs<RW_H, KSH> pl;
-        load_rows<RW_H, KSH>(pl, a.lm_head, H, v0, v1, lane);
+        // a ring of PF batches of RW_H rows stays requested: one batch ahead leaves the wave
+        // waiting a full HBM round trip per batch (a third of the bandwidth)
+        constexpr int PF = 4;
+        RowRegs<RW_H, KSH> ring[PF];
+#pragma unroll
+        for (int p = 0; p < PF; p++) load_rows<RW_H, KSH>(ring[p], a.lm_head, H, v0 + p * RW_H, v1, lane);
         __syncthreads();
         const float *x_last = a.set + lay.per_layer * (a.L - 1) + lay.xout;
         stage_input<NB, true>(x_last, H, a.g_final, a.eps, xs, rinv, red, w);
@@ -737,23 +743,25 @@ __global__ __launch_bounds__(kFusedThreads) void fused_step_kernel(FusedArgs a)
         int best_i[NB];
 #pragma unroll
         for (int b = 0; b < NB; b++) { best[b] = -INFINITY; best_i[b] = 0x7fffffff; }
-        for (int rb = v0; rb < v1; rb += RW_H) {
-            RowRegs<RW_H, KSH> nxt;
-            const bool more = rb + RW_H < v1;
-            if (more) load_rows<RW_H, KSH>(nxt, a.lm_head, H, rb + RW_H, v1, lane);   // next rows in flight
-            float acc[RW_H][NB];
-            dot_rows<NB, RW_H, KSH>(pl, xs, H, lane, acc);
+        for (int rb0 = v0; rb0 < v1; rb0 += RW_H * PF) {
 #pragma unroll
-            for (int i = 0; i < RW_H; i++)
+            for (int p = 0; p < PF; p++) {
+                const int rb = rb0 + p * RW_H;
+                float acc[RW_H][NB];
+                dot_rows<NB, RW_H, KSH>(ring[p], xs, H, lane, acc);
+                // refill the slot (rows past the end re-read the last row and are not used)
+                load_rows<RW_H, KSH>(ring[p], a.lm_head, H, rb + RW_H * PF, v1, lane);
 #pragma unroll
-                for (int b = 0; b < NB; b++) {
-                    const float v = acc[i][b] * rinv[b];
-                    if (rb + i < v1) {
-                        if (v > best[b]) { best[b] = v; best_i[b] = rb + i; }   // rows ascend: ties keep the lower
-                        if (a.logits != nullptr && lane == i * NB + b) a.logits[(long long)b * V + rb + i] = v;
+                for (int i = 0; i < RW_H; i++)
+#pragma unroll
+                    for (int b = 0; b < NB; b++) {
+                        const float v = acc[i][b] * rinv[b];
+                        if (rb + i < v1) {
+                            if (v > best[b]) { best[b] = v; best_i[b] = rb + i; }   // rows ascend: ties keep the lower
+                            if (a.logits != nullptr && lane == i * NB + b) a.logits[(long long)b * V + rb + i] = v;
+                        }
                     }
-                }
-            if (more) pl = nxt;
+            }
         }
         // block maximum per row of the batch: waves own ascending row ranges
         __syncthreads();
