@@ -147,6 +147,36 @@ __device__ __forceinline__ float ld_coherent(const float *p)
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
+// Online merge, in chunk order, of element `dim` of one head's chunk partials
+// ([chunk][G][d+2] with the running max and sum behind the d outputs).  The
+// device-coherent loads of eight chunks are issued together: one round trip
+// per eight chunks instead of one per chunk.
+__device__ __forceinline__ float merge_chunk_partials(const float *pg, int64_t chunk_stride, int nact, int D,
+                                                      int dim)
+{
+    float mn = -1e30f, ls = 0.f, os = 0.f;
+    for (int c0 = 0; c0 < nact; c0 += 8) {
+        float mc[8], lc[8], oc[8];
+#pragma unroll
+        for (int u = 0; u < 8; u++) {
+            const float *pp = pg + (int64_t)min(c0 + u, nact - 1) * chunk_stride;
+            mc[u] = ld_coherent(pp + D);
+            lc[u] = ld_coherent(pp + D + 1);
+            oc[u] = ld_coherent(pp + dim);
+        }
+#pragma unroll
+        for (int u = 0; u < 8; u++)
+            if (c0 + u < nact) {
+                const float m2 = fmaxf(mn, mc[u]);
+                const float sa = __expf(mn - m2), sb = __expf(mc[u] - m2);
+                ls = ls * sa + lc[u] * sb;
+                os = os * sa + oc[u] * sb;
+                mn = m2;
+            }
+    }
+    return os / ls;
+}
+
 // element k of batch row b of the attention output (k = head*d + dim)
 __device__ __forceinline__ void store_attn_out(const AttnArgs &a, int b, int k, int width, float v)
 {
@@ -448,18 +478,8 @@ __global__ __launch_bounds__(256) void attention_kernel(AttnArgs a)
     for (int idx = tid; idx < G * D; idx += 256) {
         const int g = idx / D, dim = idx % D;
         const float *pg = part + g * (D + 2);
-        // online merge in chunk order; the loads of different chunks are independent
-        float mn = -1e30f, ls = 0.f, os = 0.f;
-        for (int cc = 0; cc < nact; cc++) {
-            const float *pp = pg + (int64_t)cc * (G * (D + 2));
-            const float mc = ld_coherent(pp + D), lc = ld_coherent(pp + D + 1), oc = ld_coherent(pp + dim);
-            const float m2 = fmaxf(mn, mc);
-            const float sa = __expf(mn - m2), sb = __expf(mc - m2);
-            ls = ls * sa + lc * sb;
-            os = os * sa + oc * sb;
-            mn = m2;
-        }
-        store_attn_out(a, b, (j * G + g) * D + dim, a.nq * D, os / ls);
+        const float v = merge_chunk_partials(pg, (int64_t)G * (D + 2), nact, D, dim);
+        store_attn_out(a, b, (j * G + g) * D + dim, a.nq * D, v);
     }
     if (tid == 0)
         __hip_atomic_store(&a.tickets[b * a.nkv + j], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);

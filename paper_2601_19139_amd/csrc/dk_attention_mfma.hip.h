@@ -19,7 +19,8 @@
 //           already the 8 k-values the A operand wants, in the token order
 //           (tile0: 4lg..4lg+3, tile1: 4lg..4lg+3) - and B = V with tokens along
 //           k, i.e. V transposed: the wave stages its two V tiles in LDS (rows
-//           of masked-out tokens zeroed) and gathers the B operand from there.
+//           of masked-out tokens zeroed) and fetches the B operand from there
+//           with the LDS transpose read (ds_read_b64_tr_b16).
 #pragma once
 #include "dk_attention.hip.h"
 #include "dk_gemm.hip.h"
@@ -36,11 +37,11 @@ __global__ __launch_bounds__(256) void attention_mfma_kernel(AttnArgs a)
     constexpr int NS = D / 32;        // MFMAs (per hi / lo) for the scores of one tile
     constexpr int NT = D / 16;        // 16-dim column tiles of the output
     constexpr int NWV = 4;
-    constexpr int VROW = D + 4;       // LDS row stride of a staged V tile, in bf16 (8 bytes of padding)
+    constexpr int VROW = D + 16;      // LDS row stride of a staged V tile, in bf16: 4 consecutive rows start 8 banks apart
     static_assert(G <= 8, "the query group occupies the first G of 16 MFMA columns");
 
-    __shared__ float sm_q[G][D];                       // prepared q (norm, rotation, scale)
-    __shared__ uint16_t sm_v[NWV][2][BS][VROW];        // per wave: two V tiles
+    __shared__ __attribute__((aligned(16))) float sm_q[G][D];   // prepared q (norm, rotation, scale)
+    __shared__ __attribute__((aligned(16))) uint16_t sm_v[NWV][2][BS][VROW];   // per wave: two V tiles
     __shared__ float sm_o[NWV + 1][G][D];              // per wave + the new token
     __shared__ float sm_ml[NWV + 1][G][2];
     __shared__ int sm_ticket;
@@ -56,51 +57,94 @@ __global__ __launch_bounds__(256) void attention_mfma_kernel(AttnArgs a)
     const float2 *cs_row = a.cs + (int64_t)b * (D / 2);
     const int *table = a.block_tables + (int64_t)b * a.max_blocks;
 
-    // ---- prologue (row-major head layout, as in attention_kernel) ------------
-    float q[G][8];
+    // ---- requests first, arithmetic later -------------------------------------
+    // The q | k | v row, the rotation table and the gains do not depend on the
+    // sequence state: they are requested before anything else so that they are
+    // back while the first K/V tiles (requested right after, once the block table
+    // has been read) are still on their way.  Loads return in order, so the other
+    // way round the prologue would wait for the K/V tiles.
+    float4 q_raw[G][2], k_raw[2], v_raw[2], cs_raw[4];
 #pragma unroll
     for (int g = 0; g < G; g++) {
         const float *qp = row + (int64_t)(j * G + g) * D + dl;
-        const float4 lo = ldf4(qp), hi = ldf4(qp + 4);
-        q[g][0] = lo.x; q[g][1] = lo.y; q[g][2] = lo.z; q[g][3] = lo.w;
-        q[g][4] = hi.x; q[g][5] = hi.y; q[g][6] = hi.z; q[g][7] = hi.w;
+        q_raw[g][0] = ldf4(qp);
+        q_raw[g][1] = ldf4(qp + 4);
     }
     const bool upper = dl >= D / 2;
-    float2 cs[8];
     {
         const float4 *cp = reinterpret_cast<const float4 *>(cs_row + (upper ? dl - D / 2 : dl));
 #pragma unroll
-        for (int e = 0; e < 4; e++) {
-            const float4 t = cp[e];
-            cs[2 * e] = make_float2(t.x, t.y);
-            cs[2 * e + 1] = make_float2(t.z, t.w);
-        }
+        for (int e = 0; e < 4; e++) cs_raw[e] = cp[e];
     }
     const bool norm = a.g_q != nullptr;
-    float gq[8], gk[8];
+    uint4 gq_raw = make_uint4(0, 0, 0, 0), gk_raw = make_uint4(0, 0, 0, 0);
     if (norm) {
-        unpack8(ld16(a.g_q + dl), gq);
-        unpack8(ld16(a.g_k + dl), gk);
-    } else {
-#pragma unroll
-        for (int e = 0; e < 8; e++) gq[e] = gk[e] = 1.f;
+        gq_raw = ld16(a.g_q + dl);
+        gk_raw = ld16(a.g_k + dl);
     }
-    float kn[8], vn[8];
     {
         const float *kp = row + (int64_t)(a.nq + j) * D + dl;
         const float *vp = row + (int64_t)(a.nq + a.nkv + j) * D + dl;
-        const float4 klo = ldf4(kp), khi = ldf4(kp + 4), vlo = ldf4(vp), vhi = ldf4(vp + 4);
-        kn[0] = klo.x; kn[1] = klo.y; kn[2] = klo.z; kn[3] = klo.w;
-        kn[4] = khi.x; kn[5] = khi.y; kn[6] = khi.z; kn[7] = khi.w;
-        vn[0] = vlo.x; vn[1] = vlo.y; vn[2] = vlo.z; vn[3] = vlo.w;
-        vn[4] = vhi.x; vn[5] = vhi.y; vn[6] = vhi.z; vn[7] = vhi.w;
+        k_raw[0] = ldf4(kp); k_raw[1] = ldf4(kp + 4);
+        v_raw[0] = ldf4(vp); v_raw[1] = ldf4(vp + 4);
     }
+    // block-table entries of the wave's first tile pair: they depend on the chunk
+    // index only, so they are read together with the sequence length
+    const int blk_first = c * (a.chunk_tokens / BS) + 2 * wv;
+    const int phys_a = table[min(blk_first, a.max_blocks - 1)];
+    const int phys_b = table[min(blk_first + 1, a.max_blocks - 1)];
     const int T = min(max(a.seq_lens[b], 0), a.max_blocks * BS - 1);
     const int nact = (T + 1 + a.chunk_tokens - 1) / a.chunk_tokens;
     if (c >= nact) return;
     const int t0 = c * a.chunk_tokens;
     const int t1 = min(T, t0 + a.chunk_tokens);   // cached positions [t0, t1) come from the pool
     const bool owns_new = (c == nact - 1);        // position T itself
+    const int blk_end = (t1 + BS - 1) / BS;
+    // The K and V tiles of the next iteration are requested before this one is
+    // computed (the last iteration re-requests its own tiles: a cache hit, and
+    // every request is unconditional so the loads stay counted in order).
+    auto request_phys = [&](int pa, int pb, uint4 (&kw)[2][NS], uint4 (&vw)[2][NI]) {
+#pragma unroll
+        for (int u = 0; u < 2; u++) {
+            const int phys = min(max(u ? pb : pa, 0), a.num_blocks - 1);
+            const uint16_t *kt = a.pool + kv_tile_offset(a.layer, a.num_blocks, phys, 0, a.nkv, j, BS, D);
+            const uint16_t *vt = kt + (int64_t)a.nkv * BS * D;
+#pragma unroll
+            for (int s = 0; s < NS; s++) kw[u][s] = ld16(kt + ln * D + s * 32 + lg * 8);
+#pragma unroll
+            for (int i = 0; i < NI; i++) vw[u][i] = ld16(vt + i * 512 + lane * 8);
+        }
+    };
+    auto request = [&](int blk0, uint4 (&kw)[2][NS], uint4 (&vw)[2][NI]) {
+        request_phys(table[min(blk0, a.max_blocks - 1)], table[min(blk0 + 1, a.max_blocks - 1)], kw, vw);
+    };
+    uint4 kw[2][NS], vw[2][NI], kw_n[2][NS], vw_n[2][NI];
+    request_phys(phys_a, phys_b, kw, vw);
+
+    // ---- prologue (row-major head layout, as in attention_kernel) ------------
+    float q[G][8], kn[8], vn[8], gq[8], gk[8];
+    float2 cs[8];
+#pragma unroll
+    for (int g = 0; g < G; g++) {
+        q[g][0] = q_raw[g][0].x; q[g][1] = q_raw[g][0].y; q[g][2] = q_raw[g][0].z; q[g][3] = q_raw[g][0].w;
+        q[g][4] = q_raw[g][1].x; q[g][5] = q_raw[g][1].y; q[g][6] = q_raw[g][1].z; q[g][7] = q_raw[g][1].w;
+    }
+#pragma unroll
+    for (int e = 0; e < 4; e++) {
+        cs[2 * e] = make_float2(cs_raw[e].x, cs_raw[e].y);
+        cs[2 * e + 1] = make_float2(cs_raw[e].z, cs_raw[e].w);
+    }
+    if (norm) {
+        unpack8(gq_raw, gq);
+        unpack8(gk_raw, gk);
+    } else {
+#pragma unroll
+        for (int e = 0; e < 8; e++) gq[e] = gk[e] = 1.f;
+    }
+    kn[0] = k_raw[0].x; kn[1] = k_raw[0].y; kn[2] = k_raw[0].z; kn[3] = k_raw[0].w;
+    kn[4] = k_raw[1].x; kn[5] = k_raw[1].y; kn[6] = k_raw[1].z; kn[7] = k_raw[1].w;
+    vn[0] = v_raw[0].x; vn[1] = v_raw[0].y; vn[2] = v_raw[0].z; vn[3] = v_raw[0].w;
+    vn[4] = v_raw[1].x; vn[5] = v_raw[1].y; vn[6] = v_raw[1].z; vn[7] = v_raw[1].w;
 
 #pragma unroll
     for (int g = 0; g < G; g++) {
@@ -165,14 +209,15 @@ __global__ __launch_bounds__(256) void attention_mfma_kernel(AttnArgs a)
     uint4 qh[NS], ql[NS];
 #pragma unroll
     for (int s = 0; s < NS; s++) {
+        const float4 *src = reinterpret_cast<const float4 *>(&sm_q[min(ln, G - 1)][s * 32 + lg * 8]);
+        const float4 f0 = src[0], f1 = src[1];
+        const float f[8] = {f0.x, f0.y, f0.z, f0.w, f1.x, f1.y, f1.z, f1.w};
         uint32_t hw[4], lw[4];
 #pragma unroll
         for (int e = 0; e < 4; e++) {
-            const float v0 = ln < G ? sm_q[min(ln, G - 1)][s * 32 + lg * 8 + 2 * e] : 0.f;
-            const float v1 = ln < G ? sm_q[min(ln, G - 1)][s * 32 + lg * 8 + 2 * e + 1] : 0.f;
             uint16_t h0, l0, h1, l1;
-            split_bf16(v0, h0, l0);
-            split_bf16(v1, h1, l1);
+            split_bf16(ln < G ? f[2 * e] : 0.f, h0, l0);
+            split_bf16(ln < G ? f[2 * e + 1] : 0.f, h1, l1);
             hw[e] = (uint32_t)h0 | ((uint32_t)h1 << 16);
             lw[e] = (uint32_t)l0 | ((uint32_t)l1 << 16);
         }
@@ -186,20 +231,9 @@ __global__ __launch_bounds__(256) void attention_mfma_kernel(AttnArgs a)
 #pragma unroll
     for (int nt = 0; nt < NT; nt++) o[nt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
-    const int blk_end = (t1 + BS - 1) / BS;
-    for (int blk0 = t0 / BS + 2 * wv; blk0 < blk_end; blk0 += 2 * NWV) {
-        uint4 kw[2][NS], vw[2][NI];
-#pragma unroll
-        for (int u = 0; u < 2; u++) {
-            const int blk = min(blk0 + u, a.max_blocks - 1);
-            const int phys = min(max(table[blk], 0), a.num_blocks - 1);
-            const uint16_t *kt = a.pool + kv_tile_offset(a.layer, a.num_blocks, phys, 0, a.nkv, j, BS, D);
-            const uint16_t *vt = kt + (int64_t)a.nkv * BS * D;
-#pragma unroll
-            for (int s = 0; s < NS; s++) kw[u][s] = ld16(kt + ln * D + s * 32 + lg * 8);
-#pragma unroll
-            for (int i = 0; i < NI; i++) vw[u][i] = ld16(vt + i * 512 + lane * 8);
-        }
+    for (int blk0 = blk_first; blk0 < blk_end; blk0 += 2 * NWV) {
+        const int blk_next = blk0 + 2 * NWV;
+        request(blk_next < blk_end ? blk_next : blk0, kw_n, vw_n);
         // scores
         f32x4_t sc[2];
 #pragma unroll
@@ -264,28 +298,44 @@ __global__ __launch_bounds__(256) void attention_mfma_kernel(AttnArgs a)
             pl = make_uint4(lw[0], lw[1], lw[2], lw[3]);
         }
         // rescale the running output: row i of this lane is head 4*lg + i, whose
-        // alpha lives in the lanes of column 4*lg + i
-        float al[4];
+        // alpha lives in the lanes of column 4*lg + i.  Once the running maxima
+        // have settled every alpha is exactly 1 and the pass is skipped.
+        if (__any(alpha != 1.f)) {
+            float al[4];
 #pragma unroll
-        for (int i = 0; i < 4; i++) al[i] = __shfl(alpha, 4 * lg + i);
+            for (int i = 0; i < 4; i++) al[i] = __shfl(alpha, 4 * lg + i);
 #pragma unroll
-        for (int nt = 0; nt < NT; nt++)
+            for (int nt = 0; nt < NT; nt++)
 #pragma unroll
-            for (int i = 0; i < 4; i++) o[nt][i] *= al[i];
-        // O += P V : B operand gathered from the staged tiles (V transposed)
+                for (int i = 0; i < 4; i++) o[nt][i] *= al[i];
+        }
+        // O += P V : the B operand is V with tokens along k.  The LDS transpose read
+        // hands lane (column ln, lane group lg) the four tokens 4*lg..4*lg+3 of
+        // column nt*16 + ln when lane i of the group points at the 4 consecutive
+        // dims nt*16 + 4*(i%4) of token 4*lg + i/4 (layout checked on the device:
+        // lane 4g+c, element e <- address of lane 4e+g, element c).
 #pragma unroll
         for (int nt = 0; nt < NT; nt++) {
             uint32_t vwd[4];
 #pragma unroll
-            for (int e = 0; e < 4; e++) {
-                const int u = e / 2, r = 4 * lg + (2 * e) % 4;
-                const uint32_t v0 = sm_v[wv][u][r][nt * 16 + ln];
-                const uint32_t v1 = sm_v[wv][u][r + 1][nt * 16 + ln];
-                vwd[e] = v0 | (v1 << 16);
+            for (int u = 0; u < 2; u++) {
+                typedef short v4s __attribute__((ext_vector_type(4)));
+                const uint16_t *src = &sm_v[wv][u][4 * lg + (ln >> 2)][nt * 16 + 4 * (ln & 3)];
+                const v4s r = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                    (__attribute__((address_space(3))) v4s *)(src));
+                vwd[2 * u] = (uint32_t)(uint16_t)r[0] | ((uint32_t)(uint16_t)r[1] << 16);
+                vwd[2 * u + 1] = (uint32_t)(uint16_t)r[2] | ((uint32_t)(uint16_t)r[3] << 16);
             }
             const uint4 vb = make_uint4(vwd[0], vwd[1], vwd[2], vwd[3]);
             o[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(ph), as_bf16x8(vb), o[nt], 0, 0, 0);
             o[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(pl), as_bf16x8(vb), o[nt], 0, 0, 0);
+        }
+#pragma unroll
+        for (int u = 0; u < 2; u++) {
+#pragma unroll
+            for (int s = 0; s < NS; s++) kw[u][s] = kw_n[u][s];
+#pragma unroll
+            for (int i = 0; i < NI; i++) vw[u][i] = vw_n[u][i];
         }
     }
 
@@ -333,17 +383,8 @@ __global__ __launch_bounds__(256) void attention_mfma_kernel(AttnArgs a)
     for (int idx = tid; idx < G * D; idx += 256) {
         const int g = idx / D, dim = idx % D;
         const float *pg = part + g * (D + 2);
-        float mn = -1e30f, ls = 0.f, os = 0.f;
-        for (int cc = 0; cc < nact; cc++) {
-            const float *pp = pg + (int64_t)cc * (G * (D + 2));
-            const float mc = ld_coherent(pp + D), lc = ld_coherent(pp + D + 1), oc = ld_coherent(pp + dim);
-            const float m2 = fmaxf(mn, mc);
-            const float sa = __expf(mn - m2), sb = __expf(mc - m2);
-            ls = ls * sa + lc * sb;
-            os = os * sa + oc * sb;
-            mn = m2;
-        }
-        store_attn_out(a, b, (j * G + g) * D + dim, a.nq * D, os / ls);
+        const float v = merge_chunk_partials(pg, (int64_t)G * (D + 2), nact, D, dim);
+        store_attn_out(a, b, (j * G + g) * D + dim, a.nq * D, v);
     }
     if (tid == 0)
         __hip_atomic_store(&a.tickets[b * a.nkv + j], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
