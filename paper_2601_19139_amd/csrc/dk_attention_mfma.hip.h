@@ -28,7 +28,7 @@
 namespace dk {
 
 template <int D, int G>
-__global__ __launch_bounds__(256) void attention_mfma_kernel(AttnArgs a)
+__global__ __launch_bounds__(256, 2) void attention_mfma_kernel(AttnArgs a)
 {
     constexpr int BS = 16;            // tokens per block tile
     constexpr int TPR = D / 8;        // lanes per token in the row-major tile loads
@@ -158,6 +158,9 @@ __global__ __launch_bounds__(256) void attention_mfma_kernel(AttnArgs a)
 #pragma unroll
             for (int e = 0; e < 8; e++) sm_q[g][dl + e] = q[g][e];
     }
+    __syncthreads();
+    // (after the barrier, so that the other waves do not wait for it: wave 0's own
+    // first tiles are still on their way at this point)
     if (wv == 0) {
         if (owns_new) {
             // the new token: stored (bf16) at position T and kept as one more
@@ -202,7 +205,6 @@ __global__ __launch_bounds__(256) void attention_mfma_kernel(AttnArgs a)
             }
         }
     }
-    __syncthreads();
 
     // q as the B operand: lane (column g = ln, lane group lg) holds dims
     // s*32 + lg*8 .. +8 of head g, as bf16 hi and lo; columns >= G are zero
