@@ -502,7 +502,7 @@ const char *dk_last_error(void) { return g_err; }
 
 // The kernel revisions change whenever a kernel's memory behaviour changes; the
 // benchmark quotes stored counter measurements only for a matching revision.
-const char *dk_version(void) { return "decodekit 0.3 (gfx950; gemv r3, gemm r6, attention r5, moe r2, fused r1)"; }
+const char *dk_version(void) { return "decodekit 0.4 (gfx950; gemv r3, gemm r6, attention r6, moe r3, fused r2)"; }
 
 // ------------------------------------------------------------------- pool --
 dk_status dk_kv_pool_bytes(const dk_model_config *cfg, int32_t num_blocks, int32_t block_size,
@@ -977,8 +977,16 @@ static dk_status decode_step_impl(dk_model *model, dk_kv_pool *pool, const int32
             up.rinv = rinv;
             up.ohi = fhi;
             up.olo = flo;
-            DK_LAUNCH(DK_K_MOE_EXPERT, (dk::moe_expert_kernel<true, 8>), dim3((c.expert_ffn + 15) / 16, c.n_experts),
-                      dim3(512), 0, st, up);
+            // K a multiple of 128 and at least one k-step per wave: the restructured kernel
+            if (H % 128 == 0 && H / 128 >= 4) {
+                // measured at the 30B-A3B shape: small blocks (4 waves, one 16-row tile, two
+                // k-steps per round) so that many are resident per compute unit
+                DK_LAUNCH(DK_K_MOE_EXPERT, (dk::moe_expert_fast_kernel<true, 4, 1, 2>),
+                          dim3((c.expert_ffn + 15) / 16, c.n_experts), dim3(256), 0, st, up);
+            } else {
+                DK_LAUNCH(DK_K_MOE_EXPERT, (dk::moe_expert_kernel<true, 8>),
+                          dim3((c.expert_ffn + 15) / 16, c.n_experts), dim3(512), 0, st, up);
+            }
             DK_HIP(hipGetLastError());
             dk::ExpertArgs dn{};
             dn.w_a = u16(L.w_down);
@@ -990,8 +998,16 @@ static dk_status decode_step_impl(dk_model *model, dk_kv_pool *pool, const int32
             dn.xhi = fhi;
             dn.xlo = flo;
             dn.y = yexp;
-            DK_LAUNCH(DK_K_MOE_EXPERT, (dk::moe_expert_kernel<false, 4>), dim3((H + 15) / 16, c.n_experts),
-                      dim3(256), 0, st, dn);
+            if (c.expert_ffn % 768 == 0) {          // six k-steps (or a multiple): 3 waves x 2 per round
+                DK_LAUNCH(DK_K_MOE_EXPERT, (dk::moe_expert_fast_kernel<false, 3, 2, 2>), dim3((H + 31) / 32, c.n_experts),
+                          dim3(192), 0, st, dn);
+            } else if (c.expert_ffn % 128 == 0 && c.expert_ffn / 128 >= 4) {
+                DK_LAUNCH(DK_K_MOE_EXPERT, (dk::moe_expert_fast_kernel<false, 4, 2, 1>), dim3((H + 31) / 32, c.n_experts),
+                          dim3(256), 0, st, dn);
+            } else {
+                DK_LAUNCH(DK_K_MOE_EXPERT, (dk::moe_expert_kernel<false, 4>), dim3((H + 15) / 16, c.n_experts),
+                          dim3(256), 0, st, dn);
+            }
             DK_HIP(hipGetLastError());
             dk::MoeCombineArgs cb{};
             cb.x = x;

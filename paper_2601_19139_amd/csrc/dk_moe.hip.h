@@ -255,6 +255,146 @@ __global__ __launch_bounds__(KS * 64) void moe_expert_kernel(ExpertArgs a)
     }
 }
 
+// The same expert GEMMs for K a multiple of 128 (every request unconditional and
+// inside the matrix), restructured like the dense skinny GEMM: a wave requests
+// all the weight and activation pieces of a round (PD k-steps of 128 columns, RT
+// row tiles) before the first MFMA, so a block pays one memory round trip per
+// round instead of one per 32 columns.  A block covers 16*RT rows; the RT tiles
+// share the activation registers.  Wave w < RT reduces and stores tile w.
+template <bool UP, int KS, int RT, int PD>
+__global__ __launch_bounds__(KS * 64) void moe_expert_fast_kernel(ExpertArgs a)
+{
+    constexpr int NM = UP ? 2 : 1;
+    constexpr int MAXCOL = 64 * 16;   // DK_MAX_BATCH rows x up to 16 slots
+    static_assert(RT <= KS, "one wave per row tile in the epilogue");
+    __shared__ float red[KS][RT][NM][4][64];
+    __shared__ int col_row[MAXCOL];
+    __shared__ int ncol_s;
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int ln = lane & 15, lg = lane >> 4;
+    const int e = blockIdx.y;
+    const int r0 = blockIdx.x * 16 * RT;
+    const int K = a.K, N = a.N;
+
+    if (wv == 0) {
+        int n = 0;
+        const int total = a.B * a.top_k;
+        for (int base = 0; base < total; base += 64) {
+            const int i = base + lane;
+            const bool hit = i < total && a.topk_idx[i] == e;
+            const unsigned long long m = __ballot(hit);
+            if (hit) col_row[n + __popcll(m & ((1ull << lane) - 1))] = i;
+            n += __popcll(m);
+        }
+        if (lane == 0) ncol_s = n;
+    }
+    __syncthreads();
+    const int ncol = ncol_s;
+    if (ncol == 0) return;
+
+    const int nks = K >> 7;
+    const int onks = (N + 127) >> 7;
+    const uint16_t *wp0[RT], *wp1[RT];
+#pragma unroll
+    for (int t = 0; t < RT; t++) {
+        const int wrow = min(r0 + 16 * t + ln, N - 1);
+        wp0[t] = a.w_a + ((int64_t)e * N + wrow) * K + lg * 8;
+        wp1[t] = UP ? a.w_b + ((int64_t)e * N + wrow) * K + lg * 8 : nullptr;
+    }
+
+    for (int c0 = 0; c0 < ncol; c0 += 16) {   // 16 batch columns per pass
+        const int pair = col_row[min(c0 + ln, ncol - 1)];
+        const int in_row = UP ? pair / a.top_k : pair;
+        const int64_t xbase = (((int64_t)(in_row >> 4) * nks) * 4 * 64 + lg * 16 + (in_row & 15)) * 8;
+
+        f32x4_t acc[RT][NM];
+#pragma unroll
+        for (int t = 0; t < RT; t++)
+#pragma unroll
+            for (int m = 0; m < NM; m++) acc[t][m] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+        for (int ks0 = wv; ks0 < nks; ks0 += PD * KS) {
+            uint4 w0[PD][RT][4], w1[PD][RT][4], h4[PD][4], l4[PD][4];
+#pragma unroll
+            for (int p = 0; p < PD; p++) {
+                const int ks = min(ks0 + p * KS, nks - 1);   // past the end: a valid re-read, zeroed below
+#pragma unroll
+                for (int s = 0; s < 4; s++) {
+                    const int64_t xo = xbase + ((int64_t)ks * 4 + s) * 512;
+                    h4[p][s] = ld16(a.xhi + xo);
+                    l4[p][s] = ld16(a.xlo + xo);
+#pragma unroll
+                    for (int t = 0; t < RT; t++) {
+                        w0[p][t][s] = ld16(wp0[t] + ks * 128 + s * 32);
+                        if (UP) w1[p][t][s] = ld16(wp1[t] + ks * 128 + s * 32);
+                    }
+                }
+            }
+#pragma unroll
+            for (int p = 0; p < PD; p++) {
+                const bool ok = ks0 + p * KS < nks;
+#pragma unroll
+                for (int s = 0; s < 4; s++) {
+                    const uint4 z = make_uint4(0, 0, 0, 0);
+                    const uint4 hh = ok ? h4[p][s] : z, ll = ok ? l4[p][s] : z;
+#pragma unroll
+                    for (int t = 0; t < RT; t++) {
+                        acc[t][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(w0[p][t][s]), as_bf16x8(hh),
+                                                                            acc[t][0], 0, 0, 0);
+                        acc[t][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(w0[p][t][s]), as_bf16x8(ll),
+                                                                            acc[t][0], 0, 0, 0);
+                        if (UP) {
+                            acc[t][NM - 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                                as_bf16x8(w1[p][t][s]), as_bf16x8(hh), acc[t][NM - 1], 0, 0, 0);
+                            acc[t][NM - 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                                as_bf16x8(w1[p][t][s]), as_bf16x8(ll), acc[t][NM - 1], 0, 0, 0);
+                        }
+                    }
+                }
+            }
+        }
+#pragma unroll
+        for (int t = 0; t < RT; t++)
+#pragma unroll
+            for (int m = 0; m < NM; m++)
+#pragma unroll
+                for (int i = 0; i < 4; i++) red[wv][t][m][i][lane] = acc[t][m][i];
+        __syncthreads();
+        if (wv < RT && c0 + ln < ncol) {
+            // lane holds D[r0 + 16*wv + 4*lg + i][column ln]
+            float v[NM][4];
+#pragma unroll
+            for (int m = 0; m < NM; m++)
+#pragma unroll
+                for (int i = 0; i < 4; i++) {
+                    float sum = 0.f;
+#pragma unroll
+                    for (int w = 0; w < KS; w++) sum += red[w][wv][m][i][lane];
+                    v[m][i] = sum;
+                }
+            const float inv = UP ? a.rinv[in_row] : 1.f;
+#pragma unroll
+            for (int i = 0; i < 4; i++) {
+                const int r = r0 + 16 * wv + 4 * lg + i;
+                if (r >= N) continue;
+                if (UP) {
+                    const float z = v[0][i] * inv;
+                    const float out = z / (1.0f + __expf(-z)) * (v[NM - 1][i] * inv);
+                    uint16_t hi, lo;
+                    split_bf16(out, hi, lo);
+                    const int64_t oo = act_offset(pair, r, onks);
+                    a.ohi[oo] = hi;
+                    a.olo[oo] = lo;
+                } else {
+                    a.y[(int64_t)pair * N + r] = v[0][i];
+                }
+            }
+        }
+        __syncthreads();   // `red` is reused by the next pass
+    }
+}
+
 // ---------------------------------------------------------------------------
 // x[b] += sum_k w[b][k] * y[b*top_k + k]   (k in the router's order), then the
 // input of the next matrix-core GEMM: (x * next gain) as hi/lo and the sum of

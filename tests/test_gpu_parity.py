@@ -280,6 +280,12 @@ MOE_CASES = [
     # 40 rows over 4 experts: some expert serves more than 16 rows (several column passes)
     ("moe_crowded", variant("tiny_moe", n_experts=4, top_k=2, head_dim=128, n_q_heads=4, n_kv_heads=1),
      [1 + 2 * i for i in range(40)], 1),
+    # hidden and expert width multiples of 128: the restructured expert kernels (8 waves x 1 row
+    # tile for gate/up; 6 or 4 waves x 4 row tiles for down), with a crowded expert as well
+    ("moe_wide_768", variant("tiny_moe", hidden=1024, expert_ffn=768, n_experts=8, top_k=2),
+     [2 + 3 * i for i in range(20)], 2),
+    ("moe_wide_512", variant("tiny_moe", hidden=1024, expert_ffn=512, n_experts=4, top_k=2),
+     [1 + i for i in range(40)], 1),
 ]
 
 
