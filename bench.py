@@ -52,6 +52,52 @@ def cpu_baseline(shape, weights, layout, pool_bits, tokens, budget_s=12.0, max_s
                       f"(fp64 C loops, OpenMP over rows of a matrix)"}
 
 
+def bench_prefill(args, wl, dk, W, np, torch):
+    """Chunked prefill of one P-token prompt (next row after the decode step; not the headline metric)."""
+    from workloads.blocktable import build_block_tables
+    shape, P, chunk = wl.cfg, args.prefill, 64
+    lay = build_block_tables([0], 16, P + 1, seed=wl.seed_blocks)
+    weights = W.make_weights(shape, wl.seed_weights)
+    dm = dk.DeviceModel(shape, weights)
+    dkv = dk.DeviceKV(dm, lay, W.fill_kv_pool(shape, lay, wl.seed_kv, poison=False))
+    pre = dk.Prefiller(dm, dkv, max_chunk=chunk, want_logits=False)
+    toks = torch.from_numpy(W.initial_tokens(shape, P, wl.seed_tokens)).cuda()
+    table = dkv.block_tables[0]
+
+    def one_prompt():
+        for o in range(0, P, chunk):
+            part = toks[o:o + chunk]
+            last = o + chunk >= P                     # only the last chunk's prediction is needed
+            dk.prefill_chunk(dm.handle, dkv.handle, table, o, part, pre._ws_ptr, pre.ws_bytes, None,
+                             pre.next if last else None)
+
+    for _ in range(max(1, args.warmup // 4)):
+        one_prompt()
+    torch.cuda.synchronize()
+    reps = max(1, args.steps // 8)
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        one_prompt()
+    torch.cuda.synchronize()
+    wall = (time.perf_counter() - t0) / reps
+    n_chunks = (P + chunk - 1) // chunk
+    # per chunk: every dense weight once; the sequence's cached K/V once; the chunk's own K/V written
+    kv_tok = shape.n_layers * 2 * shape.n_kv_heads * shape.head_dim * 2
+    head = shape.vocab * shape.hidden * 2
+    alg = sum(shape.dense_weight_bytes() - (0 if o + chunk >= P else head) + min(o + chunk, P) * kv_tok
+              for o in range(0, P, chunk))
+    print(json.dumps({
+        "metric": "prefill_tok_per_s", "value": round(P / wall, 1), "unit": "tok/s", "n_gpus": 1,
+        "steps": reps, "ms_per_step": round(wall * 1e3, 4), "higher_is_better": True, "dtype": "bf16",
+        "data": "synthetic (seeded random-init weights)",
+        "config": {"workload": f"{shape.name}: one {P}-token prompt into an empty cache, {chunk} tokens per chunk",
+                   "chunks": n_chunks},
+        "roofline": {"bound": "hbm", "achieved": round(alg / wall / 1e9, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(alg / wall / 1e9 / HBM_PEAK_GBS, 4), "traffic": None,
+                     "note": "weights are streamed once per 64-token chunk (the decode kernels with the rows "
+                             "of one sequence); a compute-bound large-tile prefill is not built"}}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -59,6 +105,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=16)
     ap.add_argument("--workload", default="cfg1")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--prefill", type=int, default=0, metavar="P",
+                    help="measure chunked prefill instead: a P-token prompt of the workload's model shape "
+                         "into an empty cache, 64 tokens per chunk (one step = one whole prompt)")
     ap.add_argument("--kernel-per-stage", action="store_true",
                     help="never take the single persistent kernel (small batches of small dense models)")
     args = ap.parse_args()
@@ -77,6 +126,8 @@ def main():
     torch.cuda.set_device(0)
 
     wl = W.WORKLOADS[args.workload]
+    if args.prefill:
+        return bench_prefill(args, wl, dk, W, np, torch)
     shape, lay = wl.cfg, layout_for(wl)
     weights = W.make_weights(shape, wl.seed_weights)
     pool_bits = W.fill_kv_pool(shape, lay, wl.seed_kv, poison=False)

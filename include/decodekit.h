@@ -230,6 +230,38 @@ dk_status dk_decode_step(dk_model *model, dk_kv_pool *pool, const int32_t *d_blo
                          int32_t B, void *d_workspace, size_t workspace_bytes, float *d_logits,
                          int32_t *d_next_tokens, uint32_t flags, void *hip_stream);
 
+/*
+ * Chunked prefill of one sequence: what n decode steps of that sequence fed
+ * with the prompt tokens d_tokens[0..n) would do, in one pass.  This is the step
+ * that turns the part of a prompt behind the cached prefix into KV state
+ * (Algorithm 2 returns the cached KV state and the start position; Algorithm 1
+ * then generates from the full state).
+ *
+ * With `start` tokens of the sequence already in the pool, row i of the chunk
+ * is position start + i: its k and v are stored at that position (same
+ * arithmetic and rounding as dk_decode_step), it attends to positions
+ * 0..start+i, and d_next_tokens[i] / d_logits[i] are the greedy token / logits
+ * after prompt token start + i (the last row's are the first generated token).
+ *
+ *   d_block_table   device int32 [max_blocks]: the sequence's table; entries up
+ *                   to index (start+n-1)/block_size must be valid blocks, those
+ *                   holding positions >= start private to the sequence
+ *   start           >= 0; start + n <= max_blocks*block_size
+ *   d_tokens        device int32 [n], 1 <= n <= DK_MAX_BATCH
+ *   d_workspace     >= dk_workspace_bytes(model, n, max_blocks), 256-byte aligned;
+ *                   may be the workspace of the decode steps (the next persistent
+ *                   decode step re-initialises its part by itself)
+ *   d_logits        device float32 [n][vocab] or NULL
+ *   d_next_tokens   device int32 [n]; NULL together with d_logits skips the final
+ *                   norm, lm_head and argmax (a chunk that is not the last of its prompt)
+ * Longer prompts are fed chunk after chunk.  The weights are streamed once per
+ * chunk, so the cost of a chunk is that of one decode step of n rows.
+ */
+dk_status dk_prefill_chunk(dk_model *model, dk_kv_pool *pool, const int32_t *d_block_table,
+                           int32_t max_blocks, int32_t start, const int32_t *d_tokens, int32_t n,
+                           void *d_workspace, size_t workspace_bytes, float *d_logits,
+                           int32_t *d_next_tokens, void *hip_stream);
+
 /* Totals of all profiled steps of `model` so far: out_ms[DK_K_COUNT] kernel
  * execution time in milliseconds per class, out_launches[DK_K_COUNT] launches
  * per class.  reset != 0 clears the totals.  Host only. */

@@ -71,6 +71,8 @@ _SIGNATURES = {
     "dk_decode_step": (C.c_int32, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p,
                                    C.c_int32, C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p,
                                    C.c_uint32, C.c_void_p]),
+    "dk_prefill_chunk": (C.c_int32, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p,
+                                     C.c_int32, C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p, C.c_void_p]),
     "dk_workspace_reset": (C.c_int32, [C.c_void_p]),
     "dk_fused_status": (C.c_int32, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
     "dk_profile_read": (C.c_int32, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32]),
@@ -221,6 +223,14 @@ def decode_step(model, pool, d_block_tables, d_seq_lens, d_tokens, d_workspace, 
     _check(lib().dk_decode_step(model, pool, _ptr(d_block_tables), mb, _ptr(d_seq_lens),
                                 _ptr(d_tokens), B, _ptr(d_workspace), nbytes, _ptr(d_logits),
                                 _ptr(d_next_tokens), flags, _stream(stream)))
+
+
+def prefill_chunk(model, pool, d_block_table, start: int, d_tokens, d_workspace, workspace_bytes_: int,
+                  d_logits, d_next_tokens, stream=None):
+    """One prefill chunk of one sequence: d_block_table int32 [max_blocks], d_tokens int32 [n]."""
+    _check(lib().dk_prefill_chunk(model, pool, _ptr(d_block_table), int(d_block_table.numel()), int(start),
+                                  _ptr(d_tokens), int(d_tokens.numel()), _ptr(d_workspace), workspace_bytes_,
+                                  _ptr(d_logits), _ptr(d_next_tokens), _stream(stream)))
 
 
 def workspace_reset(model):

@@ -140,7 +140,7 @@ struct dk_model {
 namespace {
 
 struct Workspace {
-    size_t x, qkv, attn, act, cs, part, tickets, pmax_val, pmax_idx, total;
+    size_t x, qkv, attn, act, cs, part, tickets, pmax_val, pmax_idx, pf_seq, total;
     // batched (matrix-core) path: activations as bf16 hi/lo, sum-of-squares partials
     size_t xhi, xlo, ahi, alo, fhi, flo, ssq;
     // mixture of experts: routing of every layer, per-row 1/rms, expert outputs
@@ -235,6 +235,7 @@ Workspace carve(const dk_model_config &c, int B, int max_blocks)
     w.cs = take((size_t)B * (d / 2) * 8);
     w.part = take((size_t)B * c.n_kv_heads * w.max_chunks * G * (d + 2) * 4);
     w.tickets = take((size_t)B * c.n_kv_heads * 4);
+    w.pf_seq = take((size_t)DK_MAX_BATCH * 4);   // positions of a prefill chunk's rows
     w.batched = B > kMaxGemvBatch || c.n_experts > 0;   // expert layers use the matrix-core kernels
     w.Bp = (B + 15) / 16 * 16;
     if (w.batched) {
@@ -502,7 +503,7 @@ const char *dk_last_error(void) { return g_err; }
 
 // The kernel revisions change whenever a kernel's memory behaviour changes; the
 // benchmark quotes stored counter measurements only for a matching revision.
-const char *dk_version(void) { return "decodekit 0.4 (gfx950; gemv r3, gemm r6, attention r6, moe r3, fused r2)"; }
+const char *dk_version(void) { return "decodekit 0.5 (gfx950; gemv r3, gemm r6, attention r6, moe r3, fused r2, prefill r1)"; }
 
 // ------------------------------------------------------------------- pool --
 dk_status dk_kv_pool_bytes(const dk_model_config *cfg, int32_t num_blocks, int32_t block_size,
@@ -721,6 +722,9 @@ dk_status dk_workspace_bytes(const dk_model *model, int32_t max_B, int32_t max_b
     return DK_OK;
 }
 
+// internal to this file: the rows are consecutive positions of one sequence (chunked prefill)
+constexpr uint32_t kStepPrefill = 0x80000000u;
+
 static dk_status decode_step_impl(dk_model *model, dk_kv_pool *pool, const int32_t *d_block_tables,
                                   int32_t max_blocks, int32_t *d_seq_lens, int32_t *d_tokens, int32_t B,
                                   void *d_workspace, size_t workspace_bytes, float *d_logits,
@@ -759,6 +763,32 @@ dk_status dk_decode_step(dk_model *model, dk_kv_pool *pool, const int32_t *d_blo
     return DK_OK;
 }
 
+dk_status dk_prefill_chunk(dk_model *model, dk_kv_pool *pool, const int32_t *d_block_table,
+                           int32_t max_blocks, int32_t start, const int32_t *d_tokens, int32_t n,
+                           void *d_workspace, size_t workspace_bytes, float *d_logits,
+                           int32_t *d_next_tokens, void *hip_stream)
+{
+    if (!model || !pool || !d_block_table || !d_tokens || !d_workspace || (!d_next_tokens && d_logits))
+        return fail(DK_E_INVALID_ARG, "NULL argument");
+    if (n <= 0 || n > DK_MAX_BATCH) return fail(DK_E_INVALID_ARG, "chunk of %d tokens (1..%d)", n, DK_MAX_BATCH);
+    if (max_blocks <= 0) return fail(DK_E_INVALID_ARG, "max_blocks %d", max_blocks);
+    if (start < 0 || (int64_t)start + n > (int64_t)max_blocks * pool->block_size)
+        return fail(DK_E_INVALID_ARG, "positions %d..%d do not fit a table of %d blocks", start, start + n - 1,
+                    max_blocks);
+    if ((uintptr_t)d_workspace % 256) return fail(DK_E_INVALID_ARG, "workspace must be 256-byte aligned");
+    const Workspace w = carve(model->cfg, n, max_blocks);
+    if (workspace_bytes < w.total)
+        return fail(DK_E_WORKSPACE_TOO_SMALL, "workspace %zu bytes, %zu needed", workspace_bytes, w.total);
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    int *seq = reinterpret_cast<int *>(static_cast<char *>(d_workspace) + w.pf_seq);
+    hipLaunchKernelGGL(dk::iota_kernel, dim3(1), dim3(64), 0, st, seq, start, n);
+    DK_HIP(hipGetLastError());
+    // the step neither advances nor writes the tokens, so the cast is safe
+    return decode_step_impl(model, pool, d_block_table, max_blocks, seq, const_cast<int32_t *>(d_tokens), n,
+                            d_workspace, workspace_bytes, d_logits, d_next_tokens,
+                            DK_STEP_NO_FUSED | kStepPrefill, hip_stream);
+}
+
 dk_status dk_profile_read(dk_model *model, double *out_ms, int64_t *out_launches, int32_t reset)
 {
     if (!model || !out_ms || !out_launches) return fail(DK_E_INVALID_ARG, "NULL argument");
@@ -776,11 +806,13 @@ static dk_status decode_step_impl(dk_model *model, dk_kv_pool *pool, const int32
                                   int32_t *d_next_tokens, uint32_t flags, void *hip_stream)
 {
     if (!model || !pool || !d_block_tables || !d_seq_lens || !d_tokens || !d_workspace ||
-        !d_next_tokens)
+        (!d_next_tokens && !(flags & kStepPrefill)))
         return fail(DK_E_INVALID_ARG, "NULL argument");
     if (B <= 0 || B > DK_MAX_BATCH) return fail(DK_E_INVALID_ARG, "B %d (1..%d)", B, DK_MAX_BATCH);
     if (max_blocks <= 0) return fail(DK_E_INVALID_ARG, "max_blocks_per_seq %d", max_blocks);
-    if (flags & ~(DK_STEP_ADVANCE | DK_STEP_NO_FUSED)) return fail(DK_E_INVALID_ARG, "unknown flags 0x%x", flags);
+    if (flags & ~(DK_STEP_ADVANCE | DK_STEP_NO_FUSED | kStepPrefill))
+        return fail(DK_E_INVALID_ARG, "unknown flags 0x%x", flags);
+    const bool prefill = (flags & kStepPrefill) != 0;
     const dk_model_config &c = model->cfg;
     const dk_model_config &pc = pool->cfg;
     if (pc.n_layers != c.n_layers || pc.n_kv_heads != c.n_kv_heads || pc.head_dim != c.head_dim)
@@ -797,6 +829,9 @@ static dk_status decode_step_impl(dk_model *model, dk_kv_pool *pool, const int32
                                           B, d_logits, d_next_tokens, (flags & DK_STEP_ADVANCE) != 0, st);
         if (fs != DK_E_UNSUPPORTED_SHAPE) return fs;   // otherwise: the ordinary path below
     }
+    // a step of another shape lays the workspace out differently and overwrites the
+    // persistent kernel's hand-over buffers: its next use starts from scratch
+    if (model->fused_ws == ws && model->fused_ws_bytes != w.total) model->fused_ws = nullptr;
     float *x = reinterpret_cast<float *>(ws + w.x);
     float *qkv = reinterpret_cast<float *>(ws + w.qkv);
     float *attn = reinterpret_cast<float *>(ws + w.attn);
@@ -894,6 +929,29 @@ static dk_status decode_step_impl(dk_model *model, dk_kv_pool *pool, const int32
             a.chunk_tokens = w.chunk_tokens;
             a.max_chunks = w.max_chunks;
             a.defer_merge = w.defer_merge ? 1 : 0;
+            a.table_stride = prefill ? 0 : max_blocks;
+            a.no_append = prefill ? 1 : 0;
+            if (prefill) {
+                dk::PrefillAppendArgs pa{};
+                pa.qkv = qkv;
+                pa.cs = cs;
+                pa.g_k = a.g_k;
+                pa.pool = pool->mem;
+                pa.block_table = d_block_tables;
+                pa.seq_lens = d_seq_lens;
+                pa.max_blocks = max_blocks;
+                pa.num_blocks = pool->num_blocks;
+                pa.layer = l;
+                pa.nq = nq;
+                pa.nkv = nkv;
+                pa.eps = eps;
+                if (d == 128) {
+                    DK_LAUNCH(DK_K_ATTENTION, dk::prefill_append_kernel<128>, dim3(B), dim3(256), 0, st, pa);
+                } else {
+                    DK_LAUNCH(DK_K_ATTENTION, dk::prefill_append_kernel<64>, dim3(B), dim3(256), 0, st, pa);
+                }
+                DK_HIP(hipGetLastError());
+            }
             a.scale = (float)(1.0 / std::sqrt((double)d));
             a.eps = eps;
             const dim3 grid(w.max_chunks, nkv, B);
@@ -1071,6 +1129,9 @@ static dk_status decode_step_impl(dk_model *model, dk_kv_pool *pool, const int32
         }
     }
 
+    // a prefill chunk whose predictions nobody wants (all but the last of a prompt) ends here
+    if (prefill && d_next_tokens == nullptr && d_logits == nullptr) return DK_OK;
+    if (d_next_tokens == nullptr) return fail(DK_E_INVALID_ARG, "NULL argument");
     // logits = W_lm * rmsnorm(x); greedy token
     if (batched) {
         dk::GemmArgs g{};

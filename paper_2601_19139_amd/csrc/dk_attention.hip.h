@@ -97,6 +97,24 @@ __global__ __launch_bounds__(128) void append_kv_kernel(AppendArgs a)
     dst[i] = src[i];
 }
 
+// Chunked prefill: the rows of a step are consecutive positions of ONE sequence
+// (row b sits at position seq_lens[b]; one shared block table).  Row b's
+// attention reads the positions of rows < b from the pool, so every row's new k
+// (head norm, rotation) and v are stored by prefill_append_kernel before
+// attention starts, with exactly the arithmetic the attention kernel applies to
+// its own new token.  grid = (rows), 256 threads: aligned groups of D/8 lanes
+// take the kv heads in turn.
+struct PrefillAppendArgs {
+    const float *qkv;        // [B][(nq+2nkv)*d]
+    const float2 *cs;        // [B][d/2]
+    const uint16_t *g_k;     // [d] or null
+    uint16_t *pool;
+    const int *block_table;  // [max_blocks], shared by all rows
+    const int *seq_lens;     // [B]
+    int max_blocks, num_blocks, layer, nq, nkv;
+    float eps;
+};
+
 // ---------------------------------------------------------------------------
 // Fused q/k head norm + rotary embedding + KV append + ragged grouped-query
 // decode attention, split over the context.
@@ -135,6 +153,8 @@ struct AttnArgs {
     int chunk_tokens;        // multiple of 64
     int max_chunks;
     int defer_merge;         // 1: leave the chunk partials for the consumer to merge
+    int table_stride;        // ints between the rows' block tables (0: all rows share one table)
+    int no_append;           // 1: the new tokens' K/V are already in the pool (chunked prefill)
     float scale, eps;
 };
 
@@ -215,6 +235,69 @@ __device__ __forceinline__ void head_norm_rope(float (&h)[8], bool norm, const f
     }
 }
 
+template <int D>
+__global__ __launch_bounds__(256) void prefill_append_kernel(PrefillAppendArgs a)
+{
+    constexpr int BS = 16, TPR = D / 8;
+    const int b = blockIdx.x, tid = threadIdx.x;
+    const int dl = (tid % TPR) * 8;
+    const bool upper = dl >= D / 2;
+    const float *row = a.qkv + (int64_t)b * (a.nq + 2 * a.nkv) * D;
+    const float2 *cs_row = a.cs + (int64_t)b * (D / 2);
+    float2 cs[8];
+    {
+        const float4 *cp = reinterpret_cast<const float4 *>(cs_row + (upper ? dl - D / 2 : dl));
+#pragma unroll
+        for (int e = 0; e < 4; e++) {
+            const float4 t = cp[e];
+            cs[2 * e] = make_float2(t.x, t.y);
+            cs[2 * e + 1] = make_float2(t.z, t.w);
+        }
+    }
+    const bool norm = a.g_k != nullptr;
+    float gk[8];
+    if (norm) {
+        unpack8(ld16(a.g_k + dl), gk);
+    } else {
+#pragma unroll
+        for (int e = 0; e < 8; e++) gk[e] = 1.f;
+    }
+    const int T = min(max(a.seq_lens[b], 0), a.max_blocks * BS - 1);
+    const int phys = min(max(a.block_table[T / BS], 0), a.num_blocks - 1);
+    // whole groups of TPR lanes stay together (the head norm reduces inside a group)
+    const int heads_per_pass = 256 / TPR;
+    for (int j0 = 0; j0 < a.nkv; j0 += heads_per_pass) {
+        const int j = j0 + tid / TPR;
+        const int jc = min(j, a.nkv - 1);
+        const float *kp = row + (int64_t)(a.nq + jc) * D + dl;
+        const float *vp = row + (int64_t)(a.nq + a.nkv + jc) * D + dl;
+        const float4 klo = ldf4(kp), khi = ldf4(kp + 4), vlo = ldf4(vp), vhi = ldf4(vp + 4);
+        float kn[8] = {klo.x, klo.y, klo.z, klo.w, khi.x, khi.y, khi.z, khi.w};
+        const float vn[8] = {vlo.x, vlo.y, vlo.z, vlo.w, vhi.x, vhi.y, vhi.z, vhi.w};
+        head_norm_rope<D>(kn, norm, gk, a.eps, cs, upper);
+        uint32_t kb[4], vb[4];
+#pragma unroll
+        for (int e = 0; e < 4; e++) {
+            kb[e] = (uint32_t)f32_to_bf16_rne(kn[2 * e]) | ((uint32_t)f32_to_bf16_rne(kn[2 * e + 1]) << 16);
+            vb[e] = (uint32_t)f32_to_bf16_rne(vn[2 * e]) | ((uint32_t)f32_to_bf16_rne(vn[2 * e + 1]) << 16);
+        }
+        if (j < a.nkv) {
+            uint16_t *kt = a.pool + kv_tile_offset(a.layer, a.num_blocks, phys, 0, a.nkv, j, BS, D) +
+                           (T % BS) * D + dl;
+            uint16_t *vt = kt + (int64_t)a.nkv * BS * D;
+            *reinterpret_cast<uint4 *>(kt) = make_uint4(kb[0], kb[1], kb[2], kb[3]);
+            *reinterpret_cast<uint4 *>(vt) = make_uint4(vb[0], vb[1], vb[2], vb[3]);
+        }
+    }
+}
+
+// seq[i] = start + i: the positions of a prefill chunk's rows
+__global__ void iota_kernel(int *seq, int start, int n)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) seq[i] = start + i;
+}
+
 template <int D, int G>
 __global__ __launch_bounds__(256) void attention_kernel(AttnArgs a)
 {
@@ -234,7 +317,7 @@ __global__ __launch_bounds__(256) void attention_kernel(AttnArgs a)
     const int q_stride = (a.nq + 2 * a.nkv) * D;
     const float *row = a.qkv + (int64_t)b * q_stride;
     const float2 *cs_row = a.cs + (int64_t)b * (D / 2);
-    const int *table = a.block_tables + (int64_t)b * a.max_blocks;
+    const int *table = a.block_tables + (int64_t)b * a.table_stride;
 
     // Everything that does not depend on the sequence length is requested
     // before the length is looked at, so the loads overlap: the raw q heads and
@@ -332,7 +415,7 @@ __global__ __launch_bounds__(256) void attention_kernel(AttnArgs a)
             kn[2 * e] = __uint_as_float(k0 << 16); kn[2 * e + 1] = __uint_as_float(k1 << 16);
             vn[2 * e] = __uint_as_float(v0 << 16); vn[2 * e + 1] = __uint_as_float(v1 << 16);
         }
-        if (sub == 0) {
+        if (sub == 0 && !a.no_append) {
             const int phys = min(max(table[T / BS], 0), a.num_blocks - 1);
             uint16_t *kt = a.pool + kv_tile_offset(a.layer, a.num_blocks, phys, 0, a.nkv, j, BS, D) +
                            (T % BS) * D + dl;

@@ -55,7 +55,7 @@ __global__ __launch_bounds__(256, 2) void attention_mfma_kernel(AttnArgs a)
     const int q_stride = (a.nq + 2 * a.nkv) * D;
     const float *row = a.qkv + (int64_t)b * q_stride;
     const float2 *cs_row = a.cs + (int64_t)b * (D / 2);
-    const int *table = a.block_tables + (int64_t)b * a.max_blocks;
+    const int *table = a.block_tables + (int64_t)b * a.table_stride;
 
     // ---- requests first, arithmetic later -------------------------------------
     // The q | k | v row, the rotation table and the gains do not depend on the
@@ -176,7 +176,7 @@ __global__ __launch_bounds__(256, 2) void attention_mfma_kernel(AttnArgs a)
                 kn[2 * e] = __uint_as_float(k0 << 16); kn[2 * e + 1] = __uint_as_float(k1 << 16);
                 vn[2 * e] = __uint_as_float(v0 << 16); vn[2 * e + 1] = __uint_as_float(v1 << 16);
             }
-            if (sub == 0) {
+            if (sub == 0 && !a.no_append) {
                 const int phys = min(max(table[T / BS], 0), a.num_blocks - 1);
                 uint16_t *kt = a.pool + kv_tile_offset(a.layer, a.num_blocks, phys, 0, a.nkv, j, BS, D) +
                                (T % BS) * D + dl;

@@ -133,3 +133,44 @@ class Decoder:
         dk.decode_step(self.m.handle, self.kv.handle, self.kv.block_tables, self.seq_lens,
                        self.tokens, self._ws_ptr, self.logits, self.next, flags, stream,
                        workspace_bytes_=self.ws_bytes)
+
+
+class Prefiller:
+    """Buffers for chunked prefill of single sequences (chunks of up to `max_chunk` tokens)."""
+
+    def __init__(self, dmodel: DeviceModel, dkv: DeviceKV, max_chunk: int = 64, want_logits=True):
+        torch = _torch()
+        self.m, self.kv = dmodel, dkv
+        self.max_chunk = max_chunk
+        mb = dkv.layout.tables.shape[1]
+        self.ws_bytes = dk.workspace_bytes(dmodel.handle, max_chunk, mb)
+        self.ws = torch.empty(self.ws_bytes + 256, dtype=torch.uint8, device="cuda")
+        self._ws_ptr = (self.ws.data_ptr() + 255) // 256 * 256
+        self.next = torch.empty(max_chunk, dtype=torch.int32, device="cuda")
+        self.logits = (torch.empty((max_chunk, dmodel.shape.vocab), dtype=torch.float32, device="cuda")
+                       if want_logits else None)
+
+    def prefill(self, row: int, start: int, tokens, chunk: int = None, last_only: bool = False):
+        """Feeds `tokens` (host ints) of sequence `row` of the layout, whose first `start`
+        positions are already cached.  Returns (next tokens [n], logits [n, V] or None) on the
+        host; with last_only, only the last chunk's (the other chunks skip the lm_head)."""
+        torch = _torch()
+        chunk = chunk or self.max_chunk
+        assert 1 <= chunk <= self.max_chunk
+        table = self.kv.block_tables[row]
+        toks = torch.from_numpy(np.ascontiguousarray(tokens, dtype=np.int32)).cuda()
+        nxt, lg = [], []
+        for o in range(0, len(tokens), chunk):
+            part = toks[o:o + chunk]
+            n = int(part.numel())
+            if last_only and o + chunk < len(tokens):
+                dk.prefill_chunk(self.m.handle, self.kv.handle, table, start + o, part, self._ws_ptr,
+                                 self.ws_bytes, None, None)
+                continue
+            dk.prefill_chunk(self.m.handle, self.kv.handle, table, start + o, part, self._ws_ptr, self.ws_bytes,
+                             self.logits, self.next)
+            nxt.append(self.next[:n].cpu().numpy().copy())
+            if self.logits is not None:
+                lg.append(self.logits[:n].cpu().numpy().copy())
+        return np.concatenate(nxt), (np.concatenate(lg) if lg else None)
+

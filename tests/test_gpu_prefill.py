@@ -1,0 +1,206 @@
+"""GPU parity of chunked prefill (dk_prefill_chunk) against the CPU oracle.
+
+The oracle has no prefill: by definition of a causal decoder, feeding a prompt
+is the same as one decode step per prompt token, so the oracle runs exactly
+that, one token at a time, on its own copy of the pool.  Bars as for the decode
+step: KV addressing bit-exact (the slots written are exactly the oracle's),
+appended values equal up to the bf16 rounding of nearly equal float32 numbers,
+logits of every prompt position within relative L2 1e-2 (asserted much
+tighter), greedy tokens equal.
+"""
+import numpy as np
+import pytest
+
+import workloads as W
+from workloads.blocktable import build_block_tables
+from gpu_common import rel_l2
+
+pytestmark = pytest.mark.gpu
+
+TIGHT = 2e-4
+# Every cached value of a prefilled sequence is the kernels' own (bf16-rounded) output.  Where
+# the float32 value sits next to a rounding boundary the two sides round differently (1-2 % of
+# the elements, one bf16 step each), and with nothing but such values in the cache the logits
+# of these tiny models move by a few 1e-4.  The decode tests, whose caches are mostly seeded
+# values identical on both sides, keep the tighter bound.
+PREFILL_TIGHT = 2e-3
+
+
+@pytest.fixture(scope="module")
+def dk():
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a HIP device"
+    import paper_2601_19139_amd as dk
+    dk.lib()
+    return dk
+
+
+def variant(base, **kw):
+    return W.ModelConfig(**{**W.CONFIGS[base].as_dict(), **kw})
+
+
+def oracle_feed(orc, shape, weights, opool, table_row, start, tokens):
+    """One oracle decode step per prompt token; returns (logits [n, V], next [n])."""
+    logits, nxt = [], []
+    for i, t in enumerate(tokens):
+        r = orc.decode_step(shape, weights, opool, 16, table_row[None, :], np.array([start + i], np.int32),
+                            np.array([t], np.int32))
+        logits.append(r["logits"][0])
+        nxt.append(int(r["next"][0]))
+    return np.stack(logits), np.array(nxt, np.int32)
+
+
+def assert_greedy_agrees(g_next, g_logits, o_next, o_logits):
+    """Greedy tokens must agree; a position may differ only where the oracle itself has a
+    near tie (its margin between the two candidates is within twice the largest logit
+    difference at that position), and at most 1 % of the positions (at least one) may."""
+    bad = np.flatnonzero(g_next != o_next)
+    for i in bad:
+        margin = o_logits[i, o_next[i]] - o_logits[i, g_next[i]]
+        assert margin <= 2 * np.abs(g_logits[i] - o_logits[i]).max(), (i, margin)
+    assert len(bad) <= max(1, len(o_next) // 100), f"{len(bad)} of {len(o_next)} greedy tokens differ"
+
+
+def kv_close(g_bits, o_bits):
+    """Stored values agree up to rounding: as gpu_common.bf16_close (one bf16 step on top of
+    the float32 difference), with the float32 difference allowed PREFILL_TIGHT of the largest
+    magnitude instead of 1e-4 (deeper layers' k and v inherit the logits-level differences
+    explained above)."""
+    a = W.f32_from_bf16_bits(g_bits).astype(np.float64)
+    b = W.f32_from_bf16_bits(o_bits).astype(np.float64)
+    floor = PREFILL_TIGHT * max(float(np.abs(b).max()), 1e-30)
+    return np.abs(a - b) <= 2.0 ** -7 * np.maximum(np.abs(a), np.abs(b)) + floor
+
+
+def compare_pools(gpool, opool, before):
+    g_changed, o_changed = gpool != before, opool != before
+    assert np.array_equal(g_changed, o_changed), "prefill wrote other slots than the oracle"
+    assert kv_close(gpool[o_changed], opool[o_changed]).all()
+    assert (gpool[o_changed] != opool[o_changed]).mean() < 0.05
+
+
+CASES = [
+    # name, shape, prompt length, chunk size, greedy steps afterwards
+    ("tiny_one_chunk", variant("tiny"), 23, 64, 3),
+    ("tiny_chunks_of_5", variant("tiny", qk_norm=True), 37, 5, 2),        # chunks of 5 rows: matrix-core path
+    ("tiny_chunks_of_3", variant("tiny", qk_norm=True), 20, 3, 2),        # chunks of 3 rows: vector path
+    ("tiny_single_tokens", variant("tiny"), 6, 1, 2),
+    ("tiny_long_64", variant("tiny", qk_norm=True), 150, 64, 2),
+    ("d128_g4", variant("tiny", head_dim=128, n_q_heads=8, n_kv_heads=2, qk_norm=True), 70, 32, 2),
+    ("moe", W.CONFIGS["tiny_moe"], 41, 16, 2),
+]
+
+
+@pytest.mark.parametrize("name,shape,plen,chunk,gen", CASES, ids=[c[0] for c in CASES])
+def test_prefill_matches_token_by_token_oracle(dk, orc, name, shape, plen, chunk, gen):
+    import torch
+    lay = build_block_tables([0], 16, plen + gen + 1, seed=29)          # an empty sequence with room to grow
+    weights = W.make_weights(shape, 9)
+    before = W.fill_kv_pool(shape, lay, 10)                               # nothing cached: all slots poisoned
+    prompt = W.initial_tokens(shape, plen, 11)
+    opool = before.copy()
+    o_logits, o_next = oracle_feed(orc, shape, weights, opool, lay.tables[0], 0, prompt)
+
+    dm = dk.DeviceModel(shape, weights)
+    dkv = dk.DeviceKV(dm, lay, before)
+    pre = dk.Prefiller(dm, dkv, max_chunk=64)
+    g_next, g_logits = pre.prefill(0, 0, prompt, chunk)
+    torch.cuda.synchronize()
+    worst = rel_l2(g_logits, o_logits).max()
+    assert worst < PREFILL_TIGHT, (name, worst)
+    assert_greedy_agrees(g_next, g_logits, o_next, o_logits)
+    compare_pools(dkv.bits().reshape(before.shape), opool, before)
+
+    # chunks whose predictions are not wanted skip the lm_head; cache and last chunk are the same
+    kv2 = dk.DeviceKV(dm, lay, before)
+    n2, l2 = dk.Prefiller(dm, kv2, max_chunk=64).prefill(0, 0, prompt, chunk, last_only=True)
+    torch.cuda.synchronize()
+    assert np.array_equal(kv2.bits(), dkv.bits())
+    assert np.array_equal(l2, g_logits[-len(l2):]) and np.array_equal(n2, g_next[-len(n2):])
+    kv2.close()
+
+    # decoding continues from the prefilled state (the persistent kernel takes over for one row
+    # of the small dense shapes; its workspace is the prefill's own here)
+    dec = dk.Decoder(dm, dkv, np.array([plen], np.int32), o_next[-1:])
+    tok, sl = o_next[-1:].copy(), np.array([plen], np.int32)
+    for _ in range(gen):
+        r = orc.decode_step(shape, weights, opool, 16, lay.tables, sl, tok)
+        dec.step()
+        torch.cuda.synchronize()
+        assert rel_l2(dec.logits.cpu().numpy(), r["logits"]).max() < PREFILL_TIGHT
+        assert np.array_equal(dec.next.cpu().numpy(), r["next"])
+        tok, sl = r["next"].copy(), sl + 1
+        dec.tokens.copy_(torch.from_numpy(tok).cuda())
+        dec.seq_lens.copy_(torch.from_numpy(sl).cuda())
+    dkv.close()
+    dm.close()
+
+
+def test_prefill_behind_a_shared_prefix(dk, orc):
+    """Prefix reuse: the shared prefix is fed once; two sequences whose tables start with the
+    same blocks feed only their own suffixes from the start position the prefix ends at.  Each
+    must equal the oracle fed the whole prompt of that sequence into a private cache."""
+    import torch
+    shape = variant("tiny", qk_norm=True)
+    prefix, suf = 32, [9, 21]
+    lay = build_block_tables([prefix + suf[0], prefix + suf[1]], 16, 2, shared_prefix=prefix, n_sharers=2, seed=31)
+    assert np.array_equal(lay.tables[0, :prefix // 16], lay.tables[1, :prefix // 16])
+    weights = W.make_weights(shape, 12)
+    before = np.full(W.pool_shape(shape, lay.num_blocks, 16), W.BF16_NAN_BITS, dtype=np.uint16)
+    p_tok = W.initial_tokens(shape, prefix, 13)
+    s_tok = [W.initial_tokens(shape, suf[0], 14), W.initial_tokens(shape, suf[1], 15)]
+
+    dm = dk.DeviceModel(shape, weights)
+    dkv = dk.DeviceKV(dm, lay, before)
+    pre = dk.Prefiller(dm, dkv, max_chunk=64)
+    pre.prefill(0, 0, p_tok, 16)                                  # the prefix, once, through row 0's table
+    got = [pre.prefill(b, prefix, s_tok[b], 8) for b in range(2)]
+    torch.cuda.synchronize()
+    gpool = dkv.bits().reshape(before.shape)
+
+    for b in range(2):
+        # the oracle's private cache for this sequence: same table row, its own pool copy
+        opool = before.copy()
+        oracle_feed(orc, shape, weights, opool, lay.tables[b], 0, p_tok)
+        o_logits, o_next = oracle_feed(orc, shape, weights, opool, lay.tables[b], prefix, s_tok[b])
+        assert rel_l2(got[b][1], o_logits).max() < PREFILL_TIGHT
+        assert_greedy_agrees(got[b][0], got[b][1], o_next, o_logits)
+        mine = np.zeros(lay.num_blocks, dtype=bool)
+        mine[lay.tables[b, :(prefix + suf[b] + 15) // 16]] = True
+        changed = opool != before
+        assert np.array_equal((gpool != before)[:, mine], changed[:, mine])
+        assert kv_close(gpool[changed], opool[changed]).all()
+    dkv.close()
+
+    # sharing changes nothing: each sequence fed whole into a private cache (same chunking)
+    # gives bit for bit the logits of its suffix
+    for b in range(2):
+        lay1 = build_block_tables([prefix + suf[b]], 16, 2, seed=37 + b)
+        kv1 = dk.DeviceKV(dm, lay1, np.full(W.pool_shape(shape, lay1.num_blocks, 16), W.BF16_NAN_BITS, np.uint16))
+        pre1 = dk.Prefiller(dm, kv1, max_chunk=64)
+        pre1.prefill(0, 0, p_tok, 16)
+        nxt, lg = pre1.prefill(0, prefix, s_tok[b], 8)
+        assert np.array_equal(lg, got[b][1]) and np.array_equal(nxt, got[b][0])
+        kv1.close()
+    dm.close()
+
+
+def test_prefill_argument_checks(dk):
+    import torch
+    shape = variant("tiny")
+    lay = build_block_tables([0], 16, 20, seed=3)
+    dm = dk.DeviceModel(shape, W.make_weights(shape, 1))
+    dkv = dk.DeviceKV(dm, lay, W.fill_kv_pool(shape, lay, 2))
+    pre = dk.Prefiller(dm, dkv, max_chunk=64)
+    table = dkv.block_tables[0]
+    toks = torch.zeros(65, dtype=torch.int32, device="cuda")
+    room = int(table.numel()) * 16
+    for start, n, code in ((0, 65, "INVALID_ARG"), (-1, 4, "INVALID_ARG"), (room - 3, 4, "INVALID_ARG")):
+        with pytest.raises(dk.DecodeKitError) as e:
+            dk.prefill_chunk(dm.handle, dkv.handle, table, start, toks[:n], pre._ws_ptr, pre.ws_bytes, None, pre.next)
+        assert code in str(e.value)
+    with pytest.raises(dk.DecodeKitError) as e:
+        dk.prefill_chunk(dm.handle, dkv.handle, table, 0, toks[:4], pre._ws_ptr, 1024, None, pre.next)
+    assert "WORKSPACE_TOO_SMALL" in str(e.value)
+    dkv.close()
+    dm.close()
