@@ -12,5 +12,8 @@ from .binding import (  # noqa: F401
     kv_free_blocks, kv_offset, kv_validate_tables, append_kv,
     create_model, destroy_model, workspace_bytes, decode_step, step_routing, step_algorithmic_bytes, profile_read, fused_status, workspace_reset, prefill_chunk,
     STEP_ADVANCE, STEP_PROFILE, STEP_NO_FUSED, KERNEL_CLASSES, STATUS,
+    EngineConfig, prefix_index_create, prefix_index_destroy, prefix_index_match, prefix_index_insert,
+    prefix_index_evict_lru, prefix_index_size, engine_device_bytes, engine_create, engine_destroy,
+    engine_submit, engine_step, engine_poll, engine_forget, engine_stats,
 )
 from .runtime import DeviceModel, DeviceKV, Decoder, Prefiller  # noqa: F401

@@ -1,7 +1,9 @@
-"""ctypes binding of include/decodekit.h: same names without the dk_ prefix,
-argument marshalling only."""
+"""ctypes binding of include/decodekit.h and include/dk_engine.h: same names
+without the dk_ prefix, argument marshalling only."""
 import ctypes as C
 import os
+
+import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libdecodekit.so")
@@ -81,7 +83,40 @@ _SIGNATURES = {
                                               C.c_int32, C.c_int32, C.c_void_p, C.POINTER(C.c_uint64)]),
 }
 
+class EngineConfig(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("max_batch", "max_blocks_per_seq", "prefill_chunk", "prefix_cache")]
+
+
+class EngineStats(C.Structure):
+    _fields_ = [(n, C.c_int64) for n in ("iterations", "decode_steps", "generated_tokens", "prefill_tokens",
+                                          "reused_tokens", "evictions")] + [
+        (n, C.c_int32) for n in ("cached_blocks", "active", "pending")]
+
+
+_SIGNATURES.update({
+    "dk_prefix_index_create": (C.c_int32, [C.c_int32, C.POINTER(C.c_void_p)]),
+    "dk_prefix_index_destroy": (C.c_int32, [C.c_void_p, C.c_void_p]),
+    "dk_prefix_index_match": (C.c_int32, [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p,
+                                          C.POINTER(C.c_int32)]),
+    "dk_prefix_index_insert": (C.c_int32, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p,
+                                           C.POINTER(C.c_int32)]),
+    "dk_prefix_index_evict_lru": (C.c_int32, [C.c_void_p, C.c_void_p, C.POINTER(C.c_int32)]),
+    "dk_prefix_index_size": (C.c_int32, [C.c_void_p, C.POINTER(C.c_int32)]),
+    "dk_engine_device_bytes": (C.c_int32, [C.c_void_p, C.POINTER(EngineConfig), C.POINTER(C.c_size_t)]),
+    "dk_engine_create": (C.c_int32, [C.c_void_p, C.c_void_p, C.POINTER(EngineConfig), C.c_void_p, C.c_size_t,
+                                     C.POINTER(C.c_void_p)]),
+    "dk_engine_destroy": (C.c_int32, [C.c_void_p]),
+    "dk_engine_submit": (C.c_int32, [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32,
+                                     C.POINTER(C.c_int64)]),
+    "dk_engine_step": (C.c_int32, [C.c_void_p, C.c_void_p, C.POINTER(C.c_int32)]),
+    "dk_engine_poll": (C.c_int32, [C.c_void_p, C.c_int64, C.c_void_p, C.c_int32, C.POINTER(C.c_int32),
+                                   C.POINTER(C.c_int32), C.POINTER(C.c_int32)]),
+    "dk_engine_forget": (C.c_int32, [C.c_void_p, C.c_int64]),
+    "dk_engine_get_stats": (C.c_int32, [C.c_void_p, C.POINTER(EngineStats)]),
+})
+
 EXPORTS = tuple(_SIGNATURES)
+REQUEST_STATES = ("pending", "active", "done", "failed")
 _LIB = None
 
 
@@ -269,3 +304,97 @@ def step_algorithmic_bytes(model, pool, h_block_tables, h_seq_lens, with_logits=
                                            int(with_logits), _ptr(distinct_experts_per_layer),
                                            C.byref(out)))
     return out.value
+
+
+# ---- prefix index and engine (dk_engine.h) ------------------------------------
+
+def _i32(a):
+    return np.ascontiguousarray(a, dtype=np.int32)
+
+
+def prefix_index_create(block_size: int = 16):
+    out = C.c_void_p()
+    _check(lib().dk_prefix_index_create(block_size, C.byref(out)))
+    return out
+
+
+def prefix_index_destroy(index, pool=None):
+    _check(lib().dk_prefix_index_destroy(index, pool))
+
+
+def prefix_index_match(index, tokens, max_blocks: int):
+    """Block ids of the longest cached chain of `tokens` (at most max_blocks blocks)."""
+    t = _i32(tokens)
+    out = np.empty(max(1, max_blocks), dtype=np.int32)
+    n = C.c_int32()
+    _check(lib().dk_prefix_index_match(index, _ptr(t), t.size, max_blocks, _ptr(out), C.byref(n)))
+    return out[:n.value].copy()
+
+
+def prefix_index_insert(index, pool, tokens, blocks) -> int:
+    t, b = _i32(tokens), _i32(blocks)
+    assert t.size >= 16 * b.size
+    n = C.c_int32()
+    _check(lib().dk_prefix_index_insert(index, pool, _ptr(t), b.size, _ptr(b), C.byref(n)))
+    return n.value
+
+
+def prefix_index_evict_lru(index, pool) -> int:
+    out = C.c_int32()
+    _check(lib().dk_prefix_index_evict_lru(index, pool, C.byref(out)))
+    return out.value
+
+
+def prefix_index_size(index) -> int:
+    out = C.c_int32()
+    _check(lib().dk_prefix_index_size(index, C.byref(out)))
+    return out.value
+
+
+def engine_device_bytes(model, cfg: EngineConfig) -> int:
+    out = C.c_size_t()
+    _check(lib().dk_engine_device_bytes(model, C.byref(cfg), C.byref(out)))
+    return out.value
+
+
+def engine_create(model, pool, cfg: EngineConfig, d_arena, arena_bytes: int):
+    out = C.c_void_p()
+    _check(lib().dk_engine_create(model, pool, C.byref(cfg), _ptr(d_arena), arena_bytes, C.byref(out)))
+    return out
+
+
+def engine_destroy(engine):
+    _check(lib().dk_engine_destroy(engine))
+
+
+def engine_submit(engine, prompt, max_new_tokens: int, eos_token: int = -1) -> int:
+    p = _i32(prompt)
+    out = C.c_int64()
+    _check(lib().dk_engine_submit(engine, _ptr(p), p.size, max_new_tokens, eos_token, C.byref(out)))
+    return out.value
+
+
+def engine_step(engine, stream=None) -> int:
+    """One iteration of the scheduler; returns the number of requests still active or pending."""
+    out = C.c_int32()
+    _check(lib().dk_engine_step(engine, _stream(stream), C.byref(out)))
+    return out.value
+
+
+def engine_poll(engine, request_id: int, capacity: int = 4096):
+    """(tokens generated so far, state name, prompt tokens supplied by the prefix cache)."""
+    buf = np.empty(capacity, dtype=np.int32)
+    n, st, reused = C.c_int32(), C.c_int32(), C.c_int32()
+    _check(lib().dk_engine_poll(engine, request_id, _ptr(buf), capacity, C.byref(n), C.byref(st), C.byref(reused)))
+    return buf[:min(n.value, capacity)].copy(), REQUEST_STATES[st.value], reused.value
+
+
+def engine_forget(engine, request_id: int):
+    _check(lib().dk_engine_forget(engine, request_id))
+
+
+def engine_stats(engine) -> dict:
+    s = EngineStats()
+    _check(lib().dk_engine_get_stats(engine, C.byref(s)))
+    return {n: getattr(s, n) for n, _ in EngineStats._fields_}
+

@@ -1247,3 +1247,6 @@ dk_status dk_step_algorithmic_bytes(const dk_model *model, const dk_kv_pool *poo
 }
 
 }  // extern "C"
+
+// continuous-batching scheduler and prefix cache on top of the entry points above
+#include "dk_engine.hip.h"
