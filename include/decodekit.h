@@ -273,12 +273,21 @@ dk_status dk_workspace_reset(dk_model *model);
 
 /* The persistent step kernel bounds every wait it does; if a wait ever ran out
  * (its blocks were not all resident, e.g. on a GPU shared with other work) the
- * step's results are invalid and this reports it: out[0] = serial number of the
+ * step's results are invalid (every next token of that step is -1) and this
+ * reports it: out[0] = serial number of the
  * last step that gave up (0 = none), out[1] = waits that ran out since the
  * workspace was first used.  Synchronises the stream.  DK_E_INVALID_ARG if the
  * workspace has not been used by a persistent step of `model`. */
 dk_status dk_fused_status(const dk_model *model, const void *d_workspace, uint32_t *out,
                           void *hip_stream);
+
+/* Test hook for that failure path: the number of polls after which a block of
+ * the persistent kernel gives up a wait (0 restores the default, about 65 000,
+ * i.e. tens of milliseconds).  With a limit of 1 practically every step gives
+ * up at once; the kernel still runs to its end normally, writes the token -1
+ * for every row (and does not advance tokens / lengths under DK_STEP_ADVANCE),
+ * and dk_fused_status reports the step.  Host only. */
+dk_status dk_debug_set_wait_limit(dk_model *model, int32_t polls);
 
 /* Experts chosen in the most recent decode step that used `d_workspace` with
  * the same B and max_blocks_per_seq (mixture-of-experts models only): copies

@@ -76,6 +76,7 @@ _SIGNATURES = {
     "dk_prefill_chunk": (C.c_int32, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p,
                                      C.c_int32, C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p, C.c_void_p]),
     "dk_workspace_reset": (C.c_int32, [C.c_void_p]),
+    "dk_debug_set_wait_limit": (C.c_int32, [C.c_void_p, C.c_int32]),
     "dk_fused_status": (C.c_int32, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
     "dk_profile_read": (C.c_int32, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32]),
     "dk_step_routing": (C.c_int32, [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]),
@@ -266,6 +267,10 @@ def prefill_chunk(model, pool, d_block_table, start: int, d_tokens, d_workspace,
     _check(lib().dk_prefill_chunk(model, pool, _ptr(d_block_table), int(d_block_table.numel()), int(start),
                                   _ptr(d_tokens), int(d_tokens.numel()), _ptr(d_workspace), workspace_bytes_,
                                   _ptr(d_logits), _ptr(d_next_tokens), _stream(stream)))
+
+
+def debug_set_wait_limit(model, polls: int):
+    _check(lib().dk_debug_set_wait_limit(model, polls))
 
 
 def workspace_reset(model):

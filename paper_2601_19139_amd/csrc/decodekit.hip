@@ -134,6 +134,7 @@ struct dk_model {
     size_t fused_ws_bytes = 0;
     int fused_parity = 0;
     unsigned fused_serial = 0;
+    int fused_spin_limit = dk::kFusedSpinLimit;
     int n_cus = 0;
 };
 
@@ -477,6 +478,7 @@ dk_status launch_fused(dk_model *model, dk_kv_pool *pool, const Workspace &w, ch
     a.status = status;
     model->fused_serial = model->fused_serial + 1 == 0 ? 1 : model->fused_serial + 1;
     a.serial = model->fused_serial;
+    a.spin_limit = model->fused_spin_limit;
     std::memcpy(a.inv_freq, model->inv_freq, sizeof a.inv_freq);
     for (int l = 0; l < c.n_layers; l++) {
         const dk_layer_weights &L = model->layers[(size_t)l];
@@ -1166,6 +1168,14 @@ static dk_status decode_step_impl(dk_model *model, dk_kv_pool *pool, const int32
                       (flags & DK_STEP_ADVANCE) ? 1 : 0};
     DK_LAUNCH(DK_K_ARGMAX, dk::argmax_final_kernel, dim3(B), dim3(1024), 0, st, am);
     DK_HIP(hipGetLastError());
+    return DK_OK;
+}
+
+dk_status dk_debug_set_wait_limit(dk_model *model, int32_t polls)
+{
+    if (!model) return fail(DK_E_INVALID_ARG, "model is NULL");
+    if (polls < 0) return fail(DK_E_INVALID_ARG, "polls %d", polls);
+    model->fused_spin_limit = polls > 0 ? polls : dk::kFusedSpinLimit;
     return DK_OK;
 }
 

@@ -193,6 +193,7 @@ struct dk_engine {
     int32_t *d_tables = nullptr, *d_seq = nullptr, *d_tok = nullptr, *d_next = nullptr, *d_chunk = nullptr;
     char *d_ws = nullptr;
     size_t ws_bytes = 0;
+    bool no_fused = false;                    // the persistent step kernel gave up once: not used again
     std::vector<int32_t> h_tables;            // host mirror [M][max_blocks]
     std::vector<char> row_dirty;
 };
@@ -474,11 +475,20 @@ dk_status dk_engine_step(dk_engine *engine, void *hip_stream, int32_t *out_activ
         if (s != DK_OK) return s;
         DK_HIP(hipMemcpyAsync(e->d_seq, seq.data(), (size_t)B * 4, hipMemcpyHostToDevice, st));
         DK_HIP(hipMemcpyAsync(e->d_tok, tok.data(), (size_t)B * 4, hipMemcpyHostToDevice, st));
-        s = dk_decode_step(e->model, e->pool, e->d_tables, e->cfg.max_blocks_per_seq, e->d_seq, e->d_tok, B,
-                           e->d_ws, e->ws_bytes, nullptr, e->d_next, 0, st);
-        if (s != DK_OK) return s;
-        DK_HIP(hipMemcpyAsync(nxt.data(), e->d_next, (size_t)B * 4, hipMemcpyDeviceToHost, st));
-        DK_HIP(hipStreamSynchronize(st));
+        for (int attempt = 0; attempt < 2; attempt++) {
+            s = dk_decode_step(e->model, e->pool, e->d_tables, e->cfg.max_blocks_per_seq, e->d_seq, e->d_tok, B,
+                               e->d_ws, e->ws_bytes, nullptr, e->d_next, e->no_fused ? DK_STEP_NO_FUSED : 0u, st);
+            if (s != DK_OK) return s;
+            DK_HIP(hipMemcpyAsync(nxt.data(), e->d_next, (size_t)B * 4, hipMemcpyDeviceToHost, st));
+            DK_HIP(hipStreamSynchronize(st));
+            if (nxt[0] >= 0) break;
+            // the persistent kernel could not keep its blocks resident (its waits are bounded and it
+            // says so with the token -1): the step left lengths and tokens alone, so it is simply
+            // repeated, now and from here on as a chain of kernels
+            if (attempt == 1) return fail(DK_E_HIP, "decode step reported an invalid result twice");
+            e->no_fused = true;
+            (void)dk_workspace_reset(e->model);
+        }
         e->stats.decode_steps++;
         e->stats.generated_tokens += B;
         for (int i = 0; i < B; i++) {

@@ -64,6 +64,7 @@ struct FusedArgs {
     int nchunks;           // attention chunks per sequence the buffers have room for
     unsigned *status;      // [0] abort tag, [1] number of timeouts ever
     unsigned serial;       // this step's tag (never 0)
+    int spin_limit;        // polls before a block gives up a wait
     double inv_freq[64];
     FusedLayer layers[kFusedMaxLayers];
 };
@@ -106,6 +107,7 @@ struct Waiter {
     unsigned serial;
     int spins;
     bool aborted;
+    int limit;
     unsigned *slots;   // LDS [2][kFusedWaves]: the waves' verdicts, double-buffered so one barrier per poll suffices
     int phase;
     __device__ __forceinline__ bool done(bool ready)
@@ -119,9 +121,9 @@ struct Waiter {
         phase ^= 1;
         if (ok) return true;
         spins++;
-        if ((spins & 63) == 0 || spins > kFusedSpinLimit) {
+        if ((spins & 63) == 0 || spins > limit) {
             bool stop = ldc_u32(status) == serial;
-            if (spins > kFusedSpinLimit && !stop) {
+            if (spins > limit && !stop) {
                 if (threadIdx.x == 0) {
                     __hip_atomic_store(status, serial, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                     atomicAdd(status + 1, 1u);
@@ -330,7 +332,7 @@ __global__ __launch_bounds__(kFusedThreads) void fused_step_kernel(FusedArgs a)
     const int blk = blockIdx.x, nblk = gridDim.x;
     const int H = a.H, F = a.F, V = a.V, QD = a.nq * D, QKV = (a.nq + 2 * a.nkv) * D;
     const FusedLayout lay = fused_layout(a.L, NB, H, a.nq, a.nkv, D, F, a.nchunks, nblk);
-    Waiter w{a.status, a.serial, 0, false, wslots, 0};
+    Waiter w{a.status, a.serial, 0, false, a.spin_limit, wslots, 0};
 
     // refill the other buffer set for the next step
     {
@@ -815,8 +817,11 @@ __global__ __launch_bounds__(kFusedThreads) void fused_step_kernel(FusedArgs a)
                 for (int ww = 1; ww < kFusedWaves; ww++)
                     if (sv[ww] > bv || (sv[ww] == bv && si[ww] < bi)) { bv = sv[ww]; bi = si[ww]; }
                 if (bi == 0x7fffffff) bi = 0;
-                a.next[b] = bi;
-                if (a.advance) {
+                // a step in which some block gave up a wait has no valid result: it says so
+                // with the token -1 and does not advance the sequence
+                const bool gave_up = w.aborted || ldc_u32(a.status) == a.serial;
+                a.next[b] = gave_up ? -1 : bi;
+                if (a.advance && !gave_up) {
                     a.tokens[b] = bi;
                     a.seq_lens[b] += 1;
                 }

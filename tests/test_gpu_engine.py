@@ -219,3 +219,27 @@ def test_eviction_under_memory_pressure(dk, orc):
     assert dk.engine_poll(eng, ok)[1] == "done" and list(dk.engine_poll(eng, ok)[0]) == want[1][0][:3]
     dk.engine_destroy(eng)
     s.close()
+
+
+def test_engine_falls_back_when_the_persistent_kernel_gives_up(dk, orc):
+    """One row of a small dense model runs as the persistent kernel.  If that kernel cannot keep
+    its blocks resident it reports the step as invalid; the engine repeats the step as a chain of
+    kernels and stays on that path.  The condition is forced from the host (wait bound of one poll)."""
+    shape = variant("tiny")
+    rng = np.random.default_rng(3)
+    s = Setup(dk, shape, n_blocks=16)
+    prompt = rng.integers(0, shape.vocab, size=21).astype(np.int32)
+    exp, margins = oracle_generate(orc, shape, s.weights, prompt, 6)
+    eng, arena = s.engine(1, 4, 16, True)
+    rid = dk.engine_submit(eng, prompt, 6)
+    dk.debug_set_wait_limit(s.dm.handle, 1)
+    try:
+        run_to_completion(dk, eng)
+    finally:
+        dk.debug_set_wait_limit(s.dm.handle, 0)
+    toks, state, _ = dk.engine_poll(eng, rid)
+    n = next((i for i, m in enumerate(margins) if m < 2e-3), len(exp))
+    assert state == "done" and list(toks[:n]) == exp[:n] and (toks >= 0).all()
+    dk.engine_destroy(eng)
+    s.close()
+

@@ -135,6 +135,39 @@ def test_persistent_and_kernel_per_stage_paths_agree(dk, orc, wname, steps):
         assert np.array_equal(a, b)
 
 
+def test_persistent_kernel_gives_up_cleanly(dk, orc):
+    """Every wait of the persistent kernel is bounded.  With the bound forced down to one poll
+    (a host-side test hook) the kernel still runs to its end, marks the step invalid (token -1,
+    nothing advanced, status words set) and the next step with the normal bound is right again."""
+    import torch
+    wl = W.WORKLOADS["cfg0"]
+    shape, lay = wl.cfg, layout_for(wl)
+    weights = W.make_weights(shape, wl.seed_weights)
+    pool = W.fill_kv_pool(shape, lay, wl.seed_kv)
+    tokens = W.initial_tokens(shape, wl.batch, wl.seed_tokens)
+    dm = dk.DeviceModel(shape, weights)
+    dkv = dk.DeviceKV(dm, lay, pool)
+    dec = dk.Decoder(dm, dkv, lay.contexts, tokens)
+    dk.debug_set_wait_limit(dm.handle, 1)
+    dec.step(flags=dk.STEP_ADVANCE)
+    torch.cuda.synchronize()
+    assert (dec.next.cpu().numpy() == -1).all()
+    assert np.array_equal(dec.seq_lens.cpu().numpy(), lay.contexts)          # not advanced
+    assert np.array_equal(dec.tokens.cpu().numpy(), tokens)
+    serial, gave_up = dec.fused_status()
+    assert serial != 0 and gave_up > 0
+    dk.debug_set_wait_limit(dm.handle, 0)                                     # back to the default
+    dec.step()
+    torch.cuda.synchronize()
+    opool = pool.copy()
+    r = orc.decode_step(shape, weights, opool, 16, lay.tables, lay.contexts, tokens)
+    assert np.array_equal(dec.next.cpu().numpy(), r["next"])
+    assert rel_l2(dec.logits.cpu().numpy(), r["logits"]).max() < TIGHT
+    assert np.array_equal(dkv.bits().reshape(pool.shape) != pool, opool != pool)   # the slot was rewritten
+    dkv.close()
+    dm.close()
+
+
 FUSED_CASES = [
     # contexts around the 64-token attention chunks of the persistent kernel, for both of its
     # shape classes (head_dim 64 and 128, query groups of 2), one and two rows
