@@ -181,6 +181,22 @@ __global__ __launch_bounds__(KS * 64) void skinny_gemm_kernel(GemmArgs a)
             sv[u] = a.ssq_in[(int64_t)min(wv + u * KS, a.n_part - 1) * kSsqStride + lane];
     }
 
+    // The residual rows and the next norm's gains that the epilogue of wave rt < RT will
+    // need: requested ahead of the weight stream as well (clamped addresses; used only
+    // where valid), so that the epilogue does not end on a memory round trip.
+    float xr[MT][4], gn[4];
+    if (EPI == GEPI_RESID) {
+        const int rr = ((int)blockIdx.x * RT + min(wv, RT - 1)) * 16 + 4 * lg;
+#pragma unroll
+        for (int i = 0; i < 4; i++) {
+            const int r = min(rr + i, N - 1);
+            gn[i] = bf16_to_f32(a.gain_next[r]);
+#pragma unroll
+            for (int t = 0; t < MT; t++)
+                xr[t][i] = a.xres[(int64_t)min(t * 16 + ln, a.B - 1) * N + r];
+        }
+    }
+
     Stage st[PD];
 #pragma unroll
     for (int p = 0; p < PD; p++) issue(st[p]);
@@ -268,11 +284,11 @@ __global__ __launch_bounds__(KS * 64) void skinny_gemm_kernel(GemmArgs a)
                     a.ohi[oo] = hi;
                     a.olo[oo] = lo;
                 } else {
-                    const float xn = a.xres[(int64_t)n * N + r] + v[0][i];
+                    const float xn = xr[t][i] + v[0][i];
                     a.xres[(int64_t)n * N + r] = xn;
                     sq += xn * xn;
                     uint16_t hi, lo;
-                    split_bf16(xn * bf16_to_f32(a.gain_next[r]), hi, lo);
+                    split_bf16(xn * gn[i], hi, lo);
                     const int64_t oo = act_offset(n, r, onks);
                     a.ohi[oo] = hi;
                     a.olo[oo] = lo;
