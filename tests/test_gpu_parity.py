@@ -283,7 +283,7 @@ def test_cfg1_full_size(dk, orc):
 
 
 @pytest.mark.parametrize("wname,rows,steps", [("cfg2", (0, 9, 15), 2), ("cfg3", (3, 12), 2),
-                                              ("cfg4_l4", (1, 8, 14), 2)])
+                                              ("cfg4_l4", (1, 8, 14), 2), ("cfg4", (2, 13), 1)])
 def test_batch16_full_size_sampled_rows(dk, orc, wname, rows, steps):
     """The batch-16 workloads at full size (Llama-3.2-3B shape with ragged
     contexts and a shared 1024-token prefix; Qwen3-8B shape, context 4096):
@@ -291,7 +291,7 @@ def test_batch16_full_size_sampled_rows(dk, orc, wname, rows, steps):
     those rows is compared, and append addressing is checked for all rows.
     cfg4_l4 is the 30B-A3B mixture-of-experts shape (128 experts, top 8, expert
     width 768, ragged contexts with a shared 2048-token prefix) cut to 4 layers
-    so that its weights are 5 GB instead of 61 GB."""
+    so that its weights are 5 GB instead of 61 GB; cfg4 is the same shape with all 48 layers."""
     wl = W.WORKLOADS[wname]
     shape, lay = wl.cfg, layout_for(wl)
     if wl.n_sharers:
