@@ -145,7 +145,7 @@ struct Workspace {
     // batched (matrix-core) path: activations as bf16 hi/lo, sum-of-squares partials
     size_t xhi, xlo, ahi, alo, fhi, flo, ssq;
     // mixture of experts: routing of every layer, per-row 1/rms, expert outputs
-    size_t topk_idx, topk_w, rinv, yexp, rlogits;
+    size_t topk_idx, topk_w, rinv, yexp, rlogits, exp_cnt, exp_list;
     // persistent step kernel: two buffer sets + status words
     size_t fused_sets, fused_status;
     long long fused_set_floats;
@@ -255,6 +255,8 @@ Workspace carve(const dk_model_config &c, int B, int max_blocks)
             w.rinv = take((size_t)B * 4);
             w.yexp = take((size_t)B * c.top_k * c.hidden * 4);
             w.rlogits = take((size_t)B * c.n_experts * 4);
+            w.exp_cnt = take((size_t)c.n_experts * 4);
+            w.exp_list = take((size_t)c.n_experts * B * c.top_k * 4);
         } else {
             w.fhi = take((size_t)w.Bp * padded(act_dim) * 2);
             w.flo = take((size_t)w.Bp * padded(act_dim) * 2);
@@ -505,7 +507,7 @@ const char *dk_last_error(void) { return g_err; }
 
 // The kernel revisions change whenever a kernel's memory behaviour changes; the
 // benchmark quotes stored counter measurements only for a matching revision.
-const char *dk_version(void) { return "decodekit 0.5 (gfx950; gemv r3, gemm r6, attention r6, moe r3, fused r2, prefill r1)"; }
+const char *dk_version(void) { return "decodekit 0.6 (gfx950; gemv r3, gemm r7, attention r6, moe r4, fused r2, prefill r1)"; }
 
 // ------------------------------------------------------------------- pool --
 dk_status dk_kv_pool_bytes(const dk_model_config *cfg, int32_t num_blocks, int32_t block_size,
@@ -1020,6 +1022,9 @@ static dk_status decode_step_impl(dk_model *model, dk_kv_pool *pool, const int32
             r.topk_idx = topk_idx;
             r.topk_w = topk_w;
             r.rinv = rinv;
+            r.B = B;
+            r.exp_cnt = reinterpret_cast<int *>(ws + w.exp_cnt);
+            r.exp_list = reinterpret_cast<int *>(ws + w.exp_list);
             DK_LAUNCH(DK_K_MOE_ROUTER, dk::moe_router_logits_kernel, dim3((c.n_experts + 7) / 8, B), dim3(256),
                       0, st, r);
             DK_LAUNCH(DK_K_MOE_ROUTER, dk::moe_router_select_kernel, dim3(B), dim3(64), 0, st, r);
@@ -1031,7 +1036,8 @@ static dk_status decode_step_impl(dk_model *model, dk_kv_pool *pool, const int32
             up.K = H;
             up.B = B;
             up.top_k = c.top_k;
-            up.topk_idx = topk_idx;
+            up.exp_cnt = r.exp_cnt;
+            up.exp_list = r.exp_list;
             up.xhi = xhi;
             up.xlo = xlo;
             up.rinv = rinv;
@@ -1054,7 +1060,8 @@ static dk_status decode_step_impl(dk_model *model, dk_kv_pool *pool, const int32
             dn.K = c.expert_ffn;
             dn.B = B;
             dn.top_k = c.top_k;
-            dn.topk_idx = topk_idx;
+            dn.exp_cnt = r.exp_cnt;
+            dn.exp_list = r.exp_list;
             dn.xhi = fhi;
             dn.xlo = flo;
             dn.y = yexp;

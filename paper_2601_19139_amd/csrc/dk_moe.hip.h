@@ -1,8 +1,7 @@
 // Mixture-of-experts MLP: softmax router with top-k selection, expert SwiGLU
 // GEMMs over only the experts that some row selected, and the weighted
-// combination.  Every byte of a selected expert is streamed once per step; an
-// expert nobody selected costs a 128-entry table scan per block and no HBM
-// traffic.
+// combination.  Every byte of a selected expert is streamed once per step; the
+// blocks of an expert nobody selected read one counter and exit.
 #pragma once
 #include "dk_common.hip.h"
 #include "dk_gemm.hip.h"
@@ -16,7 +15,8 @@ namespace dk {
 //           and computes 8 router logits, two per wave.
 //   select: grid (B), one wave.  Softmax over all experts, the top_k largest
 //           probabilities (ties to the lower expert index) renormalised to sum
-//           to one.
+//           to one.  Each (row, slot) pair is appended to the list of the expert
+//           it chose, so that the expert kernels need no search.
 struct RouterArgs {
     const float *x;          // [B][H] residual stream
     const uint16_t *gain;    // [H]
@@ -27,6 +27,9 @@ struct RouterArgs {
     int *topk_idx;           // [B][top_k] experts in order of decreasing probability
     float *topk_w;           // [B][top_k] renormalised weights
     float *rinv;             // [B] 1/rms of the row (the expert GEMMs apply it)
+    int B;
+    int *exp_cnt;            // [E] pairs that chose the expert
+    int *exp_list;           // [E][B*top_k] their indices row*top_k + slot (any order)
 };
 
 __global__ __launch_bounds__(256) void moe_router_logits_kernel(RouterArgs a)
@@ -50,6 +53,8 @@ __global__ __launch_bounds__(256) void moe_router_logits_kernel(RouterArgs a)
     __syncthreads();
     const float inv = rsqrtf((red[0] + red[1] + red[2] + red[3]) / (float)a.H + a.eps);
     if (blockIdx.x == 0 && tid == 0) a.rinv[b] = inv;
+    // the counters of this block's 8 experts start at zero for the select kernel
+    if (b == 0 && tid < 8 && blockIdx.x * 8 + tid < a.E) a.exp_cnt[blockIdx.x * 8 + tid] = 0;
     // wave wv: experts 8*blockIdx.x + 2*wv, +1; lanes stride over H in 8-element pieces
     const int e0 = blockIdx.x * 8 + wv * 2;
     const uint16_t *w0 = a.w_router + (int64_t)min(e0, a.E - 1) * a.H;
@@ -119,14 +124,20 @@ __global__ __launch_bounds__(64) void moe_router_select_kernel(RouterArgs a)
             if (lane + 64 * i == be) p[i] = -1.f;   // taken
     }
     if (lane < a.top_k) {
-        a.topk_idx[b * a.top_k + lane] = my_e;
-        a.topk_w[b * a.top_k + lane] = my_w / sel_sum;
+        const int pair = b * a.top_k + lane;
+        a.topk_idx[pair] = my_e;
+        a.topk_w[pair] = my_w / sel_sum;
+        // the pair joins its expert's list (the counters were cleared by the logits kernel).
+        // The order of a list depends on timing; the expert kernels compute every pair's
+        // column independently, so their results do not.
+        const int pos = atomicAdd(a.exp_cnt + my_e, 1);
+        a.exp_list[(int64_t)my_e * (a.B * a.top_k) + pos] = pair;
     }
 }
 
 // ---------------------------------------------------------------------------
-// Expert GEMMs.  grid = (row tiles, experts).  A block first collects, in
-// order, the (row, slot) pairs that selected its expert; none -> it exits.  The
+// Expert GEMMs.  grid = (row tiles, experts).  A block looks up how many (row,
+// slot) pairs selected its expert (none -> it exits) and their ordered list.  The
 // pairs become the batch columns of 16x16x32 bf16 MFMAs exactly as in the dense
 // skinny GEMM (activations as bf16 hi + lo in act_offset() order, KS waves
 // splitting K, accumulators added through LDS in wave order).
@@ -140,7 +151,8 @@ struct ExpertArgs {
     const uint16_t *w_b;     // UP: up   [E][Fe][H]
     int N, K;                // rows and columns of one expert matrix
     int B, top_k;
-    const int *topk_idx;     // [B][top_k]
+    const int *exp_cnt;      // [E] pairs that chose the expert
+    const int *exp_list;     // [E][B*top_k] pair indices row*top_k + slot (any order)
     const uint16_t *xhi, *xlo;   // input activations (act_offset order)
     const float *rinv;       // UP: [B]
     uint16_t *ohi, *olo;     // UP: output activations (act_offset order, K' = N)
@@ -151,10 +163,7 @@ template <bool UP, int KS>
 __global__ __launch_bounds__(KS * 64) void moe_expert_kernel(ExpertArgs a)
 {
     constexpr int NM = UP ? 2 : 1;
-    constexpr int MAXCOL = 64 * 16;   // DK_MAX_BATCH rows x up to 16 slots
     __shared__ float red[KS][NM][4][64];
-    __shared__ int col_row[MAXCOL];   // the pairs that selected this expert: row*top_k + slot
-    __shared__ int ncol_s;
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -163,22 +172,9 @@ __global__ __launch_bounds__(KS * 64) void moe_expert_kernel(ExpertArgs a)
     const int r0 = blockIdx.x * 16;
     const int K = a.K, N = a.N;
 
-    if (wv == 0) {
-        // ordered compaction of the assignment table by one wave
-        int n = 0;
-        const int total = a.B * a.top_k;
-        for (int base = 0; base < total; base += 64) {
-            const int i = base + lane;
-            const bool hit = i < total && a.topk_idx[i] == e;
-            const unsigned long long m = __ballot(hit);
-            if (hit) col_row[n + __popcll(m & ((1ull << lane) - 1))] = i;
-            n += __popcll(m);
-        }
-        if (lane == 0) ncol_s = n;
-    }
-    __syncthreads();
-    const int ncol = ncol_s;
+    const int ncol = a.exp_cnt[e];
     if (ncol == 0) return;
+    const int *col_row = a.exp_list + (int64_t)e * (a.B * a.top_k);
 
     const int wrow = min(r0 + ln, N - 1);
     const uint16_t *wp0 = a.w_a + ((int64_t)e * N + wrow) * K;
@@ -265,11 +261,8 @@ template <bool UP, int KS, int RT, int PD>
 __global__ __launch_bounds__(KS * 64) void moe_expert_fast_kernel(ExpertArgs a)
 {
     constexpr int NM = UP ? 2 : 1;
-    constexpr int MAXCOL = 64 * 16;   // DK_MAX_BATCH rows x up to 16 slots
     static_assert(RT <= KS, "one wave per row tile in the epilogue");
     __shared__ float red[KS][RT][NM][4][64];
-    __shared__ int col_row[MAXCOL];
-    __shared__ int ncol_s;
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -278,21 +271,9 @@ __global__ __launch_bounds__(KS * 64) void moe_expert_fast_kernel(ExpertArgs a)
     const int r0 = blockIdx.x * 16 * RT;
     const int K = a.K, N = a.N;
 
-    if (wv == 0) {
-        int n = 0;
-        const int total = a.B * a.top_k;
-        for (int base = 0; base < total; base += 64) {
-            const int i = base + lane;
-            const bool hit = i < total && a.topk_idx[i] == e;
-            const unsigned long long m = __ballot(hit);
-            if (hit) col_row[n + __popcll(m & ((1ull << lane) - 1))] = i;
-            n += __popcll(m);
-        }
-        if (lane == 0) ncol_s = n;
-    }
-    __syncthreads();
-    const int ncol = ncol_s;
+    const int ncol = a.exp_cnt[e];
     if (ncol == 0) return;
+    const int *col_row = a.exp_list + (int64_t)e * (a.B * a.top_k);
 
     const int nks = K >> 7;
     const int onks = (N + 127) >> 7;
