@@ -262,6 +262,38 @@ dk_status dk_prefill_chunk(dk_model *model, dk_kv_pool *pool, const int32_t *d_b
                            void *d_workspace, size_t workspace_bytes, float *d_logits,
                            int32_t *d_next_tokens, void *hip_stream);
 
+/*
+ * Sampling beyond greedy (the paper does not describe its sampler; this is the
+ * usual temperature / top-k / nucleus scheme, spelled out so that it can be
+ * checked): for each row, with s_i = logit_i / temperature and
+ * p_i = exp(s_i - max s):
+ *   top_k  (0 < top_k < V): the candidates are all i with p_i >= the top_k-th
+ *          largest p (equal values at the cut all stay); otherwise every i;
+ *   top_p  (< 1): t* = the largest value such that the candidates with p_i >= t*
+ *          hold at least top_p of the candidates' total; kept = those candidates;
+ *   draw:  r = u * (total of the kept set); the result is the first kept index,
+ *          in ascending order, whose running total exceeds r, where
+ *          u = (x >> 8) / 2^24 and x is the first word of Philox4x32-10 with
+ *          counter (step low, step high, row, 0) and key (seed low, seed high).
+ * The same (seed, step, row, logits) always give the same token.
+ *
+ *   d_logits   device float32 [B][V] (e.g. the d_logits of dk_decode_step)
+ *   d_scratch  device scratch of at least dk_sample_scratch_bytes(B, V), 256-byte aligned
+ *   d_out      device int32 [B]
+ * temperature > 0, top_k >= 0 (0: off), 0 < top_p <= 1 (1: off).
+ */
+typedef struct dk_sampling {
+    float temperature;
+    int32_t top_k;
+    float top_p;
+    uint64_t seed;
+} dk_sampling;
+
+dk_status dk_sample_scratch_bytes(int32_t B, int32_t V, size_t *out_bytes);
+dk_status dk_sample_tokens(const float *d_logits, int32_t B, int32_t V, const dk_sampling *params,
+                           uint64_t step, void *d_scratch, size_t scratch_bytes, int32_t *d_out,
+                           void *hip_stream);
+
 /* Totals of all profiled steps of `model` so far: out_ms[DK_K_COUNT] kernel
  * execution time in milliseconds per class, out_launches[DK_K_COUNT] launches
  * per class.  reset != 0 clears the totals.  Host only. */

@@ -293,6 +293,82 @@ int32_t orc_argmax_f32(const float *v, int32_t n)
     return best;
 }
 
+/* ------------------------------------------------------------ sampling -- */
+/*
+ * The paper does not describe its sampler.  The definition used here:
+ *   s_i = logit_i / T,  p_i = exp(s_i - max s);
+ *   top-k (0 < k < n): candidates = every i with p_i >= the k-th largest p;
+ *   top-p (p < 1): sort the candidates' p in descending order, take values until
+ *     their running sum reaches p * (sum over the candidates); the kept set is
+ *     every candidate with p_i >= the last value taken;
+ *   draw: r = u * (sum over the kept set), the first kept index, in ascending
+ *     index order, whose running sum exceeds r.
+ * Plain double arithmetic, a full sort.
+ */
+static int cmp_desc(const void *a, const void *b)
+{
+    const double x = *(const double *)a, y = *(const double *)b;
+    return (x < y) - (x > y);
+}
+
+int32_t orc_sample(const float *logits, int32_t n, double temperature, int32_t top_k, double top_p, double u)
+{
+    double *p = (double *)malloc(sizeof(double) * (size_t)n);
+    double *sorted = (double *)malloc(sizeof(double) * (size_t)n);
+    double mx = -INFINITY;
+    for (int32_t i = 0; i < n; i++) { const double s = (double)logits[i] / temperature; if (s > mx) mx = s; }
+    for (int32_t i = 0; i < n; i++) { p[i] = exp((double)logits[i] / temperature - mx); sorted[i] = p[i]; }
+    qsort(sorted, (size_t)n, sizeof(double), cmp_desc);
+    double tau = 0.0;
+    int32_t ncand = n;
+    if (top_k > 0 && top_k < n) {
+        tau = sorted[top_k - 1];
+        while (ncand > 0 && sorted[ncand - 1] < tau) ncand--;      /* candidates: the sorted prefix >= tau */
+    }
+    if (top_p < 1.0) {
+        double z = 0.0, run = 0.0;
+        for (int32_t i = 0; i < ncand; i++) z += sorted[i];
+        for (int32_t i = 0; i < ncand; i++) {
+            run += sorted[i];
+            if (run >= top_p * z) { tau = sorted[i]; break; }
+        }
+    }
+    double total = 0.0;
+    int32_t last = 0;
+    for (int32_t i = 0; i < n; i++) if (p[i] >= tau) { total += p[i]; last = i; }
+    const double r = u * total;
+    double run = 0.0;
+    int32_t pick = last;
+    for (int32_t i = 0; i < n; i++)
+        if (p[i] >= tau) { run += p[i]; if (run > r) { pick = i; break; } }
+    free(p); free(sorted);
+    return pick;
+}
+
+/* Philox4x32-10 (Salmon et al., "Parallel random numbers: as easy as 1, 2, 3"). */
+void orc_philox4x32_10(const uint32_t counter[4], const uint32_t key[2], uint32_t out[4])
+{
+    uint32_t c0 = counter[0], c1 = counter[1], c2 = counter[2], c3 = counter[3], k0 = key[0], k1 = key[1];
+    for (int r = 0; r < 10; r++) {
+        const uint64_t a = (uint64_t)0xD2511F53u * c0, b = (uint64_t)0xCD9E8D57u * c2;
+        const uint32_t n0 = (uint32_t)(b >> 32) ^ c1 ^ k0, n1 = (uint32_t)b;
+        const uint32_t n2 = (uint32_t)(a >> 32) ^ c3 ^ k1, n3 = (uint32_t)a;
+        c0 = n0; c1 = n1; c2 = n2; c3 = n3;
+        k0 += 0x9E3779B9u; k1 += 0xBB67AE85u;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+/* The uniform number of (seed, step, row): 24 bits of the first Philox word. */
+double orc_sample_uniform(uint64_t seed, uint64_t step, uint32_t row)
+{
+    const uint32_t ctr[4] = {(uint32_t)step, (uint32_t)(step >> 32), row, 0u};
+    const uint32_t key[2] = {(uint32_t)seed, (uint32_t)(seed >> 32)};
+    uint32_t out[4];
+    orc_philox4x32_10(ctr, key, out);
+    return (double)(out[0] >> 8) / 16777216.0;
+}
+
 /* ---------------------------------------------------- one decode step --- */
 /*
  * For each sequence b (independently): embed tokens[b]; for every layer

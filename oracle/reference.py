@@ -191,6 +191,24 @@ class Oracle:
         v = np.ascontiguousarray(v, dtype=np.float32)
         return int(self.lib.orc_argmax_f32(_p(v), C.c_int32(v.size)))
 
+    # -- sampling ---------------------------------------------------------
+    def sample(self, logits, temperature, top_k, top_p, u):
+        v = np.ascontiguousarray(logits, dtype=np.float32)
+        self.lib.orc_sample.restype = C.c_int32
+        return int(self.lib.orc_sample(_p(v), C.c_int32(v.size), C.c_double(temperature), C.c_int32(top_k),
+                                       C.c_double(top_p), C.c_double(u)))
+
+    def philox4x32_10(self, counter, key):
+        c = (C.c_uint32 * 4)(*[int(x) for x in counter])
+        k = (C.c_uint32 * 2)(*[int(x) for x in key])
+        out = (C.c_uint32 * 4)()
+        self.lib.orc_philox4x32_10(c, k, out)
+        return tuple(int(x) for x in out)
+
+    def sample_uniform(self, seed, step, row):
+        self.lib.orc_sample_uniform.restype = C.c_double
+        return float(self.lib.orc_sample_uniform(C.c_uint64(seed), C.c_uint64(step), C.c_uint32(row)))
+
     # -- whole step -------------------------------------------------------
     def decode_step(self, cfg, weights, pool, block_size, block_tables, seq_lens, tokens,
                     want_logits=True, want_trace=False):

@@ -84,6 +84,10 @@ _SIGNATURES = {
                                               C.c_int32, C.c_int32, C.c_void_p, C.POINTER(C.c_uint64)]),
 }
 
+class Sampling(C.Structure):
+    _fields_ = [("temperature", C.c_float), ("top_k", C.c_int32), ("top_p", C.c_float), ("seed", C.c_uint64)]
+
+
 class EngineConfig(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("max_batch", "max_blocks_per_seq", "prefill_chunk", "prefix_cache")]
 
@@ -95,6 +99,9 @@ class EngineStats(C.Structure):
 
 
 _SIGNATURES.update({
+    "dk_sample_scratch_bytes": (C.c_int32, [C.c_int32, C.c_int32, C.POINTER(C.c_size_t)]),
+    "dk_sample_tokens": (C.c_int32, [C.c_void_p, C.c_int32, C.c_int32, C.POINTER(Sampling), C.c_uint64, C.c_void_p,
+                                     C.c_size_t, C.c_void_p, C.c_void_p]),
     "dk_prefix_index_create": (C.c_int32, [C.c_int32, C.POINTER(C.c_void_p)]),
     "dk_prefix_index_destroy": (C.c_int32, [C.c_void_p, C.c_void_p]),
     "dk_prefix_index_match": (C.c_int32, [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p,
@@ -309,6 +316,22 @@ def step_algorithmic_bytes(model, pool, h_block_tables, h_seq_lens, with_logits=
                                            int(with_logits), _ptr(distinct_experts_per_layer),
                                            C.byref(out)))
     return out.value
+
+
+def sample_scratch_bytes(B: int, V: int) -> int:
+    out = C.c_size_t()
+    _check(lib().dk_sample_scratch_bytes(B, V, C.byref(out)))
+    return out.value
+
+
+def sample_tokens(d_logits, temperature: float, top_k: int, top_p: float, seed: int, step: int, d_scratch,
+                  d_out, stream=None):
+    """d_logits float32 [B, V]; d_scratch at least sample_scratch_bytes(B, V) bytes, 256-byte
+    aligned; d_out int32 [B]."""
+    B, V = d_logits.shape
+    prm = Sampling(temperature, top_k, top_p, seed)
+    _check(lib().dk_sample_tokens(_ptr(d_logits), B, V, C.byref(prm), step, _ptr(d_scratch),
+                                  d_scratch.numel() * d_scratch.element_size(), _ptr(d_out), _stream(stream)))
 
 
 # ---- prefix index and engine (dk_engine.h) ------------------------------------

@@ -20,6 +20,7 @@
 #include "dk_gemm.hip.h"
 #include "dk_gemv.hip.h"
 #include "dk_moe.hip.h"
+#include "dk_sample.hip.h"
 
 namespace {
 
@@ -507,7 +508,7 @@ const char *dk_last_error(void) { return g_err; }
 
 // The kernel revisions change whenever a kernel's memory behaviour changes; the
 // benchmark quotes stored counter measurements only for a matching revision.
-const char *dk_version(void) { return "decodekit 0.6 (gfx950; gemv r3, gemm r7, attention r6, moe r4, fused r2, prefill r1)"; }
+const char *dk_version(void) { return "decodekit 0.7 (gfx950; gemv r3, gemm r7, attention r6, moe r4, fused r2, prefill r1, sample r1)"; }
 
 // ------------------------------------------------------------------- pool --
 dk_status dk_kv_pool_bytes(const dk_model_config *cfg, int32_t num_blocks, int32_t block_size,
@@ -791,6 +792,105 @@ dk_status dk_prefill_chunk(dk_model *model, dk_kv_pool *pool, const int32_t *d_b
     return decode_step_impl(model, pool, d_block_table, max_blocks, seq, const_cast<int32_t *>(d_tokens), n,
                             d_workspace, workspace_bytes, d_logits, d_next_tokens,
                             DK_STEP_NO_FUSED | kStepPrefill, hip_stream);
+}
+
+namespace {
+struct SampleScratch { size_t p, pmax, part_a, part_b, st_a, st_b, total; };
+SampleScratch sample_scratch(int B, int V)
+{
+    SampleScratch L{};
+    size_t off = 0;
+    auto take = [&](size_t bytes) { const size_t o = off; off = align_up(off + bytes, 256); return o; };
+    L.p = take((size_t)B * V * 4);
+    L.pmax = take((size_t)B * dk::kSampleBlocks * 4);
+    L.part_a = take((size_t)B * dk::kSampleBlocks * 16 * 4);
+    L.part_b = take((size_t)B * dk::kSampleBlocks * 16 * 4);
+    L.st_a = take((size_t)B * sizeof(dk::SampleState));
+    L.st_b = take((size_t)B * sizeof(dk::SampleState));
+    L.total = off;
+    return L;
+}
+}  // namespace
+
+dk_status dk_sample_scratch_bytes(int32_t B, int32_t V, size_t *out_bytes)
+{
+    if (!out_bytes) return fail(DK_E_INVALID_ARG, "NULL argument");
+    if (B <= 0 || V <= 0) return fail(DK_E_INVALID_ARG, "B %d, V %d", B, V);
+    *out_bytes = sample_scratch(B, V).total;
+    return DK_OK;
+}
+
+dk_status dk_sample_tokens(const float *d_logits, int32_t B, int32_t V, const dk_sampling *params,
+                           uint64_t step, void *d_scratch, size_t scratch_bytes, int32_t *d_out,
+                           void *hip_stream)
+{
+    if (!d_logits || !params || !d_scratch || !d_out) return fail(DK_E_INVALID_ARG, "NULL argument");
+    if (B <= 0 || V <= 0) return fail(DK_E_INVALID_ARG, "B %d, V %d", B, V);
+    if (!(params->temperature > 0.f)) return fail(DK_E_INVALID_ARG, "temperature must be positive");
+    if (params->top_k < 0) return fail(DK_E_INVALID_ARG, "top_k %d", params->top_k);
+    if (!(params->top_p > 0.f && params->top_p <= 1.f)) return fail(DK_E_INVALID_ARG, "top_p outside (0, 1]");
+    if ((uintptr_t)d_scratch % 256) return fail(DK_E_INVALID_ARG, "scratch must be 256-byte aligned");
+    const SampleScratch L = sample_scratch(B, V);
+    if (scratch_bytes < L.total)
+        return fail(DK_E_WORKSPACE_TOO_SMALL, "scratch %zu bytes, %zu needed", scratch_bytes, L.total);
+    char *base = static_cast<char *>(d_scratch);
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    dk::SampleArgs a{};
+    a.logits = d_logits;
+    a.p = reinterpret_cast<float *>(base + L.p);
+    a.pmax = reinterpret_cast<float *>(base + L.pmax);
+    a.out = d_out;
+    a.V = V;
+    a.temperature = params->temperature;
+    a.top_p = params->top_p;
+    a.top_k = params->top_k;
+    a.seed_lo = (uint32_t)params->seed;
+    a.seed_hi = (uint32_t)(params->seed >> 32);
+    a.step_lo = (uint32_t)step;
+    a.step_hi = (uint32_t)(step >> 32);
+    float *part[2] = {reinterpret_cast<float *>(base + L.part_a), reinterpret_cast<float *>(base + L.part_b)};
+    dk::SampleState *state[2] = {reinterpret_cast<dk::SampleState *>(base + L.st_a),
+                                 reinterpret_cast<dk::SampleState *>(base + L.st_b)};
+    int cur = 0;   // the buffers the last launch wrote
+    auto launch = [&](int stage, int grid_x) {
+        a.stage = stage;
+        a.part_in = part[cur];
+        a.st_in = state[cur];
+        a.part_out = part[cur ^ 1];
+        a.st_out = state[cur ^ 1];
+        hipLaunchKernelGGL(dk::sample_kernel, dim3(grid_x, B), dim3(dk::kSampleThreads), 0, st, a);
+        cur ^= 1;
+    };
+    const bool use_k = params->top_k > 0 && params->top_k < V, use_p = params->top_p < 1.f;
+    launch(dk::SAMPLE_MAX, dk::kSampleBlocks);
+    launch(dk::SAMPLE_EXP, dk::kSampleBlocks);
+    if (use_k) {
+        a.count = 1;
+        a.need_from_mass = 0;
+        for (int shift = 28; shift >= 0; shift -= 4) {
+            a.shift = shift;
+            a.first = (shift == 28);
+            launch(dk::SAMPLE_PASS, dk::kSampleBlocks);
+        }
+        a.settle = 1;
+        launch(dk::SAMPLE_MASS, dk::kSampleBlocks);
+    }
+    if (use_p) {
+        a.count = 0;
+        for (int shift = 28; shift >= 0; shift -= 4) {
+            a.shift = shift;
+            a.first = (shift == 28);
+            a.need_from_mass = a.first;
+            launch(dk::SAMPLE_PASS, dk::kSampleBlocks);
+        }
+        a.settle = 1;
+    } else {
+        a.settle = 0;
+    }
+    launch(dk::SAMPLE_KEEP, dk::kSampleBlocks);
+    launch(dk::SAMPLE_DRAW, 1);
+    DK_HIP(hipGetLastError());
+    return DK_OK;
 }
 
 dk_status dk_profile_read(dk_model *model, double *out_ms, int64_t *out_launches, int32_t reset)
