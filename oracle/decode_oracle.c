@@ -123,6 +123,42 @@ static void matvec(const uint16_t *W, int64_t rows, int64_t cols, const real *x,
     }
 }
 
+/* ------------------------------------- 4-bit weights (group-wise affine) -- */
+/*
+ * The precision the paper benchmarks (4-bit MLX checkpoints): every row is cut
+ * into groups of 64 consecutive columns; a group has 64 codes q in 0..15 and a
+ * bf16 scale and bias, and stands for the weights  scale * q + bias.  The
+ * matrix-vector product is the plain definition with those weights:
+ *   y_r = sum_k (scale[r][k/64] * q[r][k] + bias[r][k/64]) * x_k
+ * Canonical form: q uint8 [rows][cols], scale / bias bf16 bits [rows][cols/64].
+ */
+typedef struct {
+    const uint8_t *q;
+    const uint16_t *scale, *bias;
+} orc_q4;
+
+static void matvec_q4(const orc_q4 *m, int64_t rows, int64_t cols, const real *x, real *y)
+{
+    const int64_t groups = cols / 64;
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < rows; r++) {
+        real acc = 0;
+        for (int64_t k = 0; k < cols; k++) {
+            const real w = (real)bf16_to_f32(m->scale[r * groups + k / 64]) * (real)m->q[r * cols + k] +
+                           (real)bf16_to_f32(m->bias[r * groups + k / 64]);
+            acc += w * x[k];
+        }
+        y[r] = acc;
+    }
+}
+
+/* One projection of a layer: the 4-bit matrix if the model has them, else the bf16 one. */
+static void project(const uint16_t *w_bf16, const orc_q4 *w_q4, int64_t rows, int64_t cols, const real *x, real *y)
+{
+    if (w_q4) matvec_q4(w_q4, rows, cols, x, y);
+    else matvec(w_bf16, rows, cols, x, y);
+}
+
 /* --------------------------------------------------------------- RoPE --- */
 /* Half-split rotary embedding of one head at position pos: element i is
  * paired with element i + d/2 and the pair is rotated by pos * theta^(-2i/d). */
@@ -223,17 +259,24 @@ static void attention(const orc_config *c, const uint16_t *pool, int32_t num_blo
 static inline real silu(real z) { return z / ((real)1 + R_EXP(-z)); }
 
 /* out = Wd (silu(Wg h) * (Wu h)) with Wg, Wu [F,H], Wd [H,F] */
-static void swiglu(const uint16_t *wg, const uint16_t *wu, const uint16_t *wd,
-                   int H, int F, const real *h, real *out)
+static void swiglu_any(const uint16_t *wg, const uint16_t *wu, const uint16_t *wd,
+                       const orc_q4 *qg, const orc_q4 *qu, const orc_q4 *qd,
+                       int H, int F, const real *h, real *out)
 {
     real *g = (real *)malloc(sizeof(real) * (size_t)F);
     real *u = (real *)malloc(sizeof(real) * (size_t)F);
-    matvec(wg, F, H, h, g);
-    matvec(wu, F, H, h, u);
+    project(wg, qg, F, H, h, g);
+    project(wu, qu, F, H, h, u);
     for (int i = 0; i < F; i++) g[i] = silu(g[i]) * u[i];
-    matvec(wd, H, F, g, out);
+    project(wd, qd, H, F, g, out);
     free(g);
     free(u);
+}
+
+static void swiglu(const uint16_t *wg, const uint16_t *wu, const uint16_t *wd,
+                   int H, int F, const real *h, real *out)
+{
+    swiglu_any(wg, wu, wd, NULL, NULL, NULL, H, F, h, out);
 }
 
 /* Router: softmax over all experts, the top_k largest probabilities (ties to
@@ -384,13 +427,18 @@ double orc_sample_uniform(uint64_t seed, uint64_t step, uint32_t row)
  * trace_experts (optional, MoE): int32 [n_layers][B][top_k] chosen experts.
  * Returns 0, or a negative value for an invalid argument.
  */
-int orc_decode_step(const orc_config *c, const orc_layer *layers,
-                    const uint16_t *embed, const uint16_t *g_final, const uint16_t *lm_head,
-                    uint16_t *pool, int32_t num_blocks, int32_t block_size,
-                    const int32_t *block_tables, int32_t max_blocks_per_seq,
-                    const int32_t *seq_lens, const int32_t *tokens, int32_t B,
-                    float *logits, int32_t *next_tokens, float *trace_x,
-                    int32_t *trace_experts)
+/* q4: NULL (bf16 weights), or the model's 4-bit matrices, seven per layer in
+ * the order wq wk wv wo w_gate w_up w_down, then lm_head; the bf16 pointers of
+ * those matrices are then not read (norm gains and the embedding stay bf16). */
+enum { Q4_WQ, Q4_WK, Q4_WV, Q4_WO, Q4_GATE, Q4_UP, Q4_DOWN, Q4_PER_LAYER };
+
+static int decode_step_body(const orc_config *c, const orc_layer *layers, const orc_q4 *q4,
+                            const uint16_t *embed, const uint16_t *g_final, const uint16_t *lm_head,
+                            uint16_t *pool, int32_t num_blocks, int32_t block_size,
+                            const int32_t *block_tables, int32_t max_blocks_per_seq,
+                            const int32_t *seq_lens, const int32_t *tokens, int32_t B,
+                            float *logits, int32_t *next_tokens, float *trace_x,
+                            int32_t *trace_experts)
 {
     int H = c->hidden, d = c->head_dim, nq = c->n_q_heads, nkv = c->n_kv_heads;
     int V = c->vocab;
@@ -423,10 +471,11 @@ int orc_decode_step(const orc_config *c, const orc_layer *layers,
 
         for (int l = 0; l < c->n_layers; l++) {
             const orc_layer *L = &layers[l];
+            const orc_q4 *Q = q4 ? q4 + (int64_t)l * Q4_PER_LAYER : NULL;
             rmsnorm(x, H, L->g_attn, (real)c->rms_eps, h);
-            matvec(L->wq, (int64_t)nq * d, H, h, q);
-            matvec(L->wk, (int64_t)nkv * d, H, h, k);
-            matvec(L->wv, (int64_t)nkv * d, H, h, v);
+            project(L->wq, Q ? Q + Q4_WQ : NULL, (int64_t)nq * d, H, h, q);
+            project(L->wk, Q ? Q + Q4_WK : NULL, (int64_t)nkv * d, H, h, k);
+            project(L->wv, Q ? Q + Q4_WV : NULL, (int64_t)nkv * d, H, h, v);
             if (c->qk_norm) {
                 for (int hh = 0; hh < nq; hh++) {
                     rmsnorm(q + hh * d, d, L->g_q, (real)c->rms_eps, tmp);
@@ -441,7 +490,7 @@ int orc_decode_step(const orc_config *c, const orc_layer *layers,
             for (int j = 0; j < nkv; j++) rope(k + j * d, d, pos, c->rope_theta);
             append_kv(c, pool, num_blocks, block_size, l, table, pos, k, v);
             attention(c, pool, num_blocks, block_size, l, table, pos + 1, q, o, NULL);
-            matvec(L->wo, H, (int64_t)nq * d, o, y);
+            project(L->wo, Q ? Q + Q4_WO : NULL, H, (int64_t)nq * d, o, y);
             for (int i = 0; i < H; i++) x[i] += y[i];
 
             rmsnorm(x, H, L->g_mlp, (real)c->rms_eps, h);
@@ -449,20 +498,63 @@ int orc_decode_step(const orc_config *c, const orc_layer *layers,
                 moe(c, L, h, y, trace_experts
                         ? trace_experts + ((int64_t)l * B + b) * c->top_k : NULL, NULL);
             else
-                swiglu(L->w_gate, L->w_up, L->w_down, H, c->ffn, h, y);
+                swiglu_any(L->w_gate, L->w_up, L->w_down, Q ? Q + Q4_GATE : NULL, Q ? Q + Q4_UP : NULL,
+                           Q ? Q + Q4_DOWN : NULL, H, c->ffn, h, y);
             for (int i = 0; i < H; i++) x[i] += y[i];
             if (trace_x)
                 for (int i = 0; i < H; i++)
                     trace_x[((int64_t)(l + 1) * B + b) * H + i] = (float)x[i];
         }
         rmsnorm(x, H, g_final, (real)c->rms_eps, h);
-        matvec(lm_head, V, H, h, lg);
+        project(lm_head, q4 ? q4 + (int64_t)c->n_layers * Q4_PER_LAYER : NULL, V, H, h, lg);
         for (int i = 0; i < V; i++) lgf[i] = (float)lg[i];
         if (logits) memcpy(logits + (int64_t)b * V, lgf, sizeof(float) * (size_t)V);
         next_tokens[b] = orc_argmax_f32(lgf, V);
     }
     free(x); free(h); free(q); free(k); free(v); free(o); free(y); free(lg); free(lgf); free(tmp);
     return 0;
+}
+
+int orc_decode_step(const orc_config *c, const orc_layer *layers,
+                    const uint16_t *embed, const uint16_t *g_final, const uint16_t *lm_head,
+                    uint16_t *pool, int32_t num_blocks, int32_t block_size,
+                    const int32_t *block_tables, int32_t max_blocks_per_seq,
+                    const int32_t *seq_lens, const int32_t *tokens, int32_t B,
+                    float *logits, int32_t *next_tokens, float *trace_x,
+                    int32_t *trace_experts)
+{
+    return decode_step_body(c, layers, NULL, embed, g_final, lm_head, pool, num_blocks, block_size,
+                            block_tables, max_blocks_per_seq, seq_lens, tokens, B, logits,
+                            next_tokens, trace_x, trace_experts);
+}
+
+/* The same step for a dense model with 4-bit projections.  q_ptrs / scale_ptrs /
+ * bias_ptrs: n_layers * 7 + 1 pointers each (order as above; canonical form).
+ * hidden, n_q_heads * head_dim and ffn must be multiples of 64.  layers supplies
+ * the norm gains only. */
+int orc_decode_step_q4(const orc_config *c, const orc_layer *layers,
+                       const uint8_t *const *q_ptrs, const uint16_t *const *scale_ptrs,
+                       const uint16_t *const *bias_ptrs,
+                       const uint16_t *embed, const uint16_t *g_final,
+                       uint16_t *pool, int32_t num_blocks, int32_t block_size,
+                       const int32_t *block_tables, int32_t max_blocks_per_seq,
+                       const int32_t *seq_lens, const int32_t *tokens, int32_t B,
+                       float *logits, int32_t *next_tokens, float *trace_x)
+{
+    if (c->n_experts > 0) return -5;
+    if (c->hidden % 64 || (c->n_q_heads * c->head_dim) % 64 || c->ffn % 64) return -6;
+    const int n = c->n_layers * Q4_PER_LAYER + 1;
+    orc_q4 *m = (orc_q4 *)malloc(sizeof(orc_q4) * (size_t)n);
+    for (int i = 0; i < n; i++) {
+        m[i].q = q_ptrs[i];
+        m[i].scale = scale_ptrs[i];
+        m[i].bias = bias_ptrs[i];
+    }
+    int rc = decode_step_body(c, layers, m, embed, g_final, NULL, pool, num_blocks, block_size,
+                              block_tables, max_blocks_per_seq, seq_lens, tokens, B, logits,
+                              next_tokens, trace_x, NULL);
+    free(m);
+    return rc;
 }
 
 /* ------------------------------------- stage entry points for the tests -- */
@@ -491,6 +583,16 @@ void orc_matvec(const uint16_t *W, int64_t rows, int64_t cols, const double *x, 
 {
     real *xr = to_real(x, cols), *yr = (real *)malloc(sizeof(real) * (size_t)rows);
     matvec(W, rows, cols, xr, yr);
+    from_real(yr, rows, y);
+    free(xr); free(yr);
+}
+
+void orc_matvec_q4(const uint8_t *q, const uint16_t *scale, const uint16_t *bias, int64_t rows,
+                   int64_t cols, const double *x, double *y)
+{
+    const orc_q4 m = {q, scale, bias};
+    real *xr = to_real(x, cols), *yr = (real *)malloc(sizeof(real) * (size_t)rows);
+    matvec_q4(&m, rows, cols, xr, yr);
     from_real(yr, rows, y);
     free(xr); free(yr);
 }

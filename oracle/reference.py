@@ -131,6 +131,18 @@ class Oracle:
         self.lib.orc_matvec(_p(W_bits), C.c_int64(rows), C.c_int64(cols), _p(x), _p(y))
         return y
 
+    def matvec_q4(self, m: dict, x):
+        """y = W x for a 4-bit matrix in canonical form (dict q / scale / bias)."""
+        q = np.ascontiguousarray(m["q"], dtype=np.uint8)
+        rows, cols = q.shape
+        sc, bi = _u16(m["scale"]), _u16(m["bias"])
+        assert sc.shape == bi.shape == (rows, cols // 64) and cols % 64 == 0
+        x = _f64(x)
+        assert x.shape == (cols,)
+        y = np.empty(rows, dtype=np.float64)
+        self.lib.orc_matvec_q4(_p(q), _p(sc), _p(bi), C.c_int64(rows), C.c_int64(cols), _p(x), _p(y))
+        return y
+
     def rope(self, v, pos, theta):
         v = _f64(v).copy()
         self.lib.orc_rope(_p(v), C.c_int32(v.size), C.c_int32(pos), C.c_double(theta))
@@ -243,6 +255,48 @@ class Oracle:
         if rc != 0:
             raise ValueError(f"orc_decode_step rejected its arguments (code {rc})")
         return {"next": nxt, "logits": logits, "trace_x": trace, "experts": experts}
+
+
+    def decode_step_q4(self, cfg, qweights, pool, block_size, block_tables, seq_lens, tokens,
+                       want_logits=True, want_trace=False):
+        """decode_step for a dense model whose projections and lm_head are 4-bit
+        (canonical dicts q / scale / bias in place of the bf16 matrices)."""
+        c = self.config(cfg)
+        assert pool.dtype == np.uint16 and pool.flags.c_contiguous
+        L = cfg.n_layers
+        names = ("wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down")
+        structs = (_Layer * L)()
+        keep, mats = [], []
+        for i, lay in enumerate(qweights["layers"]):
+            s = self.layer_struct({k: v for k, v in lay.items() if k not in names})
+            keep.append(s)
+            structs[i] = s
+            mats += [lay[n] for n in names]
+        mats.append(qweights["lm_head"])
+        n = len(mats)
+        qs = [np.ascontiguousarray(m["q"], dtype=np.uint8) for m in mats]
+        ss = [_u16(m["scale"]) for m in mats]
+        bs = [_u16(m["bias"]) for m in mats]
+        qp = (C.c_void_p * n)(*[a.ctypes.data for a in qs])
+        sp = (C.c_void_p * n)(*[a.ctypes.data for a in ss])
+        bp = (C.c_void_p * n)(*[a.ctypes.data for a in bs])
+        bt = _i32(block_tables)
+        sl = _i32(seq_lens)
+        tk = _i32(tokens)
+        B = tk.size
+        assert bt.shape[0] == B and sl.size == B
+        logits = np.empty((B, cfg.vocab), dtype=np.float32) if want_logits else None
+        nxt = np.empty(B, dtype=np.int32)
+        trace = np.empty((L + 1, B, cfg.hidden), dtype=np.float32) if want_trace else None
+        self.lib.orc_decode_step_q4.restype = C.c_int
+        rc = self.lib.orc_decode_step_q4(
+            C.byref(c), structs, qp, sp, bp, _p(_u16(qweights["embed"])), _p(_u16(qweights["g_final"])),
+            _p(pool), C.c_int32(pool.shape[1]), C.c_int32(block_size),
+            _p(bt), C.c_int32(bt.shape[1]), _p(sl), _p(tk), C.c_int32(B),
+            _p(logits), _p(nxt), _p(trace))
+        if rc != 0:
+            raise ValueError(f"orc_decode_step_q4 rejected its arguments (code {rc})")
+        return {"next": nxt, "logits": logits, "trace_x": trace, "experts": None}
 
 
 _CACHE = {}

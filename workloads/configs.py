@@ -77,6 +77,10 @@ CONFIGS = {
     "qwen3_30b_a3b_l4": ModelConfig("qwen3_30b_a3b_l4", 4, 2048, 32, 4, 128, 0, 151936,
                                     rope_theta=1e6, qk_norm=True,
                                     n_experts=128, top_k=8, expert_ffn=768),
+    # Not a benchmark shape: the tiny model with every contraction length a multiple of 128,
+    # which the 4-bit weight format needs.
+    "tiny_q4": ModelConfig("tiny_q4", 2, 256, 4, 2, 64, 768, 1000,
+                           rms_eps=1e-6, rope_theta=1e4, qk_norm=True),
     # Not a benchmark shape: a few-layer MoE small enough for the oracle.
     "tiny_moe": ModelConfig("tiny_moe", 2, 256, 4, 2, 64, 0, 1024,
                             qk_norm=True, n_experts=8, top_k=2, expert_ffn=96),
@@ -116,5 +120,6 @@ WORKLOADS = {
                      shared_prefix=2048, n_sharers=8),
     "cfg4_l4": Workload("cfg4_l4", "qwen3_30b_a3b_l4", 16, 16, 32, context_range=(256, 4096),
                         shared_prefix=2048, n_sharers=8),
+    "cfg0_q4": Workload("cfg0_q4", "tiny_q4", 5, 16, 6, contexts=(40, 16, 3, 0, 65)),
     "cfg0_moe": Workload("cfg0_moe", "tiny_moe", 3, 16, 4, contexts=(33, 16, 5)),
 }

@@ -1,0 +1,53 @@
+"""4-bit weight-only quantisation of generated weights (input preparation).
+
+Group-wise affine 4-bit, the scheme of the 4-bit MLX checkpoints the paper
+benchmarks: every row of a matrix is cut into groups of 64 consecutive
+columns; a group stores 64 codes q in 0..15 and two bf16 numbers, and stands
+for the weights  scale * q + bias.  What the codes, scales and biases are is
+decided here, once, from the seeded bf16 weights; what they MEAN (the
+dequantisation and everything after it) is the method's arithmetic and lives
+in the oracle and in the HIP kernels, each with its own code.
+
+The canonical form is produced: q uint8 [N, K], scale / bias uint16 (bf16 bits)
+[N, K/64].  The oracle reads it as it is; the library's own packed layout is
+made from it by the library's Python front end.
+"""
+import numpy as np
+
+from .generate import f32_from_bf16_bits
+
+GROUP = 64
+
+
+def _bf16_bits_rne(x: np.ndarray) -> np.ndarray:
+    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32).astype(np.uint64)
+    return ((u + 0x7FFF + ((u >> 16) & 1)) >> 16).astype(np.uint16)
+
+
+def quantize_q4(w_bits: np.ndarray) -> dict:
+    """bf16 bit patterns [N, K] (K a multiple of 64) -> canonical 4-bit form."""
+    N, K = w_bits.shape
+    assert K % GROUP == 0
+    w = f32_from_bf16_bits(w_bits).reshape(N, K // GROUP, GROUP)
+    lo, hi = w.min(axis=2), w.max(axis=2)
+    scale = (hi - lo) / 15.0
+    scale[scale == 0.0] = 1.0
+    scale_bits, bias_bits = _bf16_bits_rne(scale), _bf16_bits_rne(lo)
+    s = f32_from_bf16_bits(scale_bits)[:, :, None]
+    b = f32_from_bf16_bits(bias_bits)[:, :, None]
+    q = np.clip(np.rint((w - b) / s), 0, 15).astype(np.uint8).reshape(N, K)
+    return {"q": q, "scale": scale_bits, "bias": bias_bits}
+
+
+MATRICES = ("wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down")
+
+
+def quantize_weights(weights: dict) -> dict:
+    """The 4-bit version of a dense model's weights: every projection matrix and the lm_head in
+    canonical 4-bit form (dict q/scale/bias); embedding and norm gains stay bf16."""
+    out = {"embed": weights["embed"], "g_final": weights["g_final"], "lm_head": quantize_q4(weights["lm_head"]),
+           "layers": []}
+    for L in weights["layers"]:
+        assert "w_router" not in L, "4-bit weights are implemented for dense models"
+        out["layers"].append({k: (quantize_q4(v) if k in MATRICES else v) for k, v in L.items()})
+    return out
