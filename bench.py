@@ -35,15 +35,16 @@ def cpu_baseline(shape, weights, layout, pool_bits, tokens, budget_s=12.0, max_s
     import numpy as np
     from oracle import oracle_f64
     orc = oracle_f64()
+    step = orc.decode_step_q4 if isinstance(weights["lm_head"], dict) else orc.decode_step
     rows = list(range(min(max_rows, len(tokens))))
     pool = pool_bits.copy()
     sl = layout.contexts[rows].copy()
     tok = np.asarray(tokens, dtype=np.int32)[rows].copy()
     tables = layout.tables[rows]
-    orc.decode_step(shape, weights, pool, layout.block_size, tables, sl, tok, want_logits=False)   # warm-up
+    step(shape, weights, pool, layout.block_size, tables, sl, tok, want_logits=False)   # warm-up
     sl, n, t0 = sl + 1, 0, time.perf_counter()
     while n < max_steps and (n == 0 or time.perf_counter() - t0 < budget_s):
-        r = orc.decode_step(shape, weights, pool, layout.block_size, tables, sl, tok, want_logits=False)
+        r = step(shape, weights, pool, layout.block_size, tables, sl, tok, want_logits=False)
         tok, sl, n = r["next"], sl + 1, n + 1
     dt = time.perf_counter() - t0
     threads = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
@@ -206,6 +207,9 @@ def main():
     ap.add_argument("--ttft", action="store_true",
                     help="measure time to first token through the engine with and without a prefix-cache hit "
                          "(512-token shared prefix + 32 own tokens, the shape of the paper's text prefix-cache table)")
+    ap.add_argument("--weights", choices=("bf16", "q4"), default="bf16",
+                    help="q4: the projections and the lm_head as 4-bit group-wise affine codes (groups of 64 "
+                         "columns, bf16 scale and bias), the precision the paper benchmarks; dense workloads")
     ap.add_argument("--kernel-per-stage", action="store_true",
                     help="never take the single persistent kernel (small batches of small dense models)")
     args = ap.parse_args()
@@ -232,6 +236,13 @@ def main():
         return bench_ttft(args, wl, dk, W, np, torch)
     shape, lay = wl.cfg, layout_for(wl)
     weights = W.make_weights(shape, wl.seed_weights)
+    weight_bytes = shape.dense_weight_bytes()
+    if args.weights == "q4":
+        from workloads.quant import quantize_weights
+        if weights["lm_head"] is weights["embed"]:
+            weights = {**weights, "lm_head": weights["embed"].copy()}   # the embedding table stays bf16
+        weights = quantize_weights(weights)
+        weight_bytes = weight_bytes // 4 + weight_bytes // 128 * 4       # 4 bits + (scale, bias) per 64 weights
     pool_bits = W.fill_kv_pool(shape, lay, wl.seed_kv, poison=False)
     tokens0 = W.initial_tokens(shape, wl.batch, wl.seed_tokens)
 
@@ -287,11 +298,11 @@ def main():
                                           distinct_experts_per_layer=distinct)
     kv_bytes = dk.step_algorithmic_bytes(dm.handle, dkv.handle, lay.tables, mean_ctx, with_logits=False,
                                          distinct_experts_per_layer=distinct) \
-        - shape.dense_weight_bytes() - wl.batch * shape.hidden * 2 \
+        - weight_bytes - wl.batch * shape.hidden * 2 \
         - (int(distinct.sum()) * shape.expert_bytes() if distinct is not None else 0)
     expert_bytes = int(distinct.sum()) * shape.expert_bytes() if distinct is not None else 0
     router_bytes = shape.n_layers * shape.n_experts * shape.hidden * 2
-    class_bytes = {"gemv": shape.dense_weight_bytes() - router_bytes, "gemm": shape.dense_weight_bytes() - router_bytes,
+    class_bytes = {"gemv": weight_bytes - router_bytes, "gemm": weight_bytes - router_bytes,
                    "attention": kv_bytes, "moe_expert": expert_bytes, "moe_router": router_bytes,
                    "fused_step": alg_bytes}      # the persistent kernel is the whole step
     step_dev_s = dev_ms * 1e-3 / args.steps
@@ -321,11 +332,11 @@ def main():
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "bf16",
+        "dtype": "bf16" if args.weights == "bf16" else "bf16 activations and KV, 4-bit weights (fp32 accumulation)",
         "data": "synthetic (seeded random-init weights and KV of the named shape)",
         "config": {"workload": f"{wl.name}: {shape.name} decode, batch {wl.batch}, "
                                f"context {int(lay.contexts.min())}..{int(lay.contexts.max())} growing, "
-                               f"block 16, greedy",
+                               f"block 16, greedy" + (", 4-bit weights" if args.weights == "q4" else ""),
                    "batch": wl.batch, "layers": shape.n_layers, "hidden": shape.hidden,
                    "vocab": shape.vocab},
         # the kernel class that takes most of the step; achieved = its algorithmic

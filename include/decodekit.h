@@ -164,6 +164,30 @@ dk_status dk_append_kv(dk_kv_pool *pool, int32_t layer, const int32_t *d_block_t
  * here).  DK_E_UNSUPPORTED_SHAPE for shapes outside the limits above. */
 dk_status dk_create_model(const dk_model_config *cfg, const dk_weight_ptrs *weights,
                           dk_model **out);
+
+/*
+ * The same model with 4-bit weights, the precision of the checkpoints the paper
+ * benchmarks (evaluation setup: 4-bit quantised models): group-wise affine, a
+ * group being 64 consecutive columns of a row with one bf16 scale and one bf16
+ * bias, the weight being  scale * q + bias  for the code q in 0..15.
+ * Dense models only; hidden, n_q_heads*head_dim and ffn multiples of 128.
+ *
+ * Same structs as dk_create_model; g_* and embed stay bf16 as there, while
+ * w_qkv, w_o, w_gate, w_up, w_down and lm_head each point to one packed matrix
+ * [N rows][K columns] (caller-owned device memory, 16-byte aligned) of
+ *     N*K/2 bytes of codes, then ceil(N/16) * K/128 * 128 bytes of scales and biases:
+ *   codes   row after row; a row is K/128 steps of 16 little-endian 32-bit words
+ *           indexed [lg 0..3][s 0..3]; word (lg, s) holds the 8 columns
+ *           step*128 + s*32 + lg*8 + j, column j in bits 4j..4j+3 (j = 0..7);
+ *   scales  per tile of 16 rows and per step 64 bf16 numbers indexed
+ *   biases  [lg 0..3][h 0..1][i 0..3][scale, bias]: the scale and the bias of row
+ *           16*tile + 4*lg + i for the columns step*128 + h*64 .. + 63 (rows past
+ *           N: anything finite).
+ * lm_head must not alias embed.  Steps of such a model run the matrix-core
+ * kernels at every batch size (DK_STEP_NO_FUSED has no effect).
+ */
+dk_status dk_create_model_q4(const dk_model_config *cfg, const dk_weight_ptrs *weights,
+                             dk_model **out);
 dk_status dk_destroy_model(dk_model *model);
 
 /* Bytes of device scratch a decode step needs for batches up to max_B whose

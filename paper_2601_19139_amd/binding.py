@@ -68,6 +68,7 @@ _SIGNATURES = {
     "dk_append_kv": (C.c_int32, [C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p, C.c_int32,
                                  C.c_void_p, C.c_void_p, C.c_void_p]),
     "dk_create_model": (C.c_int32, [C.POINTER(ModelConfig), C.POINTER(WeightPtrs), C.POINTER(C.c_void_p)]),
+    "dk_create_model_q4": (C.c_int32, [C.POINTER(ModelConfig), C.POINTER(WeightPtrs), C.POINTER(C.c_void_p)]),
     "dk_destroy_model": (C.c_int32, [C.c_void_p]),
     "dk_workspace_bytes": (C.c_int32, [C.c_void_p, C.c_int32, C.c_int32, C.POINTER(C.c_size_t)]),
     "dk_decode_step": (C.c_int32, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p,
@@ -246,6 +247,12 @@ def append_kv(pool, layer, d_block_tables, d_seq_lens, d_k, d_v, stream=None):
 def create_model(cfg: ModelConfig, weights: WeightPtrs):
     out = C.c_void_p()
     _check(lib().dk_create_model(C.byref(cfg), C.byref(weights), C.byref(out)))
+    return out
+
+
+def create_model_q4(cfg: ModelConfig, weights: WeightPtrs):
+    out = C.c_void_p()
+    _check(lib().dk_create_model_q4(C.byref(cfg), C.byref(weights), C.byref(out)))
     return out
 
 

@@ -127,6 +127,7 @@ struct dk_model {
     dk_model_config cfg;
     const void *embed, *lm_head, *g_final;
     std::vector<dk_layer_weights> layers;
+    bool q4 = false;   // projection matrices and lm_head are packed 4-bit (dk_create_model_q4)
     double inv_freq[64];
     Profiler prof;
     // persistent step kernel: the workspace whose buffer sets hold the "not
@@ -183,13 +184,14 @@ int fused_variant(const dk_model_config &c, int B)
 
 // The matrix-core attention kernel pays off once the group of query heads that
 // share a kv head is large (the vector-ALU kernel's multiply-adds grow with it).
-bool attention_uses_mfma(const dk_model_config &c, int B)
+bool attention_uses_mfma(const dk_model_config &c, int B, bool q4)
 {
-    const bool batched = B > kMaxGemvBatch || c.n_experts > 0;
+    const bool batched = B > kMaxGemvBatch || c.n_experts > 0 || q4;
     return batched && c.n_q_heads / c.n_kv_heads >= 4;
 }
 
-Workspace carve(const dk_model_config &c, int B, int max_blocks)
+// q4: the model's matrices are 4-bit; every batch size then takes the matrix-core kernels
+Workspace carve(const dk_model_config &c, int B, int max_blocks, bool q4)
 {
     Workspace w{};
     const int d = c.head_dim, G = c.n_q_heads / c.n_kv_heads;
@@ -201,7 +203,7 @@ Workspace carve(const dk_model_config &c, int B, int max_blocks)
     // measured on 8B-class shapes: the matrix-core kernel (query groups of 4 and
     // more) runs best with about two blocks per compute unit, the vector-ALU one
     // with about four
-    const int want_blocks = attention_uses_mfma(c, B) ? 512 : 1024;
+    const int want_blocks = attention_uses_mfma(c, B, q4) ? 512 : 1024;
     int want_chunks = (want_blocks + B * c.n_kv_heads - 1) / (B * c.n_kv_heads);
     if (want_chunks < 1) want_chunks = 1;
     int chunk = (ctx_max + want_chunks - 1) / want_chunks;
@@ -214,7 +216,7 @@ Workspace carve(const dk_model_config &c, int B, int max_blocks)
     // the output projection then merges them as it loads its input (at most 8
     // chunks, one round of loads), which saves the attention kernel a round of
     // device-wide synchronisation.
-    if (B <= kMaxGemvBatch && c.n_experts == 0) {   // the vector-ALU path only
+    if (B <= kMaxGemvBatch && c.n_experts == 0 && !q4) {   // the vector-ALU path only
         int chunk8 = ((ctx_max + 7) / 8 + 63) / 64 * 64;
         if (chunk8 < chunk) chunk8 = chunk;
         const int n8 = (ctx_max + chunk8 - 1) / chunk8;
@@ -238,7 +240,7 @@ Workspace carve(const dk_model_config &c, int B, int max_blocks)
     w.part = take((size_t)B * c.n_kv_heads * w.max_chunks * G * (d + 2) * 4);
     w.tickets = take((size_t)B * c.n_kv_heads * 4);
     w.pf_seq = take((size_t)DK_MAX_BATCH * 4);   // positions of a prefill chunk's rows
-    w.batched = B > kMaxGemvBatch || c.n_experts > 0;   // expert layers use the matrix-core kernels
+    w.batched = B > kMaxGemvBatch || c.n_experts > 0 || q4;   // expert layers and 4-bit weights use the matrix-core kernels
     w.Bp = (B + 15) / 16 * 16;
     if (w.batched) {
         w.lm_blocks = (c.vocab + 15) / 16;
@@ -266,7 +268,7 @@ Workspace carve(const dk_model_config &c, int B, int max_blocks)
     }
     w.pmax_val = take((size_t)B * w.lm_blocks * 4);
     w.pmax_idx = take((size_t)B * w.lm_blocks * 4);
-    w.fused = fused_variant(c, B) >= 0;
+    w.fused = !q4 && fused_variant(c, B) >= 0;
     if (w.fused) {
         w.fused_chunks = (ctx_max + dk::kFusedChunk - 1) / dk::kFusedChunk;
         w.fused_set_floats = dk::fused_layout(c.n_layers, B, c.hidden, c.n_q_heads, c.n_kv_heads, d, c.ffn,
@@ -345,14 +347,14 @@ dk_status launch_gemv(dk::GemvArgs a, int B, hipStream_t st)
 }
 
 // ---- skinny GEMM dispatch (batches of 5..64 rows) ---------------------------
-template <int MT, int KS, int RT, int EPI, bool NORM, bool KALIGNED>
+template <int MT, int KS, int RT, int EPI, bool NORM, bool KALIGNED, bool Q4 = false>
 dk_status launch_gemm_inst(const dk::GemmArgs &a, hipStream_t st)
 {
     constexpr size_t lds = dk::skinny_gemm_lds_bytes<MT, KS, RT, EPI>();
     static_assert(lds <= (64u << 10), "dynamic LDS above 64 KB would need a function attribute");
     const int grid = (a.N + 16 * RT - 1) / (16 * RT);
     constexpr int PD = 2;   // K-steps in flight per wave (deeper did not measure faster)
-    DK_LAUNCH(DK_K_GEMM, (dk::skinny_gemm_kernel<MT, KS, RT, PD, EPI, NORM, KALIGNED>), dim3(grid),
+    DK_LAUNCH(DK_K_GEMM, (dk::skinny_gemm_kernel<MT, KS, RT, PD, EPI, NORM, KALIGNED, Q4>), dim3(grid),
               dim3(KS * 64), lds, st, a);
     DK_HIP(hipGetLastError());
     return DK_OK;
@@ -361,6 +363,10 @@ dk_status launch_gemm_inst(const dk::GemmArgs &a, hipStream_t st)
 template <int MT, int KS, int RT, int EPI, bool NORM>
 dk_status launch_gemm_cfg(const dk::GemmArgs &a, hipStream_t st)
 {
+    if (a.q4) {
+        if (a.K % 128) return fail(DK_E_UNSUPPORTED_SHAPE, "4-bit matrix with K = %d (a multiple of 128 is needed)", a.K);
+        return launch_gemm_inst<MT, KS, RT, EPI, NORM, true, true>(a, st);
+    }
     if (a.K % 128 == 0) return launch_gemm_inst<MT, KS, RT, EPI, NORM, true>(a, st);
     return launch_gemm_inst<MT, KS, RT, EPI, NORM, false>(a, st);
 }
@@ -508,7 +514,7 @@ const char *dk_last_error(void) { return g_err; }
 
 // The kernel revisions change whenever a kernel's memory behaviour changes; the
 // benchmark quotes stored counter measurements only for a matching revision.
-const char *dk_version(void) { return "decodekit 0.7 (gfx950; gemv r3, gemm r7, attention r6, moe r4, fused r2, prefill r1, sample r1)"; }
+const char *dk_version(void) { return "decodekit 0.8 (gfx950; gemv r3, gemm r8, attention r6, moe r4, fused r2, prefill r1, sample r1)"; }
 
 // ------------------------------------------------------------------- pool --
 dk_status dk_kv_pool_bytes(const dk_model_config *cfg, int32_t num_blocks, int32_t block_size,
@@ -711,6 +717,24 @@ dk_status dk_create_model(const dk_model_config *cfg, const dk_weight_ptrs *w, d
     return DK_OK;
 }
 
+dk_status dk_create_model_q4(const dk_model_config *cfg, const dk_weight_ptrs *w, dk_model **out)
+{
+    dk_status s = check_config(cfg);
+    if (s != DK_OK) return s;
+    if (cfg->n_experts > 0)
+        return fail(DK_E_UNSUPPORTED_SHAPE, "4-bit weights are implemented for dense models");
+    const int qd = cfg->n_q_heads * cfg->head_dim;
+    if (cfg->hidden % 128 || qd % 128 || cfg->ffn % 128)
+        return fail(DK_E_UNSUPPORTED_SHAPE,
+                    "4-bit weights need hidden, n_q_heads*head_dim and ffn to be multiples of 128 (got %d, %d, %d)",
+                    cfg->hidden, qd, cfg->ffn);
+    if (w && w->embed && w->embed == w->lm_head)
+        return fail(DK_E_INVALID_ARG, "the embedding stays bf16 and cannot double as the 4-bit lm_head");
+    if ((s = dk_create_model(cfg, w, out)) != DK_OK) return s;
+    (*out)->q4 = true;
+    return DK_OK;
+}
+
 dk_status dk_destroy_model(dk_model *model)
 {
     delete model;
@@ -723,7 +747,7 @@ dk_status dk_workspace_bytes(const dk_model *model, int32_t max_B, int32_t max_b
     if (!model || !out_bytes) return fail(DK_E_INVALID_ARG, "NULL argument");
     if (max_B <= 0 || max_B > DK_MAX_BATCH) return fail(DK_E_INVALID_ARG, "max_B %d (1..%d)", max_B, DK_MAX_BATCH);
     if (max_blocks <= 0) return fail(DK_E_INVALID_ARG, "max_blocks_per_seq %d", max_blocks);
-    *out_bytes = carve(model->cfg, max_B, max_blocks).total;
+    *out_bytes = carve(model->cfg, max_B, max_blocks, model->q4).total;
     return DK_OK;
 }
 
@@ -781,7 +805,7 @@ dk_status dk_prefill_chunk(dk_model *model, dk_kv_pool *pool, const int32_t *d_b
         return fail(DK_E_INVALID_ARG, "positions %d..%d do not fit a table of %d blocks", start, start + n - 1,
                     max_blocks);
     if ((uintptr_t)d_workspace % 256) return fail(DK_E_INVALID_ARG, "workspace must be 256-byte aligned");
-    const Workspace w = carve(model->cfg, n, max_blocks);
+    const Workspace w = carve(model->cfg, n, max_blocks, model->q4);
     if (workspace_bytes < w.total)
         return fail(DK_E_WORKSPACE_TOO_SMALL, "workspace %zu bytes, %zu needed", workspace_bytes, w.total);
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
@@ -922,7 +946,7 @@ static dk_status decode_step_impl(dk_model *model, dk_kv_pool *pool, const int32
     if (pc.n_layers != c.n_layers || pc.n_kv_heads != c.n_kv_heads || pc.head_dim != c.head_dim)
         return fail(DK_E_INVALID_ARG, "pool was created for a different model shape");
     if ((uintptr_t)d_workspace % 256) return fail(DK_E_INVALID_ARG, "workspace must be 256-byte aligned");
-    const Workspace w = carve(c, B, max_blocks);
+    const Workspace w = carve(c, B, max_blocks, model->q4);
     if (workspace_bytes < w.total)
         return fail(DK_E_WORKSPACE_TOO_SMALL, "workspace %zu bytes, %zu needed", workspace_bytes, w.total);
 
@@ -990,6 +1014,7 @@ static dk_status decode_step_impl(dk_model *model, dk_kv_pool *pool, const int32
             g.N = qkv_dim;
             g.K = H;
             g.B = B;
+            g.q4 = model->q4;
             g.xhi = xhi;
             g.xlo = xlo;
             g.ssq_in = ssq;
@@ -1059,7 +1084,7 @@ static dk_status decode_step_impl(dk_model *model, dk_kv_pool *pool, const int32
             a.scale = (float)(1.0 / std::sqrt((double)d));
             a.eps = eps;
             const dim3 grid(w.max_chunks, nkv, B);
-            const bool use_mfma = attention_uses_mfma(c, B);
+            const bool use_mfma = attention_uses_mfma(c, B, model->q4);
             s = (d == 128) ? launch_attention_d<128>(a, nq / nkv, grid, use_mfma, st)
                            : launch_attention_d<64>(a, nq / nkv, grid, use_mfma, st);
             if (s != DK_OK) return s;
@@ -1071,6 +1096,7 @@ static dk_status decode_step_impl(dk_model *model, dk_kv_pool *pool, const int32
             g.N = H;
             g.K = nq * d;
             g.B = B;
+            g.q4 = model->q4;
             g.xhi = ahi;
             g.xlo = alo;
             g.xres = x;
@@ -1195,6 +1221,7 @@ static dk_status decode_step_impl(dk_model *model, dk_kv_pool *pool, const int32
             g.N = c.ffn;
             g.K = H;
             g.B = B;
+            g.q4 = model->q4;
             g.xhi = xhi;
             g.xlo = xlo;
             g.ssq_in = ssq;
@@ -1208,6 +1235,7 @@ static dk_status decode_step_impl(dk_model *model, dk_kv_pool *pool, const int32
             h.N = H;
             h.K = c.ffn;
             h.B = B;
+            h.q4 = model->q4;
             h.xhi = fhi;
             h.xlo = flo;
             h.xres = x;
@@ -1248,6 +1276,7 @@ static dk_status decode_step_impl(dk_model *model, dk_kv_pool *pool, const int32
         g.N = c.vocab;
         g.K = H;
         g.B = B;
+        g.q4 = model->q4;
         g.xhi = xhi;
         g.xlo = xlo;
         g.ssq_in = ssq;
@@ -1313,7 +1342,7 @@ dk_status dk_step_routing(const dk_model *model, const void *d_workspace, int32_
     if (!model || !d_workspace || !h_out) return fail(DK_E_INVALID_ARG, "NULL argument");
     if (model->cfg.n_experts <= 0) return fail(DK_E_INVALID_ARG, "the model has no expert layers");
     if (B <= 0 || B > DK_MAX_BATCH || max_blocks <= 0) return fail(DK_E_INVALID_ARG, "B %d, max_blocks_per_seq %d", B, max_blocks);
-    const Workspace w = carve(model->cfg, B, max_blocks);
+    const Workspace w = carve(model->cfg, B, max_blocks, model->q4);
     const size_t bytes = (size_t)model->cfg.n_layers * B * model->cfg.top_k * 4;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     DK_HIP(hipMemcpyAsync(h_out, static_cast<const char *>(d_workspace) + w.topk_idx, bytes,
@@ -1342,7 +1371,14 @@ dk_status dk_step_algorithmic_bytes(const dk_model *model, const dk_kv_pool *poo
     } else {
         per_layer += 3 * H * (uint64_t)c.ffn;
     }
-    bytes += 2 * ((uint64_t)c.n_layers * per_layer + (uint64_t)c.vocab * H);
+    const uint64_t weights = (uint64_t)c.n_layers * per_layer + (uint64_t)c.vocab * H;
+    if (model->q4) {
+        // half a byte per weight plus a bf16 scale and bias per 64 weights; norm gains aside,
+        // every matrix of a 4-bit model is in that format
+        bytes += weights / 2 + weights / 64 * 4;
+    } else {
+        bytes += 2 * weights;
+    }
     // live KV: every distinct (block, slot) once, including this step's token
     std::set<int64_t> slots;
     for (int32_t b = 0; b < B; b++) {

@@ -19,6 +19,17 @@
 // loads is one contiguous 1 KB run per wave.  With NORM the RMSNorm of
 // the input is fused: the producer stored (x * gain) as hi/lo plus per-tile
 // sums of x^2; the scalar 1/rms per batch row is applied in the epilogue.
+//
+// Q4: the weights are 4-bit codes with a bf16 scale and bias per group of 64
+// columns (w = scale * q + bias).  A lane's 16-byte load then carries a whole
+// K-step (32 codes) of its row.  The product is evaluated exactly as
+//   sum_g ( scale_g * sum_{k in g} q_k x_k  +  bias_g * sum_{k in g} x_k ):
+// the codes go to the matrix cores as the bf16 numbers 0..15, a second product
+// with an all-ones operand gives the group sums of x, and fused multiply-adds
+// apply scale and bias to the fp32 tiles.  (Feeding the codes as 128 + q, which
+// is a two-instruction bit pattern, was measured to cost three decimal digits:
+// the matrix cores do not keep the full fp32 sum while adding products, and the
+// offset term, 17 times the useful one, has to cancel afterwards.)
 #pragma once
 #include "dk_common.hip.h"
 
@@ -32,9 +43,10 @@ enum { GEPI_STORE = 0, GEPI_RESID = 1, GEPI_SWIGLU = 2 };
 constexpr int kSsqStride = 64;  // floats per row of the sum-of-squares partial table
 
 struct GemmArgs {
-    const uint16_t *W;       // [N][K]
-    const uint16_t *W2;      // GEPI_SWIGLU: the "up" matrix [N][K]
+    const uint16_t *W;       // [N][K] bf16; Q4: the packed 4-bit matrix (codes, then scale/bias tiles)
+    const uint16_t *W2;      // GEPI_SWIGLU: the "up" matrix, same format as W
     int N, K, B;             // B valid batch rows (<= 16*MT)
+    int q4;                  // host side only: W / W2 are packed 4-bit matrices (selects the Q4 kernels)
     const uint16_t *xhi;     // hi part of the input, bf16 in act_offset() order
     const uint16_t *xlo;     // lo part
     // NORM: sum over p < n_part of ssq_in[p][n] = sum_k x[n][k]^2
@@ -70,9 +82,14 @@ __device__ __forceinline__ bf16x8_t as_bf16x8(const uint4 &u)
 
 // KALIGNED: K is a multiple of 128 (every real model shape); the K-steps are then
 // whole and the loaded registers feed the MFMAs untouched.
-template <int MT, int KS, int RT, int PD, int EPI, bool NORM, bool KALIGNED>
+// Q4 (needs KALIGNED): per row K/2 bytes of codes, a K-step of 128 columns being 16 words
+// [lane group lg][sub-step s] whose nibble j (bits 4j..4j+3) is column s*32 + lg*8 + j;
+// after the N rows, per 16-row tile and K-step 128 bytes [lg][group h of the step][row 4*lg+i]
+// of (scale, bias) bf16 pairs - the order in which the accumulator lanes need them.
+template <int MT, int KS, int RT, int PD, int EPI, bool NORM, bool KALIGNED, bool Q4 = false>
 __global__ __launch_bounds__(KS * 64) void skinny_gemm_kernel(GemmArgs a)
 {
+    static_assert(!Q4 || KALIGNED, "4-bit weights need whole K-steps");
     constexpr int NM = (EPI == GEPI_SWIGLU) ? 2 : 1;
     constexpr int NA = NM * RT;   // weight tiles (accumulator sets) per wave
     static_assert(KS * NA * MT <= 32, "LDS reduction buffer is limited to 32 KB");
@@ -108,6 +125,30 @@ __global__ __launch_bounds__(KS * 64) void skinny_gemm_kernel(GemmArgs a)
         const int g = (int)blockIdx.x;
         const int ks = min(it_i * KS + wv, nks - 1);
         const int kb = ks * 128 + lg * 8;
+        if constexpr (Q4) {
+            const int n_tiles16 = (N + 15) >> 4;
+#pragma unroll
+            for (int m = 0; m < NA; m++) {
+                const uint8_t *base = reinterpret_cast<const uint8_t *>((m / RT) ? a.W2 : a.W);
+                const int tile = min(g * RT + (m % RT), n_tiles16 - 1);
+                const int wrow = min(tile * 16 + ln, N - 1);
+                st.wa[m][0] = ld16(base + (int64_t)wrow * (K >> 1) + ks * 64 + lg * 16);
+                const uint8_t *sb = base + (int64_t)N * (K >> 1) + (((int64_t)tile * nks + ks) * 4 + lg) * 32;
+                st.wa[m][1] = ld16(sb);
+                st.wa[m][2] = ld16(sb + 16);
+            }
+            const int64_t xb = ((int64_t)ks * 4 * 64 + lane) * 8;
+#pragma unroll
+            for (int s = 0; s < 4; s++)
+#pragma unroll
+                for (int t = 0; t < MT; t++) {
+                    const int64_t xo = xb + ((int64_t)t * nks * 4 + s) * 512;
+                    st.bh[t][s] = ld16(a.xhi + xo);
+                    st.bl[t][s] = ld16(a.xlo + xo);
+                }
+            it_i++;
+            return;
+        }
         const uint16_t *wq[NA];
 #pragma unroll
         for (int m = 0; m < NA; m++) {
@@ -134,6 +175,57 @@ __global__ __launch_bounds__(KS * 64) void skinny_gemm_kernel(GemmArgs a)
     auto consume = [&](Stage &st, int it) {
         const int ks = it * KS + wv;
         if (ks >= nks) return;   // a padding step of this wave (uniform branch)
+        if constexpr (Q4) {
+            const uint4 one4 = make_uint4(0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u);
+            const f32x4_t zero = f32x4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int h = 0; h < 2; h++) {
+                // group sums of x for this lane's batch row (the same in all four accumulator rows)
+                f32x4_t S[MT];
+#pragma unroll
+                for (int t = 0; t < MT; t++) {
+                    S[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(one4), as_bf16x8(st.bh[t][2 * h]), zero, 0, 0, 0);
+                    S[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(one4), as_bf16x8(st.bl[t][2 * h]), S[t], 0, 0, 0);
+                    S[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(one4), as_bf16x8(st.bh[t][2 * h + 1]), S[t], 0, 0, 0);
+                    S[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(one4), as_bf16x8(st.bl[t][2 * h + 1]), S[t], 0, 0, 0);
+                }
+#pragma unroll
+                for (int m = 0; m < NA; m++) {
+                    const uint4 sb = st.wa[m][1 + h];
+                    const uint32_t sbw[4] = {sb.x, sb.y, sb.z, sb.w};
+                    float sc[4], b2[4];
+#pragma unroll
+                    for (int i = 0; i < 4; i++) {
+                        sc[i] = __uint_as_float(sbw[i] << 16);
+                        b2[i] = __uint_as_float(sbw[i] & 0xFFFF0000u);
+                    }
+                    // the eight codes of a word as exact bf16 numbers: bytes of nibbles, byte -> float,
+                    // then the upper halves of two floats side by side
+                    auto codes = [](uint32_t w) {
+                        const uint32_t ev = w & 0x0F0F0F0Fu, od = (w >> 4) & 0x0F0F0F0Fu;
+                        uint4 r;
+                        r.x = __builtin_amdgcn_perm(__float_as_uint((float)(od & 0xFFu)), __float_as_uint((float)(ev & 0xFFu)), 0x07060302u);
+                        r.y = __builtin_amdgcn_perm(__float_as_uint((float)((od >> 8) & 0xFFu)), __float_as_uint((float)((ev >> 8) & 0xFFu)), 0x07060302u);
+                        r.z = __builtin_amdgcn_perm(__float_as_uint((float)((od >> 16) & 0xFFu)), __float_as_uint((float)((ev >> 16) & 0xFFu)), 0x07060302u);
+                        r.w = __builtin_amdgcn_perm(__float_as_uint((float)(od >> 24)), __float_as_uint((float)(ev >> 24)), 0x07060302u);
+                        return r;
+                    };
+                    const uint4 a0 = codes(h ? st.wa[m][0].z : st.wa[m][0].x);
+                    const uint4 a1 = codes(h ? st.wa[m][0].w : st.wa[m][0].y);
+#pragma unroll
+                    for (int t = 0; t < MT; t++) {
+                        f32x4_t D = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(a0), as_bf16x8(st.bh[t][2 * h]), zero, 0, 0, 0);
+                        D = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(a0), as_bf16x8(st.bl[t][2 * h]), D, 0, 0, 0);
+                        D = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(a1), as_bf16x8(st.bh[t][2 * h + 1]), D, 0, 0, 0);
+                        D = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(a1), as_bf16x8(st.bl[t][2 * h + 1]), D, 0, 0, 0);
+#pragma unroll
+                        for (int i = 0; i < 4; i++)
+                            acc[m][t][i] = fmaf(sc[i], D[i], fmaf(b2[i], S[t][i], acc[m][t][i]));
+                    }
+                }
+            }
+            return;
+        }
         if (KALIGNED) {
 #pragma unroll
             for (int s = 0; s < 4; s++)

@@ -10,26 +10,30 @@ GROUP = 64
 
 
 def pack_q4(*mats: dict) -> np.ndarray:
-    """Canonical matrices with the same K, stacked by rows, in the library's layout:
-    code words, then all scales, then all biases.
-
-    Codes: per row, K/128 steps of 128 columns; a step is 16 little-endian 32-bit words
-    [4 lane groups lg][4 sub-steps s]; word (lg, s) holds the 8 columns
-    step*128 + s*32 + lg*8 + j:  nibble i (bits 4i..4i+3) is column j = 2i, nibble 4+i is
-    column j = 2i+1  (i = 0..3)."""
-    q = np.concatenate([m["q"] for m in mats], axis=0)
+    """Canonical matrices with the same K, stacked by rows, as one packed matrix in the
+    layout dk_create_model_q4 documents: N*K/2 bytes of codes, then per 16-row tile and
+    128-column step 128 bytes of (scale, bias) pairs.  Returns uint8."""
+    q = np.concatenate([np.asarray(m["q"], dtype=np.uint8) for m in mats], axis=0)
+    scale = np.concatenate([np.asarray(m["scale"], dtype=np.uint16) for m in mats], axis=0)
+    bias = np.concatenate([np.asarray(m["bias"], dtype=np.uint16) for m in mats], axis=0)
     N, K = q.shape
-    assert K % 128 == 0
-    v = q.reshape(N, K // 128, 4, 4, 4, 2).astype(np.uint32)       # [row][step][s][lg][i][parity]
-    v = v.transpose(0, 1, 3, 2, 4, 5)                               # [row][step][lg][s][i][parity]
-    shifts = (4 * np.arange(4, dtype=np.uint32))[:, None] + np.array([0, 16], dtype=np.uint32)[None, :]
-    words = (v << shifts).sum(axis=(4, 5), dtype=np.uint32)         # [row][step][lg][s]
-    scale = np.concatenate([m["scale"] for m in mats], axis=0)
-    bias = np.concatenate([m["bias"] for m in mats], axis=0)
-    return np.concatenate([words.astype("<u4").reshape(-1).view(np.uint8), scale.reshape(-1).view(np.uint8),
-                           bias.reshape(-1).view(np.uint8)])
+    if K % 128 or scale.shape != (N, K // GROUP) or bias.shape != scale.shape:
+        raise ValueError("4-bit matrix: K must be a multiple of 128, scale/bias [N, K/64]")
+    # codes: word (lg, s) of a step holds columns s*32 + lg*8 + j, column j in bits 4j..4j+3
+    v = q.reshape(N, K // 128, 4, 4, 8).astype(np.uint32)          # [row][step][s][lg][j]
+    v = v.transpose(0, 1, 3, 2, 4)                                  # [row][step][lg][s][j]
+    words = (v << (4 * np.arange(8, dtype=np.uint32))).sum(axis=4, dtype=np.uint32)   # [row][step][lg][s]
+    # scales and biases: [tile][step][lg][h][i][scale, bias] for row 16*tile + 4*lg + i
+    tiles = (N + 15) // 16
+    sb = np.zeros((tiles * 16, K // GROUP, 2), dtype=np.uint16)
+    sb[:N, :, 0] = scale
+    sb[:N, :, 1] = bias
+    sb = sb.reshape(tiles, 4, 4, K // 128, 2, 2)                    # [tile][lg][i][step][h][sb]
+    sb = sb.transpose(0, 3, 1, 4, 2, 5)                             # [tile][step][lg][h][i][sb]
+    return np.concatenate([words.astype("<u4").reshape(-1).view(np.uint8),
+                           np.ascontiguousarray(sb).reshape(-1).view(np.uint8)])
 
 
 def q4_bytes(n: int, k: int) -> int:
-    """Bytes of a packed [n, k] matrix: half a byte per weight plus two bf16 per group of 64."""
-    return n * k // 2 + 2 * n * (k // GROUP) * 2
+    """Bytes of a packed [n, k] matrix."""
+    return n * k // 2 + (n + 15) // 16 * (k // 128) * 128

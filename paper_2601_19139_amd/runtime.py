@@ -6,6 +6,7 @@ import ctypes as C
 import numpy as np
 
 from . import binding as dk
+from .q4 import pack_q4
 
 
 def _torch():
@@ -24,16 +25,23 @@ def _dev_bf16(bits: np.ndarray):
 
 class DeviceModel:
     """Weights resident in HBM + the library's model handle.  q, k and v
-    matrices are stored as one [(nq+2nkv)*d, H] matrix (rows q, then k, then v)."""
+    matrices are stored as one [(nq+2nkv)*d, H] matrix (rows q, then k, then v).
+
+    Matrices given as dicts (q / scale / bias: the canonical 4-bit form) make a
+    4-bit model: every projection and the lm_head must then be in that form."""
 
     def __init__(self, shape, weights: dict):
         self.shape = shape
         self.cfg = dk.ModelConfig.from_shape(shape)
         self.tensors = []
         keep = self.tensors.append
+        self.q4 = isinstance(weights["lm_head"], dict)
 
-        def up(a):
-            t = _dev_bf16(a)
+        def up(*a):
+            if self.q4 and isinstance(a[0], dict):
+                t = _torch().from_numpy(pack_q4(*a)).cuda()
+            else:
+                t = _dev_bf16(a[0] if len(a) == 1 else np.concatenate(a, axis=0))
             keep(t)
             return t.data_ptr()
 
@@ -44,7 +52,7 @@ class DeviceModel:
         for i, L in enumerate(weights["layers"]):
             s = self._layers[i]
             s.g_attn = up(L["g_attn"])
-            s.w_qkv = up(np.concatenate([L["wq"], L["wk"], L["wv"]], axis=0))
+            s.w_qkv = up(L["wq"], L["wk"], L["wv"])
             s.g_q = up(L["g_q"]) if "g_q" in L else None
             s.g_k = up(L["g_k"]) if "g_k" in L else None
             s.w_o = up(L["wo"])
@@ -54,7 +62,7 @@ class DeviceModel:
             s.w_down = up(L["w_down"])
             s.w_router = up(L["w_router"]) if "w_router" in L else None
         self._ptrs = dk.WeightPtrs(embed, lm_head, g_final, self._layers)
-        self.handle = dk.create_model(self.cfg, self._ptrs)
+        self.handle = (dk.create_model_q4 if self.q4 else dk.create_model)(self.cfg, self._ptrs)
 
     def close(self):
         if self.handle is not None:

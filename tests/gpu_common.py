@@ -41,8 +41,10 @@ def run_both(orc, shape, weights, layout, pool_bits, tokens, steps, teacher_forc
            "gpu_experts": [], "orc_experts": []}
     for s in range(steps):
         dk.kv_validate_tables(dkv.handle, layout.tables, sl)
-        r = orc.decode_step(shape, weights, opool, layout.block_size, layout.tables, sl, otok,
-                            want_trace=bool(shape.n_experts))
+        # a 4-bit model (matrices given as q / scale / bias) takes the oracle's 4-bit step
+        step = orc.decode_step_q4 if isinstance(weights["lm_head"], dict) else orc.decode_step
+        r = step(shape, weights, opool, layout.block_size, layout.tables, sl, otok,
+                 want_trace=bool(shape.n_experts))
         dec.step(flags=gpu_flags)
         torch.cuda.synchronize()
         if shape.n_experts:
@@ -120,8 +122,8 @@ def run_sampled(orc, shape, weights, layout, pool_bits, tokens, steps, rows):
     out = {"gpu_logits": [], "orc_logits": [], "gpu_next": [], "orc_next": []}
     for s in range(steps):
         dk.kv_validate_tables(dkv.handle, layout.tables, sl)
-        r = orc.decode_step(shape, weights, opool, layout.block_size, layout.tables[rows], sl[rows],
-                            tok[rows])
+        step = orc.decode_step_q4 if isinstance(weights["lm_head"], dict) else orc.decode_step
+        r = step(shape, weights, opool, layout.block_size, layout.tables[rows], sl[rows], tok[rows])
         dec.step()
         torch.cuda.synchronize()
         g_next = dec.next.cpu().numpy().copy()

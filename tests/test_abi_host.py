@@ -177,6 +177,63 @@ def test_model_shape_checks_and_workspace():
     assert "layer 5" in str(e.value)
 
 
+def test_q4_model_checks_and_bytes():
+    """dk_create_model_q4: dense shapes with every contraction length a multiple of 128; the
+    algorithmic bytes count 4.5 bits per weight."""
+    shape = W.CONFIGS["qwen3_8b"]
+    cfg, ptrs, _keep = fake_model(shape)
+    with pytest.raises(dk.DecodeKitError) as e:       # fake_model aliases lm_head and embed
+        dk.create_model_q4(cfg, ptrs)
+    assert e.value.status == "DK_E_INVALID_ARG"
+    ptrs.lm_head = 0x2000
+    m = dk.create_model_q4(cfg, ptrs)
+    lay = layout_for(W.WORKLOADS["cfg3"])
+    pool = dk.create_kv_pool(cfg, lay.num_blocks, 16, 0x1000, dk.kv_pool_bytes(cfg, lay.num_blocks, 16))
+    got = dk.step_algorithmic_bytes(m, pool, lay.tables, lay.contexts, with_logits=False)
+    n_weights = shape.dense_weight_bytes() // 2
+    want = (n_weights // 2 + n_weights // 64 * 4
+            + lay.unique_live_tokens(extra=1) * shape.kv_bytes_per_token() + 16 * shape.hidden * 2)
+    assert got == want
+    # every batch size takes the batched path: the workspace holds the bf16 hi/lo activations
+    m16 = dk.create_model(cfg, ptrs)
+    assert dk.workspace_bytes(m, 1, 40) > dk.workspace_bytes(m16, 1, 40)
+    dk.destroy_model(m16)
+    dk.destroy_kv_pool(pool)
+    dk.destroy_model(m)
+    for sname in ("tiny", "tiny_moe"):                # ffn 688; mixture of experts
+        c2, p2, _k2 = fake_model(W.CONFIGS[sname])
+        p2.lm_head = 0x2000
+        with pytest.raises(dk.DecodeKitError) as e:
+            dk.create_model_q4(c2, p2)
+        assert e.value.status == "DK_E_UNSUPPORTED_SHAPE", sname
+
+
+def test_pack_q4_layout():
+    """The packed 4-bit layout, element by element against its description."""
+    from paper_2601_19139_amd import pack_q4, q4_bytes
+    rng = np.random.default_rng(1)
+    N, K = 21, 256
+    m = {"q": rng.integers(0, 16, size=(N, K), dtype=np.uint8),
+         "scale": rng.integers(0, 65536, size=(N, K // 64), dtype=np.uint16),
+         "bias": rng.integers(0, 65536, size=(N, K // 64), dtype=np.uint16)}
+    buf = pack_q4(m)
+    assert buf.dtype == np.uint8 and buf.size == q4_bytes(N, K) == N * K // 2 + 2 * 2 * 128
+    words = buf[:N * K // 2].view("<u4").reshape(N, K // 128, 4, 4)
+    sb = buf[N * K // 2:].view(np.uint16).reshape(2, K // 128, 4, 2, 4, 2)
+    for _ in range(300):
+        r, k = int(rng.integers(N)), int(rng.integers(K))
+        step, s, lg, j = k // 128, (k % 128) // 32, (k % 32) // 8, k % 8
+        nib = (int(words[r, step, lg, s]) >> (4 * j)) & 15
+        assert nib == m["q"][r, k]
+        t, lgr, i, h = r // 16, (r % 16) // 4, r % 4, (k % 128) // 64
+        assert sb[t, step, lgr, h, i, 0] == m["scale"][r, k // 64]
+        assert sb[t, step, lgr, h, i, 1] == m["bias"][r, k // 64]
+    # stacking by rows equals packing the stacked matrix
+    a = {k: v[:16] for k, v in m.items()}
+    b = {k: v[16:] for k, v in m.items()}
+    assert np.array_equal(pack_q4(a, b), buf)
+
+
 @pytest.mark.parametrize("wname,expect_gb", [("cfg1", 1.251), ("cfg3", 24.80)])
 def test_algorithmic_bytes_match_the_formula(wname, expect_gb):
     wl = W.WORKLOADS[wname]

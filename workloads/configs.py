@@ -72,6 +72,9 @@ CONFIGS = {
     "qwen3_30b_a3b": ModelConfig("qwen3_30b_a3b", 48, 2048, 32, 4, 128, 0, 151936,
                                  rope_theta=1e6, qk_norm=True,
                                  n_experts=128, top_k=8, expert_ffn=768),
+    # The 8B shape cut to 4 layers: every kernel at its real size, a tenth of the weights.
+    "qwen3_8b_l4": ModelConfig("qwen3_8b_l4", 4, 4096, 32, 8, 128, 12288, 151936,
+                               rope_theta=1e6, qk_norm=True),
     # The 30B-A3B shape cut to 4 layers: every kernel runs at its real size while
     # weights stay at 5 GB (the 48-layer model is 61 GB).
     "qwen3_30b_a3b_l4": ModelConfig("qwen3_30b_a3b_l4", 4, 2048, 32, 4, 128, 0, 151936,
@@ -116,6 +119,7 @@ WORKLOADS = {
     "cfg2": Workload("cfg2", "llama32_3b", 16, 16, 64, context_range=(128, 2048),
                      shared_prefix=1024, n_sharers=8),
     "cfg3": Workload("cfg3", "qwen3_8b", 16, 16, 64, contexts=(4096,) * 16),
+    "cfg3_l4": Workload("cfg3_l4", "qwen3_8b_l4", 16, 16, 64, contexts=(4096,) * 16),
     "cfg4": Workload("cfg4", "qwen3_30b_a3b", 16, 16, 32, context_range=(256, 4096),
                      shared_prefix=2048, n_sharers=8),
     "cfg4_l4": Workload("cfg4_l4", "qwen3_30b_a3b_l4", 16, 16, 32, context_range=(256, 4096),

@@ -42,12 +42,22 @@ def quantize_q4(w_bits: np.ndarray) -> dict:
 MATRICES = ("wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down")
 
 
-def quantize_weights(weights: dict) -> dict:
+def quantize_weights(weights: dict, threads: int = 8) -> dict:
     """The 4-bit version of a dense model's weights: every projection matrix and the lm_head in
-    canonical 4-bit form (dict q/scale/bias); embedding and norm gains stay bf16."""
-    out = {"embed": weights["embed"], "g_final": weights["g_final"], "lm_head": quantize_q4(weights["lm_head"]),
-           "layers": []}
-    for L in weights["layers"]:
+    canonical 4-bit form (dict q/scale/bias); embedding and norm gains stay bf16.  Matrices are
+    quantised on a few threads (numpy releases the interpreter lock in its array loops)."""
+    from concurrent.futures import ThreadPoolExecutor
+    jobs = [(None, "lm_head", weights["lm_head"])]
+    for i, L in enumerate(weights["layers"]):
         assert "w_router" not in L, "4-bit weights are implemented for dense models"
-        out["layers"].append({k: (quantize_q4(v) if k in MATRICES else v) for k, v in L.items()})
+        jobs += [(i, k, v) for k, v in L.items() if k in MATRICES]
+    with ThreadPoolExecutor(max_workers=threads) as ex:
+        done = list(ex.map(lambda j: quantize_q4(j[2]), jobs))
+    out = {"embed": weights["embed"], "g_final": weights["g_final"],
+           "layers": [dict(L) for L in weights["layers"]]}
+    for (i, k, _), m in zip(jobs, done):
+        if i is None:
+            out[k] = m
+        else:
+            out["layers"][i][k] = m
     return out
