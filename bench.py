@@ -318,7 +318,7 @@ def main():
     achieved = dom_bytes_per_launch / (dom["avg_us"] * 1e-6) / 1e9
     traffic = None
     rev, measured = MEASURED_TRAFFIC.get((wl.name, dominant), (None, None))
-    if rev is not None and rev in dk.version():
+    if rev is not None and rev in dk.version() and args.weights == "bf16":   # counters were taken with bf16 weights
         traffic = measured
 
     out = {

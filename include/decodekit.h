@@ -183,8 +183,9 @@ dk_status dk_create_model(const dk_model_config *cfg, const dk_weight_ptrs *weig
  *   biases  [lg 0..3][h 0..1][i 0..3][scale, bias]: the scale and the bias of row
  *           16*tile + 4*lg + i for the columns step*128 + h*64 .. + 63 (rows past
  *           N: anything finite).
- * lm_head must not alias embed.  Steps of such a model run the matrix-core
- * kernels at every batch size (DK_STEP_NO_FUSED has no effect).
+ * lm_head must not alias embed.  Steps of such a model run the single persistent
+ * kernel where it applies (as for bf16 weights) and otherwise the matrix-core
+ * kernels, at every batch size.
  */
 dk_status dk_create_model_q4(const dk_model_config *cfg, const dk_weight_ptrs *weights,
                              dk_model **out);

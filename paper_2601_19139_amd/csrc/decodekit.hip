@@ -268,7 +268,7 @@ Workspace carve(const dk_model_config &c, int B, int max_blocks, bool q4)
     }
     w.pmax_val = take((size_t)B * w.lm_blocks * 4);
     w.pmax_idx = take((size_t)B * w.lm_blocks * 4);
-    w.fused = !q4 && fused_variant(c, B) >= 0;
+    w.fused = fused_variant(c, B) >= 0;
     if (w.fused) {
         w.fused_chunks = (ctx_max + dk::kFusedChunk - 1) / dk::kFusedChunk;
         w.fused_set_floats = dk::fused_layout(c.n_layers, B, c.hidden, c.n_q_heads, c.n_kv_heads, d, c.ffn,
@@ -423,10 +423,15 @@ dk_status launch_attention_d(const dk::AttnArgs &a, int G, dim3 grid, bool mfma,
 }
 
 template <int NB, int D, int G, int KSH, int KSQ, int KSF>
-dk_status launch_fused_inst(const dk::FusedArgs &a, hipStream_t st)
+dk_status launch_fused_inst(const dk::FusedArgs &a, bool q4, hipStream_t st)
 {
-    DK_LAUNCH(DK_K_FUSED_STEP, (dk::fused_step_kernel<NB, D, G, KSH, KSQ, KSF>), dim3(kFusedBlocks),
-              dim3(dk::kFusedThreads), 0, st, a);
+    if (q4) {
+        DK_LAUNCH(DK_K_FUSED_STEP, (dk::fused_step_kernel<NB, D, G, KSH, KSQ, KSF, true>), dim3(kFusedBlocks),
+                  dim3(dk::kFusedThreads), 0, st, a);
+    } else {
+        DK_LAUNCH(DK_K_FUSED_STEP, (dk::fused_step_kernel<NB, D, G, KSH, KSQ, KSF, false>), dim3(kFusedBlocks),
+                  dim3(dk::kFusedThreads), 0, st, a);
+    }
     DK_HIP(hipGetLastError());
     return DK_OK;
 }
@@ -499,10 +504,10 @@ dk_status launch_fused(dk_model *model, dk_kv_pool *pool, const Workspace &w, ch
     model->fused_parity ^= 1;
     const int v = fused_variant(c, B);
     dk_status s = DK_E_UNSUPPORTED_SHAPE;
-    if (v == 0 && B == 1) s = launch_fused_inst<1, 64, 2, 1, 1, 2>(a, st);
-    else if (v == 0 && B == 2) s = launch_fused_inst<2, 64, 2, 1, 1, 2>(a, st);
-    else if (v == 1 && B == 1) s = launch_fused_inst<1, 128, 2, 2, 4, 6>(a, st);
-    else if (v == 1 && B == 2) s = launch_fused_inst<2, 128, 2, 2, 4, 6>(a, st);
+    if (v == 0 && B == 1) s = launch_fused_inst<1, 64, 2, 1, 1, 2>(a, model->q4, st);
+    else if (v == 0 && B == 2) s = launch_fused_inst<2, 64, 2, 1, 1, 2>(a, model->q4, st);
+    else if (v == 1 && B == 1) s = launch_fused_inst<1, 128, 2, 2, 4, 6>(a, model->q4, st);
+    else if (v == 1 && B == 2) s = launch_fused_inst<2, 128, 2, 2, 4, 6>(a, model->q4, st);
     return s;
 }
 

@@ -212,53 +212,126 @@ __device__ __forceinline__ void wave_rows(int N, int wv, int &r0, int &r1)
 }
 
 // Weights of up to RW rows x KS 512-element pieces, one 16-byte piece per lane.
-template <int RW, int KS>
+//
+// Q4 (4-bit codes, a bf16 scale and bias per 64 columns; layout of dk_create_model_q4): a lane
+// holds 8 bytes = the 16 codes of half a lane-group unit, which all belong to ONE group, plus that
+// group's (scale, bias) pair.  Unit c of a row (c = 0 .. K/16-1) is step c/8, lane group (c/2)%4,
+// half c%2, and covers the columns step*128 + half*64 + lg*8 + {0..7} and the same + 32.
+template <int RW, int KS, bool Q4 = false>
 struct RowRegs {
     uint4 w[RW][KS];
 };
 template <int RW, int KS>
-__device__ __forceinline__ void load_rows(RowRegs<RW, KS> &r, const uint16_t *W, int K, int row0, int row_end,
-                                          int lane)
+struct RowRegs<RW, KS, true> {
+    static constexpr int KQ = (KS + 1) / 2;   // pieces of 64 units = 1024 columns
+    uint2 w[RW][KQ];
+    uint32_t sb[RW][KQ];
+};
+// N: rows of the whole matrix (Q4: the scale/bias tiles follow the N rows of codes)
+template <int RW, int KS, bool Q4>
+__device__ __forceinline__ void load_rows(RowRegs<RW, KS, Q4> &r, const uint16_t *W, int N, int K, int row0,
+                                          int row_end, int lane)
 {
+    if constexpr (Q4) {
+        const uint8_t *Wb = reinterpret_cast<const uint8_t *>(W);
+        const int units = K >> 4, nks = K >> 7;
+        const uint8_t *sbase = Wb + (long long)N * (K >> 1);
 #pragma unroll
-    for (int i = 0; i < RW; i++)
+        for (int i = 0; i < RW; i++) {
+            const int row = max(min(row0 + i, row_end - 1), 0);
+            const uint8_t *codes = Wb + (long long)row * (K >> 1);
+            const long long tile_off = (long long)(row >> 4) * nks * 128 + ((row & 15) >> 2) * 32 + (row & 3) * 4;
 #pragma unroll
-        for (int s = 0; s < KS; s++) {
-            const int k = s * 512 + lane * 8;
-            // rows / pieces outside the matrix read a valid address and are not used
-            const int row = min(row0 + i, row_end - 1);
-            r.w[i][s] = ld16(W + (long long)max(row, 0) * K + min(k, K - 8));
+            for (int s = 0; s < RowRegs<RW, KS, true>::KQ; s++) {
+                const int c = min(s * 64 + lane, units - 1);   // units past the row: a valid address, not used
+                r.w[i][s] = *reinterpret_cast<const uint2 *>(codes + c * 8);
+                r.sb[i][s] = *reinterpret_cast<const uint32_t *>(sbase + tile_off + (c >> 3) * 128 + (c & 1) * 16);
+            }
         }
+    } else {
+#pragma unroll
+        for (int i = 0; i < RW; i++)
+#pragma unroll
+            for (int s = 0; s < KS; s++) {
+                const int k = s * 512 + lane * 8;
+                // rows / pieces outside the matrix read a valid address and are not used
+                const int row = min(row0 + i, row_end - 1);
+                r.w[i][s] = ld16(W + (long long)max(row, 0) * K + min(k, K - 8));
+            }
+    }
 }
 // acc[i][b] = sum_k W[row0+i][k] * xs[b][k]   (all lanes get the sums)
-template <int NB, int RW, int KS>
-__device__ __forceinline__ void dot_rows(const RowRegs<RW, KS> &r, const float *xs, int K, int lane,
+template <int NB, int RW, int KS, bool Q4>
+__device__ __forceinline__ void dot_rows(const RowRegs<RW, KS, Q4> &r, const float *xs, int K, int lane,
                                          float (&acc)[RW][NB])
 {
 #pragma unroll
     for (int i = 0; i < RW; i++)
 #pragma unroll
         for (int b = 0; b < NB; b++) acc[i][b] = 0.f;
+    if constexpr (Q4) {
 #pragma unroll
-    for (int s = 0; s < KS; s++) {
-        const int k = s * 512 + lane * 8;
-        if (k < K) {
-            float xv[NB][8];
+        for (int s = 0; s < RowRegs<RW, KS, true>::KQ; s++) {
+            const int c = s * 64 + lane;
+            if (c < (K >> 4)) {
+                const int k0 = (c >> 3) * 128 + (c & 1) * 64 + ((c >> 1) & 3) * 8;
+                float xv[NB][16], sx[NB];
 #pragma unroll
-            for (int b = 0; b < NB; b++) {
-                const float4 lo = *reinterpret_cast<const float4 *>(xs + b * K + k);
-                const float4 hi = *reinterpret_cast<const float4 *>(xs + b * K + k + 4);
-                xv[b][0] = lo.x; xv[b][1] = lo.y; xv[b][2] = lo.z; xv[b][3] = lo.w;
-                xv[b][4] = hi.x; xv[b][5] = hi.y; xv[b][6] = hi.z; xv[b][7] = hi.w;
+                for (int b = 0; b < NB; b++) {
+#pragma unroll
+                    for (int h = 0; h < 2; h++) {
+                        const float4 lo = *reinterpret_cast<const float4 *>(xs + b * K + k0 + h * 32);
+                        const float4 hi = *reinterpret_cast<const float4 *>(xs + b * K + k0 + h * 32 + 4);
+                        xv[b][h * 8 + 0] = lo.x; xv[b][h * 8 + 1] = lo.y; xv[b][h * 8 + 2] = lo.z; xv[b][h * 8 + 3] = lo.w;
+                        xv[b][h * 8 + 4] = hi.x; xv[b][h * 8 + 5] = hi.y; xv[b][h * 8 + 6] = hi.z; xv[b][h * 8 + 7] = hi.w;
+                    }
+                    float t = 0.f;
+#pragma unroll
+                    for (int e = 0; e < 16; e++) t += xv[b][e];
+                    sx[b] = t;
+                }
+#pragma unroll
+                for (int i = 0; i < RW; i++) {
+                    const uint32_t cw[2] = {r.w[i][s].x, r.w[i][s].y};
+                    float qf[16];
+#pragma unroll
+                    for (int h = 0; h < 2; h++)
+#pragma unroll
+                        for (int j = 0; j < 8; j++) qf[h * 8 + j] = (float)((cw[h] >> (4 * j)) & 15u);
+                    const float sc = __uint_as_float(r.sb[i][s] << 16);
+                    const float bi = __uint_as_float(r.sb[i][s] & 0xFFFF0000u);
+#pragma unroll
+                    for (int b = 0; b < NB; b++) {
+                        float dq = 0.f;
+#pragma unroll
+                        for (int e = 0; e < 16; e++) dq += qf[e] * xv[b][e];
+                        acc[i][b] += sc * dq + bi * sx[b];
+                    }
+                }
             }
+        }
+    } else {
 #pragma unroll
-            for (int i = 0; i < RW; i++) {
-                float wf[8];
-                unpack8(r.w[i][s], wf);
+        for (int s = 0; s < KS; s++) {
+            const int k = s * 512 + lane * 8;
+            if (k < K) {
+                float xv[NB][8];
 #pragma unroll
-                for (int b = 0; b < NB; b++)
+                for (int b = 0; b < NB; b++) {
+                    const float4 lo = *reinterpret_cast<const float4 *>(xs + b * K + k);
+                    const float4 hi = *reinterpret_cast<const float4 *>(xs + b * K + k + 4);
+                    xv[b][0] = lo.x; xv[b][1] = lo.y; xv[b][2] = lo.z; xv[b][3] = lo.w;
+                    xv[b][4] = hi.x; xv[b][5] = hi.y; xv[b][6] = hi.z; xv[b][7] = hi.w;
+                }
 #pragma unroll
-                    for (int e = 0; e < 8; e++) acc[i][b] += wf[e] * xv[b][e];
+                for (int i = 0; i < RW; i++) {
+                    float wf[8];
+                    unpack8(r.w[i][s], wf);
+#pragma unroll
+                    for (int b = 0; b < NB; b++)
+#pragma unroll
+                        for (int e = 0; e < 8; e++) acc[i][b] += wf[e] * xv[b][e];
+                }
             }
         }
     }
@@ -276,14 +349,14 @@ constexpr int kFusedMaxBlockRows = 64;
 
 // sm_y[b][row - b0] = scale_b * W[row] . xs[b] for the wave's rows; the first RW
 // rows come from `pre` (requested before the input was awaited).
-template <int NB, int RW, int KS>
-__device__ __forceinline__ void gemv_rows(RowRegs<RW, KS> &pre, const uint16_t *W, int K, int r0, int r1, int b0,
-                                          const float *xs, const float (&scale)[NB], float *sm_y, int lane)
+template <int NB, int RW, int KS, bool Q4>
+__device__ __forceinline__ void gemv_rows(RowRegs<RW, KS, Q4> &pre, const uint16_t *W, int N, int K, int r0, int r1,
+                                          int b0, const float *xs, const float (&scale)[NB], float *sm_y, int lane)
 {
     for (int rb = r0; rb < r1; rb += RW) {
-        if (rb != r0) load_rows<RW, KS>(pre, W, K, rb, r1, lane);
+        if (rb != r0) load_rows<RW, KS, Q4>(pre, W, N, K, rb, r1, lane);
         float acc[RW][NB];
-        dot_rows<NB, RW, KS>(pre, xs, K, lane, acc);
+        dot_rows<NB, RW, KS, Q4>(pre, xs, K, lane, acc);
         float v = 0.f;
 #pragma unroll
         for (int i = 0; i < RW; i++)
@@ -307,7 +380,7 @@ __device__ __forceinline__ void publish_rows(float *out, int N, int b0, int n, c
     }
 }
 
-template <int NB, int D, int G, int KSH, int KSQ, int KSF>
+template <int NB, int D, int G, int KSH, int KSQ, int KSF, bool Q4 = false>
 __global__ __launch_bounds__(kFusedThreads) void fused_step_kernel(FusedArgs a)
 {
     constexpr int BS = 16, TPR = D / 8, TPW = 64 / TPR, NI = BS / TPW;
@@ -356,8 +429,8 @@ __global__ __launch_bounds__(kFusedThreads) void fused_step_kernel(FusedArgs a)
     block_rows(QKV, qkv_b0, qkv_n);
     block_rows(H, h_b0, h_n);
     block_rows(F, f_b0, f_n);
-    RowRegs<RW_H, KSH> pre_h;
-    load_rows<RW_H, KSH>(pre_h, a.layers[0].w_qkv, H, r0, r1, lane);
+    RowRegs<RW_H, KSH, Q4> pre_h;
+    load_rows<RW_H, KSH, Q4>(pre_h, a.layers[0].w_qkv, QKV, H, r0, r1, lane);
     float rinv[NB], ones[NB];
 #pragma unroll
     for (int b = 0; b < NB; b++) ones[b] = 1.f;
@@ -396,13 +469,13 @@ __global__ __launch_bounds__(kFusedThreads) void fused_step_kernel(FusedArgs a)
         const float *x_in = l ? a.set + lay.per_layer * (l - 1) + lay.xout : nullptr;   // layer 0: embedding
 
         // ---- q|k|v = W_qkv rmsnorm(x) ------------------------------------------------
-        gemv_rows<NB, RW_H, KSH>(pre_h, Lw.w_qkv, H, r0, r1, qkv_b0, xs, rinv, sm_y, lane);
+        gemv_rows<NB, RW_H, KSH, Q4>(pre_h, Lw.w_qkv, QKV, H, r0, r1, qkv_b0, xs, rinv, sm_y, lane);
         publish_rows<NB>(b_qkv, QKV, qkv_b0, qkv_n, sm_y, 0.f);
         // ---- attention: request the K/V tiles, then wait for q|k|v --------------------
-        RowRegs<RW_Q, KSQ> pre_q;
+        RowRegs<RW_Q, KSQ, Q4> pre_q;
         int q0, q1;
         wave_rows(H, wv, q0, q1);
-        load_rows<RW_Q, KSQ>(pre_q, Lw.w_o, QD, q0, q1, lane);
+        load_rows<RW_Q, KSQ, Q4>(pre_q, Lw.w_o, H, QD, q0, q1, lane);
         // the residual of the element this thread will publish: the layer's input, which is
         // the embedding row (layer 0) or the previous x_out (complete: the block consumed it)
         float rv_o = 0.f;
@@ -669,26 +742,26 @@ __global__ __launch_bounds__(kFusedThreads) void fused_step_kernel(FusedArgs a)
         {
             float dummy[NB];
             stage_input<NB, false>(b_attn, QD, nullptr, a.eps, xs, dummy, red, w);
-            gemv_rows<NB, RW_Q, KSQ>(pre_q, Lw.w_o, QD, q0, q1, h_b0, xs, ones, sm_y, lane);
+            gemv_rows<NB, RW_Q, KSQ, Q4>(pre_q, Lw.w_o, H, QD, q0, q1, h_b0, xs, ones, sm_y, lane);
             publish_rows<NB>(b_xmid, H, h_b0, h_n, sm_y, rv_o);
         }
         // ---- act = silu(W_g h) * (W_u h), h = rmsnorm(x_mid) ----------------------------
         {
             int f0, f1;
             wave_rows(F, wv, f0, f1);
-            RowRegs<RW_GU, KSH> pg, pu;
-            load_rows<RW_GU, KSH>(pg, Lw.w_gate, H, f0, f1, lane);
-            load_rows<RW_GU, KSH>(pu, Lw.w_up, H, f0, f1, lane);
+            RowRegs<RW_GU, KSH, Q4> pg, pu;
+            load_rows<RW_GU, KSH, Q4>(pg, Lw.w_gate, F, H, f0, f1, lane);
+            load_rows<RW_GU, KSH, Q4>(pu, Lw.w_up, F, H, f0, f1, lane);
             __syncthreads();   // xs is about to be overwritten
             stage_input<NB, true>(b_xmid, H, Lw.g_mlp, a.eps, xs, rinv, red, w);
             for (int rb = f0; rb < f1; rb += RW_GU) {
                 if (rb != f0) {
-                    load_rows<RW_GU, KSH>(pg, Lw.w_gate, H, rb, f1, lane);
-                    load_rows<RW_GU, KSH>(pu, Lw.w_up, H, rb, f1, lane);
+                    load_rows<RW_GU, KSH, Q4>(pg, Lw.w_gate, F, H, rb, f1, lane);
+                    load_rows<RW_GU, KSH, Q4>(pu, Lw.w_up, F, H, rb, f1, lane);
                 }
                 float ag[RW_GU][NB], au[RW_GU][NB];
-                dot_rows<NB, RW_GU, KSH>(pg, xs, H, lane, ag);
-                dot_rows<NB, RW_GU, KSH>(pu, xs, H, lane, au);
+                dot_rows<NB, RW_GU, KSH, Q4>(pg, xs, H, lane, ag);
+                dot_rows<NB, RW_GU, KSH, Q4>(pu, xs, H, lane, au);
                 float v = 0.f;
 #pragma unroll
                 for (int i = 0; i < RW_GU; i++)
@@ -707,8 +780,8 @@ __global__ __launch_bounds__(kFusedThreads) void fused_step_kernel(FusedArgs a)
         {
             int d0, d1;
             wave_rows(H, wv, d0, d1);
-            RowRegs<RW_F, KSF> pd;
-            load_rows<RW_F, KSF>(pd, Lw.w_down, F, d0, d1, lane);
+            RowRegs<RW_F, KSF, Q4> pd;
+            load_rows<RW_F, KSF, Q4>(pd, Lw.w_down, H, F, d0, d1, lane);
             float rv_d = 0.f;
             if (tid < h_n * NB) {
                 const int b = tid / h_n, r = tid - b * h_n;
@@ -717,12 +790,12 @@ __global__ __launch_bounds__(kFusedThreads) void fused_step_kernel(FusedArgs a)
             __syncthreads();
             float dummy[NB];
             stage_input<NB, false>(b_act, F, nullptr, a.eps, xs, dummy, red, w);
-            gemv_rows<NB, RW_F, KSF>(pd, Lw.w_down, F, d0, d1, h_b0, xs, ones, sm_y, lane);
+            gemv_rows<NB, RW_F, KSF, Q4>(pd, Lw.w_down, H, F, d0, d1, h_b0, xs, ones, sm_y, lane);
             publish_rows<NB>(b_xout, H, h_b0, h_n, sm_y, rv_d);
         }
         // ---- next layer's q|k|v weights ahead, then its input --------------------------------
         if (l + 1 < a.L) {
-            load_rows<RW_H, KSH>(pre_h, a.layers[l + 1].w_qkv, H, r0, r1, lane);
+            load_rows<RW_H, KSH, Q4>(pre_h, a.layers[l + 1].w_qkv, QKV, H, r0, r1, lane);
             __syncthreads();
             stage_input<NB, true>(b_xout, H, a.layers[l + 1].g_attn, a.eps, xs, rinv, red, w);
         }
@@ -735,9 +808,9 @@ __global__ __launch_bounds__(kFusedThreads) void fused_step_kernel(FusedArgs a)
         // a ring of PF batches of RW_H rows stays requested: one batch ahead leaves the wave
         // waiting a full HBM round trip per batch (a third of the bandwidth)
         constexpr int PF = 4;
-        RowRegs<RW_H, KSH> ring[PF];
+        RowRegs<RW_H, KSH, Q4> ring[PF];
 #pragma unroll
-        for (int p = 0; p < PF; p++) load_rows<RW_H, KSH>(ring[p], a.lm_head, H, v0 + p * RW_H, v1, lane);
+        for (int p = 0; p < PF; p++) load_rows<RW_H, KSH, Q4>(ring[p], a.lm_head, V, H, v0 + p * RW_H, v1, lane);
         __syncthreads();
         const float *x_last = a.set + lay.per_layer * (a.L - 1) + lay.xout;
         stage_input<NB, true>(x_last, H, a.g_final, a.eps, xs, rinv, red, w);
@@ -750,9 +823,9 @@ __global__ __launch_bounds__(kFusedThreads) void fused_step_kernel(FusedArgs a)
             for (int p = 0; p < PF; p++) {
                 const int rb = rb0 + p * RW_H;
                 float acc[RW_H][NB];
-                dot_rows<NB, RW_H, KSH>(ring[p], xs, H, lane, acc);
+                dot_rows<NB, RW_H, KSH, Q4>(ring[p], xs, H, lane, acc);
                 // refill the slot (rows past the end re-read the last row and are not used)
-                load_rows<RW_H, KSH>(ring[p], a.lm_head, H, rb + RW_H * PF, v1, lane);
+                load_rows<RW_H, KSH, Q4>(ring[p], a.lm_head, V, H, rb + RW_H * PF, v1, lane);
 #pragma unroll
                 for (int i = 0; i < RW_H; i++)
 #pragma unroll

@@ -37,9 +37,20 @@ class DeviceModel:
         keep = self.tensors.append
         self.q4 = isinstance(weights["lm_head"], dict)
 
+        packed = {}
+        if self.q4:
+            # pack on a few threads (numpy releases the interpreter lock): seconds instead of minutes at 8B
+            from concurrent.futures import ThreadPoolExecutor
+            jobs = [(weights["lm_head"],)]
+            for L in weights["layers"]:
+                jobs += [(L["wq"], L["wk"], L["wv"]), (L["wo"],), (L["w_gate"],), (L["w_up"],), (L["w_down"],)]
+            with ThreadPoolExecutor(max_workers=8) as ex:
+                for j, buf in zip(jobs, ex.map(lambda j: pack_q4(*j), jobs)):
+                    packed[id(j[0])] = buf
+
         def up(*a):
             if self.q4 and isinstance(a[0], dict):
-                t = _torch().from_numpy(pack_q4(*a)).cuda()
+                t = _torch().from_numpy(packed.pop(id(a[0]))).cuda()
             else:
                 t = _dev_bf16(a[0] if len(a) == 1 else np.concatenate(a, axis=0))
             keep(t)

@@ -82,6 +82,23 @@ def test_q4_shapes_and_edges(dk, orc, name, shape, contexts, steps):
     check_pool(out, pool, shape, lay, steps)
 
 
+@pytest.mark.parametrize("contexts", [[37], [64, 5]], ids=["batch1", "batch2"])
+def test_q4_both_paths_for_small_batches(dk, orc, contexts):
+    """Batches of 1-2 rows take the single persistent kernel (vector-ALU dot products over the
+    packed codes); with DK_STEP_NO_FUSED the same step runs kernel per stage on the matrix cores.
+    Both must meet the oracle."""
+    shape = W.CONFIGS["tiny_q4"]
+    lay = build_block_tables(contexts, 16, 3, seed=29)
+    weights = quantize_weights(W.make_weights(shape, 10))
+    pool = W.fill_kv_pool(shape, lay, 11)
+    tokens = W.initial_tokens(shape, len(contexts), 12)
+    for flags in (0, dk.STEP_NO_FUSED):
+        out = run_both(orc, shape, weights, lay, pool, tokens, 3, gpu_flags=flags)
+        worst, agree = check_parity(out)
+        assert worst < TIGHT and agree == 1.0, (flags, worst, agree)
+        check_pool(out, pool, shape, lay, 3)
+
+
 def test_q4_distinct_scales_and_biases_per_group(dk, orc):
     """Codes, scales and biases drawn independently (no relation to a bf16 matrix): a scale or bias
     taken from the wrong row, group or half of a K-step changes the logits by far more than the bound."""
