@@ -53,6 +53,43 @@ def cpu_baseline(shape, weights, layout, pool_bits, tokens, budget_s=12.0, max_s
                       f"(fp64 C loops, OpenMP over rows of a matrix)"}
 
 
+def batch16_line(args, wl, dk, W, np, torch, dm, tok_s_batch1):
+    """The same model with 16 concurrent sequences of the workload's context length (private caches):
+    the other end of the paper's 1 -> 16 concurrent-request sweep.  Reported beside the batch-1 figure."""
+    from workloads.blocktable import build_block_tables
+    shape = wl.cfg
+    ctx, B, span = int(wl.contexts[0]), 16, 64
+    lay = build_block_tables([ctx] * B, wl.block_size, span, seed=wl.seed_blocks)
+    pool_bits = W.fill_kv_pool(shape, lay, wl.seed_kv, poison=False)
+    dkv = dk.DeviceKV(dm, lay, pool_bits)
+    dec = dk.Decoder(dm, dkv, lay.contexts, W.initial_tokens(shape, B, wl.seed_tokens), want_logits=True)
+    d_ctx0, d_tok0 = dec.seq_lens.clone(), dec.tokens.clone()
+    steps = min(args.steps, span)
+
+    def run(n):
+        dec.seq_lens.copy_(d_ctx0)
+        dec.tokens.copy_(d_tok0)
+        for _ in range(n):
+            dec.step(flags=dk.STEP_ADVANCE)
+
+    run(min(args.warmup, span))
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    run(steps)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    mean_ctx = (lay.contexts + (steps - 1) // 2).astype(np.int32)
+    alg = dk.step_algorithmic_bytes(dm.handle, dkv.handle, lay.tables, mean_ctx, with_logits=True)
+    tok_s = B * steps / wall
+    out = {"workload": f"{shape.name} decode, batch {B}, context {ctx} growing, private caches, greedy",
+           "value": round(tok_s, 2), "unit": "tok/s", "steps": steps, "ms_per_step": round(wall * 1e3 / steps, 5),
+           "vs_batch1": round(tok_s / tok_s_batch1, 2), "algorithmic_bytes_per_step": int(alg),
+           "achieved_GBs": round(alg / (wall / steps) / 1e9, 1),
+           "frac": round(alg / (wall / steps) / 1e9 / HBM_PEAK_GBS, 4)}
+    dkv.close()
+    return out
+
+
 def bench_prefill(args, wl, dk, W, np, torch):
     """Chunked prefill of one P-token prompt (next row after the decode step; not the headline metric)."""
     from workloads.blocktable import build_block_tables
@@ -355,6 +392,8 @@ def main():
     }
     if distinct is not None:
         out["distinct_experts_per_layer_mean"] = round(float(distinct.mean()), 2)
+    if wl.batch == 1 and wl.contexts:
+        out["batch16"] = batch16_line(args, wl, dk, W, np, torch, dm, tok_s)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(shape, weights, lay, pool_bits, tokens0,
                                            max_steps=min(64, span - 1))   # the tables have room for `span` tokens
