@@ -18,6 +18,7 @@
 #include "dk_attention_mfma.hip.h"
 #include "dk_fused.hip.h"
 #include "dk_gemm.hip.h"
+#include "dk_gemm_shared.hip.h"
 #include "dk_gemv.hip.h"
 #include "dk_moe.hip.h"
 #include "dk_sample.hip.h"
@@ -144,6 +145,8 @@ namespace {
 
 struct Workspace {
     size_t x, qkv, attn, act, cs, part, tickets, pmax_val, pmax_idx, pf_seq, total;
+    size_t kpart;          // partial tiles of K-sliced GEMMs; their tickets follow the attention tickets
+    int n_tickets;         // attention tickets + GEMM tickets (all cleared at the start of a step)
     // batched (matrix-core) path: activations as bf16 hi/lo, sum-of-squares partials
     size_t xhi, xlo, ahi, alo, fhi, flo, ssq;
     // mixture of experts: routing of every layer, per-row 1/rms, expert outputs
@@ -188,6 +191,37 @@ bool attention_uses_mfma(const dk_model_config &c, int B, bool q4)
 {
     const bool batched = B > kMaxGemvBatch || c.n_experts > 0 || q4;
     return batched && c.n_q_heads / c.n_kv_heads >= 4;
+}
+
+// Which kernel a batched GEMM takes: w == 0 the K-split-per-wave kernel (skinny_gemm_kernel),
+// otherwise shared_gemm_kernel with w waves per block and K cut into `slices` across blocks.
+// Measured on the 0.6B / 3B / 8B shapes: sharing the activation tile pays for the lm_head from 17
+// batch rows on, for the gate/up pair of a large model from 17 rows on, and for the other large
+// layer matrices from 33 rows on; everything smaller is faster with the other kernel.
+struct GemmPlan { int w, slices; };
+GemmPlan gemm_plan(int epi, int N, int K, int Bp, bool q4)
+{
+    const int mt = Bp / 16;
+    const long long elems = (long long)N * K;
+    if (q4 || mt < 2 || K % 128) return {0, 1};
+    if (epi == dk::GEPI_STORE) {
+        if ((N + 15) / 16 >= 4096) return {8, 1};
+        if (mt >= 3 && elems >= (12ll << 20)) return {4, 2};
+    } else if (epi == dk::GEPI_SWIGLU) {
+        if (elems >= (mt >= 3 ? (20ll << 20) : (40ll << 20))) return {4, 1};
+    } else {
+        if (mt >= 3 && elems >= (40ll << 20)) return {4, 4};
+    }
+    return {0, 1};
+}
+// Row blocks (= tickets) and partial-tile floats of that plan.
+void gemm_plan_needs(int epi, int N, int K, int Bp, bool q4, size_t &tickets, size_t &part_floats)
+{
+    const GemmPlan p = gemm_plan(epi, N, K, Bp, q4);
+    if (p.w == 0 || p.slices == 1) return;
+    const size_t tiles = (size_t)(N + 15) / 16;
+    tickets = std::max(tickets, (tiles + p.w - 1) / p.w);
+    part_floats = std::max(part_floats, dk::shared_gemm_part_floats(N, p.slices, epi == dk::GEPI_SWIGLU ? 2 : 1, Bp / 16));
 }
 
 // q4: the model's matrices are 4-bit; every batch size then takes the matrix-core kernels
@@ -238,10 +272,23 @@ Workspace carve(const dk_model_config &c, int B, int max_blocks, bool q4)
     w.act = take((size_t)B * act_dim * 4);
     w.cs = take((size_t)B * (d / 2) * 8);
     w.part = take((size_t)B * c.n_kv_heads * w.max_chunks * G * (d + 2) * 4);
-    w.tickets = take((size_t)B * c.n_kv_heads * 4);
+    w.Bp = (B + 15) / 16 * 16;
+    size_t gemm_tickets = 0, gemm_part = 0;
+    {
+        const int H = c.hidden, qd = c.n_q_heads * d;
+        gemm_plan_needs(dk::GEPI_STORE, (int)qkv_dim, H, w.Bp, q4, gemm_tickets, gemm_part);
+        gemm_plan_needs(dk::GEPI_RESID, H, qd, w.Bp, q4, gemm_tickets, gemm_part);
+        if (c.n_experts == 0) {
+            gemm_plan_needs(dk::GEPI_SWIGLU, c.ffn, H, w.Bp, q4, gemm_tickets, gemm_part);
+            gemm_plan_needs(dk::GEPI_RESID, H, c.ffn, w.Bp, q4, gemm_tickets, gemm_part);
+        }
+        gemm_plan_needs(dk::GEPI_STORE, c.vocab, H, w.Bp, q4, gemm_tickets, gemm_part);
+    }
+    w.n_tickets = B * c.n_kv_heads + (int)gemm_tickets;
+    w.tickets = take((size_t)w.n_tickets * 4);
+    w.kpart = take(gemm_part * 4);
     w.pf_seq = take((size_t)DK_MAX_BATCH * 4);   // positions of a prefill chunk's rows
     w.batched = B > kMaxGemvBatch || c.n_experts > 0 || q4;   // expert layers and 4-bit weights use the matrix-core kernels
-    w.Bp = (B + 15) / 16 * 16;
     if (w.batched) {
         w.lm_blocks = (c.vocab + 15) / 16;
         auto padded = [](size_t k) { return (k + 127) / 128 * 128; };   // whole K-steps
@@ -376,10 +423,49 @@ dk_status launch_gemm_cfg(const dk::GemmArgs &a, hipStream_t st)
 // activations; it pays when enough blocks remain to fill the chip (measured on
 // the 8B-class shapes: 4 tiles per wave for the lm_head, 2 for the fused q/k/v
 // matrix, 1 for the square-ish projections and the gate/up pair).
+// ---- shared-activation GEMM dispatch (see gemm_plan) -------------------------
+template <int MT, int W, int EPI, bool NORM>
+dk_status launch_shared_gemm_inst(const dk::GemmArgs &a, int slices, hipStream_t st)
+{
+    constexpr size_t lds = dk::shared_gemm_lds_bytes(MT);
+    auto kernel = dk::shared_gemm_kernel<MT, W, 1, 2, EPI, NORM>;
+    static bool lds_allowed = false;   // above 64 KB together with the kernel's static LDS: ask once
+    if (!lds_allowed) {
+        DK_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                   (int)lds));
+        lds_allowed = true;
+    }
+    const int tiles = (a.N + 15) / 16;
+    DK_LAUNCH(DK_K_GEMM, kernel, dim3((tiles + W - 1) / W, slices), dim3(W * 64), lds, st, a);
+    DK_HIP(hipGetLastError());
+    return DK_OK;
+}
+
+template <int EPI, bool NORM>
+dk_status launch_shared_gemm(const dk::GemmArgs &a, int Bp, const GemmPlan &p, hipStream_t st)
+{
+    if (p.slices > 1 && (a.kpart == nullptr || a.ktickets == nullptr))
+        return fail(DK_E_INVALID_ARG, "K-sliced GEMM without its partial buffer");
+    const int mt = Bp / 16;
+    if constexpr (EPI == dk::GEPI_STORE) {
+        if (p.w == 8 && mt == 2) return launch_shared_gemm_inst<2, 8, EPI, NORM>(a, p.slices, st);
+        if (p.w == 8 && mt == 3) return launch_shared_gemm_inst<3, 8, EPI, NORM>(a, p.slices, st);
+        if (p.w == 8 && mt == 4) return launch_shared_gemm_inst<4, 8, EPI, NORM>(a, p.slices, st);
+    }
+    if constexpr (EPI == dk::GEPI_SWIGLU) {
+        if (p.w == 4 && mt == 2) return launch_shared_gemm_inst<2, 4, EPI, NORM>(a, p.slices, st);
+    }
+    if (p.w == 4 && mt == 3) return launch_shared_gemm_inst<3, 4, EPI, NORM>(a, p.slices, st);
+    if (p.w == 4 && mt == 4) return launch_shared_gemm_inst<4, 4, EPI, NORM>(a, p.slices, st);
+    return fail(DK_E_INVALID_ARG, "no shared-activation GEMM for %d rows and %d waves", Bp, p.w);
+}
+
 template <int EPI, bool NORM>
 dk_status launch_gemm(const dk::GemmArgs &a, int Bp, hipStream_t st)
 {
     constexpr int NM = (EPI == dk::GEPI_SWIGLU) ? 2 : 1;
+    const GemmPlan plan = gemm_plan(EPI, a.N, a.K, Bp, a.q4 != 0);
+    if (plan.w) return launch_shared_gemm<EPI, NORM>(a, Bp, plan, st);
     const int tiles = (a.N + 15) / 16;
     switch (Bp / 16) {
         case 1:
@@ -519,7 +605,7 @@ const char *dk_last_error(void) { return g_err; }
 
 // The kernel revisions change whenever a kernel's memory behaviour changes; the
 // benchmark quotes stored counter measurements only for a matching revision.
-const char *dk_version(void) { return "decodekit 0.8 (gfx950; gemv r3, gemm r8, attention r6, moe r4, fused r2, prefill r1, sample r1)"; }
+const char *dk_version(void) { return "decodekit 0.8 (gfx950; gemv r3, gemm r9, attention r6, moe r4, fused r2, prefill r1, sample r1)"; }
 
 // ------------------------------------------------------------------- pool --
 dk_status dk_kv_pool_bytes(const dk_model_config *cfg, int32_t num_blocks, int32_t block_size,
@@ -972,6 +1058,8 @@ static dk_status decode_step_impl(dk_model *model, dk_kv_pool *pool, const int32
     float2 *cs = reinterpret_cast<float2 *>(ws + w.cs);
     float *part = reinterpret_cast<float *>(ws + w.part);
     int *tickets = reinterpret_cast<int *>(ws + w.tickets);
+    float *kpart = reinterpret_cast<float *>(ws + w.kpart);
+    int *ktickets = tickets + B * c.n_kv_heads;   // behind the attention tickets, cleared with them
     float *pmax_val = reinterpret_cast<float *>(ws + w.pmax_val);
     int *pmax_idx = reinterpret_cast<int *>(ws + w.pmax_idx);
     uint16_t *xhi = reinterpret_cast<uint16_t *>(ws + w.xhi), *xlo = reinterpret_cast<uint16_t *>(ws + w.xlo);
@@ -995,7 +1083,7 @@ static dk_status decode_step_impl(dk_model *model, dk_kv_pool *pool, const int32
         e.x = x;
         e.cs = cs;
         e.tickets = tickets;
-        e.n_tickets = B * nkv;
+        e.n_tickets = w.n_tickets;
         e.H = H;
         e.half = d / 2;
         e.V = c.vocab;
@@ -1020,6 +1108,8 @@ static dk_status decode_step_impl(dk_model *model, dk_kv_pool *pool, const int32
             g.K = H;
             g.B = B;
             g.q4 = model->q4;
+            g.kpart = kpart;
+            g.ktickets = ktickets;
             g.xhi = xhi;
             g.xlo = xlo;
             g.ssq_in = ssq;
@@ -1102,6 +1192,8 @@ static dk_status decode_step_impl(dk_model *model, dk_kv_pool *pool, const int32
             g.K = nq * d;
             g.B = B;
             g.q4 = model->q4;
+            g.kpart = kpart;
+            g.ktickets = ktickets;
             g.xhi = ahi;
             g.xlo = alo;
             g.xres = x;
@@ -1227,6 +1319,8 @@ static dk_status decode_step_impl(dk_model *model, dk_kv_pool *pool, const int32
             g.K = H;
             g.B = B;
             g.q4 = model->q4;
+            g.kpart = kpart;
+            g.ktickets = ktickets;
             g.xhi = xhi;
             g.xlo = xlo;
             g.ssq_in = ssq;
@@ -1241,6 +1335,8 @@ static dk_status decode_step_impl(dk_model *model, dk_kv_pool *pool, const int32
             h.K = c.ffn;
             h.B = B;
             h.q4 = model->q4;
+            h.kpart = kpart;
+            h.ktickets = ktickets;
             h.xhi = fhi;
             h.xlo = flo;
             h.xres = x;
@@ -1282,6 +1378,8 @@ static dk_status decode_step_impl(dk_model *model, dk_kv_pool *pool, const int32
         g.K = H;
         g.B = B;
         g.q4 = model->q4;
+        g.kpart = kpart;
+        g.ktickets = ktickets;
         g.xhi = xhi;
         g.xlo = xlo;
         g.ssq_in = ssq;

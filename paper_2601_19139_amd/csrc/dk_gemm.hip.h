@@ -65,6 +65,10 @@ struct GemmArgs {
     float *xres;
     const uint16_t *gain_next;  // [N]
     float *ssq_out;
+    // shared_gemm_kernel with K cut into slices: partial tiles and one ticket per row block
+    // (zero before the launch, zero after)
+    float *kpart;
+    int *ktickets;
 };
 
 __device__ __forceinline__ void split_bf16(float x, uint16_t &hi, uint16_t &lo)
@@ -78,6 +82,78 @@ __device__ __forceinline__ bf16x8_t as_bf16x8(const uint4 &u)
     union { uint4 u; bf16x8_t v; } c;
     c.u = u;
     return c.v;
+}
+
+// Epilogue of one finished 16-row tile.  The lane holds D[row0 + 4*lg + i][n = 16*t + ln], i = 0..3, in
+// v[t][matrix][i] (already scaled by 1/rms where the input norm is fused).  xr / gn: the residual rows and the
+// next norm's gains of exactly those elements (GEPI_RESID; loaded by the caller ahead of the weight stream).
+template <int MT, int EPI>
+__device__ __forceinline__ void gemm_tile_epilogue(const GemmArgs &a, int out_tile, int lane,
+                                                   const float (&v)[MT][(EPI == GEPI_SWIGLU) ? 2 : 1][4],
+                                                   const float (&xr)[MT][4], const float (&gn)[4])
+{
+    constexpr int NM = (EPI == GEPI_SWIGLU) ? 2 : 1;
+    const int ln = lane & 15, lg = lane >> 4;
+    const int N = a.N;
+    const int onks = (N + 127) >> 7;   // K-steps of the GEMM that consumes this output
+    const int n_tiles = (N + 15) >> 4;
+    const int row0 = out_tile * 16;
+    float best = -INFINITY;
+    int best_i = 0x7fffffff;
+#pragma unroll
+    for (int t = 0; t < MT; t++) {
+        const int n = t * 16 + ln;
+        const bool nvalid = n < a.B;
+        const int rr = row0 + 4 * lg;
+        float sq = 0.f;
+#pragma unroll
+        for (int i = 0; i < 4; i++) {
+            const int r = rr + i;
+            if (!nvalid || r >= N) continue;
+            if (EPI == GEPI_STORE) {
+                const float out = v[t][0][i];
+                if (a.y != nullptr) a.y[(int64_t)n * N + r] = out;
+                if (out > best) { best = out; best_i = r; }
+            } else if (EPI == GEPI_SWIGLU) {
+                const float z = v[t][0][i];
+                const float out = z / (1.0f + __expf(-z)) * v[t][NM - 1][i];
+                uint16_t hi, lo;
+                split_bf16(out, hi, lo);
+                const int64_t oo = act_offset(n, r, onks);
+                a.ohi[oo] = hi;
+                a.olo[oo] = lo;
+            } else {
+                const float xn = xr[t][i] + v[t][0][i];
+                a.xres[(int64_t)n * N + r] = xn;
+                sq += xn * xn;
+                uint16_t hi, lo;
+                split_bf16(xn * gn[i], hi, lo);
+                const int64_t oo = act_offset(n, r, onks);
+                a.ohi[oo] = hi;
+                a.olo[oo] = lo;
+            }
+        }
+        if (EPI == GEPI_RESID) {
+            // the tile's 16 rows of batch row n are spread over the 4 lane groups
+            sq += __shfl_xor(sq, 16);
+            sq += __shfl_xor(sq, 32);
+            if (lg == 0) a.ssq_out[(int64_t)out_tile * kSsqStride + n] = nvalid ? sq : 0.f;
+        }
+        if (EPI == GEPI_STORE && a.pmax_val != nullptr) {
+#pragma unroll
+            for (int off = 16; off < 64; off <<= 1) {
+                const float ov = __shfl_xor(best, off);
+                const int oi = __shfl_xor(best_i, off);
+                if (ov > best || (ov == best && oi < best_i)) { best = ov; best_i = oi; }
+            }
+            if (lg == 0 && nvalid) {
+                a.pmax_val[(int64_t)n * n_tiles + out_tile] = best;
+                a.pmax_idx[(int64_t)n * n_tiles + out_tile] = best_i;
+            }
+            best = -INFINITY;
+            best_i = 0x7fffffff;
+        }
+    }
 }
 
 // KALIGNED: K is a multiple of 128 (every real model shape); the K-steps are then
@@ -293,8 +369,6 @@ __global__ __launch_bounds__(KS * 64) void skinny_gemm_kernel(GemmArgs a)
 #pragma unroll
     for (int p = 0; p < PD; p++) issue(st[p]);
 
-    const int onks = (N + 127) >> 7;   // K-steps of the GEMM that consumes this output
-    const int n_tiles = (N + 15) >> 4;
     {
         for (int it = 0; it + PD < niter2; it += PD) {
 #pragma unroll
@@ -329,14 +403,11 @@ __global__ __launch_bounds__(KS * 64) void skinny_gemm_kernel(GemmArgs a)
         // D[row0 + 4*lg + i][n = 16*t + ln], i = 0..3.
         const int rt = wv;
         const int out_tile = (int)blockIdx.x * RT + rt;
-        const int row0 = out_tile * 16;
-        if (row0 >= N) return;
-        float best = -INFINITY;
-        int best_i = 0x7fffffff;
+        if (out_tile * 16 >= N) return;
+        float v[MT][NM][4];
 #pragma unroll
         for (int t = 0; t < MT; t++) {
             const int n = t * 16 + ln;
-            float v[NM][4];
 #pragma unroll
             for (int m = 0; m < NM; m++)
 #pragma unroll
@@ -344,7 +415,7 @@ __global__ __launch_bounds__(KS * 64) void skinny_gemm_kernel(GemmArgs a)
                     float s = 0.f;
 #pragma unroll
                     for (int w = 0; w < KS; w++) s += rb[w][m * RT + rt][t][i][lane];
-                    v[m][i] = s;
+                    v[t][m][i] = s;
                 }
             if (NORM) {
                 float s = 0.f;
@@ -354,59 +425,10 @@ __global__ __launch_bounds__(KS * 64) void skinny_gemm_kernel(GemmArgs a)
 #pragma unroll
                 for (int m = 0; m < NM; m++)
 #pragma unroll
-                    for (int i = 0; i < 4; i++) v[m][i] *= inv;
-            }
-            const bool nvalid = n < a.B;
-            const int rr = row0 + 4 * lg;
-            float sq = 0.f;
-#pragma unroll
-            for (int i = 0; i < 4; i++) {
-                const int r = rr + i;
-                if (!nvalid || r >= N) continue;
-                if (EPI == GEPI_STORE) {
-                    const float out = v[0][i];
-                    if (a.y != nullptr) a.y[(int64_t)n * N + r] = out;
-                    if (out > best) { best = out; best_i = r; }
-                } else if (EPI == GEPI_SWIGLU) {
-                    const float z = v[0][i];
-                    const float out = z / (1.0f + __expf(-z)) * v[NM - 1][i];
-                    uint16_t hi, lo;
-                    split_bf16(out, hi, lo);
-                    const int64_t oo = act_offset(n, r, onks);
-                    a.ohi[oo] = hi;
-                    a.olo[oo] = lo;
-                } else {
-                    const float xn = xr[t][i] + v[0][i];
-                    a.xres[(int64_t)n * N + r] = xn;
-                    sq += xn * xn;
-                    uint16_t hi, lo;
-                    split_bf16(xn * gn[i], hi, lo);
-                    const int64_t oo = act_offset(n, r, onks);
-                    a.ohi[oo] = hi;
-                    a.olo[oo] = lo;
-                }
-            }
-            if (EPI == GEPI_RESID) {
-                // the tile's 16 rows of batch row n are spread over the 4 lane groups
-                sq += __shfl_xor(sq, 16);
-                sq += __shfl_xor(sq, 32);
-                if (lg == 0) a.ssq_out[(int64_t)out_tile * kSsqStride + n] = nvalid ? sq : 0.f;
-            }
-            if (EPI == GEPI_STORE && a.pmax_val != nullptr) {
-#pragma unroll
-                for (int off = 16; off < 64; off <<= 1) {
-                    const float ov = __shfl_xor(best, off);
-                    const int oi = __shfl_xor(best_i, off);
-                    if (ov > best || (ov == best && oi < best_i)) { best = ov; best_i = oi; }
-                }
-                if (lg == 0 && nvalid) {
-                    a.pmax_val[(int64_t)n * n_tiles + out_tile] = best;
-                    a.pmax_idx[(int64_t)n * n_tiles + out_tile] = best_i;
-                }
-                best = -INFINITY;
-                best_i = 0x7fffffff;
+                    for (int i = 0; i < 4; i++) v[t][m][i] *= inv;
             }
         }
+        gemm_tile_epilogue<MT, EPI>(a, out_tile, lane, v, xr, gn);
     }
 }
 

@@ -306,6 +306,28 @@ def test_batch16_full_size_sampled_rows(dk, orc, wname, rows, steps):
     check_pool_sampled(out, pool, shape, lay, steps, rows)
 
 
+@pytest.mark.parametrize("batch", [20, 40, 64])
+def test_wide_batches_of_a_large_layer(dk, orc, batch):
+    """From 17 rows on the lm_head, and from 33 rows on every large layer matrix, runs in the
+    GEMM whose waves share one activation tile in LDS (with K cut across blocks and a last-arriver
+    sum for the down projection).  One layer with matrices large enough to take each of those
+    paths (q/k/v 6144 x 2048, gate/up 20480 x 2048, down 2048 x 20480, vocabulary 70003), two
+    steps so that the tickets are used twice; sampled rows against the oracle."""
+    shape = variant("tiny", n_layers=1, hidden=2048, n_q_heads=32, n_kv_heads=8, head_dim=128, ffn=20480,
+                    vocab=70003, qk_norm=True, rope_theta=1e6)
+    contexts = [(37 * i) % 150 for i in range(batch)]
+    lay = build_block_tables(contexts, 16, 2, seed=31)
+    weights = W.make_weights(shape, 12)
+    pool = W.fill_kv_pool(shape, lay, 13)
+    tokens = W.initial_tokens(shape, batch, 14)
+    rows = (0, batch // 2, batch - 1)
+    out = run_sampled(orc, shape, weights, lay, pool, tokens, 2, rows)
+    worst, agree = check_parity(out)
+    print(f"batch {batch}: worst rel-L2 {worst:.3e}, greedy agreement {agree:.3f}")
+    assert worst < TIGHT and agree == 1.0
+    check_pool_sampled(out, pool, shape, lay, 2, rows)
+
+
 MOE_CASES = [
     ("cfg0_moe", W.CONFIGS["tiny_moe"], [33, 16, 5], 4),
     ("moe_batch1", W.CONFIGS["tiny_moe"], [21], 3),
