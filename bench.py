@@ -53,6 +53,21 @@ def cpu_baseline(shape, weights, layout, pool_bits, tokens, budget_s=12.0, max_s
                       f"(fp64 C loops, OpenMP over rows of a matrix)"}
 
 
+def dtype_name(args):
+    return "bf16" if args.weights == "bf16" else "bf16 activations and KV, 4-bit weights (fp32 accumulation)"
+
+
+def make_model_weights(args, W, shape, seed):
+    """Seeded weights of the shape; with --weights q4 the projections and the lm_head quantised to 4 bits."""
+    weights = W.make_weights(shape, seed)
+    if args.weights == "q4":
+        from workloads.quant import quantize_weights
+        if weights["lm_head"] is weights["embed"]:
+            weights = {**weights, "lm_head": weights["embed"].copy()}   # the embedding table stays bf16
+        weights = quantize_weights(weights)
+    return weights
+
+
 def batch16_line(args, wl, dk, W, np, torch, dm, tok_s_batch1):
     """The same model with 16 concurrent sequences of the workload's context length (private caches):
     the other end of the paper's 1 -> 16 concurrent-request sweep.  Reported beside the batch-1 figure."""
@@ -95,7 +110,7 @@ def bench_prefill(args, wl, dk, W, np, torch):
     from workloads.blocktable import build_block_tables
     shape, P, chunk = wl.cfg, args.prefill, 64
     lay = build_block_tables([0], 16, P + 1, seed=wl.seed_blocks)
-    weights = W.make_weights(shape, wl.seed_weights)
+    weights = make_model_weights(args, W, shape, wl.seed_weights)
     dm = dk.DeviceModel(shape, weights)
     dkv = dk.DeviceKV(dm, lay, W.fill_kv_pool(shape, lay, wl.seed_kv, poison=False))
     pre = dk.Prefiller(dm, dkv, max_chunk=chunk, want_logits=False)
@@ -126,7 +141,7 @@ def bench_prefill(args, wl, dk, W, np, torch):
               for o in range(0, P, chunk))
     print(json.dumps({
         "metric": "prefill_tok_per_s", "value": round(P / wall, 1), "unit": "tok/s", "n_gpus": 1,
-        "steps": reps, "ms_per_step": round(wall * 1e3, 4), "higher_is_better": True, "dtype": "bf16",
+        "steps": reps, "ms_per_step": round(wall * 1e3, 4), "higher_is_better": True, "dtype": dtype_name(args),
         "data": "synthetic (seeded random-init weights)",
         "config": {"workload": f"{shape.name}: one {P}-token prompt into an empty cache, {chunk} tokens per chunk",
                    "chunks": n_chunks},
@@ -140,7 +155,7 @@ def bench_serve(args, wl, dk, W, np, torch):
     """The scheduler end to end: C requests submitted at once, run until all are done."""
     shape, C, P, NEW, STEM = wl.cfg, args.serve, 512, 128, 256
     assert 1 <= C <= 64
-    weights = W.make_weights(shape, wl.seed_weights)
+    weights = make_model_weights(args, W, shape, wl.seed_weights)
     dm = dk.DeviceModel(shape, weights)
     per_seq = (P + NEW + 15) // 16 + 1
     n_blocks = C * per_seq + 64
@@ -173,7 +188,7 @@ def bench_serve(args, wl, dk, W, np, torch):
     gen_tokens = st["generated_tokens"] - 2 * C  # tokens of the steady decode phase (after the first iteration)
     print(json.dumps({
         "metric": "engine_aggregate_decode_tok_per_s", "value": round(gen_tokens / gen_s, 1), "unit": "tok/s",
-        "n_gpus": 1, "higher_is_better": True, "dtype": "bf16", "data": "synthetic (seeded random-init weights)",
+        "n_gpus": 1, "higher_is_better": True, "dtype": dtype_name(args), "data": "synthetic (seeded random-init weights)",
         "config": {"workload": f"{shape.name}: {C} concurrent requests, {P}-token prompts sharing a {STEM}-token "
                                f"stem, {NEW} new tokens each, continuous batching with prefix cache",
                    "concurrency": C},
@@ -189,7 +204,7 @@ def bench_serve(args, wl, dk, W, np, torch):
 def bench_ttft(args, wl, dk, W, np, torch):
     """Time to first token of a prompt whose 512-token prefix is / is not in the prefix cache."""
     shape, PREFIX, OWN = wl.cfg, 512, 32
-    weights = W.make_weights(shape, wl.seed_weights)
+    weights = make_model_weights(args, W, shape, wl.seed_weights)
     dm = dk.DeviceModel(shape, weights)
     per_seq = (PREFIX + OWN + 15) // 16 + 2
     n_blocks = 16 * per_seq
@@ -219,7 +234,7 @@ def bench_ttft(args, wl, dk, W, np, torch):
     m, h = float(np.median(miss)), float(np.median(hit))
     print(json.dumps({
         "metric": "ttft_ms", "value": round(h * 1e3, 3), "unit": "ms", "higher_is_better": False, "n_gpus": 1,
-        "dtype": "bf16", "data": "synthetic (seeded random-init weights)",
+        "dtype": dtype_name(args), "data": "synthetic (seeded random-init weights)",
         "config": {"workload": f"{shape.name}: {PREFIX}-token shared prefix + {OWN} own tokens, first token, "
                                f"through the engine (prefix cache hit vs miss)"},
         "ttft_miss_ms": round(m * 1e3, 3), "ttft_hit_ms": round(h * 1e3, 3), "speedup": round(m / h, 2),
@@ -272,13 +287,9 @@ def main():
     if args.ttft:
         return bench_ttft(args, wl, dk, W, np, torch)
     shape, lay = wl.cfg, layout_for(wl)
-    weights = W.make_weights(shape, wl.seed_weights)
+    weights = make_model_weights(args, W, shape, wl.seed_weights)
     weight_bytes = shape.dense_weight_bytes()
     if args.weights == "q4":
-        from workloads.quant import quantize_weights
-        if weights["lm_head"] is weights["embed"]:
-            weights = {**weights, "lm_head": weights["embed"].copy()}   # the embedding table stays bf16
-        weights = quantize_weights(weights)
         weight_bytes = weight_bytes // 4 + weight_bytes // 128 * 4       # 4 bits + (scale, bias) per 64 weights
     pool_bits = W.fill_kv_pool(shape, lay, wl.seed_kv, poison=False)
     tokens0 = W.initial_tokens(shape, wl.batch, wl.seed_tokens)
@@ -369,7 +380,7 @@ def main():
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "bf16" if args.weights == "bf16" else "bf16 activations and KV, 4-bit weights (fp32 accumulation)",
+        "dtype": dtype_name(args),
         "data": "synthetic (seeded random-init weights and KV of the named shape)",
         "config": {"workload": f"{wl.name}: {shape.name} decode, batch {wl.batch}, "
                                f"context {int(lay.contexts.min())}..{int(lay.contexts.max())} growing, "

@@ -203,7 +203,15 @@ GemmPlan gemm_plan(int epi, int N, int K, int Bp, bool q4)
 {
     const int mt = Bp / 16;
     const long long elems = (long long)N * K;
-    if (q4 || mt < 2 || K % 128) return {0, 1};
+    if (K % 128) return {0, 1};
+    if (q4) {
+        // 4-bit weights: the kernels are bound by the matrix cores and the code conversion rather than by
+        // the activation traffic; sharing pays for the lm_head (every batch size) and the gate/up pair
+        if (epi == dk::GEPI_STORE && (N + 15) / 16 >= 4096) return {8, 1};
+        if (epi == dk::GEPI_SWIGLU && mt >= 2 && elems >= (20ll << 20)) return {8, 2};
+        return {0, 1};
+    }
+    if (mt < 2) return {0, 1};
     if (epi == dk::GEPI_STORE) {
         if ((N + 15) / 16 >= 4096) return {8, 1};
         if (mt >= 3 && elems >= (12ll << 20)) return {4, 2};
@@ -424,11 +432,11 @@ dk_status launch_gemm_cfg(const dk::GemmArgs &a, hipStream_t st)
 // the 8B-class shapes: 4 tiles per wave for the lm_head, 2 for the fused q/k/v
 // matrix, 1 for the square-ish projections and the gate/up pair).
 // ---- shared-activation GEMM dispatch (see gemm_plan) -------------------------
-template <int MT, int W, int EPI, bool NORM>
+template <int MT, int W, int EPI, bool NORM, bool Q4 = false>
 dk_status launch_shared_gemm_inst(const dk::GemmArgs &a, int slices, hipStream_t st)
 {
     constexpr size_t lds = dk::shared_gemm_lds_bytes(MT);
-    auto kernel = dk::shared_gemm_kernel<MT, W, 1, 2, EPI, NORM>;
+    auto kernel = dk::shared_gemm_kernel<MT, W, 1, 2, EPI, NORM, Q4>;
     static bool lds_allowed = false;   // above 64 KB together with the kernel's static LDS: ask once
     if (!lds_allowed) {
         DK_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -447,6 +455,17 @@ dk_status launch_shared_gemm(const dk::GemmArgs &a, int Bp, const GemmPlan &p, h
     if (p.slices > 1 && (a.kpart == nullptr || a.ktickets == nullptr))
         return fail(DK_E_INVALID_ARG, "K-sliced GEMM without its partial buffer");
     const int mt = Bp / 16;
+    if (a.q4) {
+        if constexpr (EPI == dk::GEPI_STORE) {
+            if (p.w == 8 && mt == 1) return launch_shared_gemm_inst<1, 8, EPI, NORM, true>(a, p.slices, st);
+        }
+        if constexpr (EPI != dk::GEPI_RESID) {
+            if (p.w == 8 && mt == 2) return launch_shared_gemm_inst<2, 8, EPI, NORM, true>(a, p.slices, st);
+            if (p.w == 8 && mt == 3) return launch_shared_gemm_inst<3, 8, EPI, NORM, true>(a, p.slices, st);
+            if (p.w == 8 && mt == 4) return launch_shared_gemm_inst<4, 8, EPI, NORM, true>(a, p.slices, st);
+        }
+        return fail(DK_E_INVALID_ARG, "no shared-activation 4-bit GEMM for %d rows and %d waves", Bp, p.w);
+    }
     if constexpr (EPI == dk::GEPI_STORE) {
         if (p.w == 8 && mt == 2) return launch_shared_gemm_inst<2, 8, EPI, NORM>(a, p.slices, st);
         if (p.w == 8 && mt == 3) return launch_shared_gemm_inst<3, 8, EPI, NORM>(a, p.slices, st);

@@ -84,6 +84,19 @@ __device__ __forceinline__ bf16x8_t as_bf16x8(const uint4 &u)
     return c.v;
 }
 
+// The eight 4-bit codes of a word (code j in bits 4j..4j+3) as exact bf16 numbers, in matrix-core
+// operand order: bytes of nibbles, byte -> float, then the upper halves of two floats side by side.
+__device__ __forceinline__ uint4 q4_codes_bf16(uint32_t w)
+{
+    const uint32_t ev = w & 0x0F0F0F0Fu, od = (w >> 4) & 0x0F0F0F0Fu;
+    uint4 r;
+    r.x = __builtin_amdgcn_perm(__float_as_uint((float)(od & 0xFFu)), __float_as_uint((float)(ev & 0xFFu)), 0x07060302u);
+    r.y = __builtin_amdgcn_perm(__float_as_uint((float)((od >> 8) & 0xFFu)), __float_as_uint((float)((ev >> 8) & 0xFFu)), 0x07060302u);
+    r.z = __builtin_amdgcn_perm(__float_as_uint((float)((od >> 16) & 0xFFu)), __float_as_uint((float)((ev >> 16) & 0xFFu)), 0x07060302u);
+    r.w = __builtin_amdgcn_perm(__float_as_uint((float)(od >> 24)), __float_as_uint((float)(ev >> 24)), 0x07060302u);
+    return r;
+}
+
 // Epilogue of one finished 16-row tile.  The lane holds D[row0 + 4*lg + i][n = 16*t + ln], i = 0..3, in
 // v[t][matrix][i] (already scaled by 1/rms where the input norm is fused).  xr / gn: the residual rows and the
 // next norm's gains of exactly those elements (GEPI_RESID; loaded by the caller ahead of the weight stream).
@@ -275,19 +288,8 @@ __global__ __launch_bounds__(KS * 64) void skinny_gemm_kernel(GemmArgs a)
                         sc[i] = __uint_as_float(sbw[i] << 16);
                         b2[i] = __uint_as_float(sbw[i] & 0xFFFF0000u);
                     }
-                    // the eight codes of a word as exact bf16 numbers: bytes of nibbles, byte -> float,
-                    // then the upper halves of two floats side by side
-                    auto codes = [](uint32_t w) {
-                        const uint32_t ev = w & 0x0F0F0F0Fu, od = (w >> 4) & 0x0F0F0F0Fu;
-                        uint4 r;
-                        r.x = __builtin_amdgcn_perm(__float_as_uint((float)(od & 0xFFu)), __float_as_uint((float)(ev & 0xFFu)), 0x07060302u);
-                        r.y = __builtin_amdgcn_perm(__float_as_uint((float)((od >> 8) & 0xFFu)), __float_as_uint((float)((ev >> 8) & 0xFFu)), 0x07060302u);
-                        r.z = __builtin_amdgcn_perm(__float_as_uint((float)((od >> 16) & 0xFFu)), __float_as_uint((float)((ev >> 16) & 0xFFu)), 0x07060302u);
-                        r.w = __builtin_amdgcn_perm(__float_as_uint((float)(od >> 24)), __float_as_uint((float)(ev >> 24)), 0x07060302u);
-                        return r;
-                    };
-                    const uint4 a0 = codes(h ? st.wa[m][0].z : st.wa[m][0].x);
-                    const uint4 a1 = codes(h ? st.wa[m][0].w : st.wa[m][0].y);
+                    const uint4 a0 = q4_codes_bf16(h ? st.wa[m][0].z : st.wa[m][0].x);
+                    const uint4 a1 = q4_codes_bf16(h ? st.wa[m][0].w : st.wa[m][0].y);
 #pragma unroll
                     for (int t = 0; t < MT; t++) {
                         f32x4_t D = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(a0), as_bf16x8(st.bh[t][2 * h]), zero, 0, 0, 0);

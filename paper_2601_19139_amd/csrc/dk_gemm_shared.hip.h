@@ -36,7 +36,9 @@ constexpr size_t shared_gemm_lds_bytes(int MT) { return (size_t)2 * 512 * MT * 1
 
 // W waves per block, RT row tiles per wave (GEPI_SWIGLU: of each of the two matrices), PD K-steps
 // in flight per wave.  K must be a multiple of 128.  grid = (ceil(tiles / (W*RT)), slices).
-template <int MT, int W, int RT, int PD, int EPI, bool NORM>
+// Q4: packed 4-bit weights, evaluated as in skinny_gemm_kernel's Q4 variant (codes through the matrix
+// cores, group sums of x from an all-ones operand, scale and bias applied to the fp32 tiles).
+template <int MT, int W, int RT, int PD, int EPI, bool NORM, bool Q4 = false>
 __global__ __launch_bounds__(W * 64) void shared_gemm_kernel(GemmArgs a)
 {
     constexpr int NM = (EPI == GEPI_SWIGLU) ? 2 : 1;
@@ -70,7 +72,7 @@ __global__ __launch_bounds__(W * 64) void shared_gemm_kernel(GemmArgs a)
     // Same pipeline discipline as skinny_gemm_kernel: no conditional loads, every wave runs a
     // multiple of PD steps, steps past the slice read clamped addresses and are not used.
     struct Stage {
-        uint4 wa[NA][4], act[PPT];
+        uint4 wa[NA][Q4 ? 3 : 4], act[PPT];   // Q4: codes of the whole step, (scale, bias) of its two groups
     };
     int it_i = 0;
     auto issue = [&](Stage &st) {
@@ -83,10 +85,20 @@ __global__ __launch_bounds__(W * 64) void shared_gemm_kernel(GemmArgs a)
         }
 #pragma unroll
         for (int m = 0; m < NA; m++) {
-            const int wrow = min((tile0 + (m % RT)) * 16 + ln, N - 1);   // rows past the end are clamped
-            const uint16_t *wq = ((m / RT) ? a.W2 : a.W) + (int64_t)wrow * K + ks * 128 + lg * 8;
+            if constexpr (Q4) {
+                const uint8_t *base = reinterpret_cast<const uint8_t *>((m / RT) ? a.W2 : a.W);
+                const int tile = min(tile0 + (m % RT), n_tiles - 1);
+                const int wrow = min(tile * 16 + ln, N - 1);
+                st.wa[m][0] = ld16(base + (int64_t)wrow * (K >> 1) + ks * 64 + lg * 16);
+                const uint8_t *sb = base + (int64_t)N * (K >> 1) + (((int64_t)tile * nks + ks) * 4 + lg) * 32;
+                st.wa[m][1] = ld16(sb);
+                st.wa[m][2] = ld16(sb + 16);
+            } else {
+                const int wrow = min((tile0 + (m % RT)) * 16 + ln, N - 1);   // rows past the end are clamped
+                const uint16_t *wq = ((m / RT) ? a.W2 : a.W) + (int64_t)wrow * K + ks * 128 + lg * 8;
 #pragma unroll
-            for (int s = 0; s < 4; s++) st.wa[m][s] = ld16(wq + s * 32);
+                for (int s = 0; s < 4; s++) st.wa[m][s] = ld16(wq + s * 32);
+            }
         }
         it_i++;
     };
@@ -98,6 +110,48 @@ __global__ __launch_bounds__(W * 64) void shared_gemm_kernel(GemmArgs a)
         // one barrier per step is enough with two slots: nobody can write this slot again
         // before every wave has passed the next step's barrier, i.e. has finished reading it
         __syncthreads();
+        if constexpr (Q4) {
+            const uint4 one4 = make_uint4(0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u);
+            const f32x4_t zero = f32x4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int h = 0; h < 2; h++) {
+                uint4 c0[NA], c1[NA];
+                float sc[NA][4], bi[NA][4];
+#pragma unroll
+                for (int m = 0; m < NA; m++) {
+                    c0[m] = q4_codes_bf16(h ? st.wa[m][0].z : st.wa[m][0].x);
+                    c1[m] = q4_codes_bf16(h ? st.wa[m][0].w : st.wa[m][0].y);
+                    const uint4 sb = st.wa[m][1 + h];
+                    const uint32_t sbw[4] = {sb.x, sb.y, sb.z, sb.w};
+#pragma unroll
+                    for (int i = 0; i < 4; i++) {
+                        sc[m][i] = __uint_as_float(sbw[i] << 16);
+                        bi[m][i] = __uint_as_float(sbw[i] & 0xFFFF0000u);
+                    }
+                }
+#pragma unroll
+                for (int t = 0; t < MT; t++) {
+                    const uint4 bh0 = slot[t * 512 + (2 * h) * 64 + lane], bl0 = slot[t * 512 + 256 + (2 * h) * 64 + lane];
+                    const uint4 bh1 = slot[t * 512 + (2 * h + 1) * 64 + lane], bl1 = slot[t * 512 + 256 + (2 * h + 1) * 64 + lane];
+                    // group sums of x for this lane's batch row (the same in all four accumulator rows)
+                    f32x4_t S = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(one4), as_bf16x8(bh0), zero, 0, 0, 0);
+                    S = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(one4), as_bf16x8(bl0), S, 0, 0, 0);
+                    S = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(one4), as_bf16x8(bh1), S, 0, 0, 0);
+                    S = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(one4), as_bf16x8(bl1), S, 0, 0, 0);
+#pragma unroll
+                    for (int m = 0; m < NA; m++) {
+                        f32x4_t D = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(c0[m]), as_bf16x8(bh0), zero, 0, 0, 0);
+                        D = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(c0[m]), as_bf16x8(bl0), D, 0, 0, 0);
+                        D = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(c1[m]), as_bf16x8(bh1), D, 0, 0, 0);
+                        D = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(c1[m]), as_bf16x8(bl1), D, 0, 0, 0);
+#pragma unroll
+                        for (int i = 0; i < 4; i++)
+                            acc[m][t][i] = fmaf(sc[m][i], D[i], fmaf(bi[m][i], S[i], acc[m][t][i]));
+                    }
+                }
+            }
+            return;
+        }
 #pragma unroll
         for (int s = 0; s < 4; s++)
 #pragma unroll

@@ -99,6 +99,25 @@ def test_q4_both_paths_for_small_batches(dk, orc, contexts):
         check_pool(out, pool, shape, lay, 3)
 
 
+@pytest.mark.parametrize("batch", [20, 40, 64])
+def test_q4_wide_batches_of_a_large_layer(dk, orc, batch):
+    """From 17 rows on the gate/up pair of a large layer (here 10240 x 2048) runs, like the lm_head at every
+    batch size, in the GEMM whose waves share one activation tile, with K cut in two across blocks."""
+    shape = variant("tiny_q4", n_layers=1, hidden=2048, n_q_heads=16, n_kv_heads=8, head_dim=128, ffn=10240,
+                    vocab=70003, rope_theta=1e6)
+    contexts = [(29 * i) % 120 for i in range(batch)]
+    lay = build_block_tables(contexts, 16, 2, seed=37)
+    weights = quantize_weights(W.make_weights(shape, 15))
+    pool = W.fill_kv_pool(shape, lay, 16)
+    tokens = W.initial_tokens(shape, batch, 17)
+    rows = (0, batch // 2, batch - 1)
+    out = run_sampled(orc, shape, weights, lay, pool, tokens, 2, rows)
+    worst, agree = check_parity(out)
+    print(f"4-bit, batch {batch}: worst rel-L2 {worst:.3e}, greedy agreement {agree:.3f}")
+    assert worst < TIGHT and agree == 1.0
+    check_pool_sampled(out, pool, shape, lay, 2, rows)
+
+
 def test_q4_distinct_scales_and_biases_per_group(dk, orc):
     """Codes, scales and biases drawn independently (no relation to a bf16 matrix): a scale or bias
     taken from the wrong row, group or half of a K-step changes the logits by far more than the bound."""
