@@ -196,8 +196,8 @@ bool attention_uses_mfma(const dk_model_config &c, int B, bool q4)
 // Which kernel a batched GEMM takes: w == 0 the K-split-per-wave kernel (skinny_gemm_kernel),
 // otherwise shared_gemm_kernel with w waves per block and K cut into `slices` across blocks.
 // Measured on the 0.6B / 3B / 8B shapes: sharing the activation tile pays for the lm_head from 17
-// batch rows on, for the gate/up pair of a large model from 17 rows on, and for the other large
-// layer matrices from 33 rows on; everything smaller is faster with the other kernel.
+// batch rows on (with a short K also at 16), for the gate/up pair of a large model from 17 rows on, and
+// for the other large layer matrices from 33 rows on; everything smaller is faster with the other kernel.
 struct GemmPlan { int w, slices; };
 GemmPlan gemm_plan(int epi, int N, int K, int Bp, bool q4)
 {
@@ -211,7 +211,9 @@ GemmPlan gemm_plan(int epi, int N, int K, int Bp, bool q4)
         if (epi == dk::GEPI_SWIGLU && mt >= 2 && elems >= (20ll << 20)) return {8, 2};
         return {0, 1};
     }
-    if (mt < 2) return {0, 1};
+    // 16 rows: only the lm_head, and only while K is short (measured: 106 -> 67 us at K = 1024,
+    // 181 -> 150 us at K = 3072, 250 -> 276 us at K = 4096)
+    if (mt < 2) return (epi == dk::GEPI_STORE && (N + 15) / 16 >= 4096 && K <= 3072) ? GemmPlan{8, 1} : GemmPlan{0, 1};
     if (epi == dk::GEPI_STORE) {
         if ((N + 15) / 16 >= 4096) return {8, 1};
         if (mt >= 3 && elems >= (12ll << 20)) return {4, 2};
@@ -467,6 +469,7 @@ dk_status launch_shared_gemm(const dk::GemmArgs &a, int Bp, const GemmPlan &p, h
         return fail(DK_E_INVALID_ARG, "no shared-activation 4-bit GEMM for %d rows and %d waves", Bp, p.w);
     }
     if constexpr (EPI == dk::GEPI_STORE) {
+        if (p.w == 8 && mt == 1) return launch_shared_gemm_inst<1, 8, EPI, NORM>(a, p.slices, st);
         if (p.w == 8 && mt == 2) return launch_shared_gemm_inst<2, 8, EPI, NORM>(a, p.slices, st);
         if (p.w == 8 && mt == 3) return launch_shared_gemm_inst<3, 8, EPI, NORM>(a, p.slices, st);
         if (p.w == 8 && mt == 4) return launch_shared_gemm_inst<4, 8, EPI, NORM>(a, p.slices, st);
