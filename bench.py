@@ -266,7 +266,7 @@ def main():
                     help="never take the single persistent kernel (small batches of small dense models)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU; --gpus must be 1", file=sys.stderr)
+        print("bench.py: the library runs on one GPU; --gpus must be 1", file=sys.stderr)
         sys.exit(2)
 
     import numpy as np

@@ -46,7 +46,7 @@ enum {
     DK_E_HIP = -6
 };
 
-/* Limits of this build (dk_create_model / dk_decode_step reject beyond). */
+/* Limits of the library (dk_create_model / dk_decode_step reject beyond). */
 #define DK_MAX_BATCH 64
 #define DK_MAX_EXPERTS 256
 

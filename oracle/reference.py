@@ -18,8 +18,8 @@ def _lib_path(real: str) -> str:
 
 def build(force: bool = False) -> None:
     """Compile both builds of the oracle: arithmetic in double (the reference
-    for every parity test) and in float (the precision the benchmark spec
-    names; kept to show the two agree)."""
+    for every parity test) and in float (single precision; kept to show the
+    two agree)."""
     os.makedirs(_BUILD, exist_ok=True)
     for real, flag in (("f64", []), ("f32", ["-DORC_REAL_FLOAT"])):
         out = _lib_path(real)
