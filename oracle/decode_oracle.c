@@ -306,8 +306,10 @@ static void route(const orc_config *c, const uint16_t *w_router, const real *h,
     free(taken);
 }
 
-static void moe(const orc_config *c, const orc_layer *L, const real *h, real *out,
-                int32_t *idx_out, real *wts_out)
+/* qg / qu / qd: NULL, or the 4-bit gate / up / down matrices of ALL experts stacked by rows
+ * (expert e owns rows e*Fe.. of gate and up, rows e*H.. of down); the router stays bf16. */
+static void moe_any(const orc_config *c, const orc_layer *L, const orc_q4 *qg, const orc_q4 *qu, const orc_q4 *qd,
+                    const real *h, real *out, int32_t *idx_out, real *wts_out)
 {
     int H = c->hidden, Fe = c->expert_ffn, K = c->top_k;
     int32_t *idx = (int32_t *)malloc(sizeof(int32_t) * (size_t)K);
@@ -317,7 +319,15 @@ static void moe(const orc_config *c, const orc_layer *L, const real *h, real *ou
     for (int i = 0; i < H; i++) out[i] = 0;
     for (int k = 0; k < K; k++) {
         int64_t e = idx[k];
-        swiglu(L->w_gate + e * Fe * H, L->w_up + e * Fe * H, L->w_down + e * H * Fe, H, Fe, h, y);
+        if (qg) {
+            /* expert e's rows of the stacked matrices */
+            const orc_q4 g = {qg->q + e * Fe * H, qg->scale + e * Fe * (H / 64), qg->bias + e * Fe * (H / 64)};
+            const orc_q4 u = {qu->q + e * Fe * H, qu->scale + e * Fe * (H / 64), qu->bias + e * Fe * (H / 64)};
+            const orc_q4 d = {qd->q + e * H * Fe, qd->scale + e * H * (Fe / 64), qd->bias + e * H * (Fe / 64)};
+            swiglu_any(NULL, NULL, NULL, &g, &u, &d, H, Fe, h, y);
+        } else {
+            swiglu(L->w_gate + e * Fe * H, L->w_up + e * Fe * H, L->w_down + e * H * Fe, H, Fe, h, y);
+        }
         for (int i = 0; i < H; i++) out[i] += wts[k] * y[i];
     }
     if (idx_out) memcpy(idx_out, idx, sizeof(int32_t) * (size_t)K);
@@ -325,6 +335,12 @@ static void moe(const orc_config *c, const orc_layer *L, const real *h, real *ou
     free(idx);
     free(wts);
     free(y);
+}
+
+static void moe(const orc_config *c, const orc_layer *L, const real *h, real *out,
+                int32_t *idx_out, real *wts_out)
+{
+    moe_any(c, L, NULL, NULL, NULL, h, out, idx_out, wts_out);
 }
 
 /* -------------------------------------------------------------- argmax -- */
@@ -495,8 +511,8 @@ static int decode_step_body(const orc_config *c, const orc_layer *layers, const 
 
             rmsnorm(x, H, L->g_mlp, (real)c->rms_eps, h);
             if (c->n_experts > 0)
-                moe(c, L, h, y, trace_experts
-                        ? trace_experts + ((int64_t)l * B + b) * c->top_k : NULL, NULL);
+                moe_any(c, L, Q ? Q + Q4_GATE : NULL, Q ? Q + Q4_UP : NULL, Q ? Q + Q4_DOWN : NULL, h, y,
+                        trace_experts ? trace_experts + ((int64_t)l * B + b) * c->top_k : NULL, NULL);
             else
                 swiglu_any(L->w_gate, L->w_up, L->w_down, Q ? Q + Q4_GATE : NULL, Q ? Q + Q4_UP : NULL,
                            Q ? Q + Q4_DOWN : NULL, H, c->ffn, h, y);
@@ -528,10 +544,11 @@ int orc_decode_step(const orc_config *c, const orc_layer *layers,
                             next_tokens, trace_x, trace_experts);
 }
 
-/* The same step for a dense model with 4-bit projections.  q_ptrs / scale_ptrs /
+/* The same step for a model with 4-bit projections.  q_ptrs / scale_ptrs /
  * bias_ptrs: n_layers * 7 + 1 pointers each (order as above; canonical form).
- * hidden, n_q_heads * head_dim and ffn must be multiples of 64.  layers supplies
- * the norm gains only. */
+ * hidden, n_q_heads * head_dim and ffn (expert_ffn) must be multiples of 64.
+ * Mixture-of-experts layers: gate / up / down hold all experts stacked by rows;
+ * layers supplies the norm gains and the (bf16) router. */
 int orc_decode_step_q4(const orc_config *c, const orc_layer *layers,
                        const uint8_t *const *q_ptrs, const uint16_t *const *scale_ptrs,
                        const uint16_t *const *bias_ptrs,
@@ -539,10 +556,10 @@ int orc_decode_step_q4(const orc_config *c, const orc_layer *layers,
                        uint16_t *pool, int32_t num_blocks, int32_t block_size,
                        const int32_t *block_tables, int32_t max_blocks_per_seq,
                        const int32_t *seq_lens, const int32_t *tokens, int32_t B,
-                       float *logits, int32_t *next_tokens, float *trace_x)
+                       float *logits, int32_t *next_tokens, float *trace_x, int32_t *trace_experts)
 {
-    if (c->n_experts > 0) return -5;
-    if (c->hidden % 64 || (c->n_q_heads * c->head_dim) % 64 || c->ffn % 64) return -6;
+    const int width = c->n_experts > 0 ? c->expert_ffn : c->ffn;
+    if (c->hidden % 64 || (c->n_q_heads * c->head_dim) % 64 || width % 64) return -6;
     const int n = c->n_layers * Q4_PER_LAYER + 1;
     orc_q4 *m = (orc_q4 *)malloc(sizeof(orc_q4) * (size_t)n);
     for (int i = 0; i < n; i++) {
@@ -552,7 +569,7 @@ int orc_decode_step_q4(const orc_config *c, const orc_layer *layers,
     }
     int rc = decode_step_body(c, layers, m, embed, g_final, NULL, pool, num_blocks, block_size,
                               block_tables, max_blocks_per_seq, seq_lens, tokens, B, logits,
-                              next_tokens, trace_x, NULL);
+                              next_tokens, trace_x, trace_experts);
     free(m);
     return rc;
 }

@@ -259,8 +259,9 @@ class Oracle:
 
     def decode_step_q4(self, cfg, qweights, pool, block_size, block_tables, seq_lens, tokens,
                        want_logits=True, want_trace=False):
-        """decode_step for a dense model whose projections and lm_head are 4-bit
-        (canonical dicts q / scale / bias in place of the bf16 matrices)."""
+        """decode_step for a model whose projections and lm_head are 4-bit (canonical
+        dicts q / scale / bias in place of the bf16 matrices; expert matrices [E, N, K]
+        as q [E, N, K], scale / bias [E, N, K/64]; the router stays bf16)."""
         c = self.config(cfg)
         assert pool.dtype == np.uint16 and pool.flags.c_contiguous
         L = cfg.n_layers
@@ -274,6 +275,8 @@ class Oracle:
             mats += [lay[n] for n in names]
         mats.append(qweights["lm_head"])
         n = len(mats)
+        experts = (np.empty((L, len(tokens), cfg.top_k), dtype=np.int32)
+                   if (want_trace and cfg.n_experts) else None)
         qs = [np.ascontiguousarray(m["q"], dtype=np.uint8) for m in mats]
         ss = [_u16(m["scale"]) for m in mats]
         bs = [_u16(m["bias"]) for m in mats]
@@ -293,10 +296,10 @@ class Oracle:
             C.byref(c), structs, qp, sp, bp, _p(_u16(qweights["embed"])), _p(_u16(qweights["g_final"])),
             _p(pool), C.c_int32(pool.shape[1]), C.c_int32(block_size),
             _p(bt), C.c_int32(bt.shape[1]), _p(sl), _p(tk), C.c_int32(B),
-            _p(logits), _p(nxt), _p(trace))
+            _p(logits), _p(nxt), _p(trace), _p(experts))
         if rc != 0:
             raise ValueError(f"orc_decode_step_q4 rejected its arguments (code {rc})")
-        return {"next": nxt, "logits": logits, "trace_x": trace, "experts": None}
+        return {"next": nxt, "logits": logits, "trace_x": trace, "experts": experts}
 
 
 _CACHE = {}

@@ -20,7 +20,7 @@ import numpy as np
 import pytest
 
 import workloads as W
-from workloads.blocktable import layout_for
+from workloads.blocktable import layout_for, build_block_tables
 from workloads.quant import quantize_q4, quantize_weights, MATRICES
 
 
@@ -79,6 +79,11 @@ def exact_q4_model(cfg, seed):
     qw = {"embed": w["embed"], "g_final": w["g_final"], "layers": []}
 
     def make(shape):
+        if len(shape) == 3:                      # a stack of expert matrices: row by row like one matrix
+            e, n, k = shape
+            bits, m = make((e * n, k))
+            return bits.reshape(shape), {"q": m["q"].reshape(shape), "scale": m["scale"].reshape(e, n, k // 64),
+                                         "bias": m["bias"].reshape(e, n, k // 64)}
         n, k = shape
         q = rng.integers(0, 16, size=(n, k), dtype=np.uint8)
         e = rng.integers(5, 8, size=(n, k // 64))
@@ -112,6 +117,28 @@ def test_q4_step_equals_bf16_step_on_exactly_representable_weights(orc):
         assert np.array_equal(a["trace_x"], b["trace_x"])
         assert np.array_equal(a["next"], b["next"])
         assert np.array_equal(pool_a.view(np.uint16), pool_b.view(np.uint16))
+        tok, sl = a["next"], sl + 1
+
+
+def test_q4_moe_step_equals_bf16_step_on_exactly_representable_weights(orc):
+    """Mixture of experts: the 4-bit gate / up / down stacks [E, N, K] feed the expert the (bf16) router
+    chose; same experts, same logits, bit for bit, as the bf16 step on the same numbers."""
+    cfg = W.ModelConfig(**{**W.CONFIGS["tiny_moe"].as_dict(), "expert_ffn": 128})
+    lay = build_block_tables([33, 16, 5], 16, 3, seed=2)
+    w, qw = exact_q4_model(cfg, 13)
+    for L, QL in zip(w["layers"], qw["layers"]):
+        assert L["w_gate"].shape == (cfg.n_experts, 128, cfg.hidden) and QL["w_router"] is L["w_router"]
+    pool_a = W.fill_kv_pool(cfg, lay, 1)
+    pool_b = pool_a.copy()
+    tok = W.initial_tokens(cfg, 3, 2)
+    sl = lay.contexts.copy()
+    for s in range(3):
+        a = orc.decode_step(cfg, w, pool_a, 16, lay.tables, sl, tok, want_trace=True)
+        b = orc.decode_step_q4(cfg, qw, pool_b, 16, lay.tables, sl, tok, want_trace=True)
+        assert np.array_equal(a["experts"], b["experts"])
+        assert np.array_equal(a["logits"], b["logits"])
+        assert np.array_equal(a["trace_x"], b["trace_x"])
+        assert np.array_equal(pool_a, pool_b)
         tok, sl = a["next"], sl + 1
 
 

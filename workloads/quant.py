@@ -25,7 +25,13 @@ def _bf16_bits_rne(x: np.ndarray) -> np.ndarray:
 
 
 def quantize_q4(w_bits: np.ndarray) -> dict:
-    """bf16 bit patterns [N, K] (K a multiple of 64) -> canonical 4-bit form."""
+    """bf16 bit patterns [N, K] (K a multiple of 64) -> canonical 4-bit form.  A stack of expert
+    matrices [E, N, K] is quantised row by row like one matrix and keeps its leading axis."""
+    if w_bits.ndim == 3:
+        E, N, K = w_bits.shape
+        m = quantize_q4(w_bits.reshape(E * N, K))
+        return {"q": m["q"].reshape(E, N, K), "scale": m["scale"].reshape(E, N, K // GROUP),
+                "bias": m["bias"].reshape(E, N, K // GROUP)}
     N, K = w_bits.shape
     assert K % GROUP == 0
     w = f32_from_bf16_bits(w_bits).reshape(N, K // GROUP, GROUP)
@@ -43,13 +49,12 @@ MATRICES = ("wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down")
 
 
 def quantize_weights(weights: dict, threads: int = 8) -> dict:
-    """The 4-bit version of a dense model's weights: every projection matrix and the lm_head in
-    canonical 4-bit form (dict q/scale/bias); embedding and norm gains stay bf16.  Matrices are
+    """The 4-bit version of a model's weights: every projection matrix (expert stacks included) and the
+    lm_head in canonical 4-bit form (dict q/scale/bias); embedding, norm gains and routers stay bf16.  Matrices are
     quantised on a few threads (numpy releases the interpreter lock in its array loops)."""
     from concurrent.futures import ThreadPoolExecutor
     jobs = [(None, "lm_head", weights["lm_head"])]
     for i, L in enumerate(weights["layers"]):
-        assert "w_router" not in L, "4-bit weights are implemented for dense models"
         jobs += [(i, k, v) for k, v in L.items() if k in MATRICES]
     with ThreadPoolExecutor(max_workers=threads) as ex:
         done = list(ex.map(lambda j: quantize_q4(j[2]), jobs))
