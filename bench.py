@@ -288,9 +288,14 @@ def main():
         return bench_ttft(args, wl, dk, W, np, torch)
     shape, lay = wl.cfg, layout_for(wl)
     weights = make_model_weights(args, W, shape, wl.seed_weights)
-    weight_bytes = shape.dense_weight_bytes()
+    router_bytes = shape.n_layers * shape.n_experts * shape.hidden * 2    # routers stay bf16
+    weight_bytes = shape.dense_weight_bytes()                             # attention, dense MLP, lm_head, routers
+    one_expert_bytes = shape.expert_bytes()
     if args.weights == "q4":
-        weight_bytes = weight_bytes // 4 + weight_bytes // 128 * 4       # 4 bits + (scale, bias) per 64 weights
+        def q4(b):                                                        # 4 bits + (scale, bias) per 64 weights
+            return b // 4 + b // 128 * 4
+        weight_bytes = q4(weight_bytes - router_bytes) + router_bytes
+        one_expert_bytes = q4(one_expert_bytes)
     pool_bits = W.fill_kv_pool(shape, lay, wl.seed_kv, poison=False)
     tokens0 = W.initial_tokens(shape, wl.batch, wl.seed_tokens)
 
@@ -347,9 +352,8 @@ def main():
     kv_bytes = dk.step_algorithmic_bytes(dm.handle, dkv.handle, lay.tables, mean_ctx, with_logits=False,
                                          distinct_experts_per_layer=distinct) \
         - weight_bytes - wl.batch * shape.hidden * 2 \
-        - (int(distinct.sum()) * shape.expert_bytes() if distinct is not None else 0)
-    expert_bytes = int(distinct.sum()) * shape.expert_bytes() if distinct is not None else 0
-    router_bytes = shape.n_layers * shape.n_experts * shape.hidden * 2
+        - (int(distinct.sum()) * one_expert_bytes if distinct is not None else 0)
+    expert_bytes = int(distinct.sum()) * one_expert_bytes if distinct is not None else 0
     class_bytes = {"gemv": weight_bytes - router_bytes, "gemm": weight_bytes - router_bytes,
                    "attention": kv_bytes, "moe_expert": expert_bytes, "moe_router": router_bytes,
                    "fused_step": alg_bytes}      # the persistent kernel is the whole step

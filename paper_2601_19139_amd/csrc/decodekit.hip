@@ -834,13 +834,15 @@ dk_status dk_create_model_q4(const dk_model_config *cfg, const dk_weight_ptrs *w
 {
     dk_status s = check_config(cfg);
     if (s != DK_OK) return s;
-    if (cfg->n_experts > 0)
-        return fail(DK_E_UNSUPPORTED_SHAPE, "4-bit weights are implemented for dense models");
     const int qd = cfg->n_q_heads * cfg->head_dim;
-    if (cfg->hidden % 128 || qd % 128 || cfg->ffn % 128)
+    const int width = cfg->n_experts > 0 ? cfg->expert_ffn : cfg->ffn;
+    if (cfg->hidden % 128 || qd % 128 || width % 128)
         return fail(DK_E_UNSUPPORTED_SHAPE,
-                    "4-bit weights need hidden, n_q_heads*head_dim and ffn to be multiples of 128 (got %d, %d, %d)",
-                    cfg->hidden, qd, cfg->ffn);
+                    "4-bit weights need hidden, n_q_heads*head_dim and the MLP width to be multiples of 128 "
+                    "(got %d, %d, %d)", cfg->hidden, qd, width);
+    if (cfg->n_experts > 0 && (cfg->hidden < 512 || cfg->expert_ffn < 512))
+        return fail(DK_E_UNSUPPORTED_SHAPE, "4-bit experts need hidden and expert_ffn of at least 512 (got %d, %d)",
+                    cfg->hidden, cfg->expert_ffn);
     if (w && w->embed && w->embed == w->lm_head)
         return fail(DK_E_INVALID_ARG, "the embedding stays bf16 and cannot double as the 4-bit lm_head");
     if ((s = dk_create_model(cfg, w, out)) != DK_OK) return s;
@@ -1279,6 +1281,7 @@ static dk_status decode_step_impl(dk_model *model, dk_kv_pool *pool, const int32
             up.w_b = u16(L.w_up);
             up.N = c.expert_ffn;
             up.K = H;
+            up.n_experts = c.n_experts;
             up.B = B;
             up.top_k = c.top_k;
             up.exp_cnt = r.exp_cnt;
@@ -1289,7 +1292,10 @@ static dk_status decode_step_impl(dk_model *model, dk_kv_pool *pool, const int32
             up.ohi = fhi;
             up.olo = flo;
             // K a multiple of 128 and at least one k-step per wave: the restructured kernel
-            if (H % 128 == 0 && H / 128 >= 4) {
+            if (model->q4) {   // shapes checked by dk_create_model_q4
+                DK_LAUNCH(DK_K_MOE_EXPERT, (dk::moe_expert_fast_kernel<true, 4, 1, 2, true>),
+                          dim3((c.expert_ffn + 15) / 16, c.n_experts), dim3(256), 0, st, up);
+            } else if (H % 128 == 0 && H / 128 >= 4) {
                 // measured at the 30B-A3B shape: small blocks (4 waves, one 16-row tile, two
                 // k-steps per round) so that many are resident per compute unit
                 DK_LAUNCH(DK_K_MOE_EXPERT, (dk::moe_expert_fast_kernel<true, 4, 1, 2>),
@@ -1303,6 +1309,7 @@ static dk_status decode_step_impl(dk_model *model, dk_kv_pool *pool, const int32
             dn.w_a = u16(L.w_down);
             dn.N = H;
             dn.K = c.expert_ffn;
+            dn.n_experts = c.n_experts;
             dn.B = B;
             dn.top_k = c.top_k;
             dn.exp_cnt = r.exp_cnt;
@@ -1310,7 +1317,13 @@ static dk_status decode_step_impl(dk_model *model, dk_kv_pool *pool, const int32
             dn.xhi = fhi;
             dn.xlo = flo;
             dn.y = yexp;
-            if (c.expert_ffn % 768 == 0) {          // six k-steps (or a multiple): 3 waves x 2 per round
+            if (model->q4 && c.expert_ffn % 768 == 0) {
+                DK_LAUNCH(DK_K_MOE_EXPERT, (dk::moe_expert_fast_kernel<false, 3, 2, 2, true>), dim3((H + 31) / 32, c.n_experts),
+                          dim3(192), 0, st, dn);
+            } else if (model->q4) {
+                DK_LAUNCH(DK_K_MOE_EXPERT, (dk::moe_expert_fast_kernel<false, 4, 2, 1, true>), dim3((H + 31) / 32, c.n_experts),
+                          dim3(256), 0, st, dn);
+            } else if (c.expert_ffn % 768 == 0) {          // six k-steps (or a multiple): 3 waves x 2 per round
                 DK_LAUNCH(DK_K_MOE_EXPERT, (dk::moe_expert_fast_kernel<false, 3, 2, 2>), dim3((H + 31) / 32, c.n_experts),
                           dim3(192), 0, st, dn);
             } else if (c.expert_ffn % 128 == 0 && c.expert_ffn / 128 >= 4) {
@@ -1490,16 +1503,18 @@ dk_status dk_step_algorithmic_bytes(const dk_model *model, const dk_kv_pool *poo
     uint64_t bytes = 0;
     if (c.n_experts > 0) {
         if (!distinct_experts) return fail(DK_E_INVALID_ARG, "MoE model needs distinct_experts_per_layer");
-        per_layer += (uint64_t)c.n_experts * H;
-        for (int l = 0; l < c.n_layers; l++)
-            bytes += 2 * (uint64_t)distinct_experts[l] * 3 * H * (uint64_t)c.expert_ffn;
+        for (int l = 0; l < c.n_layers; l++) {
+            const uint64_t ew = (uint64_t)distinct_experts[l] * 3 * H * (uint64_t)c.expert_ffn;
+            bytes += model->q4 ? ew / 2 + ew / 64 * 4 : 2 * ew;
+        }
+        bytes += 2 * (uint64_t)c.n_layers * c.n_experts * H;   // routers (bf16 in either format)
     } else {
         per_layer += 3 * H * (uint64_t)c.ffn;
     }
     const uint64_t weights = (uint64_t)c.n_layers * per_layer + (uint64_t)c.vocab * H;
     if (model->q4) {
-        // half a byte per weight plus a bf16 scale and bias per 64 weights; norm gains aside,
-        // every matrix of a 4-bit model is in that format
+        // half a byte per weight plus a bf16 scale and bias per 64 weights; norm gains, routers and
+        // the embedding aside, every matrix of a 4-bit model is in that format
         bytes += weights / 2 + weights / 64 * 4;
     } else {
         bytes += 2 * weights;

@@ -150,6 +150,7 @@ struct ExpertArgs {
     const uint16_t *w_a;     // UP: gate [E][Fe][H];  DOWN: down [E][H][Fe]
     const uint16_t *w_b;     // UP: up   [E][Fe][H]
     int N, K;                // rows and columns of one expert matrix
+    int n_experts;           // Q4: the packed matrices hold all experts stacked by rows (E*N rows)
     int B, top_k;
     const int *exp_cnt;      // [E] pairs that chose the expert
     const int *exp_list;     // [E][B*top_k] pair indices row*top_k + slot (any order)
@@ -257,7 +258,11 @@ __global__ __launch_bounds__(KS * 64) void moe_expert_kernel(ExpertArgs a)
 // row tiles) before the first MFMA, so a block pays one memory round trip per
 // round instead of one per 32 columns.  A block covers 16*RT rows; the RT tiles
 // share the activation registers.  Wave w < RT reduces and stores tile w.
-template <bool UP, int KS, int RT, int PD>
+//
+// Q4: w_a / w_b are packed 4-bit matrices (layout of dk_create_model_q4) of E*N rows, expert e owning rows
+// e*N..; N a multiple of 16.  Evaluated as in the dense 4-bit GEMM: codes through the matrix cores, the
+// group sums of x from an all-ones operand, scale and bias applied to the fp32 tiles.
+template <bool UP, int KS, int RT, int PD, bool Q4 = false>
 __global__ __launch_bounds__(KS * 64) void moe_expert_fast_kernel(ExpertArgs a)
 {
     constexpr int NM = UP ? 2 : 1;
@@ -278,12 +283,20 @@ __global__ __launch_bounds__(KS * 64) void moe_expert_fast_kernel(ExpertArgs a)
     const int nks = K >> 7;
     const int onks = (N + 127) >> 7;
     const uint16_t *wp0[RT], *wp1[RT];
+    // Q4: byte offsets of the lane's codes (row of its tile) and of its tiles' (scale, bias) pieces
+    int64_t qc[RT], qs[RT];
 #pragma unroll
     for (int t = 0; t < RT; t++) {
         const int wrow = min(r0 + 16 * t + ln, N - 1);
         wp0[t] = a.w_a + ((int64_t)e * N + wrow) * K + lg * 8;
         wp1[t] = UP ? a.w_b + ((int64_t)e * N + wrow) * K + lg * 8 : nullptr;
+        if (Q4) {
+            const int tile = min((r0 >> 4) + t, (N >> 4) - 1);
+            qc[t] = ((int64_t)e * N + min(tile * 16 + ln, N - 1)) * (K >> 1) + lg * 16;
+            qs[t] = (int64_t)a.n_experts * N * (K >> 1) + (((int64_t)e * (N >> 4) + tile) * nks * 4 + lg) * 32;
+        }
     }
+    const uint8_t *qa = reinterpret_cast<const uint8_t *>(a.w_a), *qb = reinterpret_cast<const uint8_t *>(a.w_b);
 
     for (int c0 = 0; c0 < ncol; c0 += 16) {   // 16 batch columns per pass
         const int pair = col_row[min(c0 + ln, ncol - 1)];
@@ -305,12 +318,62 @@ __global__ __launch_bounds__(KS * 64) void moe_expert_fast_kernel(ExpertArgs a)
                     const int64_t xo = xbase + ((int64_t)ks * 4 + s) * 512;
                     h4[p][s] = ld16(a.xhi + xo);
                     l4[p][s] = ld16(a.xlo + xo);
+                    if (!Q4) {
 #pragma unroll
-                    for (int t = 0; t < RT; t++) {
-                        w0[p][t][s] = ld16(wp0[t] + ks * 128 + s * 32);
-                        if (UP) w1[p][t][s] = ld16(wp1[t] + ks * 128 + s * 32);
+                        for (int t = 0; t < RT; t++) {
+                            w0[p][t][s] = ld16(wp0[t] + ks * 128 + s * 32);
+                            if (UP) w1[p][t][s] = ld16(wp1[t] + ks * 128 + s * 32);
+                        }
                     }
                 }
+                if (Q4) {
+                    // [0]: the step's 32 codes of the lane's row; [1], [2]: (scale, bias) of its two groups
+#pragma unroll
+                    for (int t = 0; t < RT; t++) {
+                        w0[p][t][0] = ld16(qa + qc[t] + ks * 64);
+                        w0[p][t][1] = ld16(qa + qs[t] + (int64_t)ks * 128);
+                        w0[p][t][2] = ld16(qa + qs[t] + (int64_t)ks * 128 + 16);
+                        if (UP) {
+                            w1[p][t][0] = ld16(qb + qc[t] + ks * 64);
+                            w1[p][t][1] = ld16(qb + qs[t] + (int64_t)ks * 128);
+                            w1[p][t][2] = ld16(qb + qs[t] + (int64_t)ks * 128 + 16);
+                        }
+                    }
+                }
+            }
+            if constexpr (Q4) {
+                const uint4 one4 = make_uint4(0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u);
+                const f32x4_t zero = f32x4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int p = 0; p < PD; p++) {
+                    if (ks0 + p * KS >= nks) continue;   // past the end of K (the same for the whole wave)
+#pragma unroll
+                    for (int h = 0; h < 2; h++) {
+                        const uint4 bh0 = h4[p][2 * h], bl0 = l4[p][2 * h], bh1 = h4[p][2 * h + 1], bl1 = l4[p][2 * h + 1];
+                        f32x4_t S = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(one4), as_bf16x8(bh0), zero, 0, 0, 0);
+                        S = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(one4), as_bf16x8(bl0), S, 0, 0, 0);
+                        S = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(one4), as_bf16x8(bh1), S, 0, 0, 0);
+                        S = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(one4), as_bf16x8(bl1), S, 0, 0, 0);
+#pragma unroll
+                        for (int t = 0; t < RT; t++)
+#pragma unroll
+                            for (int m = 0; m < NM; m++) {
+                                const uint4 cw = m ? w1[p][t][0] : w0[p][t][0];
+                                const uint4 sb = m ? w1[p][t][1 + h] : w0[p][t][1 + h];
+                                const uint32_t sbw[4] = {sb.x, sb.y, sb.z, sb.w};
+                                const uint4 cq0 = q4_codes_bf16(h ? cw.z : cw.x), cq1 = q4_codes_bf16(h ? cw.w : cw.y);
+                                f32x4_t D = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(cq0), as_bf16x8(bh0), zero, 0, 0, 0);
+                                D = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(cq0), as_bf16x8(bl0), D, 0, 0, 0);
+                                D = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(cq1), as_bf16x8(bh1), D, 0, 0, 0);
+                                D = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(cq1), as_bf16x8(bl1), D, 0, 0, 0);
+#pragma unroll
+                                for (int i = 0; i < 4; i++)
+                                    acc[t][m][i] = fmaf(__uint_as_float(sbw[i] << 16), D[i],
+                                                        fmaf(__uint_as_float(sbw[i] & 0xFFFF0000u), S[i], acc[t][m][i]));
+                            }
+                    }
+                }
+                continue;
             }
 #pragma unroll
             for (int p = 0; p < PD; p++) {

@@ -41,12 +41,20 @@ class DeviceModel:
         if self.q4:
             # pack on a few threads (numpy releases the interpreter lock): seconds instead of minutes at 8B
             from concurrent.futures import ThreadPoolExecutor
+            def flat(m):   # a stack of expert matrices [E, N, K] is packed as one matrix of E*N rows
+                if m["q"].ndim == 2:
+                    return m
+                e, n, k = m["q"].shape
+                return {"q": m["q"].reshape(e * n, k), "scale": m["scale"].reshape(e * n, -1),
+                        "bias": m["bias"].reshape(e * n, -1), "_of": m}
+
             jobs = [(weights["lm_head"],)]
             for L in weights["layers"]:
-                jobs += [(L["wq"], L["wk"], L["wv"]), (L["wo"],), (L["w_gate"],), (L["w_up"],), (L["w_down"],)]
+                jobs += [(L["wq"], L["wk"], L["wv"]), (L["wo"],), (flat(L["w_gate"]),), (flat(L["w_up"]),),
+                         (flat(L["w_down"]),)]
             with ThreadPoolExecutor(max_workers=8) as ex:
                 for j, buf in zip(jobs, ex.map(lambda j: pack_q4(*j), jobs)):
-                    packed[id(j[0])] = buf
+                    packed[id(j[0].get("_of", j[0]))] = buf
 
         def up(*a):
             if self.q4 and isinstance(a[0], dict):

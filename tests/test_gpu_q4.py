@@ -118,6 +118,47 @@ def test_q4_wide_batches_of_a_large_layer(dk, orc, batch):
     check_pool_sampled(out, pool, shape, lay, 2, rows)
 
 
+Q4_MOE_CASES = [
+    # hidden and expert width multiples of 128 and at least 512: the restructured expert kernels with packed
+    # 4-bit expert stacks (down projection: the 768-wide and the generic variant), a crowded expert
+    ("moe_768", variant("tiny_moe", hidden=1024, expert_ffn=768, n_experts=8, top_k=2), [2 + 3 * i for i in range(20)], 2),
+    ("moe_512_crowded", variant("tiny_moe", hidden=1024, expert_ffn=512, n_experts=4, top_k=2), [1 + i for i in range(40)], 1),
+    ("moe_batch1", variant("tiny_moe", hidden=512, expert_ffn=512, n_experts=8, top_k=2), [21], 3),
+]
+
+
+@pytest.mark.parametrize("name,shape,contexts,steps", Q4_MOE_CASES, ids=[c[0] for c in Q4_MOE_CASES])
+def test_q4_mixture_of_experts(dk, orc, name, shape, contexts, steps):
+    """4-bit expert stacks (the router stays bf16): same experts chosen, logits within the bound."""
+    lay = build_block_tables(contexts, 16, steps, seed=41)
+    weights = quantize_weights(W.make_weights(shape, 18))
+    pool = W.fill_kv_pool(shape, lay, 19)
+    tokens = W.initial_tokens(shape, len(contexts), 20)
+    out = run_both(orc, shape, weights, lay, pool, tokens, steps)
+    for g, o in zip(out["gpu_experts"], out["orc_experts"]):
+        assert np.array_equal(np.sort(g, axis=-1), np.sort(o, axis=-1)), name
+    worst, agree = check_parity(out)
+    print(f"{name}: worst rel-L2 {worst:.3e}, greedy agreement {agree:.3f}")
+    assert worst < TIGHT and agree == 1.0, (name, worst, agree)
+    check_pool(out, pool, shape, lay, steps)
+
+
+def test_cfg4_shape_q4_sampled_rows(dk, orc):
+    """The 30B-A3B mixture-of-experts shape (128 experts, top 8, expert width 768; cut to 4 layers) with
+    4-bit weights at batch 16, ragged contexts with a shared 2048-token prefix: sampled rows."""
+    wl = W.WORKLOADS["cfg4_l4"]
+    shape, lay = wl.cfg, layout_for(wl)
+    weights = quantize_weights(W.make_weights(shape, wl.seed_weights))
+    pool = W.fill_kv_pool(shape, lay, wl.seed_kv)
+    tokens = W.initial_tokens(shape, wl.batch, wl.seed_tokens)
+    rows = (1, 8, 14)
+    out = run_sampled(orc, shape, weights, lay, pool, tokens, 1, rows)
+    worst, agree = check_parity(out)
+    print(f"cfg4_l4 shape, 4-bit: worst rel-L2 {worst:.3e}, greedy agreement {agree:.3f} on rows {rows}")
+    assert worst < TIGHT
+    check_pool_sampled(out, pool, shape, lay, 1, rows)
+
+
 def test_q4_distinct_scales_and_biases_per_group(dk, orc):
     """Codes, scales and biases drawn independently (no relation to a bf16 matrix): a scale or bias
     taken from the wrong row, group or half of a K-step changes the logits by far more than the bound."""
