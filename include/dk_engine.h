@@ -100,7 +100,7 @@ typedef struct dk_engine_stats {
 } dk_engine_stats;
 
 /* Device bytes the engine needs in its arena (block tables, lengths, tokens and
- * the workspaces of dk_decode_step / dk_prefill_chunk). */
+ * the workspaces of dk_decode_step / dk_prefill_chunk, logits and sampler scratch). */
 dk_status dk_engine_device_bytes(const dk_model *model, const dk_engine_config *cfg, size_t *out_bytes);
 
 /* d_arena: caller-owned device memory of at least dk_engine_device_bytes, 256-byte
@@ -127,6 +127,13 @@ dk_status dk_engine_submit(dk_engine *engine, const int32_t *h_prompt, int32_t n
  * state DK_REQ_FAILED (only possible when the pool is too small for the batch).
  * *out_active (may be NULL) = |B| + |Q| afterwards: 0 means nothing is left to do. */
 dk_status dk_engine_step(dk_engine *engine, void *hip_stream, int32_t *out_active);
+
+/* Sampling beyond greedy for every token generated from now on (dk_sampling and its exact
+ * definition: decodekit.h, dk_sample_tokens).  params == NULL returns to greedy.  The random number of
+ * a token is that of dk_sample_tokens with step = the number of sampler calls since this call (one per
+ * admitted request for its first token, one per decode iteration) and row = the request's row in that
+ * iteration: the same requests submitted in the same order give the same tokens. */
+dk_status dk_engine_set_sampling(dk_engine *engine, const dk_sampling *params);
 
 enum { DK_REQ_PENDING = 0, DK_REQ_ACTIVE = 1, DK_REQ_DONE = 2, DK_REQ_FAILED = 3 };
 

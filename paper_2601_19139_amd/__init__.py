@@ -14,7 +14,7 @@ from .binding import (  # noqa: F401
     STEP_ADVANCE, STEP_PROFILE, STEP_NO_FUSED, KERNEL_CLASSES, STATUS,
     EngineConfig, prefix_index_create, prefix_index_destroy, prefix_index_match, prefix_index_insert,
     prefix_index_evict_lru, prefix_index_size, engine_device_bytes, engine_create, engine_destroy,
-    engine_submit, engine_step, engine_poll, engine_forget, engine_stats,
+    engine_submit, engine_step, engine_poll, engine_forget, engine_stats, engine_set_sampling,
 )
 from .q4 import pack_q4, q4_bytes  # noqa: F401
 from .runtime import DeviceModel, DeviceKV, Decoder, Prefiller  # noqa: F401

@@ -118,6 +118,7 @@ _SIGNATURES.update({
     "dk_engine_submit": (C.c_int32, [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32,
                                      C.POINTER(C.c_int64)]),
     "dk_engine_step": (C.c_int32, [C.c_void_p, C.c_void_p, C.POINTER(C.c_int32)]),
+    "dk_engine_set_sampling": (C.c_int32, [C.c_void_p, C.POINTER(Sampling)]),
     "dk_engine_poll": (C.c_int32, [C.c_void_p, C.c_int64, C.c_void_p, C.c_int32, C.POINTER(C.c_int32),
                                    C.POINTER(C.c_int32), C.POINTER(C.c_int32)]),
     "dk_engine_forget": (C.c_int32, [C.c_void_p, C.c_int64]),
@@ -414,6 +415,15 @@ def engine_step(engine, stream=None) -> int:
     out = C.c_int32()
     _check(lib().dk_engine_step(engine, _stream(stream), C.byref(out)))
     return out.value
+
+
+def engine_set_sampling(engine, temperature: float = None, top_k: int = 0, top_p: float = 1.0, seed: int = 0):
+    """Sample every token generated from now on (temperature None: back to greedy)."""
+    if temperature is None:
+        _check(lib().dk_engine_set_sampling(engine, None))
+        return
+    prm = Sampling(temperature, top_k, top_p, seed)
+    _check(lib().dk_engine_set_sampling(engine, C.byref(prm)))
 
 
 def engine_poll(engine, request_id: int, capacity: int = 4096):

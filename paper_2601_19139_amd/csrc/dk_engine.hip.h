@@ -194,13 +194,21 @@ struct dk_engine {
     char *d_ws = nullptr;
     size_t ws_bytes = 0;
     bool no_fused = false;                    // the persistent step kernel gave up once: not used again
+    // sampling beyond greedy (dk_engine_set_sampling): logits of a step, the sampler's scratch and output
+    bool sampling = false;
+    dk_sampling sampling_params{};
+    uint64_t sample_step = 0;                 // counter of the sampler's random numbers: one per sampled batch
+    float *d_logits = nullptr;
+    char *d_sample_ws = nullptr;
+    size_t sample_ws_bytes = 0;
+    int32_t *d_sampled = nullptr;
     std::vector<int32_t> h_tables;            // host mirror [M][max_blocks]
     std::vector<char> row_dirty;
 };
 
 namespace {
 
-struct ArenaLayout { size_t tables, seq, tok, next, chunk, ws, ws_bytes, total; };
+struct ArenaLayout { size_t tables, seq, tok, next, chunk, ws, ws_bytes, logits, sample_ws, sample_ws_bytes, sampled, total; };
 
 dk_status engine_layout(const dk_model *model, const dk_engine_config *cfg, ArenaLayout *L)
 {
@@ -228,6 +236,16 @@ dk_status engine_layout(const dk_model *model, const dk_engine_config *cfg, Aren
     L->chunk = take((size_t)DK_MAX_BATCH * 4);
     L->ws = take(ws);
     L->ws_bytes = ws;
+    // sampling: logits of every row of a step (or of a prefill chunk), scratch, tokens
+    const int rows = std::max(cfg->max_batch, cfg->prefill_chunk);
+    const dk_model_config &mc = model->cfg;
+    size_t sws = 0;
+    const dk_status ms = dk_sample_scratch_bytes(cfg->max_batch, mc.vocab, &sws);
+    if (ms != DK_OK) return ms;
+    L->logits = take((size_t)rows * mc.vocab * 4);
+    L->sample_ws = take(sws);
+    L->sample_ws_bytes = sws;
+    L->sampled = take((size_t)DK_MAX_BATCH * 4);
     L->total = off;
     return DK_OK;
 }
@@ -314,11 +332,20 @@ dk_status engine_admit(dk_engine *e, EngineRequest *r, hipStream_t st)
         const bool last = o + n >= P;
         DK_HIP(hipMemcpyAsync(e->d_chunk, r->prompt.data() + o, (size_t)n * 4, hipMemcpyHostToDevice, st));
         s = dk_prefill_chunk(e->model, e->pool, d_table, e->cfg.max_blocks_per_seq, o, e->d_chunk, n, e->d_ws,
-                             e->ws_bytes, nullptr, last ? e->d_next : nullptr, st);
+                             e->ws_bytes, (last && e->sampling) ? e->d_logits : nullptr, last ? e->d_next : nullptr, st);
         if (s != DK_OK) { engine_release_blocks(e, r); return s; }
         if (last) {
             int32_t first = 0;
-            DK_HIP(hipMemcpyAsync(&first, e->d_next + (n - 1), 4, hipMemcpyDeviceToHost, st));
+            const int32_t *d_first = e->d_next + (n - 1);
+            if (e->sampling) {
+                // the prompt's last position decides the first token: one row through the sampler
+                const dk_model_config &mc = e->model->cfg;
+                s = dk_sample_tokens(e->d_logits + (size_t)(n - 1) * mc.vocab, 1, mc.vocab, &e->sampling_params,
+                                     e->sample_step++, e->d_sample_ws, e->sample_ws_bytes, e->d_sampled, st);
+                if (s != DK_OK) { engine_release_blocks(e, r); return s; }
+                d_first = e->d_sampled;
+            }
+            DK_HIP(hipMemcpyAsync(&first, d_first, 4, hipMemcpyDeviceToHost, st));
             DK_HIP(hipStreamSynchronize(st));
             r->out.push_back(first);
             r->last = first;
@@ -388,6 +415,10 @@ dk_status dk_engine_create(dk_model *model, dk_kv_pool *pool, const dk_engine_co
     e->d_next = reinterpret_cast<int32_t *>(base + L.next);
     e->d_chunk = reinterpret_cast<int32_t *>(base + L.chunk);
     e->d_ws = base + L.ws;
+    e->d_logits = reinterpret_cast<float *>(base + L.logits);
+    e->d_sample_ws = base + L.sample_ws;
+    e->sample_ws_bytes = L.sample_ws_bytes;
+    e->d_sampled = reinterpret_cast<int32_t *>(base + L.sampled);
     e->ws_bytes = L.ws_bytes;
     e->h_tables.assign((size_t)cfg->max_batch * cfg->max_blocks_per_seq, -1);
     e->row_dirty.assign((size_t)cfg->max_batch, 1);
@@ -469,7 +500,8 @@ dk_status dk_engine_step(dk_engine *engine, void *hip_stream, int32_t *out_activ
     }
     if (!e->active.empty()) {
         const int B = (int)e->active.size();
-        std::vector<int32_t> seq((size_t)B), tok((size_t)B), nxt((size_t)B);
+        std::vector<int32_t> seq((size_t)B), tok((size_t)B), nxt((size_t)B), smp((size_t)B);
+        const dk_model_config &mc = e->model->cfg;
         for (int i = 0; i < B; i++) { seq[(size_t)i] = e->active[(size_t)i]->T; tok[(size_t)i] = e->active[(size_t)i]->last; }
         dk_status s = engine_upload_rows(e, st);
         if (s != DK_OK) return s;
@@ -477,9 +509,17 @@ dk_status dk_engine_step(dk_engine *engine, void *hip_stream, int32_t *out_activ
         DK_HIP(hipMemcpyAsync(e->d_tok, tok.data(), (size_t)B * 4, hipMemcpyHostToDevice, st));
         for (int attempt = 0; attempt < 2; attempt++) {
             s = dk_decode_step(e->model, e->pool, e->d_tables, e->cfg.max_blocks_per_seq, e->d_seq, e->d_tok, B,
-                               e->d_ws, e->ws_bytes, nullptr, e->d_next, e->no_fused ? DK_STEP_NO_FUSED : 0u, st);
+                               e->d_ws, e->ws_bytes, e->sampling ? e->d_logits : nullptr, e->d_next,
+                               e->no_fused ? DK_STEP_NO_FUSED : 0u, st);
             if (s != DK_OK) return s;
             DK_HIP(hipMemcpyAsync(nxt.data(), e->d_next, (size_t)B * 4, hipMemcpyDeviceToHost, st));
+            if (e->sampling) {
+                // the greedy tokens above still tell whether the step was valid; the sampled ones are used
+                s = dk_sample_tokens(e->d_logits, B, mc.vocab, &e->sampling_params, e->sample_step, e->d_sample_ws,
+                                     e->sample_ws_bytes, e->d_sampled, st);
+                if (s != DK_OK) return s;
+                DK_HIP(hipMemcpyAsync(smp.data(), e->d_sampled, (size_t)B * 4, hipMemcpyDeviceToHost, st));
+            }
             DK_HIP(hipStreamSynchronize(st));
             if (nxt[0] >= 0) break;
             // the persistent kernel could not keep its blocks resident (its waits are bounded and it
@@ -491,6 +531,10 @@ dk_status dk_engine_step(dk_engine *engine, void *hip_stream, int32_t *out_activ
         }
         e->stats.decode_steps++;
         e->stats.generated_tokens += B;
+        if (e->sampling) {
+            e->sample_step++;
+            nxt = smp;
+        }
         for (int i = 0; i < B; i++) {
             EngineRequest *r = e->active[(size_t)i];
             r->out.push_back(nxt[(size_t)i]);
@@ -506,6 +550,22 @@ dk_status dk_engine_step(dk_engine *engine, void *hip_stream, int32_t *out_activ
     }
     if (worked) e->stats.iterations++;
     if (out_active) *out_active = (int32_t)(e->active.size() + e->queue.size());
+    return DK_OK;
+}
+
+dk_status dk_engine_set_sampling(dk_engine *engine, const dk_sampling *params)
+{
+    if (!engine) return fail(DK_E_INVALID_ARG, "NULL argument");
+    if (!params) {
+        engine->sampling = false;
+        return DK_OK;
+    }
+    if (!(params->temperature > 0.f) || params->top_k < 0 || !(params->top_p > 0.f) || params->top_p > 1.f)
+        return fail(DK_E_INVALID_ARG, "sampling parameters: temperature %g (> 0), top_k %d (>= 0), top_p %g (0 < p <= 1)",
+                    (double)params->temperature, params->top_k, (double)params->top_p);
+    engine->sampling = true;
+    engine->sampling_params = *params;
+    engine->sample_step = 0;
     return DK_OK;
 }
 

@@ -243,3 +243,66 @@ def test_engine_falls_back_when_the_persistent_kernel_gives_up(dk, orc):
     dk.engine_destroy(eng)
     s.close()
 
+
+
+def oracle_generate_sampled(orc, shape, weights, prompt, max_new, temperature, top_k, top_p, seed):
+    """One request alone, its tokens drawn by the oracle's sampler with the engine's counters for a
+    single request: sampler call k (the first token is call 0) of row 0."""
+    total = len(prompt) + max_new
+    lay = build_block_tables([0], BS, total + 1, seed=1)
+    pool = np.full(W.pool_shape(shape, lay.num_blocks, BS), W.BF16_NAN_BITS, dtype=np.uint16)
+    out, tok = [], None
+    for t in range(total - 1):
+        feed = prompt[t] if t < len(prompt) else tok
+        r = orc.decode_step(shape, weights, pool, BS, lay.tables, np.array([t], np.int32), np.array([feed], np.int32))
+        if t >= len(prompt) - 1:
+            u = orc.sample_uniform(seed, len(out), 0)
+            tok = orc.sample(r["logits"][0], temperature, top_k, top_p, u)
+            out.append(tok)
+            if len(out) >= max_new:
+                break
+    return out
+
+
+def test_engine_sampling(dk, orc):
+    """dk_engine_set_sampling: top_k = 1 is the argmax and must reproduce the greedy outputs; a real
+    distribution is reproducible, differs from greedy, and for a single request equals the oracle's
+    sampler fed the oracle's logits with the same counters."""
+    shape = variant("tiny", qk_norm=True)
+    rng = np.random.default_rng(5)
+    reqs = make_requests(shape, rng)[:5]
+    s = Setup(dk, shape, n_blocks=96)
+
+    def run(sampling, requests, max_batch=4):
+        eng, arena = s.engine(max_batch, 8, 16, True)
+        if sampling is not None:
+            dk.engine_set_sampling(eng, *sampling)
+        ids = [dk.engine_submit(eng, p, n) for p, n in requests]
+        run_to_completion(dk, eng)
+        outs = [list(dk.engine_poll(eng, rid)[0]) for rid in ids]
+        dk.engine_destroy(eng)
+        return outs
+
+    greedy = run(None, reqs)
+    assert run((1.0, 1, 1.0, 9), reqs) == greedy                      # only the largest weight is kept
+    hot = (1.5, 0, 0.95, 1234)
+    a, b = run(hot, reqs), run(hot, reqs)
+    assert a == b and a != greedy
+    assert all(0 <= t < shape.vocab for o in a for t in o)
+    assert run((1.5, 0, 0.95, 99), reqs) != a                          # another seed, other tokens
+    # one request alone: token by token against the oracle's sampler
+    prompt, new = reqs[1][0], 12
+    want = oracle_generate_sampled(orc, shape, s.weights, prompt, new, *hot)
+    got = run(hot, [(prompt, new)], max_batch=1)[0]
+    assert got == want, (got, want)
+    # switching back to greedy
+    eng, arena = s.engine(4, 8, 16, True)
+    dk.engine_set_sampling(eng, *hot)
+    dk.engine_set_sampling(eng, None)
+    ids = [dk.engine_submit(eng, p, n) for p, n in reqs]
+    run_to_completion(dk, eng)
+    assert [list(dk.engine_poll(eng, rid)[0]) for rid in ids] == greedy
+    with pytest.raises(dk.DecodeKitError):
+        dk.engine_set_sampling(eng, 0.0, 0, 1.0, 1)
+    dk.engine_destroy(eng)
+    s.close()
