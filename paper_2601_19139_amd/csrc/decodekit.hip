@@ -862,7 +862,11 @@ dk_status dk_workspace_bytes(const dk_model *model, int32_t max_B, int32_t max_b
     if (!model || !out_bytes) return fail(DK_E_INVALID_ARG, "NULL argument");
     if (max_B <= 0 || max_B > DK_MAX_BATCH) return fail(DK_E_INVALID_ARG, "max_B %d (1..%d)", max_B, DK_MAX_BATCH);
     if (max_blocks <= 0) return fail(DK_E_INVALID_ARG, "max_blocks_per_seq %d", max_blocks);
-    *out_bytes = carve(model->cfg, max_B, max_blocks, model->q4).total;
+    // the layout depends on the batch size (which kernels run, which buffers they need): a workspace
+    // "for batches up to max_B" has to hold the largest of them
+    size_t need = 0;
+    for (int b = 1; b <= max_B; b++) need = std::max(need, carve(model->cfg, b, max_blocks, model->q4).total);
+    *out_bytes = need;
     return DK_OK;
 }
 

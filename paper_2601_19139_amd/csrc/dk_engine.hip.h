@@ -218,14 +218,11 @@ dk_status engine_layout(const dk_model *model, const dk_engine_config *cfg, Aren
     if (cfg->prefill_chunk < 1 || cfg->prefill_chunk > DK_MAX_BATCH)
         return fail(DK_E_INVALID_ARG, "prefill_chunk %d (1..%d)", cfg->prefill_chunk, DK_MAX_BATCH);
     if (cfg->max_blocks_per_seq < 1) return fail(DK_E_INVALID_ARG, "max_blocks_per_seq %d", cfg->max_blocks_per_seq);
+    // a decode step may run with any batch 1..M and a prefill chunk with any size up to the configured one
     size_t ws = 0;
-    // a decode step may run with any batch 1..M and a prefill chunk with any size up to the
-    // configured one; the workspace layout depends on the row count, so take the largest
-    for (int b = 1; b <= std::max(cfg->max_batch, cfg->prefill_chunk); b++) {
-        size_t need = 0;
-        const dk_status s = dk_workspace_bytes(model, b, cfg->max_blocks_per_seq, &need);
+    {
+        const dk_status s = dk_workspace_bytes(model, std::max(cfg->max_batch, cfg->prefill_chunk), cfg->max_blocks_per_seq, &ws);
         if (s != DK_OK) return s;
-        ws = std::max(ws, need);
     }
     size_t off = 0;
     auto take = [&](size_t bytes) { const size_t o = off; off = align_up(off + bytes, 256); return o; };

@@ -177,6 +177,18 @@ def test_model_shape_checks_and_workspace():
     assert "layer 5" in str(e.value)
 
 
+def test_workspace_covers_every_smaller_batch():
+    """dk_workspace_bytes(model, B) is the need of the largest layout among batches 1..B (the layout
+    changes with the batch size: persistent kernel up to 2 rows, vector-ALU path up to 4, matrix cores
+    above, K-sliced GEMMs from 33 rows), so it never decreases with B."""
+    for name in ("qwen3_0p6b", "qwen3_8b", "qwen3_30b_a3b_l4", "tiny"):
+        cfg, ptrs, _keep = fake_model(W.CONFIGS[name])
+        m = dk.create_model(cfg, ptrs)
+        sizes = [dk.workspace_bytes(m, b, 40) for b in range(1, 65)]
+        assert all(a <= b for a, b in zip(sizes, sizes[1:])), name
+        dk.destroy_model(m)
+
+
 def test_q4_model_checks_and_bytes():
     """dk_create_model_q4: dense shapes with every contraction length a multiple of 128; the
     algorithmic bytes count 4.5 bits per weight."""
