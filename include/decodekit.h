@@ -200,6 +200,10 @@ dk_status dk_workspace_bytes(const dk_model *model, int32_t max_B, int32_t max_b
 #define DK_STEP_ADVANCE 1u /* after the step: d_tokens[b] = next token, d_seq_lens[b] += 1 */
 #define DK_STEP_NO_FUSED 4u /* do not use the single persistent step kernel even where it
                                applies (batches of 1-2 rows of small dense models) */
+/* HIP graphs: with DK_STEP_NO_FUSED a step enqueues kernels only and keeps no host state between
+ * calls, so it may be captured into a graph and replayed (with DK_STEP_ADVANCE every replay moves
+ * the sequences on); call it once eagerly on the device first.  The persistent kernel alternates
+ * two buffer sets and counts steps on the host: it must not be captured. */
 #define DK_STEP_PROFILE 2u /* time every kernel of the step with its own start/stop events;
                               the call then synchronises the stream before it returns and
                               adds the times to the totals dk_profile_read returns */

@@ -363,3 +363,67 @@ def test_mixture_of_experts(dk, orc, name, shape, contexts, steps):
     # a near-tie in the router may legitimately pick another expert; with these
     # seeds none does
     assert same == total, f"{name}: routing differs on {total - same} of {total} (layer, row) pairs"
+
+
+@pytest.mark.parametrize("batch", [2, 20])
+def test_decode_step_replays_in_a_hip_graph(dk, orc, batch):
+    """The kernel-per-stage step keeps no host state between calls and enqueues only kernels, so a
+    caller can capture it in a HIP graph (the persistent kernel alternates buffer sets on the host and
+    is excluded with DK_STEP_NO_FUSED).  Eight replays, with eager work and synchronisation between
+    them, must give the tokens of eight eager steps, and the last one the oracle's logits."""
+    import torch
+    shape = variant("tiny", qk_norm=True, vocab=70003 if batch > 16 else 1024)
+    contexts = [(13 * i) % 70 for i in range(batch)]
+    steps = 8
+    lay = build_block_tables(contexts, 16, steps + 1, seed=43)
+    weights = W.make_weights(shape, 20)
+    pool = W.fill_kv_pool(shape, lay, 21)
+    tokens = W.initial_tokens(shape, batch, 22)
+    flags = dk.STEP_ADVANCE | dk.STEP_NO_FUSED
+    dm = dk.DeviceModel(shape, weights)
+
+    def fresh():
+        dkv = dk.DeviceKV(dm, lay, pool)
+        return dkv, dk.Decoder(dm, dkv, lay.contexts, tokens)
+
+    dkv, dec = fresh()
+    eager = []
+    for _ in range(steps):
+        dec.step(flags=flags)
+        torch.cuda.synchronize()
+        eager.append(dec.next.cpu().numpy().copy())
+    eager_logits = dec.logits.cpu().numpy().copy()
+    dkv.close()
+
+    dkv, dec = fresh()
+    stream = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(stream):
+        dec.step(flags=flags, stream=stream.cuda_stream)          # step 0 eagerly (also the one-time set-up calls)
+        stream.synchronize()
+        got = [dec.next.cpu().numpy().copy()]
+        graph.capture_begin()
+        dec.step(flags=flags, stream=stream.cuda_stream)
+        graph.capture_end()
+    scratch = torch.zeros(1 << 20, device="cuda")
+    for _ in range(steps - 1):
+        graph.replay()
+        torch.cuda.synchronize()
+        got.append(dec.next.cpu().numpy().copy())
+        scratch += 1.0                                            # the program's own eager work between replays
+        torch.cuda.synchronize()
+    for a, b in zip(eager, got):
+        assert np.array_equal(a, b)
+    assert np.array_equal(dec.logits.cpu().numpy(), eager_logits)  # same kernels, same order: bit for bit
+    assert np.array_equal(dec.seq_lens.cpu().numpy(), lay.contexts + steps)
+    # and the replayed chain is the oracle's: teacher-free comparison of the last step's logits
+    opool, sl, tok = pool.copy(), lay.contexts.copy(), tokens.copy()
+    agree = True
+    for k in range(steps):
+        r = orc.decode_step(shape, weights, opool, 16, lay.tables, sl, tok)
+        agree = agree and np.array_equal(r["next"], got[k])
+        sl, tok = sl + 1, r["next"]
+    assert agree, "free-running greedy tokens left the oracle's path (no near-tie expected with this seed)"
+    assert rel_l2(dec.logits.cpu().numpy(), r["logits"]).max() < 1e-3
+    dkv.close()
+    dm.close()
