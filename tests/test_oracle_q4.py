@@ -177,3 +177,23 @@ def test_quantize_weights_covers_every_projection():
             assert set(L[n]) == {"q", "scale", "bias"}
         assert L["g_attn"].dtype == np.uint16
     assert qw["lm_head"]["q"].shape == (cfg.vocab, cfg.hidden)
+
+
+def test_q4_oracle_reproduces_stored_fixture(orc):
+    """Drift detector: tests/golden/cfg0_q4_oracle.json was written by tests/golden/make_golden.py from
+    the oracle (and the input quantiser) alone."""
+    import json
+    import os
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "cfg0_q4_oracle.json")
+    gold = json.load(open(path))
+    wl = W.WORKLOADS["cfg0_q4"]
+    cfg, lay = wl.cfg, layout_for(wl)
+    qw = quantize_weights(W.make_weights(cfg, wl.seed_weights))
+    pool = W.fill_kv_pool(cfg, lay, wl.seed_kv)
+    tok = W.initial_tokens(cfg, wl.batch, wl.seed_tokens)
+    sl = lay.contexts.copy()
+    for g in gold["steps"]:
+        r = orc.decode_step_q4(cfg, qw, pool, wl.block_size, lay.tables, sl, tok)
+        assert [int(t) for t in r["next"]] == g["next"]
+        assert np.allclose(r["logits"][:, :8], np.array(g["logits_0_8"]), rtol=1e-6, atol=1e-7)
+        tok, sl = r["next"], sl + 1
