@@ -6,7 +6,10 @@ every layer (q/k/v projection, head norm + rotary embedding + KV append,
 ragged paged attention, output projection, SwiGLU MLP), final norm, lm_head
 and greedy argmax - one new token for each of the B sequences.  Inputs
 (weights, KV pool, block tables, tokens) are resident in HBM before the timed
-region.  Prints one JSON line.
+region.  Prints one JSON line: the contract fields, `roofline` (the dominant kernel
+class against the published HBM peak and against a read-only streaming kernel
+measured on the spot), `step_roofline` (the whole step), per-kernel times, the
+batch-16 figure of the same model (batch-1 workloads) and the CPU oracle's rate.
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg1]
 """
@@ -66,6 +69,25 @@ def make_model_weights(args, W, shape, seed):
             weights = {**weights, "lm_head": weights["embed"].copy()}   # the embedding table stays bf16
         weights = quantize_weights(weights)
     return weights
+
+
+def read_ceiling(dk, torch):
+    """Read-only bandwidth of a plain streaming kernel on this device (dk_read_stream over 2 GiB that no
+    cache holds, best of five launches): the practical ceiling next to the published peak."""
+    buf = torch.empty(2 << 30, dtype=torch.uint8, device="cuda")
+    buf.fill_(1)
+    sink = torch.zeros(4096, dtype=torch.int32, device="cuda")
+    best = None
+    for _ in range(6):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        dk.read_stream(buf, sink)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1)
+        best = ms if best is None else min(best, ms)
+    del buf
+    return (2 << 30) / (best * 1e-3) / 1e9
 
 
 def batch16_line(args, wl, dk, W, np, torch, dm, tok_s_batch1):
@@ -359,6 +381,7 @@ def main():
                    "fused_step": alg_bytes}      # the persistent kernel is the whole step
     step_dev_s = dev_ms * 1e-3 / args.steps
     achieved_step = alg_bytes / step_dev_s / 1e9
+    ceiling = read_ceiling(dk, torch)
     kernels = {}
     for k, (ms, cnt) in prof.items():
         if cnt:
@@ -397,9 +420,12 @@ def main():
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
                      "kernel": dominant, "launches_per_step": dom["launches_per_step"],
                      "avg_launch_us": dom["avg_us"],
-                     "algorithmic_bytes_per_launch": int(dom_bytes_per_launch)},
+                     "algorithmic_bytes_per_launch": int(dom_bytes_per_launch),
+                     # the same against what a plain read-only streaming kernel reaches on this device
+                     "measured_read_ceiling": round(ceiling, 1), "frac_of_ceiling": round(achieved / ceiling, 4)},
         # the whole step (every launch): algorithmic bytes / device time of the timed region
         "step_roofline": {"achieved": round(achieved_step, 1), "frac": round(achieved_step / HBM_PEAK_GBS, 4),
+                          "frac_of_ceiling": round(achieved_step / ceiling, 4),
                           "unit": "GB/s", "algorithmic_bytes_per_step": int(alg_bytes),
                           "device_ms_per_step": round(step_dev_s * 1e3, 5)},
         "kernels": kernels,

@@ -81,6 +81,7 @@ _SIGNATURES = {
     "dk_fused_status": (C.c_int32, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
     "dk_profile_read": (C.c_int32, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32]),
     "dk_step_routing": (C.c_int32, [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]),
+    "dk_read_stream": (C.c_int32, [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]),
     "dk_step_algorithmic_bytes": (C.c_int32, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p,
                                               C.c_int32, C.c_int32, C.c_void_p, C.POINTER(C.c_uint64)]),
 }
@@ -259,6 +260,11 @@ def create_model_q4(cfg: ModelConfig, weights: WeightPtrs):
 
 def destroy_model(model):
     _check(lib().dk_destroy_model(model))
+
+
+def read_stream(d_buf, d_sink, stream=None):
+    """Enqueues the read-only streaming kernel over the whole of d_buf (measurement aid)."""
+    _check(lib().dk_read_stream(_ptr(d_buf), d_buf.numel() * d_buf.element_size(), _ptr(d_sink), _stream(stream)))
 
 
 def workspace_bytes(model, max_B: int, max_blocks_per_seq: int) -> int:
