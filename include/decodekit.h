@@ -370,8 +370,8 @@ dk_status dk_step_algorithmic_bytes(const dk_model *model, const dk_kv_pool *poo
                                     uint64_t *out_bytes);
 
 /* Measurement aid: enqueues one kernel that reads `bytes` bytes (a multiple of 16) of device memory
- * once, 16 bytes per lane and eight loads in flight per lane, and does nothing else (a 4-byte word per
- * block goes to d_sink, device memory of at least 8 KB).  Timed by the caller over a buffer larger than
+ * once, 16 bytes per lane and eight loads in flight per lane, one block per compute unit, and does nothing
+ * else (d_sink: device memory of at least 8 KB, practically never written).  Timed by the caller over a buffer larger than
  * the caches it gives the read-only bandwidth a streaming kernel can reach on this device, the practical
  * ceiling the decode kernels are compared with beside the published peak. */
 dk_status dk_read_stream(const void *d_buf, size_t bytes, void *d_sink, void *hip_stream);

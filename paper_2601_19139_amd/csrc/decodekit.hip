@@ -1568,7 +1568,12 @@ dk_status dk_read_stream(const void *d_buf, size_t bytes, void *d_sink, void *hi
 {
     if (!d_buf || !d_sink) return fail(DK_E_INVALID_ARG, "NULL argument");
     if (bytes == 0 || bytes % 16 || (uintptr_t)d_buf % 16) return fail(DK_E_INVALID_ARG, "bytes %zu (a positive multiple of 16, 16-byte aligned)", bytes);
-    hipLaunchKernelGGL(read_stream_kernel, dim3(2048), dim3(256), 0, static_cast<hipStream_t>(hip_stream),
+    // one block per compute unit, looping: the shape that read fastest in sweeps of 256..65536 blocks of
+    // 256..1024 threads, grid-strided or one contiguous chunk per block (6.6 TB/s against 5.2-6.3)
+    int dev = 0, cus = 0;
+    DK_HIP(hipGetDevice(&dev));
+    DK_HIP(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+    hipLaunchKernelGGL(read_stream_kernel, dim3(cus > 0 ? cus : 256), dim3(256), 0, static_cast<hipStream_t>(hip_stream),
                        static_cast<const uint4 *>(d_buf), bytes / 16, static_cast<uint32_t *>(d_sink));
     DK_HIP(hipGetLastError());
     return DK_OK;
