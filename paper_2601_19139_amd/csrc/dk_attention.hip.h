@@ -167,34 +167,52 @@ __device__ __forceinline__ float ld_coherent(const float *p)
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-// Online merge, in chunk order, of element `dim` of one head's chunk partials
-// ([chunk][G][d+2] with the running max and sum behind the d outputs).  The
-// device-coherent loads of eight chunks are issued together: one round trip
-// per eight chunks instead of one per chunk.
-__device__ __forceinline__ float merge_chunk_partials(const float *pg, int64_t chunk_stride, int nact, int D,
-                                                      int dim)
+// Online merge, in chunk order, of the chunk partials of one (row, kv head): [chunk][G][d+2] with the
+// running max and sum behind the d outputs.  Thread tid produces elements idx = tid, tid + 256, ... of
+// the G*d outputs (v[i] for idx = tid + 256*i; entries past G*d are not meaningful).  The device-coherent
+// loads of eight chunks for ALL of a thread's elements are issued together: one round trip per eight
+// chunks for the whole block instead of one per element and eight chunks.
+template <int G, int D>
+__device__ __forceinline__ void merge_chunk_partials(const float *part, int nact, int tid,
+                                                     float (&v)[(G * D + 255) / 256])
 {
-    float mn = -1e30f, ls = 0.f, os = 0.f;
-    for (int c0 = 0; c0 < nact; c0 += 8) {
-        float mc[8], lc[8], oc[8];
+    constexpr int NE = (G * D + 255) / 256, MR = 8;
+    constexpr int64_t stride = (int64_t)G * (D + 2);
+    float mn[NE], ls[NE], os[NE];
+    const float *pe[NE];
+    int dim[NE];
 #pragma unroll
-        for (int u = 0; u < 8; u++) {
-            const float *pp = pg + (int64_t)min(c0 + u, nact - 1) * chunk_stride;
-            mc[u] = ld_coherent(pp + D);
-            lc[u] = ld_coherent(pp + D + 1);
-            oc[u] = ld_coherent(pp + dim);
-        }
-#pragma unroll
-        for (int u = 0; u < 8; u++)
-            if (c0 + u < nact) {
-                const float m2 = fmaxf(mn, mc[u]);
-                const float sa = __expf(mn - m2), sb = __expf(mc[u] - m2);
-                ls = ls * sa + lc[u] * sb;
-                os = os * sa + oc[u] * sb;
-                mn = m2;
-            }
+    for (int i = 0; i < NE; i++) {
+        const int idx = min(tid + 256 * i, G * D - 1);   // clamped: a valid address, result unused
+        mn[i] = -1e30f; ls[i] = 0.f; os[i] = 0.f;
+        dim[i] = idx % D;
+        pe[i] = part + (idx / D) * (D + 2);
     }
-    return os / ls;
+    for (int c0 = 0; c0 < nact; c0 += MR) {
+        float mc[NE][MR], lc[NE][MR], oc[NE][MR];
+#pragma unroll
+        for (int i = 0; i < NE; i++)
+#pragma unroll
+            for (int u = 0; u < MR; u++) {
+                const float *pp = pe[i] + (int64_t)min(c0 + u, nact - 1) * stride;
+                mc[i][u] = ld_coherent(pp + D);
+                lc[i][u] = ld_coherent(pp + D + 1);
+                oc[i][u] = ld_coherent(pp + dim[i]);
+            }
+#pragma unroll
+        for (int i = 0; i < NE; i++)
+#pragma unroll
+            for (int u = 0; u < MR; u++)
+                if (c0 + u < nact) {
+                    const float m2 = fmaxf(mn[i], mc[i][u]);
+                    const float sa = __expf(mn[i] - m2), sb = __expf(mc[i][u] - m2);
+                    ls[i] = ls[i] * sa + lc[i][u] * sb;
+                    os[i] = os[i] * sa + oc[i][u] * sb;
+                    mn[i] = m2;
+                }
+    }
+#pragma unroll
+    for (int i = 0; i < NE; i++) v[i] = os[i] / ls[i];
 }
 
 // element k of batch row b of the attention output (k = head*d + dim)
@@ -558,11 +576,12 @@ __global__ __launch_bounds__(256) void attention_kernel(AttnArgs a)
                                            __HIP_MEMORY_SCOPE_AGENT);
     __syncthreads();
     if (sm_ticket != nact - 1) return;
-    for (int idx = tid; idx < G * D; idx += 256) {
-        const int g = idx / D, dim = idx % D;
-        const float *pg = part + g * (D + 2);
-        const float v = merge_chunk_partials(pg, (int64_t)G * (D + 2), nact, D, dim);
-        store_attn_out(a, b, (j * G + g) * D + dim, a.nq * D, v);
+    float mv[(G * D + 255) / 256];
+    merge_chunk_partials<G, D>(part, nact, tid, mv);
+#pragma unroll
+    for (int i = 0; i < (G * D + 255) / 256; i++) {
+        const int idx = tid + 256 * i;
+        if (idx < G * D) store_attn_out(a, b, j * G * D + idx, a.nq * D, mv[i]);
     }
     if (tid == 0)
         __hip_atomic_store(&a.tickets[b * a.nkv + j], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);

@@ -382,11 +382,12 @@ __global__ __launch_bounds__(256, 2) void attention_mfma_kernel(AttnArgs a)
                                            __HIP_MEMORY_SCOPE_AGENT);
     __syncthreads();
     if (sm_ticket != nact - 1) return;
-    for (int idx = tid; idx < G * D; idx += 256) {
-        const int g = idx / D, dim = idx % D;
-        const float *pg = part + g * (D + 2);
-        const float v = merge_chunk_partials(pg, (int64_t)G * (D + 2), nact, D, dim);
-        store_attn_out(a, b, (j * G + g) * D + dim, a.nq * D, v);
+    float mv[(G * D + 255) / 256];
+    merge_chunk_partials<G, D>(part, nact, tid, mv);
+#pragma unroll
+    for (int i = 0; i < (G * D + 255) / 256; i++) {
+        const int idx = tid + 256 * i;
+        if (idx < G * D) store_attn_out(a, b, j * G * D + idx, a.nq * D, mv[i]);
     }
     if (tid == 0)
         __hip_atomic_store(&a.tickets[b * a.nkv + j], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
