@@ -204,6 +204,9 @@ struct dk_engine {
     int32_t *d_sampled = nullptr;
     std::vector<int32_t> h_tables;            // host mirror [M][max_blocks]
     std::vector<char> row_dirty;
+    // lengths and last tokens on the device are stale (the batch changed, or tokens were sampled on the side);
+    // otherwise the decode step advances them itself and nothing is uploaded
+    bool state_dirty = true;
 };
 
 namespace {
@@ -273,6 +276,7 @@ void engine_set_row(dk_engine *e, int row, const EngineRequest *r)
     std::fill(dst, dst + e->cfg.max_blocks_per_seq, -1);
     std::copy(r->blocks.begin(), r->blocks.end(), dst);
     e->row_dirty[(size_t)row] = 1;
+    e->state_dirty = true;
 }
 
 dk_status engine_upload_rows(dk_engine *e, hipStream_t st)
@@ -502,12 +506,17 @@ dk_status dk_engine_step(dk_engine *engine, void *hip_stream, int32_t *out_activ
         for (int i = 0; i < B; i++) { seq[(size_t)i] = e->active[(size_t)i]->T; tok[(size_t)i] = e->active[(size_t)i]->last; }
         dk_status s = engine_upload_rows(e, st);
         if (s != DK_OK) return s;
-        DK_HIP(hipMemcpyAsync(e->d_seq, seq.data(), (size_t)B * 4, hipMemcpyHostToDevice, st));
-        DK_HIP(hipMemcpyAsync(e->d_tok, tok.data(), (size_t)B * 4, hipMemcpyHostToDevice, st));
+        if (e->state_dirty || e->sampling) {
+            DK_HIP(hipMemcpyAsync(e->d_seq, seq.data(), (size_t)B * 4, hipMemcpyHostToDevice, st));
+            DK_HIP(hipMemcpyAsync(e->d_tok, tok.data(), (size_t)B * 4, hipMemcpyHostToDevice, st));
+            e->state_dirty = false;
+        }
+        // greedy: the step feeds its own tokens and lengths to the next one (an invalid step advances nothing)
+        const uint32_t advance = e->sampling ? 0u : DK_STEP_ADVANCE;
         for (int attempt = 0; attempt < 2; attempt++) {
             s = dk_decode_step(e->model, e->pool, e->d_tables, e->cfg.max_blocks_per_seq, e->d_seq, e->d_tok, B,
                                e->d_ws, e->ws_bytes, e->sampling ? e->d_logits : nullptr, e->d_next,
-                               e->no_fused ? DK_STEP_NO_FUSED : 0u, st);
+                               advance | (e->no_fused ? DK_STEP_NO_FUSED : 0u), st);
             if (s != DK_OK) return s;
             DK_HIP(hipMemcpyAsync(nxt.data(), e->d_next, (size_t)B * 4, hipMemcpyDeviceToHost, st));
             if (e->sampling) {
