@@ -16,6 +16,7 @@
 
 #include "dk_attention.hip.h"
 #include "dk_attention_mfma.hip.h"
+#include "dk_attention_prefill.hip.h"
 #include "dk_fused.hip.h"
 #include "dk_gemm.hip.h"
 #include "dk_gemm_shared.hip.h"
@@ -159,6 +160,7 @@ struct Workspace {
     int Bp;             // batch rows padded to a multiple of 16
     bool batched;
     int chunk_tokens, max_chunks, lm_blocks;
+    int pf_chunk_tokens, pf_max_chunks;   // the same split for the kernel that takes a prefill chunk's rows in groups
     bool defer_merge;   // small problems: the output projection merges the attention chunks
 };
 
@@ -281,7 +283,18 @@ Workspace carve(const dk_model_config &c, int B, int max_blocks, bool q4)
     w.attn = take((size_t)B * c.n_q_heads * d * 4);
     w.act = take((size_t)B * act_dim * 4);
     w.cs = take((size_t)B * (d / 2) * 8);
-    w.part = take((size_t)B * c.n_kv_heads * w.max_chunks * G * (d + 2) * 4);
+    size_t part_floats = (size_t)B * c.n_kv_heads * w.max_chunks * G * (d + 2);
+    {   // rows of a prefill chunk in groups of 16 / G: fewer, larger work items, so a finer split
+        const int rpb = std::max(1, 16 / G);
+        const int groups = (B + rpb - 1) / rpb;
+        int want = (512 + groups * c.n_kv_heads - 1) / (groups * c.n_kv_heads);
+        int pchunk = ((ctx_max + want - 1) / want + 63) / 64 * 64;
+        if (pchunk < 256) pchunk = 256;
+        w.pf_chunk_tokens = pchunk;
+        w.pf_max_chunks = (ctx_max + pchunk - 1) / pchunk;
+        part_floats = std::max(part_floats, (size_t)groups * c.n_kv_heads * w.pf_max_chunks * 16 * (d + 2));
+    }
+    w.part = take(part_floats * 4);
     w.Bp = (B + 15) / 16 * 16;
     size_t gemm_tickets = 0, gemm_part = 0;
     {
@@ -530,6 +543,27 @@ dk_status launch_attention_d(const dk::AttnArgs &a, int G, dim3 grid, bool mfma,
     return DK_OK;
 }
 
+template <int D>
+dk_status launch_prefill_attention_d(const dk::AttnArgs &a, int G, dim3 grid, hipStream_t st)
+{
+#define DK_PF_ATTN_CASE(g)                                                                              \
+    case g:                                                                                             \
+        DK_LAUNCH(DK_K_ATTENTION, (dk::prefill_attention_kernel<D, g>), grid, dim3(256), 0, st, a);     \
+        break;
+    switch (G) {
+        DK_PF_ATTN_CASE(1)
+        DK_PF_ATTN_CASE(2)
+        DK_PF_ATTN_CASE(3)
+        DK_PF_ATTN_CASE(4)
+        DK_PF_ATTN_CASE(6)
+        DK_PF_ATTN_CASE(8)
+        default: return fail(DK_E_UNSUPPORTED_SHAPE, "query group size %d", G);
+    }
+#undef DK_PF_ATTN_CASE
+    DK_HIP(hipGetLastError());
+    return DK_OK;
+}
+
 template <int NB, int D, int G, int KSH, int KSQ, int KSF>
 dk_status launch_fused_inst(const dk::FusedArgs &a, bool q4, hipStream_t st)
 {
@@ -648,7 +682,7 @@ const char *dk_last_error(void) { return g_err; }
 
 // The kernel revisions change whenever a kernel's memory behaviour changes; the
 // benchmark quotes stored counter measurements only for a matching revision.
-const char *dk_version(void) { return "decodekit 0.8 (gfx950; gemv r3, gemm r9, attention r7, moe r4, fused r2, prefill r1, sample r1)"; }
+const char *dk_version(void) { return "decodekit 0.8 (gfx950; gemv r3, gemm r9, attention r7, moe r4, fused r2, prefill r2, sample r1)"; }
 
 // ------------------------------------------------------------------- pool --
 dk_status dk_kv_pool_bytes(const dk_model_config *cfg, int32_t num_blocks, int32_t block_size,
@@ -1227,10 +1261,21 @@ static dk_status decode_step_impl(dk_model *model, dk_kv_pool *pool, const int32
             }
             a.scale = (float)(1.0 / std::sqrt((double)d));
             a.eps = eps;
-            const dim3 grid(w.max_chunks, nkv, B);
-            const bool use_mfma = attention_uses_mfma(c, B, model->q4);
-            s = (d == 128) ? launch_attention_d<128>(a, nq / nkv, grid, use_mfma, st)
-                           : launch_attention_d<64>(a, nq / nkv, grid, use_mfma, st);
+            a.n_rows = B;
+            if (prefill && batched) {
+                // rows of one sequence: 16 / G of them share every K/V tile
+                const int G = nq / nkv;
+                a.chunk_tokens = w.pf_chunk_tokens;
+                a.max_chunks = w.pf_max_chunks;
+                const dim3 grid(nkv, w.pf_max_chunks, (B + 16 / G - 1) / (16 / G));
+                s = (d == 128) ? launch_prefill_attention_d<128>(a, G, grid, st)
+                               : launch_prefill_attention_d<64>(a, G, grid, st);
+            } else {
+                const dim3 grid(w.max_chunks, nkv, B);
+                const bool use_mfma = attention_uses_mfma(c, B, model->q4);
+                s = (d == 128) ? launch_attention_d<128>(a, nq / nkv, grid, use_mfma, st)
+                               : launch_attention_d<64>(a, nq / nkv, grid, use_mfma, st);
+            }
             if (s != DK_OK) return s;
         }
         // x += W_o * attn

@@ -155,6 +155,7 @@ struct AttnArgs {
     int defer_merge;         // 1: leave the chunk partials for the consumer to merge
     int table_stride;        // ints between the rows' block tables (0: all rows share one table)
     int no_append;           // 1: the new tokens' K/V are already in the pool (chunked prefill)
+    int n_rows;              // batch rows (the kernel that groups rows checks against it)
     float scale, eps;
 };
 
@@ -172,12 +173,12 @@ __device__ __forceinline__ float ld_coherent(const float *p)
 // the G*d outputs (v[i] for idx = tid + 256*i; entries past G*d are not meaningful).  The device-coherent
 // loads of eight chunks for ALL of a thread's elements are issued together: one round trip per eight
 // chunks for the whole block instead of one per element and eight chunks.
-template <int G, int D>
+template <int G, int D, int SG = G>
 __device__ __forceinline__ void merge_chunk_partials(const float *part, int nact, int tid,
                                                      float (&v)[(G * D + 255) / 256])
 {
     constexpr int NE = (G * D + 255) / 256, MR = 8;
-    constexpr int64_t stride = (int64_t)G * (D + 2);
+    constexpr int64_t stride = (int64_t)SG * (D + 2);   // a chunk's record holds SG >= G heads
     float mn[NE], ls[NE], os[NE];
     const float *pe[NE];
     int dim[NE];

@@ -88,6 +88,15 @@ CASES = [
     ("tiny_long_64", variant("tiny", qk_norm=True), 150, 64, 2),
     ("d128_g4", variant("tiny", head_dim=128, n_q_heads=8, n_kv_heads=2, qk_norm=True), 70, 32, 2),
     ("moe", W.CONFIGS["tiny_moe"], 41, 16, 2),
+    # Contexts beyond 256 positions: the kernel that takes the rows of a chunk in groups (16 / G rows
+    # share a K/V tile) splits the context, so chunk partials, ticket and merge are exercised; query
+    # groups of every supported size, row counts that leave the last group ragged.
+    ("tiny_long_700", variant("tiny", qk_norm=True), 700, 64, 1),
+    ("d128_g4_long", variant("tiny", head_dim=128, n_q_heads=8, n_kv_heads=2, qk_norm=True), 530, 48, 1),
+    ("g3_ragged", variant("tiny", n_q_heads=6), 300, 37, 1),
+    ("g8", variant("tiny", n_q_heads=8, n_kv_heads=1, qk_norm=True), 290, 64, 1),
+    ("g1", variant("tiny", n_q_heads=2), 280, 50, 1),
+    ("g6", variant("tiny", n_q_heads=6, n_kv_heads=1), 100, 9, 1),
 ]
 
 
