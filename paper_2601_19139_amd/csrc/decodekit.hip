@@ -197,9 +197,10 @@ bool attention_uses_mfma(const dk_model_config &c, int B, bool q4)
 
 // Which kernel a batched GEMM takes: w == 0 the K-split-per-wave kernel (skinny_gemm_kernel),
 // otherwise shared_gemm_kernel with w waves per block and K cut into `slices` across blocks.
-// Measured on the 0.6B / 3B / 8B shapes: sharing the activation tile pays for the lm_head from 17
-// batch rows on (with a short K also at 16), for the gate/up pair of a large model from 17 rows on, and
-// for the other large layer matrices from 33 rows on; everything smaller is faster with the other kernel.
+// From a sweep (16..64 batch rows; waves 4 / 8; slices 1..8) over the layer matrices of the 0.6B, 3B,
+// 8B and 30B-A3B shapes, HBM-cold: four K slices win wherever the matrix is large enough to hide the
+// hand-over of the partial tiles - 1.05-1.25x at 16 rows, 1.2-2.2x at 32..64 rows - and lose
+// (0.75-0.9x) on the few-MB matrices of the 0.6B shape, which stay with the other kernel.
 struct GemmPlan { int w, slices; };
 GemmPlan gemm_plan(int epi, int N, int K, int Bp, bool q4)
 {
@@ -207,22 +208,29 @@ GemmPlan gemm_plan(int epi, int N, int K, int Bp, bool q4)
     const long long elems = (long long)N * K;
     if (K % 128) return {0, 1};
     if (q4) {
-        // 4-bit weights: the kernels are bound by the matrix cores and the code conversion rather than by
-        // the activation traffic; sharing pays for the lm_head (every batch size) and the gate/up pair
-        if (epi == dk::GEPI_STORE && (N + 15) / 16 >= 4096) return {8, 1};
-        if (epi == dk::GEPI_SWIGLU && mt >= 2 && elems >= (20ll << 20)) return {8, 2};
+        // 4-bit weights (the same sweep): the lm_head at every batch size; q | k | v from 32 rows on;
+        // the gate/up pair and the down projection of the 3B / 8B shapes; never the output projection
+        if (epi == dk::GEPI_STORE) {
+            if ((N + 15) / 16 >= 4096) return {8, 1};
+            if (mt >= 2 && elems >= (8ll << 20)) return {8, 4};
+        } else if (epi == dk::GEPI_SWIGLU) {
+            if (elems >= (40ll << 20)) return {8, 2};
+            if (elems >= (20ll << 20)) return {8, 4};
+        } else {
+            if (elems >= (mt >= 2 ? (20ll << 20) : (40ll << 20))) return {4, 8};
+        }
         return {0, 1};
     }
-    // 16 rows: only the lm_head, and only while K is short (measured: 106 -> 67 us at K = 1024,
-    // 181 -> 150 us at K = 3072, 250 -> 276 us at K = 4096)
-    if (mt < 2) return (epi == dk::GEPI_STORE && (N + 15) / 16 >= 4096 && K <= 3072) ? GemmPlan{8, 1} : GemmPlan{0, 1};
     if (epi == dk::GEPI_STORE) {
-        if ((N + 15) / 16 >= 4096) return {8, 1};
-        if (mt >= 3 && elems >= (12ll << 20)) return {4, 2};
+        // lm_head: one slice (thousands of row blocks).  At 16 rows only while K is short (measured:
+        // 106 -> 67 us at K = 1024, 181 -> 150 us at K = 3072, 250 -> 276 us at K = 4096)
+        if ((N + 15) / 16 >= 4096) return (mt >= 2 || K <= 3072) ? GemmPlan{8, 1} : GemmPlan{0, 1};
+        if (elems >= (mt >= 2 ? (8ll << 20) : (20ll << 20))) return {8, 4};   // q | k | v
     } else if (epi == dk::GEPI_SWIGLU) {
-        if (elems >= (mt >= 3 ? (20ll << 20) : (40ll << 20))) return {4, 1};
+        if (elems >= (20ll << 20)) return (mt == 1 && elems >= (40ll << 20)) ? GemmPlan{4, 4} : GemmPlan{8, 4};
     } else {
-        if (mt >= 3 && elems >= (40ll << 20)) return {4, 4};
+        if (elems >= (8ll << 20)) return {4, 4};                              // output projection, down
+        if (mt >= 2 && K >= 3072 && elems >= (3ll << 20)) return {4, 4};      // down of a small model
     }
     return {0, 1};
 }
@@ -296,8 +304,9 @@ Workspace carve(const dk_model_config &c, int B, int max_blocks, bool q4)
     }
     w.part = take(part_floats * 4);
     w.Bp = (B + 15) / 16 * 16;
+    w.batched = B > kMaxGemvBatch || c.n_experts > 0 || q4;   // expert layers and 4-bit weights use the matrix-core kernels
     size_t gemm_tickets = 0, gemm_part = 0;
-    {
+    if (w.batched) {
         const int H = c.hidden, qd = c.n_q_heads * d;
         gemm_plan_needs(dk::GEPI_STORE, (int)qkv_dim, H, w.Bp, q4, gemm_tickets, gemm_part);
         gemm_plan_needs(dk::GEPI_RESID, H, qd, w.Bp, q4, gemm_tickets, gemm_part);
@@ -311,7 +320,6 @@ Workspace carve(const dk_model_config &c, int B, int max_blocks, bool q4)
     w.tickets = take((size_t)w.n_tickets * 4);
     w.kpart = take(gemm_part * 4);
     w.pf_seq = take((size_t)DK_MAX_BATCH * 4);   // positions of a prefill chunk's rows
-    w.batched = B > kMaxGemvBatch || c.n_experts > 0 || q4;   // expert layers and 4-bit weights use the matrix-core kernels
     if (w.batched) {
         w.lm_blocks = (c.vocab + 15) / 16;
         auto padded = [](size_t k) { return (k + 127) / 128 * 128; };   // whole K-steps
@@ -469,29 +477,39 @@ dk_status launch_shared_gemm(const dk::GemmArgs &a, int Bp, const GemmPlan &p, h
 {
     if (p.slices > 1 && (a.kpart == nullptr || a.ktickets == nullptr))
         return fail(DK_E_INVALID_ARG, "K-sliced GEMM without its partial buffer");
+    if (p.slices < 1 || p.slices > a.K / 128) return fail(DK_E_INVALID_ARG, "%d K slices of %d columns", p.slices, a.K);
     const int mt = Bp / 16;
     if (a.q4) {
-        if constexpr (EPI == dk::GEPI_STORE) {
+        if constexpr (EPI == dk::GEPI_RESID) {
+            if (p.w == 4 && mt == 1) return launch_shared_gemm_inst<1, 4, EPI, NORM, true>(a, p.slices, st);
+            if (p.w == 4 && mt == 2) return launch_shared_gemm_inst<2, 4, EPI, NORM, true>(a, p.slices, st);
+            if (p.w == 4 && mt == 3) return launch_shared_gemm_inst<3, 4, EPI, NORM, true>(a, p.slices, st);
+            if (p.w == 4 && mt == 4) return launch_shared_gemm_inst<4, 4, EPI, NORM, true>(a, p.slices, st);
+        } else {
             if (p.w == 8 && mt == 1) return launch_shared_gemm_inst<1, 8, EPI, NORM, true>(a, p.slices, st);
-        }
-        if constexpr (EPI != dk::GEPI_RESID) {
             if (p.w == 8 && mt == 2) return launch_shared_gemm_inst<2, 8, EPI, NORM, true>(a, p.slices, st);
             if (p.w == 8 && mt == 3) return launch_shared_gemm_inst<3, 8, EPI, NORM, true>(a, p.slices, st);
             if (p.w == 8 && mt == 4) return launch_shared_gemm_inst<4, 8, EPI, NORM, true>(a, p.slices, st);
         }
         return fail(DK_E_INVALID_ARG, "no shared-activation 4-bit GEMM for %d rows and %d waves", Bp, p.w);
     }
-    if constexpr (EPI == dk::GEPI_STORE) {
+    // instances: 8 waves for q | k | v, the lm_head and the gate/up pair, 4 waves for the residual
+    // projections (and the gate/up pair of a large model at 16 rows)
+    if constexpr (EPI == dk::GEPI_STORE || EPI == dk::GEPI_SWIGLU) {
         if (p.w == 8 && mt == 1) return launch_shared_gemm_inst<1, 8, EPI, NORM>(a, p.slices, st);
         if (p.w == 8 && mt == 2) return launch_shared_gemm_inst<2, 8, EPI, NORM>(a, p.slices, st);
         if (p.w == 8 && mt == 3) return launch_shared_gemm_inst<3, 8, EPI, NORM>(a, p.slices, st);
         if (p.w == 8 && mt == 4) return launch_shared_gemm_inst<4, 8, EPI, NORM>(a, p.slices, st);
     }
     if constexpr (EPI == dk::GEPI_SWIGLU) {
-        if (p.w == 4 && mt == 2) return launch_shared_gemm_inst<2, 4, EPI, NORM>(a, p.slices, st);
+        if (p.w == 4 && mt == 1) return launch_shared_gemm_inst<1, 4, EPI, NORM>(a, p.slices, st);
     }
-    if (p.w == 4 && mt == 3) return launch_shared_gemm_inst<3, 4, EPI, NORM>(a, p.slices, st);
-    if (p.w == 4 && mt == 4) return launch_shared_gemm_inst<4, 4, EPI, NORM>(a, p.slices, st);
+    if constexpr (EPI == dk::GEPI_RESID) {
+        if (p.w == 4 && mt == 1) return launch_shared_gemm_inst<1, 4, EPI, NORM>(a, p.slices, st);
+        if (p.w == 4 && mt == 2) return launch_shared_gemm_inst<2, 4, EPI, NORM>(a, p.slices, st);
+        if (p.w == 4 && mt == 3) return launch_shared_gemm_inst<3, 4, EPI, NORM>(a, p.slices, st);
+        if (p.w == 4 && mt == 4) return launch_shared_gemm_inst<4, 4, EPI, NORM>(a, p.slices, st);
+    }
     return fail(DK_E_INVALID_ARG, "no shared-activation GEMM for %d rows and %d waves", Bp, p.w);
 }
 
@@ -682,7 +700,7 @@ const char *dk_last_error(void) { return g_err; }
 
 // The kernel revisions change whenever a kernel's memory behaviour changes; the
 // benchmark quotes stored counter measurements only for a matching revision.
-const char *dk_version(void) { return "decodekit 0.8 (gfx950; gemv r3, gemm r9, attention r7, moe r4, fused r2, prefill r2, sample r1)"; }
+const char *dk_version(void) { return "decodekit 0.8 (gfx950; gemv r3, gemm r10, attention r7, moe r4, fused r2, prefill r2, sample r1)"; }
 
 // ------------------------------------------------------------------- pool --
 dk_status dk_kv_pool_bytes(const dk_model_config *cfg, int32_t num_blocks, int32_t block_size,

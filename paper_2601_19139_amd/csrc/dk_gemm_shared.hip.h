@@ -76,7 +76,7 @@ __global__ __launch_bounds__(W * 64) void shared_gemm_kernel(GemmArgs a)
     };
     int it_i = 0;
     auto issue = [&](Stage &st) {
-        const int ks = min(ks0 + it_i, ks1 - 1);
+        const int ks = max(min(ks0 + it_i, ks1 - 1), 0);   // (an empty slice - more slices than steps - reads step 0, unused)
 #pragma unroll
         for (int p = 0; p < PPT; p++) {
             const int piece = p * TPB + tid;
@@ -103,7 +103,7 @@ __global__ __launch_bounds__(W * 64) void shared_gemm_kernel(GemmArgs a)
         it_i++;
     };
     auto consume = [&](Stage &st, int it) {
-        if (it >= niter) return;   // a padding step (the same for the whole block)
+        if (it < 0 || it >= niter) return;   // a padding step (the same for the whole block)
         uint4 *slot = sm_act[it & 1];
 #pragma unroll
         for (int p = 0; p < PPT; p++) slot[p * TPB + tid] = st.act[p];
@@ -234,19 +234,41 @@ __global__ __launch_bounds__(W * 64) void shared_gemm_kernel(GemmArgs a)
         __syncthreads();
         if (!sm_last) return;
         if (tid == 0) __hip_atomic_store(&a.ktickets[blockIdx.x], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        // Slices are added in slice order (the result does not depend on who arrived last).  The
+        // device-coherent loads of a slice - one per accumulator element - are independent and
+        // are all issued before the first is used; the next slice is requested before this one
+        // is added, so a round trip is paid per slice, not per element.
+        const float *pbase[NA];
 #pragma unroll
         for (int m = 0; m < NA; m++) {
             const int tile = min(tile0 + (m % RT), n_tiles - 1);
-            const float *pp = a.kpart + ((size_t)(m / RT) * n_tiles + tile) * MT * 256;
+            pbase[m] = a.kpart + ((size_t)(m / RT) * n_tiles + tile) * MT * 256 + lane;
+        }
+        auto fetch = [&](int q, f32x4_t (&v)[NA][MT]) {
+            const size_t off = (size_t)min(q, S - 1) * slice_floats;
 #pragma unroll
-            for (int t = 0; t < MT; t++)
+            for (int m = 0; m < NA; m++)
 #pragma unroll
-                for (int i = 0; i < 4; i++) {
-                    float s = 0.f;
-                    for (int q = 0; q < S; q++)
-                        s += __hip_atomic_load(pp + (size_t)q * slice_floats + (t * 4 + i) * 64 + lane, __ATOMIC_RELAXED,
-                                               __HIP_MEMORY_SCOPE_AGENT);
-                    acc[m][t][i] = s;
+                for (int t = 0; t < MT; t++)
+#pragma unroll
+                    for (int i = 0; i < 4; i++)
+                        v[m][t][i] = __hip_atomic_load(pbase[m] + off + (t * 4 + i) * 64, __ATOMIC_RELAXED,
+                                                       __HIP_MEMORY_SCOPE_AGENT);
+        };
+        f32x4_t cur[NA][MT], nxt[NA][MT];
+        fetch(0, cur);
+#pragma unroll
+        for (int m = 0; m < NA; m++)
+#pragma unroll
+            for (int t = 0; t < MT; t++) acc[m][t] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+        for (int q = 0; q < S; q++) {
+            fetch(q + 1, nxt);       // (past the last slice: the last one again, unused)
+#pragma unroll
+            for (int m = 0; m < NA; m++)
+#pragma unroll
+                for (int t = 0; t < MT; t++) {
+                    acc[m][t] += cur[m][t];
+                    cur[m][t] = nxt[m][t];
                 }
         }
     } else {
