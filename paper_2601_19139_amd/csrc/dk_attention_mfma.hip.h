@@ -27,6 +27,131 @@
 
 namespace dk {
 
+// One iteration of the matrix-core inner loop, shared by the decode kernel below and the
+// chunked-prefill kernel (dk_attention_prefill.hip.h): a wave's pair of 16-token block tiles
+// starting at block blk0, already in registers (kw: K tiles as the A operand, vw: V tiles row
+// major), against the 16 query columns in qh / ql.  Column ln attends to positions < t1_col;
+// V rows of positions >= t1_stage (>= every column's limit) are zeroed while staged, since
+// they may hold anything.  Running maximum, sum and output of the wave are updated in place.
+template <int D>
+struct MfmaAttnRun {
+    float m_run, l_run;          // column ln, over this lane group's tokens
+    f32x4_t o[D / 16];           // O[column 4*lg + i][dim 16*nt + ln]
+    __device__ __forceinline__ void init()
+    {
+        m_run = -1e30f;
+        l_run = 0.f;
+#pragma unroll
+        for (int nt = 0; nt < D / 16; nt++) o[nt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    }
+};
+
+template <int D, int VROW>
+__device__ __forceinline__ void mfma_attend_tile_pair(const uint4 (&kw)[2][D / 32], const uint4 (&vw)[2][16 / (512 / D)],
+                                                      const uint4 (&qh)[D / 32], const uint4 (&ql)[D / 32],
+                                                      uint16_t (*sm_vw)[16][VROW], int blk0, int t1_stage,
+                                                      int t1_col, int lane, MfmaAttnRun<D> &r)
+{
+    constexpr int BS = 16, TPR = D / 8, TPW = 64 / TPR, NI = BS / TPW, NS = D / 32, NT = D / 16;
+    const int dl = (lane % TPR) * 8, sub = lane / TPR;
+    const int ln = lane & 15, lg = lane >> 4;
+    // scores
+    f32x4_t sc[2];
+#pragma unroll
+    for (int u = 0; u < 2; u++) {
+        sc[u] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int s = 0; s < NS; s++) {
+            sc[u] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(kw[u][s]), as_bf16x8(qh[s]), sc[u], 0, 0, 0);
+            sc[u] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(kw[u][s]), as_bf16x8(ql[s]), sc[u], 0, 0, 0);
+        }
+    }
+    // stage V while the scores are computed
+#pragma unroll
+    for (int u = 0; u < 2; u++)
+#pragma unroll
+        for (int i = 0; i < NI; i++) {
+            const int row = i * TPW + sub;
+            const bool ok = (blk0 + u) * BS + row < t1_stage;
+            const uint4 w = ok ? vw[u][i] : make_uint4(0, 0, 0, 0);
+            uint2 *dst = reinterpret_cast<uint2 *>(&sm_vw[u][row][dl]);
+            dst[0] = make_uint2(w.x, w.y);
+            dst[1] = make_uint2(w.z, w.w);
+        }
+    // online softmax of column ln over the 8 tokens of this lane
+    float p[2][4];
+    float mx = r.m_run;
+#pragma unroll
+    for (int u = 0; u < 2; u++)
+#pragma unroll
+        for (int i = 0; i < 4; i++) {
+            const bool ok = (blk0 + u) * BS + 4 * lg + i < t1_col;
+            p[u][i] = ok ? sc[u][i] : -1e30f;
+            mx = fmaxf(mx, p[u][i]);
+        }
+    mx = fmaxf(mx, __shfl_xor(mx, 16));
+    mx = fmaxf(mx, __shfl_xor(mx, 32));      // the column's max over all 32 tokens and the past
+    const float alpha = __expf(r.m_run - mx);
+    r.m_run = mx;
+    float psum = 0.f;
+#pragma unroll
+    for (int u = 0; u < 2; u++)
+#pragma unroll
+        for (int i = 0; i < 4; i++) {
+            const bool ok = (blk0 + u) * BS + 4 * lg + i < t1_col;
+            p[u][i] = ok ? __expf(p[u][i] - mx) : 0.f;
+            psum += p[u][i];
+        }
+    r.l_run = r.l_run * alpha + psum;
+    // P as the A operand (bf16 hi / lo): k-slot e <-> (tile e/4, token 4*lg + e%4)
+    uint4 ph, pl;
+    {
+        uint32_t hw[4], lw[4];
+#pragma unroll
+        for (int e = 0; e < 4; e++) {
+            uint16_t h0, l0, h1, l1;
+            split_bf16(p[e / 2][(2 * e) % 4], h0, l0);
+            split_bf16(p[e / 2][(2 * e) % 4 + 1], h1, l1);
+            hw[e] = (uint32_t)h0 | ((uint32_t)h1 << 16);
+            lw[e] = (uint32_t)l0 | ((uint32_t)l1 << 16);
+        }
+        ph = make_uint4(hw[0], hw[1], hw[2], hw[3]);
+        pl = make_uint4(lw[0], lw[1], lw[2], lw[3]);
+    }
+    // rescale the running output: row i of this lane is column 4*lg + i, whose alpha lives in
+    // the lanes of that column.  Once the running maxima have settled every alpha is exactly 1
+    // and the pass is skipped.
+    if (__any(alpha != 1.f)) {
+        float al[4];
+#pragma unroll
+        for (int i = 0; i < 4; i++) al[i] = __shfl(alpha, 4 * lg + i);
+#pragma unroll
+        for (int nt = 0; nt < NT; nt++)
+#pragma unroll
+            for (int i = 0; i < 4; i++) r.o[nt][i] *= al[i];
+    }
+    // O += P V : the B operand is V with tokens along k.  The LDS transpose read hands lane
+    // (column ln, lane group lg) the four tokens 4*lg..4*lg+3 of column nt*16 + ln when lane i
+    // of the group points at the 4 consecutive dims nt*16 + 4*(i%4) of token 4*lg + i/4 (layout
+    // checked on the device: lane 4g+c, element e <- address of lane 4e+g, element c).
+#pragma unroll
+    for (int nt = 0; nt < NT; nt++) {
+        uint32_t vwd[4];
+#pragma unroll
+        for (int u = 0; u < 2; u++) {
+            typedef short v4s __attribute__((ext_vector_type(4)));
+            const uint16_t *src = &sm_vw[u][4 * lg + (ln >> 2)][nt * 16 + 4 * (ln & 3)];
+            const v4s rr = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                (__attribute__((address_space(3))) v4s *)(src));
+            vwd[2 * u] = (uint32_t)(uint16_t)rr[0] | ((uint32_t)(uint16_t)rr[1] << 16);
+            vwd[2 * u + 1] = (uint32_t)(uint16_t)rr[2] | ((uint32_t)(uint16_t)rr[3] << 16);
+        }
+        const uint4 vb = make_uint4(vwd[0], vwd[1], vwd[2], vwd[3]);
+        r.o[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(ph), as_bf16x8(vb), r.o[nt], 0, 0, 0);
+        r.o[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(pl), as_bf16x8(vb), r.o[nt], 0, 0, 0);
+    }
+}
+
 template <int D, int G>
 __global__ __launch_bounds__(256, 2) void attention_mfma_kernel(AttnArgs a)
 {
@@ -228,110 +353,12 @@ __global__ __launch_bounds__(256, 2) void attention_mfma_kernel(AttnArgs a)
     }
 
     // ---- main loop: a pair of block tiles (32 tokens) per iteration -----------
-    float m_run = -1e30f, l_run = 0.f;     // column ln, over this lane group's tokens
-    f32x4_t o[NT];                          // O[head 4*lg + i][dim 16*nt + ln]
-#pragma unroll
-    for (int nt = 0; nt < NT; nt++) o[nt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-
+    MfmaAttnRun<D> run;
+    run.init();
     for (int blk0 = blk_first; blk0 < blk_end; blk0 += 2 * NWV) {
         const int blk_next = blk0 + 2 * NWV;
         request(blk_next < blk_end ? blk_next : blk0, kw_n, vw_n);
-        // scores
-        f32x4_t sc[2];
-#pragma unroll
-        for (int u = 0; u < 2; u++) {
-            sc[u] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int s = 0; s < NS; s++) {
-                sc[u] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(kw[u][s]), as_bf16x8(qh[s]), sc[u], 0, 0, 0);
-                sc[u] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(kw[u][s]), as_bf16x8(ql[s]), sc[u], 0, 0, 0);
-            }
-        }
-        // stage V (rows of positions >= t1 zeroed) while the scores are computed
-#pragma unroll
-        for (int u = 0; u < 2; u++)
-#pragma unroll
-            for (int i = 0; i < NI; i++) {
-                const int r = i * TPW + sub;
-                const bool ok = (blk0 + u) * BS + r < t1;
-                const uint4 w = ok ? vw[u][i] : make_uint4(0, 0, 0, 0);
-                uint2 *dst = reinterpret_cast<uint2 *>(&sm_v[wv][u][r][dl]);
-                dst[0] = make_uint2(w.x, w.y);
-                dst[1] = make_uint2(w.z, w.w);
-            }
-        // online softmax of column ln over the 8 tokens of this lane
-        float p[2][4];
-        float mx = m_run;
-#pragma unroll
-        for (int u = 0; u < 2; u++)
-#pragma unroll
-            for (int i = 0; i < 4; i++) {
-                const bool ok = (blk0 + u) * BS + 4 * lg + i < t1;
-                p[u][i] = ok ? sc[u][i] : -1e30f;
-                mx = fmaxf(mx, p[u][i]);
-            }
-        mx = fmaxf(mx, __shfl_xor(mx, 16));
-        mx = fmaxf(mx, __shfl_xor(mx, 32));      // the column's max over all 32 tokens and the past
-        const float alpha = __expf(m_run - mx);
-        m_run = mx;
-        float psum = 0.f;
-#pragma unroll
-        for (int u = 0; u < 2; u++)
-#pragma unroll
-            for (int i = 0; i < 4; i++) {
-                const bool ok = (blk0 + u) * BS + 4 * lg + i < t1;
-                p[u][i] = ok ? __expf(p[u][i] - mx) : 0.f;
-                psum += p[u][i];
-            }
-        l_run = l_run * alpha + psum;
-        // P as the A operand (bf16 hi / lo): k-slot e <-> (tile e/4, token 4*lg + e%4)
-        uint4 ph, pl;
-        {
-            uint32_t hw[4], lw[4];
-#pragma unroll
-            for (int e = 0; e < 4; e++) {
-                uint16_t h0, l0, h1, l1;
-                split_bf16(p[e / 2][(2 * e) % 4], h0, l0);
-                split_bf16(p[e / 2][(2 * e) % 4 + 1], h1, l1);
-                hw[e] = (uint32_t)h0 | ((uint32_t)h1 << 16);
-                lw[e] = (uint32_t)l0 | ((uint32_t)l1 << 16);
-            }
-            ph = make_uint4(hw[0], hw[1], hw[2], hw[3]);
-            pl = make_uint4(lw[0], lw[1], lw[2], lw[3]);
-        }
-        // rescale the running output: row i of this lane is head 4*lg + i, whose
-        // alpha lives in the lanes of column 4*lg + i.  Once the running maxima
-        // have settled every alpha is exactly 1 and the pass is skipped.
-        if (__any(alpha != 1.f)) {
-            float al[4];
-#pragma unroll
-            for (int i = 0; i < 4; i++) al[i] = __shfl(alpha, 4 * lg + i);
-#pragma unroll
-            for (int nt = 0; nt < NT; nt++)
-#pragma unroll
-                for (int i = 0; i < 4; i++) o[nt][i] *= al[i];
-        }
-        // O += P V : the B operand is V with tokens along k.  The LDS transpose read
-        // hands lane (column ln, lane group lg) the four tokens 4*lg..4*lg+3 of
-        // column nt*16 + ln when lane i of the group points at the 4 consecutive
-        // dims nt*16 + 4*(i%4) of token 4*lg + i/4 (layout checked on the device:
-        // lane 4g+c, element e <- address of lane 4e+g, element c).
-#pragma unroll
-        for (int nt = 0; nt < NT; nt++) {
-            uint32_t vwd[4];
-#pragma unroll
-            for (int u = 0; u < 2; u++) {
-                typedef short v4s __attribute__((ext_vector_type(4)));
-                const uint16_t *src = &sm_v[wv][u][4 * lg + (ln >> 2)][nt * 16 + 4 * (ln & 3)];
-                const v4s r = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                    (__attribute__((address_space(3))) v4s *)(src));
-                vwd[2 * u] = (uint32_t)(uint16_t)r[0] | ((uint32_t)(uint16_t)r[1] << 16);
-                vwd[2 * u + 1] = (uint32_t)(uint16_t)r[2] | ((uint32_t)(uint16_t)r[3] << 16);
-            }
-            const uint4 vb = make_uint4(vwd[0], vwd[1], vwd[2], vwd[3]);
-            o[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(ph), as_bf16x8(vb), o[nt], 0, 0, 0);
-            o[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(pl), as_bf16x8(vb), o[nt], 0, 0, 0);
-        }
+        mfma_attend_tile_pair<D, VROW>(kw, vw, qh, ql, sm_v[wv], blk0, t1, t1, lane, run);
 #pragma unroll
         for (int u = 0; u < 2; u++) {
 #pragma unroll
@@ -340,6 +367,9 @@ __global__ __launch_bounds__(256, 2) void attention_mfma_kernel(AttnArgs a)
             for (int i = 0; i < NI; i++) vw[u][i] = vw_n[u][i];
         }
     }
+    float l_run = run.l_run;
+    const float m_run = run.m_run;
+    const f32x4_t (&o)[NT] = run.o;
 
     // ---- per-wave state to LDS -------------------------------------------------
     // the column sum is spread over the four lane groups

@@ -10,10 +10,9 @@
 // Every row's own k and v are already in the pool (prefill_append_kernel runs
 // first), so there is no "new token" special case: column col attends to the
 // positions 0..T(col) of the pool, and the causal mask inside the group is the
-// per-column limit.  Apart from that limit the main loop is the one of
-// attention_mfma_kernel (scores = K q with q as bf16 hi + lo, online softmax per
-// column, output = P V with V staged in LDS and fetched with the LDS transpose
-// read).  A tile past a column's limit contributes exactly nothing to it, and an
+// per-column limit.  The inner loop is the decode kernel's (mfma_attend_tile_pair:
+// scores = K q with q as bf16 hi + lo, online softmax per column, output = P V
+// with V staged in LDS and fetched with the LDS transpose read), given that limit.  A tile past a column's limit contributes exactly nothing to it, and an
 // empty chunk partial merges as exactly nothing, so a row's result depends on
 // the chunk length only, not on which rows share its group.
 //
@@ -24,8 +23,7 @@
 // all groups), and a short context, with one active chunk, still spreads over
 // all dies.
 #pragma once
-#include "dk_attention.hip.h"
-#include "dk_gemm.hip.h"
+#include "dk_attention_mfma.hip.h"
 
 namespace dk {
 
@@ -156,105 +154,12 @@ __global__ __launch_bounds__(256, 2) void prefill_attention_kernel(AttnArgs a)
     }
 
     // ---- main loop: a pair of block tiles (32 tokens) per iteration -----------
-    float m_run = -1e30f, l_run = 0.f;     // column ln, over this lane group's tokens
-    f32x4_t o[NT];                          // O[column 4*lg + i][dim 16*nt + ln]
-#pragma unroll
-    for (int nt = 0; nt < NT; nt++) o[nt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-
+    MfmaAttnRun<D> run;
+    run.init();
     for (int blk0 = blk_first; blk0 < blk_end; blk0 += 2 * NWV) {
         const int blk_next = blk0 + 2 * NWV;
         request(blk_next < blk_end ? blk_next : blk0, kw_n, vw_n);
-        f32x4_t sc[2];
-#pragma unroll
-        for (int u = 0; u < 2; u++) {
-            sc[u] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int s = 0; s < NS; s++) {
-                sc[u] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(kw[u][s]), as_bf16x8(qh[s]), sc[u], 0, 0, 0);
-                sc[u] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(kw[u][s]), as_bf16x8(ql[s]), sc[u], 0, 0, 0);
-            }
-        }
-        // stage V (rows of positions no column attends to are zeroed: they may hold anything)
-#pragma unroll
-        for (int u = 0; u < 2; u++)
-#pragma unroll
-            for (int i = 0; i < NI; i++) {
-                const int r = i * TPW + sub;
-                const bool ok = (blk0 + u) * BS + r < t1;
-                const uint4 w = ok ? vw[u][i] : make_uint4(0, 0, 0, 0);
-                uint2 *dst = reinterpret_cast<uint2 *>(&sm_v[wv][u][r][dl]);
-                dst[0] = make_uint2(w.x, w.y);
-                dst[1] = make_uint2(w.z, w.w);
-            }
-        // online softmax of column ln over the 8 tokens of this lane
-        float p[2][4];
-        float mx = m_run;
-#pragma unroll
-        for (int u = 0; u < 2; u++)
-#pragma unroll
-            for (int i = 0; i < 4; i++) {
-                const bool ok = (blk0 + u) * BS + 4 * lg + i < t1c;
-                p[u][i] = ok ? sc[u][i] : -1e30f;
-                mx = fmaxf(mx, p[u][i]);
-            }
-        mx = fmaxf(mx, __shfl_xor(mx, 16));
-        mx = fmaxf(mx, __shfl_xor(mx, 32));
-        const float alpha = __expf(m_run - mx);
-        m_run = mx;
-        float psum = 0.f;
-#pragma unroll
-        for (int u = 0; u < 2; u++)
-#pragma unroll
-            for (int i = 0; i < 4; i++) {
-                const bool ok = (blk0 + u) * BS + 4 * lg + i < t1c;
-                p[u][i] = ok ? __expf(p[u][i] - mx) : 0.f;
-                psum += p[u][i];
-            }
-        l_run = l_run * alpha + psum;
-        // P as the A operand (bf16 hi / lo): k-slot e <-> (tile e/4, token 4*lg + e%4)
-        uint4 ph, pl;
-        {
-            uint32_t hw[4], lw[4];
-#pragma unroll
-            for (int e = 0; e < 4; e++) {
-                uint16_t h0, l0, h1, l1;
-                split_bf16(p[e / 2][(2 * e) % 4], h0, l0);
-                split_bf16(p[e / 2][(2 * e) % 4 + 1], h1, l1);
-                hw[e] = (uint32_t)h0 | ((uint32_t)h1 << 16);
-                lw[e] = (uint32_t)l0 | ((uint32_t)l1 << 16);
-            }
-            ph = make_uint4(hw[0], hw[1], hw[2], hw[3]);
-            pl = make_uint4(lw[0], lw[1], lw[2], lw[3]);
-        }
-        // rescale the running output: row i of this lane is column 4*lg + i, whose alpha
-        // lives in the lanes of that column (exactly 1 once the maxima have settled)
-        if (__any(alpha != 1.f)) {
-            float al[4];
-#pragma unroll
-            for (int i = 0; i < 4; i++) al[i] = __shfl(alpha, 4 * lg + i);
-#pragma unroll
-            for (int nt = 0; nt < NT; nt++)
-#pragma unroll
-                for (int i = 0; i < 4; i++) o[nt][i] *= al[i];
-        }
-        // O += P V, V through the LDS transpose read (lane 4g+c, element e <- address of
-        // lane 4e+g, element c)
-#pragma unroll
-        for (int nt = 0; nt < NT; nt++) {
-            uint32_t vwd[4];
-#pragma unroll
-            for (int u = 0; u < 2; u++) {
-                typedef short v4s __attribute__((ext_vector_type(4)));
-                const uint16_t *src = &sm_v[wv][u][4 * lg + (ln >> 2)][nt * 16 + 4 * (ln & 3)];
-                const v4s r = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                    (__attribute__((address_space(3))) v4s *)(src));
-                vwd[2 * u] = (uint32_t)(uint16_t)r[0] | ((uint32_t)(uint16_t)r[1] << 16);
-                vwd[2 * u + 1] = (uint32_t)(uint16_t)r[2] | ((uint32_t)(uint16_t)r[3] << 16);
-            }
-            const uint4 vb = make_uint4(vwd[0], vwd[1], vwd[2], vwd[3]);
-            o[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(ph), as_bf16x8(vb), o[nt], 0, 0, 0);
-            o[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(pl), as_bf16x8(vb), o[nt], 0, 0, 0);
-        }
+        mfma_attend_tile_pair<D, VROW>(kw, vw, qh, ql, sm_v[wv], blk0, t1, t1c, lane, run);
 #pragma unroll
         for (int u = 0; u < 2; u++) {
 #pragma unroll
@@ -263,6 +168,9 @@ __global__ __launch_bounds__(256, 2) void prefill_attention_kernel(AttnArgs a)
             for (int i = 0; i < NI; i++) vw[u][i] = vw_n[u][i];
         }
     }
+    float l_run = run.l_run;
+    const float m_run = run.m_run;
+    const f32x4_t (&o)[NT] = run.o;
 
     // ---- per-wave state to LDS (over the V tiles: every wave is done with them) ----
     l_run += __shfl_xor(l_run, 16);
