@@ -221,16 +221,26 @@ GemmPlan gemm_plan(int epi, int N, int K, int Bp, bool q4)
         }
         return {0, 1};
     }
+    // K slices of a bf16 layer matrix handled by blocks of w waves: as many as still give one round of
+    // blocks on the 256 compute units (a second, partly filled round costs more than the slices save;
+    // 3B down projection at 16 rows: 4 slices / 192 blocks 16.4 us, 5 / 240 14.5, 6 / 288 19.9), at
+    // least four K-steps per slice; matrices with many row blocks take four slices.
+    auto slices = [&](int w) {
+        const int row_blocks = ((N + 15) / 16 + w - 1) / w;
+        if (row_blocks > 128) return 4;
+        int s = std::min(std::min(256 / row_blocks, 8), K / 512);
+        return std::max(s, 1);
+    };
     if (epi == dk::GEPI_STORE) {
         // lm_head: one slice (thousands of row blocks).  At 16 rows only while K is short (measured:
         // 106 -> 67 us at K = 1024, 181 -> 150 us at K = 3072, 250 -> 276 us at K = 4096)
         if ((N + 15) / 16 >= 4096) return (mt >= 2 || K <= 3072) ? GemmPlan{8, 1} : GemmPlan{0, 1};
-        if (elems >= (mt >= 2 ? (8ll << 20) : (20ll << 20))) return {8, 4};   // q | k | v
+        if (elems >= (mt >= 2 ? (8ll << 20) : (20ll << 20))) return {8, slices(8)};   // q | k | v
     } else if (epi == dk::GEPI_SWIGLU) {
-        if (elems >= (20ll << 20)) return (mt == 1 && elems >= (40ll << 20)) ? GemmPlan{4, 4} : GemmPlan{8, 4};
+        if (elems >= (20ll << 20)) return (mt == 1 && elems >= (40ll << 20)) ? GemmPlan{4, slices(4)} : GemmPlan{8, slices(8)};
     } else {
-        if (elems >= (8ll << 20)) return {4, 4};                              // output projection, down
-        if (mt >= 2 && K >= 3072 && elems >= (3ll << 20)) return {4, 4};      // down of a small model
+        if (elems >= (8ll << 20)) return {4, slices(4)};                              // output projection, down
+        if (mt >= 2 && K >= 3072 && elems >= (3ll << 20)) return {4, slices(4)};      // down of a small model
     }
     return {0, 1};
 }
