@@ -108,13 +108,7 @@ __device__ __forceinline__ void mfma_attend_tile_pair(const uint4 (&kw)[2][D / 3
     {
         uint32_t hw[4], lw[4];
 #pragma unroll
-        for (int e = 0; e < 4; e++) {
-            uint16_t h0, l0, h1, l1;
-            split_bf16(p[e / 2][(2 * e) % 4], h0, l0);
-            split_bf16(p[e / 2][(2 * e) % 4 + 1], h1, l1);
-            hw[e] = (uint32_t)h0 | ((uint32_t)h1 << 16);
-            lw[e] = (uint32_t)l0 | ((uint32_t)l1 << 16);
-        }
+        for (int e = 0; e < 4; e++) split_bf16x2(p[e / 2][(2 * e) % 4], p[e / 2][(2 * e) % 4 + 1], hw[e], lw[e]);
         ph = make_uint4(hw[0], hw[1], hw[2], hw[3]);
         pl = make_uint4(lw[0], lw[1], lw[2], lw[3]);
     }
@@ -143,8 +137,7 @@ __device__ __forceinline__ void mfma_attend_tile_pair(const uint4 (&kw)[2][D / 3
             const uint16_t *src = &sm_vw[u][4 * lg + (ln >> 2)][nt * 16 + 4 * (ln & 3)];
             const v4s rr = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
                 (__attribute__((address_space(3))) v4s *)(src));
-            vwd[2 * u] = (uint32_t)(uint16_t)rr[0] | ((uint32_t)(uint16_t)rr[1] << 16);
-            vwd[2 * u + 1] = (uint32_t)(uint16_t)rr[2] | ((uint32_t)(uint16_t)rr[3] << 16);
+            __builtin_memcpy(&vwd[2 * u], &rr, 8);   // elements 0, 1 | 2, 3 as two words
         }
         const uint4 vb = make_uint4(vwd[0], vwd[1], vwd[2], vwd[3]);
         r.o[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(ph), as_bf16x8(vb), r.o[nt], 0, 0, 0);

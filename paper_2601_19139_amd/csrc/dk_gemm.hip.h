@@ -77,6 +77,13 @@ __device__ __forceinline__ void split_bf16(float x, uint16_t &hi, uint16_t &lo)
     lo = f32_to_bf16_rne(x - bf16_to_f32(hi));
 }
 
+// the same for two values: a in the low half-words of hi / lo, b in the high ones
+__device__ __forceinline__ void split_bf16x2(float a, float b, uint32_t &hi, uint32_t &lo)
+{
+    hi = f32x2_to_bf16x2_rne(a, b);
+    lo = f32x2_to_bf16x2_rne(a - bf16lo(hi), b - bf16hi(hi));
+}
+
 __device__ __forceinline__ bf16x8_t as_bf16x8(const uint4 &u)
 {
     union { uint4 u; bf16x8_t v; } c;
