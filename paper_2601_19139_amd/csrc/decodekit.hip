@@ -305,7 +305,7 @@ Workspace carve(const dk_model_config &c, int B, int max_blocks, bool q4)
     {   // rows of a prefill chunk in groups of 16 / G: fewer, larger work items, so a finer split
         const int rpb = std::max(1, 16 / G);
         const int groups = (B + rpb - 1) / rpb;
-        int want = (512 + groups * c.n_kv_heads - 1) / (groups * c.n_kv_heads);
+        int want = std::max(1, 768 / (groups * c.n_kv_heads));   // three blocks per compute unit, one round
         int pchunk = ((ctx_max + want - 1) / want + 63) / 64 * 64;
         if (pchunk < 256) pchunk = 256;
         w.pf_chunk_tokens = pchunk;

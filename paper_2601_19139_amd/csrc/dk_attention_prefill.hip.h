@@ -16,6 +16,12 @@
 // empty chunk partial merges as exactly nothing, so a row's result depends on
 // the chunk length only, not on which rows share its group.
 //
+// K/V come from the L2 here (every tile is read by all row groups), and the kernel
+// is bound by its instructions, not by the stream: a wave requests its tile pair
+// and uses it in the same iteration, three blocks per compute unit cover the
+// latency (holding the next pair in registers as the decode kernel does costs the
+// third block: measured slower from 2 k tokens of context on).
+//
 // grid = (kv heads, chunks, row groups); chunk partials of a (group, kv head)
 // are merged, in chunk order, by the block that takes its last ticket.  The kv
 // head is the fastest block index: consecutive blocks go to consecutive compute
@@ -28,7 +34,7 @@
 namespace dk {
 
 template <int D, int G>
-__global__ __launch_bounds__(256, 2) void prefill_attention_kernel(AttnArgs a)
+__global__ __launch_bounds__(256, 3) void prefill_attention_kernel(AttnArgs a)
 {
     constexpr int BS = 16;            // tokens per block tile
     constexpr int TPR = D / 8;        // lanes per head vector in the row-major prologue
@@ -92,8 +98,7 @@ __global__ __launch_bounds__(256, 2) void prefill_attention_kernel(AttnArgs a)
             for (int i = 0; i < NI; i++) vw[u][i] = ld16(vt + i * 512 + lane * 8);
         }
     };
-    uint4 kw[2][NS], vw[2][NI], kw_n[2][NS], vw_n[2][NI];
-    request(blk_first, kw, vw);
+    uint4 kw[2][NS], vw[2][NI];
 
     // ---- prologue: head norm, rotation and scale of q, one column per lane group --
     {
@@ -157,16 +162,8 @@ __global__ __launch_bounds__(256, 2) void prefill_attention_kernel(AttnArgs a)
     MfmaAttnRun<D> run;
     run.init();
     for (int blk0 = blk_first; blk0 < blk_end; blk0 += 2 * NWV) {
-        const int blk_next = blk0 + 2 * NWV;
-        request(blk_next < blk_end ? blk_next : blk0, kw_n, vw_n);
+        request(blk0, kw, vw);
         mfma_attend_tile_pair<D, VROW>(kw, vw, qh, ql, sm_v[wv], blk0, t1, t1c, lane, run);
-#pragma unroll
-        for (int u = 0; u < 2; u++) {
-#pragma unroll
-            for (int s = 0; s < NS; s++) kw[u][s] = kw_n[u][s];
-#pragma unroll
-            for (int i = 0; i < NI; i++) vw[u][i] = vw_n[u][i];
-        }
     }
     float l_run = run.l_run;
     const float m_run = run.m_run;
