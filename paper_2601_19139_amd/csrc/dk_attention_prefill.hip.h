@@ -48,16 +48,17 @@ __global__ __launch_bounds__(256, 3) void prefill_attention_kernel(AttnArgs a)
     constexpr int NCOL = RPB * G;     // MFMA columns in use
     static_assert(G >= 1 && G <= 8, "a group holds at least two rows");
     constexpr int V_BYTES = NWV * 2 * BS * VROW * 2;
-    constexpr int O_BYTES = NWV * 16 * D * 4;
+    constexpr int QROW = D + 4;       // LDS row stride of q and of the waves' outputs, in floats: rows 4 banks apart
+    constexpr int O_BYTES = NWV * 16 * QROW * 4;
     constexpr int RAW_BYTES = V_BYTES > O_BYTES ? V_BYTES : O_BYTES;
 
-    __shared__ __attribute__((aligned(16))) float sm_q[16][D];   // prepared q of every column (unused: 0)
+    __shared__ __attribute__((aligned(16))) float sm_q[16][QROW];   // prepared q of every column (unused: 0)
     // the staged V tiles during the main loop, the waves' outputs after it
     __shared__ __attribute__((aligned(16))) unsigned char sm_raw[RAW_BYTES];
     __shared__ float sm_ml[NWV][16][2];
     __shared__ int sm_ticket;
     typedef uint16_t (*VTiles)[2][BS][VROW];
-    typedef float (*OTiles)[16][D];
+    typedef float (*OTiles)[16][QROW];
     VTiles sm_v = reinterpret_cast<VTiles>(sm_raw);
     OTiles sm_o = reinterpret_cast<OTiles>(sm_raw);
 
