@@ -306,13 +306,15 @@ def test_batch16_full_size_sampled_rows(dk, orc, wname, rows, steps):
     check_pool_sampled(out, pool, shape, lay, steps, rows)
 
 
-@pytest.mark.parametrize("batch", [20, 40, 64])
+@pytest.mark.parametrize("batch", [16, 20, 40, 64])
 def test_wide_batches_of_a_large_layer(dk, orc, batch):
-    """From 17 rows on the lm_head, and from 33 rows on every large layer matrix, runs in the
-    GEMM whose waves share one activation tile in LDS (with K cut across blocks and a last-arriver
-    sum for the down projection).  One layer with matrices large enough to take each of those
-    paths (q/k/v 6144 x 2048, gate/up 20480 x 2048, down 2048 x 20480, vocabulary 70003), two
-    steps so that the tickets are used twice; sampled rows against the oracle."""
+    """Large layer matrices run, from 16 rows on, in the GEMM whose waves share one activation
+    tile in LDS, with K cut across blocks and the last block to arrive adding the slices in slice
+    order (the lm_head joins from 17 rows on, with one slice).  One layer with matrices large enough
+    to take each of those paths (q/k/v 6144 x 2048, gate/up 20480 x 2048, down 2048 x 20480,
+    vocabulary 70003), two steps so that the tickets are used twice; sampled rows against the
+    oracle.  Which block arrives last varies from run to run, the sums must not: a second run from
+    the same state gives the same bits."""
     shape = variant("tiny", n_layers=1, hidden=2048, n_q_heads=32, n_kv_heads=8, head_dim=128, ffn=20480,
                     vocab=70003, qk_norm=True, rope_theta=1e6)
     contexts = [(37 * i) % 150 for i in range(batch)]
@@ -326,6 +328,10 @@ def test_wide_batches_of_a_large_layer(dk, orc, batch):
     print(f"batch {batch}: worst rel-L2 {worst:.3e}, greedy agreement {agree:.3f}")
     assert worst < TIGHT and agree == 1.0
     check_pool_sampled(out, pool, shape, lay, 2, rows)
+    again = run_sampled(orc, shape, weights, lay, pool, tokens, 2, rows)
+    for a, b in zip(out["gpu_logits"], again["gpu_logits"]):
+        assert np.array_equal(a, b)
+    assert np.array_equal(out["gpu_pool"], again["gpu_pool"])
 
 
 MOE_CASES = [
