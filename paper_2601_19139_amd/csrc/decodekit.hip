@@ -442,9 +442,16 @@ dk_status launch_gemm_inst(const dk::GemmArgs &a, hipStream_t st)
     constexpr size_t lds = dk::skinny_gemm_lds_bytes<MT, KS, RT, EPI>();
     static_assert(lds <= (64u << 10), "dynamic LDS above 64 KB would need a function attribute");
     const int grid = (a.N + 16 * RT - 1) / (16 * RT);
-    constexpr int PD = 2;   // K-steps in flight per wave (deeper did not measure faster)
-    DK_LAUNCH(DK_K_GEMM, (dk::skinny_gemm_kernel<MT, KS, RT, PD, EPI, NORM, KALIGNED, Q4>), dim3(grid),
-              dim3(KS * 64), lds, st, a);
+    // K-steps in flight per wave: two (deeper did not measure faster); one where a wave has a single
+    // step anyway (K <= 128 * KS: the second stage would only fetch a step it never uses - q/k/v of
+    // the 0.6B shape at 16 rows 6.3 -> 5.4 us, gate/up 8.1 -> 6.8 us)
+    if ((a.K + 127) / 128 <= KS) {
+        DK_LAUNCH(DK_K_GEMM, (dk::skinny_gemm_kernel<MT, KS, RT, 1, EPI, NORM, KALIGNED, Q4>), dim3(grid),
+                  dim3(KS * 64), lds, st, a);
+    } else {
+        DK_LAUNCH(DK_K_GEMM, (dk::skinny_gemm_kernel<MT, KS, RT, 2, EPI, NORM, KALIGNED, Q4>), dim3(grid),
+                  dim3(KS * 64), lds, st, a);
+    }
     DK_HIP(hipGetLastError());
     return DK_OK;
 }
