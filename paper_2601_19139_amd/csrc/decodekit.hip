@@ -240,7 +240,9 @@ GemmPlan gemm_plan(int epi, int N, int K, int Bp, bool q4)
     } else if (epi == dk::GEPI_SWIGLU) {
         if (elems >= (20ll << 20)) return (mt == 1 && elems >= (40ll << 20)) ? GemmPlan{4, slices(4)} : GemmPlan{8, slices(8)};
     } else {
-        if (elems >= (8ll << 20)) return {4, slices(4)};                              // output projection, down
+        // output projection, down.  At 16 rows only the down projections: the square-ish output
+        // projections are as fast or faster with two-wave blocks of the other kernel (3B: 8.8 vs 9.6 us)
+        if (elems >= (mt >= 2 ? (8ll << 20) : (20ll << 20))) return {4, slices(4)};
         if (mt >= 2 && K >= 3072 && elems >= (3ll << 20)) return {4, slices(4)};      // down of a small model
     }
     return {0, 1};
@@ -543,9 +545,9 @@ dk_status launch_gemm(const dk::GemmArgs &a, int Bp, hipStream_t st)
             if constexpr (NM == 1) {
                 if (tiles >= 4096) return launch_gemm_cfg<1, 8, 4, EPI, NORM>(a, st);
                 if (tiles >= 320) return launch_gemm_cfg<1, 8, 2, EPI, NORM>(a, st);
-                // few row tiles (a quarter of the compute units or less): two waves per block,
+                // residual projections with at most one block per compute unit: two waves per block,
                 // less to add up across waves (0.6B shape: O 5.9 -> 5.1 us, down 8.8 -> 8.2 us)
-                if (tiles <= 64 && !a.q4) return launch_gemm_cfg<1, 2, 1, EPI, NORM>(a, st);
+                if (tiles <= 256 && EPI == dk::GEPI_RESID && !a.q4) return launch_gemm_cfg<1, 2, 1, EPI, NORM>(a, st);
             }
             return launch_gemm_cfg<1, 8, 1, EPI, NORM>(a, st);
         case 2:
