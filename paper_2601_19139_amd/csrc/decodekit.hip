@@ -162,6 +162,7 @@ struct Workspace {
     int chunk_tokens, max_chunks, lm_blocks;
     int pf_chunk_tokens, pf_max_chunks;   // the same split for the kernel that takes a prefill chunk's rows in groups
     bool defer_merge;   // small problems: the output projection merges the attention chunks
+    bool attn_light;    // matrix-core attention without the register double buffer (short chunks)
 };
 
 constexpr int kMaxGemvBatch = 4;  // up to here the vector-ALU GEMV; above, the matrix-core GEMM
@@ -270,12 +271,23 @@ Workspace carve(const dk_model_config &c, int B, int max_blocks, bool q4)
     // measured on 8B-class shapes: the matrix-core kernel (query groups of 3 and
     // more) runs best with about two blocks per compute unit, the vector-ALU one
     // with about four
-    const int want_blocks = attention_uses_mfma(c, B, q4) ? 512 : 1024;
-    int want_chunks = (want_blocks + B * c.n_kv_heads - 1) / (B * c.n_kv_heads);
-    if (want_chunks < 1) want_chunks = 1;
-    int chunk = (ctx_max + want_chunks - 1) / want_chunks;
-    chunk = (chunk + 63) / 64 * 64;
-    if (chunk < 64) chunk = 64;
+    auto chunk_for = [&](int want_blocks) {
+        int want_chunks = (want_blocks + B * c.n_kv_heads - 1) / (B * c.n_kv_heads);
+        if (want_chunks < 1) want_chunks = 1;
+        int ch = (ctx_max + want_chunks - 1) / want_chunks;
+        ch = (ch + 63) / 64 * 64;
+        return ch < 64 ? 64 : ch;
+    };
+    int chunk = chunk_for(attention_uses_mfma(c, B, q4) ? 512 : 1024);
+    // The matrix-core kernel with short chunks (at most four iterations per wave) and query
+    // groups of up to 4: three lighter blocks per compute unit instead of two that hold the next
+    // tiles in registers (3B shape, ragged contexts up to 2 k: 25.4 -> 22.7 us per launch; with
+    // 4 k contexts or groups of 8 that variant is slower and is not taken)
+    w.attn_light = false;
+    if (attention_uses_mfma(c, B, q4) && G <= 4 && chunk_for(768) <= 512) {
+        chunk = chunk_for(768);
+        w.attn_light = true;
+    }
     w.chunk_tokens = chunk;
     w.max_chunks = (ctx_max + chunk - 1) / chunk;
     w.defer_merge = false;
@@ -561,13 +573,26 @@ dk_status launch_gemm(const dk::GemmArgs &a, int Bp, hipStream_t st)
     }
 }
 
+// light: without the register double buffer (short chunks, query groups of up to 4: the host's choice)
+template <int D, int G>
+void launch_attention_mfma(const dk::AttnArgs &a, dim3 grid, bool light, hipStream_t st)
+{
+    if constexpr (G <= 4) {
+        if (light) {
+            DK_LAUNCH(DK_K_ATTENTION, (dk::attention_mfma_kernel<D, G, false>), grid, dim3(256), 0, st, a);
+            return;
+        }
+    }
+    DK_LAUNCH(DK_K_ATTENTION, (dk::attention_mfma_kernel<D, G, true>), grid, dim3(256), 0, st, a);
+}
+
 // mfma: the matrix-core inner loop (batched path); otherwise the vector-ALU one
 template <int D>
-dk_status launch_attention_d(const dk::AttnArgs &a, int G, dim3 grid, bool mfma, hipStream_t st)
+dk_status launch_attention_d(const dk::AttnArgs &a, int G, dim3 grid, bool mfma, bool light, hipStream_t st)
 {
 #define DK_ATTN_CASE(g)                                                                              \
     case g:                                                                                          \
-        if (mfma) DK_LAUNCH(DK_K_ATTENTION, (dk::attention_mfma_kernel<D, g>), grid, dim3(256), 0, st, a); \
+        if (mfma) launch_attention_mfma<D, g>(a, grid, light, st);                                     \
         else DK_LAUNCH(DK_K_ATTENTION, (dk::attention_kernel<D, g>), grid, dim3(256), 0, st, a);     \
         break;
     switch (G) {
@@ -723,7 +748,7 @@ const char *dk_last_error(void) { return g_err; }
 
 // The kernel revisions change whenever a kernel's memory behaviour changes; the
 // benchmark quotes stored counter measurements only for a matching revision.
-const char *dk_version(void) { return "decodekit 0.8 (gfx950; gemv r3, gemm r10, attention r7, moe r4, fused r2, prefill r2, sample r1)"; }
+const char *dk_version(void) { return "decodekit 0.8 (gfx950; gemv r3, gemm r10, attention r8, moe r4, fused r2, prefill r2, sample r1)"; }
 
 // ------------------------------------------------------------------- pool --
 dk_status dk_kv_pool_bytes(const dk_model_config *cfg, int32_t num_blocks, int32_t block_size,
@@ -1314,8 +1339,8 @@ static dk_status decode_step_impl(dk_model *model, dk_kv_pool *pool, const int32
             } else {
                 const dim3 grid(w.max_chunks, nkv, B);
                 const bool use_mfma = attention_uses_mfma(c, B, model->q4);
-                s = (d == 128) ? launch_attention_d<128>(a, nq / nkv, grid, use_mfma, st)
-                               : launch_attention_d<64>(a, nq / nkv, grid, use_mfma, st);
+                s = (d == 128) ? launch_attention_d<128>(a, nq / nkv, grid, use_mfma, w.attn_light, st)
+                               : launch_attention_d<64>(a, nq / nkv, grid, use_mfma, w.attn_light, st);
             }
             if (s != DK_OK) return s;
         }

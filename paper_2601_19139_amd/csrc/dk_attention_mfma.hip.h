@@ -145,8 +145,8 @@ __device__ __forceinline__ void mfma_attend_tile_pair(const uint4 (&kw)[2][D / 3
     }
 }
 
-template <int D, int G>
-__global__ __launch_bounds__(256, 2) void attention_mfma_kernel(AttnArgs a)
+template <int D, int G, bool PREFETCH>
+__global__ __launch_bounds__(256, PREFETCH ? 2 : 3) void attention_mfma_kernel(AttnArgs a)
 {
     constexpr int BS = 16;            // tokens per block tile
     constexpr int TPR = D / 8;        // lanes per token in the row-major tile loads
@@ -236,7 +236,7 @@ __global__ __launch_bounds__(256, 2) void attention_mfma_kernel(AttnArgs a)
     auto request = [&](int blk0, uint4 (&kw)[2][NS], uint4 (&vw)[2][NI]) {
         request_phys(table[min(blk0, a.max_blocks - 1)], table[min(blk0 + 1, a.max_blocks - 1)], kw, vw);
     };
-    uint4 kw[2][NS], vw[2][NI], kw_n[2][NS], vw_n[2][NI];
+    uint4 kw[2][NS], vw[2][NI];
     request_phys(phys_a, phys_b, kw, vw);
 
     // ---- prologue (row-major head layout, as in attention_kernel) ------------
@@ -348,16 +348,28 @@ __global__ __launch_bounds__(256, 2) void attention_mfma_kernel(AttnArgs a)
     // ---- main loop: a pair of block tiles (32 tokens) per iteration -----------
     MfmaAttnRun<D> run;
     run.init();
-    for (int blk0 = blk_first; blk0 < blk_end; blk0 += 2 * NWV) {
-        const int blk_next = blk0 + 2 * NWV;
-        request(blk_next < blk_end ? blk_next : blk0, kw_n, vw_n);
-        mfma_attend_tile_pair<D, VROW>(kw, vw, qh, ql, sm_v[wv], blk0, t1, t1, lane, run);
+    if constexpr (PREFETCH) {
+        // long chunks: the next tile pair is requested before this one is used (two blocks per
+        // compute unit; the stream is what matters)
+        uint4 kw_n[2][NS], vw_n[2][NI];
+        for (int blk0 = blk_first; blk0 < blk_end; blk0 += 2 * NWV) {
+            const int blk_next = blk0 + 2 * NWV;
+            request(blk_next < blk_end ? blk_next : blk0, kw_n, vw_n);
+            mfma_attend_tile_pair<D, VROW>(kw, vw, qh, ql, sm_v[wv], blk0, t1, t1, lane, run);
 #pragma unroll
-        for (int u = 0; u < 2; u++) {
+            for (int u = 0; u < 2; u++) {
 #pragma unroll
-            for (int s = 0; s < NS; s++) kw[u][s] = kw_n[u][s];
+                for (int s = 0; s < NS; s++) kw[u][s] = kw_n[u][s];
 #pragma unroll
-            for (int i = 0; i < NI; i++) vw[u][i] = vw_n[u][i];
+                for (int i = 0; i < NI; i++) vw[u][i] = vw_n[u][i];
+            }
+        }
+    } else {
+        // short chunks (a few iterations per wave): no second set of tile registers, three
+        // blocks per compute unit cover the latency instead
+        for (int blk0 = blk_first; blk0 < blk_end; blk0 += 2 * NWV) {
+            if (blk0 != blk_first) request(blk0, kw, vw);
+            mfma_attend_tile_pair<D, VROW>(kw, vw, qh, ql, sm_v[wv], blk0, t1, t1, lane, run);
         }
     }
     float l_run = run.l_run;
