@@ -162,7 +162,8 @@ struct Workspace {
     int chunk_tokens, max_chunks, lm_blocks;
     int pf_chunk_tokens, pf_max_chunks;   // the same split for the kernel that takes a prefill chunk's rows in groups
     bool defer_merge;   // small problems: the output projection merges the attention chunks
-    bool attn_light;    // matrix-core attention without the register double buffer (short chunks)
+    bool attn_mfma;     // the matrix-core attention kernel (otherwise the vector-ALU one)
+    bool attn_light;    // ... without the register double buffer (short chunks)
 };
 
 constexpr int kMaxGemvBatch = 4;  // up to here the vector-ALU GEMV; above, the matrix-core GEMM
@@ -186,15 +187,6 @@ int fused_variant(const dk_model_config &c, int B)
             return i;
     }
     return -1;
-}
-
-// The matrix-core attention kernel pays off once the group of query heads that
-// share a kv head is large (the vector-ALU kernel's multiply-adds grow with it):
-// measured 6 % faster per launch at groups of 3 (3B shape, 16 rows), equal at 2.
-bool attention_uses_mfma(const dk_model_config &c, int B, bool q4)
-{
-    const bool batched = B > kMaxGemvBatch || c.n_experts > 0 || q4;
-    return batched && c.n_q_heads / c.n_kv_heads >= 3;
 }
 
 // Which kernel a batched GEMM takes: w == 0 the K-split-per-wave kernel (skinny_gemm_kernel),
@@ -268,25 +260,34 @@ Workspace carve(const dk_model_config &c, int B, int max_blocks, bool q4)
     // split the context so that rows * kv heads * chunks gives the chip a few
     // blocks per compute unit
     const int ctx_max = max_blocks * 16;
-    // measured on 8B-class shapes: the matrix-core kernel (query groups of 3 and
-    // more) runs best with about two blocks per compute unit, the vector-ALU one
-    // with about four
+    // Which attention kernel, and how finely the context is split.  Measured:
+    //  * the matrix-core kernel pays off once the group of query heads that share a kv head is
+    //    large (the vector-ALU kernel's multiply-adds grow with it): from groups of 3 on; it runs
+    //    best with about two blocks per compute unit, the vector-ALU one with about four;
+    //  * with short chunks (at most 512 tokens: four iterations per wave) and groups of up to 4, a
+    //    lighter matrix-core variant - no second set of tile registers, three blocks per compute
+    //    unit, one round of at most 768 blocks - beats both (3B shape, ragged contexts up to 2 k:
+    //    25.4 -> 22.5 us per launch; 0.6B shape, 16 rows of context 512: 15.1 -> 12.9 us); with 4 k
+    //    contexts or groups of 8 it is slower and is not taken.
+    const bool batched_attn = B > kMaxGemvBatch || c.n_experts > 0 || q4;
+    const int pairs = B * c.n_kv_heads;
+    auto round64 = [](int v) { v = (v + 63) / 64 * 64; return v < 64 ? 64 : v; };
     auto chunk_for = [&](int want_blocks) {
-        int want_chunks = (want_blocks + B * c.n_kv_heads - 1) / (B * c.n_kv_heads);
-        if (want_chunks < 1) want_chunks = 1;
-        int ch = (ctx_max + want_chunks - 1) / want_chunks;
-        ch = (ch + 63) / 64 * 64;
-        return ch < 64 ? 64 : ch;
+        const int want_chunks = std::max(1, (want_blocks + pairs - 1) / pairs);
+        return round64((ctx_max + want_chunks - 1) / want_chunks);
     };
-    int chunk = chunk_for(attention_uses_mfma(c, B, q4) ? 512 : 1024);
-    // The matrix-core kernel with short chunks (at most four iterations per wave) and query
-    // groups of up to 4: three lighter blocks per compute unit instead of two that hold the next
-    // tiles in registers (3B shape, ragged contexts up to 2 k: 25.4 -> 22.7 us per launch; with
-    // 4 k contexts or groups of 8 that variant is slower and is not taken)
-    w.attn_light = false;
-    if (attention_uses_mfma(c, B, q4) && G <= 4 && chunk_for(768) <= 512) {
-        chunk = chunk_for(768);
-        w.attn_light = true;
+    const int light_chunks = std::max(1, 768 / pairs);
+    const int light_chunk = round64((ctx_max + light_chunks - 1) / light_chunks);
+    int chunk;
+    w.attn_mfma = w.attn_light = false;
+    if (batched_attn && G >= 2 && G <= 4 && light_chunk <= 512) {
+        w.attn_mfma = w.attn_light = true;
+        chunk = light_chunk;
+    } else if (batched_attn && G >= 3) {
+        w.attn_mfma = true;
+        chunk = chunk_for(512);
+    } else {
+        chunk = chunk_for(1024);
     }
     w.chunk_tokens = chunk;
     w.max_chunks = (ctx_max + chunk - 1) / chunk;
@@ -1338,7 +1339,7 @@ static dk_status decode_step_impl(dk_model *model, dk_kv_pool *pool, const int32
                                : launch_prefill_attention_d<64>(a, G, grid, st);
             } else {
                 const dim3 grid(w.max_chunks, nkv, B);
-                const bool use_mfma = attention_uses_mfma(c, B, model->q4);
+                const bool use_mfma = w.attn_mfma;
                 s = (d == 128) ? launch_attention_d<128>(a, nq / nkv, grid, use_mfma, w.attn_light, st)
                                : launch_attention_d<64>(a, nq / nkv, grid, use_mfma, w.attn_light, st);
             }

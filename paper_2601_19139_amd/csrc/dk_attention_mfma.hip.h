@@ -9,8 +9,9 @@
 //
 //   scores  S[token][g] = sum_dim K[token][dim] * q[g][dim]
 //           16x16x32 bf16 MFMAs with A = the K tile straight from the pool (lane
-//           = token row, 16-byte loads) and B = q as bf16 hi + lo (two MFMAs per
-//           32 dims, so q keeps ~16 significant bits); the G query heads of the
+//           = token row, 16-byte loads) and B = q as three bf16 terms (three MFMAs
+//           per 32 dims, so q keeps 24 significant bits: an error in a score is an
+//           equal relative error in its probability); the G query heads of the
 //           group are the first G of the 16 columns.
 //   softmax online per column: the lane (column g, lane group lg) holds tokens
 //           4*lg..4*lg+3 of each tile; running max / sum as usual.
@@ -30,9 +31,35 @@ namespace dk {
 // One iteration of the matrix-core inner loop, shared by the decode kernel below and the
 // chunked-prefill kernel (dk_attention_prefill.hip.h): a wave's pair of 16-token block tiles
 // starting at block blk0, already in registers (kw: K tiles as the A operand, vw: V tiles row
-// major), against the 16 query columns in qh / ql.  Column ln attends to positions < t1_col;
+// major), against the 16 query columns in qt.  Column ln attends to positions < t1_col;
 // V rows of positions >= t1_stage (>= every column's limit) are zeroed while staged, since
 // they may hold anything.  Running maximum, sum and output of the wave are updated in place.
+// q as the B operand of the score MFMAs: lane (column ln, lane group lg) holds dims s*32 + lg*8 .. +8
+// of its column, as THREE bf16 terms whose sum has 24 significant bits.  K is exact bf16, so the
+// scores then carry float32 accuracy; with two terms (16 bits) a score of magnitude 30 was off by
+// 2e-4 absolute, which a row with a handful of cached tokens shows undiminished in its output.
+template <int D>
+__device__ __forceinline__ void mfma_q_operand(const float *qrow, bool valid, int lg, uint4 (&qt)[3][D / 32])
+{
+#pragma unroll
+    for (int s = 0; s < D / 32; s++) {
+        const float4 *src = reinterpret_cast<const float4 *>(qrow + s * 32 + lg * 8);
+        const float4 f0 = src[0], f1 = src[1];
+        const float f[8] = {f0.x, f0.y, f0.z, f0.w, f1.x, f1.y, f1.z, f1.w};
+        uint32_t w[3][4];
+#pragma unroll
+        for (int e = 0; e < 4; e++) {
+            const float a = valid ? f[2 * e] : 0.f, b = valid ? f[2 * e + 1] : 0.f;
+            w[0][e] = f32x2_to_bf16x2_rne(a, b);
+            const float ra = a - bf16lo(w[0][e]), rb = b - bf16hi(w[0][e]);
+            w[1][e] = f32x2_to_bf16x2_rne(ra, rb);
+            w[2][e] = f32x2_to_bf16x2_rne(ra - bf16lo(w[1][e]), rb - bf16hi(w[1][e]));
+        }
+#pragma unroll
+        for (int t = 0; t < 3; t++) qt[t][s] = make_uint4(w[t][0], w[t][1], w[t][2], w[t][3]);
+    }
+}
+
 template <int D>
 struct MfmaAttnRun {
     float m_run, l_run;          // column ln, over this lane group's tokens
@@ -48,7 +75,7 @@ struct MfmaAttnRun {
 
 template <int D, int VROW>
 __device__ __forceinline__ void mfma_attend_tile_pair(const uint4 (&kw)[2][D / 32], const uint4 (&vw)[2][16 / (512 / D)],
-                                                      const uint4 (&qh)[D / 32], const uint4 (&ql)[D / 32],
+                                                      const uint4 (&qt)[3][D / 32],
                                                       uint16_t (*sm_vw)[16][VROW], int blk0, int t1_stage,
                                                       int t1_col, int lane, MfmaAttnRun<D> &r)
 {
@@ -62,8 +89,9 @@ __device__ __forceinline__ void mfma_attend_tile_pair(const uint4 (&kw)[2][D / 3
         sc[u] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int s = 0; s < NS; s++) {
-            sc[u] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(kw[u][s]), as_bf16x8(qh[s]), sc[u], 0, 0, 0);
-            sc[u] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(kw[u][s]), as_bf16x8(ql[s]), sc[u], 0, 0, 0);
+#pragma unroll
+            for (int t = 0; t < 3; t++)
+                sc[u] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(kw[u][s]), as_bf16x8(qt[t][s]), sc[u], 0, 0, 0);
         }
     }
     // stage V while the scores are computed
@@ -324,26 +352,9 @@ __global__ __launch_bounds__(256, PREFETCH ? 2 : 3) void attention_mfma_kernel(A
         }
     }
 
-    // q as the B operand: lane (column g = ln, lane group lg) holds dims
-    // s*32 + lg*8 .. +8 of head g, as bf16 hi and lo; columns >= G are zero
-    uint4 qh[NS], ql[NS];
-#pragma unroll
-    for (int s = 0; s < NS; s++) {
-        const float4 *src = reinterpret_cast<const float4 *>(&sm_q[min(ln, G - 1)][s * 32 + lg * 8]);
-        const float4 f0 = src[0], f1 = src[1];
-        const float f[8] = {f0.x, f0.y, f0.z, f0.w, f1.x, f1.y, f1.z, f1.w};
-        uint32_t hw[4], lw[4];
-#pragma unroll
-        for (int e = 0; e < 4; e++) {
-            uint16_t h0, l0, h1, l1;
-            split_bf16(ln < G ? f[2 * e] : 0.f, h0, l0);
-            split_bf16(ln < G ? f[2 * e + 1] : 0.f, h1, l1);
-            hw[e] = (uint32_t)h0 | ((uint32_t)h1 << 16);
-            lw[e] = (uint32_t)l0 | ((uint32_t)l1 << 16);
-        }
-        qh[s] = make_uint4(hw[0], hw[1], hw[2], hw[3]);
-        ql[s] = make_uint4(lw[0], lw[1], lw[2], lw[3]);
-    }
+    // q as the B operand (columns >= G are zero)
+    uint4 qt[3][NS];
+    mfma_q_operand<D>(sm_q[min(ln, G - 1)], ln < G, lg, qt);
 
     // ---- main loop: a pair of block tiles (32 tokens) per iteration -----------
     MfmaAttnRun<D> run;
@@ -355,7 +366,7 @@ __global__ __launch_bounds__(256, PREFETCH ? 2 : 3) void attention_mfma_kernel(A
         for (int blk0 = blk_first; blk0 < blk_end; blk0 += 2 * NWV) {
             const int blk_next = blk0 + 2 * NWV;
             request(blk_next < blk_end ? blk_next : blk0, kw_n, vw_n);
-            mfma_attend_tile_pair<D, VROW>(kw, vw, qh, ql, sm_v[wv], blk0, t1, t1, lane, run);
+            mfma_attend_tile_pair<D, VROW>(kw, vw, qt, sm_v[wv], blk0, t1, t1, lane, run);
 #pragma unroll
             for (int u = 0; u < 2; u++) {
 #pragma unroll
@@ -369,7 +380,7 @@ __global__ __launch_bounds__(256, PREFETCH ? 2 : 3) void attention_mfma_kernel(A
         // blocks per compute unit cover the latency instead
         for (int blk0 = blk_first; blk0 < blk_end; blk0 += 2 * NWV) {
             if (blk0 != blk_first) request(blk0, kw, vw);
-            mfma_attend_tile_pair<D, VROW>(kw, vw, qh, ql, sm_v[wv], blk0, t1, t1, lane, run);
+            mfma_attend_tile_pair<D, VROW>(kw, vw, qt, sm_v[wv], blk0, t1, t1, lane, run);
         }
     }
     float l_run = run.l_run;

@@ -11,7 +11,7 @@
 // first), so there is no "new token" special case: column col attends to the
 // positions 0..T(col) of the pool, and the causal mask inside the group is the
 // per-column limit.  The inner loop is the decode kernel's (mfma_attend_tile_pair:
-// scores = K q with q as bf16 hi + lo, online softmax per column, output = P V
+// scores = K q with q as three bf16 terms, online softmax per column, output = P V
 // with V staged in LDS and fetched with the LDS transpose read), given that limit.  A tile past a column's limit contributes exactly nothing to it, and an
 // empty chunk partial merges as exactly nothing, so a row's result depends on
 // the chunk length only, not on which rows share its group.
@@ -138,33 +138,15 @@ __global__ __launch_bounds__(256, 3) void prefill_attention_kernel(AttnArgs a)
     }
     __syncthreads();
 
-    // q as the B operand: lane (column ln, lane group lg) holds dims s*32 + lg*8 .. +8
-    // of its column, as bf16 hi and lo
-    uint4 qh[NS], ql[NS];
-#pragma unroll
-    for (int s = 0; s < NS; s++) {
-        const float4 *src = reinterpret_cast<const float4 *>(&sm_q[ln][s * 32 + lg * 8]);
-        const float4 f0 = src[0], f1 = src[1];
-        const float f[8] = {f0.x, f0.y, f0.z, f0.w, f1.x, f1.y, f1.z, f1.w};
-        uint32_t hw[4], lw[4];
-#pragma unroll
-        for (int e = 0; e < 4; e++) {
-            uint16_t h0, l0, h1, l1;
-            split_bf16(f[2 * e], h0, l0);
-            split_bf16(f[2 * e + 1], h1, l1);
-            hw[e] = (uint32_t)h0 | ((uint32_t)h1 << 16);
-            lw[e] = (uint32_t)l0 | ((uint32_t)l1 << 16);
-        }
-        qh[s] = make_uint4(hw[0], hw[1], hw[2], hw[3]);
-        ql[s] = make_uint4(lw[0], lw[1], lw[2], lw[3]);
-    }
+    uint4 qt[3][NS];   // q as the B operand
+    mfma_q_operand<D>(sm_q[ln], true, lg, qt);
 
     // ---- main loop: a pair of block tiles (32 tokens) per iteration -----------
     MfmaAttnRun<D> run;
     run.init();
     for (int blk0 = blk_first; blk0 < blk_end; blk0 += 2 * NWV) {
         request(blk0, kw, vw);
-        mfma_attend_tile_pair<D, VROW>(kw, vw, qh, ql, sm_v[wv], blk0, t1, t1c, lane, run);
+        mfma_attend_tile_pair<D, VROW>(kw, vw, qt, sm_v[wv], blk0, t1, t1c, lane, run);
     }
     float l_run = run.l_run;
     const float m_run = run.m_run;
