@@ -236,7 +236,6 @@ GemmPlan gemm_plan(int epi, int N, int K, int Bp, bool q4)
         // output projection, down.  At 16 rows only the down projections: the square-ish output
         // projections are as fast or faster with two-wave blocks of the other kernel (3B: 8.8 vs 9.6 us)
         if (elems >= (mt >= 2 ? (8ll << 20) : (20ll << 20))) return {4, slices(4)};
-        if (mt >= 2 && K >= 3072 && elems >= (3ll << 20)) return {4, slices(4)};      // down of a small model
     }
     return {0, 1};
 }
@@ -451,20 +450,21 @@ dk_status launch_gemv(dk::GemvArgs a, int B, hipStream_t st)
 }
 
 // ---- skinny GEMM dispatch (batches of 5..64 rows) ---------------------------
+// col_groups > 1: the batch rows are split into that many groups of 16*MT across blockIdx.y
 template <int MT, int KS, int RT, int EPI, bool NORM, bool KALIGNED, bool Q4 = false>
-dk_status launch_gemm_inst(const dk::GemmArgs &a, hipStream_t st)
+dk_status launch_gemm_inst(const dk::GemmArgs &a, int col_groups, hipStream_t st)
 {
     constexpr size_t lds = dk::skinny_gemm_lds_bytes<MT, KS, RT, EPI>();
     static_assert(lds <= (64u << 10), "dynamic LDS above 64 KB would need a function attribute");
-    const int grid = (a.N + 16 * RT - 1) / (16 * RT);
+    const dim3 grid((a.N + 16 * RT - 1) / (16 * RT), col_groups);
     // K-steps in flight per wave: two (deeper did not measure faster); one where a wave has a single
     // step anyway (K <= 128 * KS: the second stage would only fetch a step it never uses - q/k/v of
     // the 0.6B shape at 16 rows 6.3 -> 5.4 us, gate/up 8.1 -> 6.8 us)
     if ((a.K + 127) / 128 <= KS) {
-        DK_LAUNCH(DK_K_GEMM, (dk::skinny_gemm_kernel<MT, KS, RT, 1, EPI, NORM, KALIGNED, Q4>), dim3(grid),
+        DK_LAUNCH(DK_K_GEMM, (dk::skinny_gemm_kernel<MT, KS, RT, 1, EPI, NORM, KALIGNED, Q4>), grid,
                   dim3(KS * 64), lds, st, a);
     } else {
-        DK_LAUNCH(DK_K_GEMM, (dk::skinny_gemm_kernel<MT, KS, RT, 2, EPI, NORM, KALIGNED, Q4>), dim3(grid),
+        DK_LAUNCH(DK_K_GEMM, (dk::skinny_gemm_kernel<MT, KS, RT, 2, EPI, NORM, KALIGNED, Q4>), grid,
                   dim3(KS * 64), lds, st, a);
     }
     DK_HIP(hipGetLastError());
@@ -472,14 +472,14 @@ dk_status launch_gemm_inst(const dk::GemmArgs &a, hipStream_t st)
 }
 
 template <int MT, int KS, int RT, int EPI, bool NORM>
-dk_status launch_gemm_cfg(const dk::GemmArgs &a, hipStream_t st)
+dk_status launch_gemm_cfg(const dk::GemmArgs &a, hipStream_t st, int col_groups = 1)
 {
     if (a.q4) {
         if (a.K % 128) return fail(DK_E_UNSUPPORTED_SHAPE, "4-bit matrix with K = %d (a multiple of 128 is needed)", a.K);
-        return launch_gemm_inst<MT, KS, RT, EPI, NORM, true, true>(a, st);
+        return launch_gemm_inst<MT, KS, RT, EPI, NORM, true, true>(a, col_groups, st);
     }
-    if (a.K % 128 == 0) return launch_gemm_inst<MT, KS, RT, EPI, NORM, true>(a, st);
-    return launch_gemm_inst<MT, KS, RT, EPI, NORM, false>(a, st);
+    if (a.K % 128 == 0) return launch_gemm_inst<MT, KS, RT, EPI, NORM, true>(a, col_groups, st);
+    return launch_gemm_inst<MT, KS, RT, EPI, NORM, false>(a, col_groups, st);
 }
 
 // A wave that handles several 16-row weight tiles per K-step reuses the
@@ -553,16 +553,21 @@ dk_status launch_gemm(const dk::GemmArgs &a, int Bp, hipStream_t st)
     const GemmPlan plan = gemm_plan(EPI, a.N, a.K, Bp, a.q4 != 0);
     if (plan.w) return launch_shared_gemm<EPI, NORM>(a, Bp, plan, st);
     const int tiles = (a.N + 15) / 16;
-    switch (Bp / 16) {
+    // A small matrix (at most one 16-row tile per compute unit) at 32..64 rows: the 16-row kernel
+    // over every group of 16 batch rows at once (blockIdx.y), instead of 64 blocks that each
+    // carry all the rows through one long epilogue (0.6B shape at 64 rows: O 14.3 -> 6 us).
+    const int mt = Bp / 16;
+    const int col_groups = (mt >= 2 && tiles <= 256) ? mt : 1;
+    switch (col_groups > 1 ? 1 : mt) {
         case 1:
             if constexpr (NM == 1) {
                 if (tiles >= 4096) return launch_gemm_cfg<1, 8, 4, EPI, NORM>(a, st);
                 if (tiles >= 320) return launch_gemm_cfg<1, 8, 2, EPI, NORM>(a, st);
                 // residual projections with at most one block per compute unit: two waves per block,
                 // less to add up across waves (0.6B shape: O 5.9 -> 5.1 us, down 8.8 -> 8.2 us)
-                if (tiles <= 256 && EPI == dk::GEPI_RESID && !a.q4) return launch_gemm_cfg<1, 2, 1, EPI, NORM>(a, st);
+                if (tiles <= 256 && EPI == dk::GEPI_RESID && !a.q4) return launch_gemm_cfg<1, 2, 1, EPI, NORM>(a, st, col_groups);
             }
-            return launch_gemm_cfg<1, 8, 1, EPI, NORM>(a, st);
+            return launch_gemm_cfg<1, 8, 1, EPI, NORM>(a, st, col_groups);
         case 2:
             if constexpr (NM == 1) {
                 if (tiles >= 1024) return launch_gemm_cfg<2, 8, 2, EPI, NORM>(a, st);

@@ -199,6 +199,32 @@ __global__ __launch_bounds__(KS * 64) void skinny_gemm_kernel(GemmArgs a)
     const int ln = lane & 15, lg = lane >> 4;
     const int K = a.K, N = a.N;
     const int nks = (K + 127) >> 7;
+    if (gridDim.y > 1) {
+        // The batch rows are split across blockIdx.y in groups of 16*MT: a small matrix (few row
+        // tiles) then still gives every compute unit a block, each with a quarter of the epilogue,
+        // and the weights, read once per group, stay in the caches.  Every table is tile-major or
+        // row-major in the batch row, so a group is the same problem behind shifted pointers.
+        const int ct = (int)blockIdx.y * MT;   // first column tile of this block
+        const int64_t onks = (N + 127) >> 7, n_tiles = (N + 15) >> 4;
+        a.xhi += (int64_t)ct * nks * 2048;
+        a.xlo += (int64_t)ct * nks * 2048;
+        if (NORM) a.ssq_in += 16 * ct;
+        if (EPI == GEPI_STORE) {
+            if (a.y != nullptr) a.y += (int64_t)16 * ct * N;
+            if (a.pmax_val != nullptr) {
+                a.pmax_val += (int64_t)16 * ct * n_tiles;
+                a.pmax_idx += (int64_t)16 * ct * n_tiles;
+            }
+        } else {
+            a.ohi += (int64_t)ct * onks * 2048;
+            a.olo += (int64_t)ct * onks * 2048;
+        }
+        if (EPI == GEPI_RESID) {
+            a.xres += (int64_t)16 * ct * N;
+            a.ssq_out += 16 * ct;
+        }
+        a.B = min(16 * MT, a.B - 16 * ct);
+    }
     const int niter = (nks + KS - 1) / KS;   // K-steps per wave and row group
     const int niter2 = (niter + PD - 1) / PD * PD;   // padded to the pipeline depth
 
@@ -355,7 +381,7 @@ __global__ __launch_bounds__(KS * 64) void skinny_gemm_kernel(GemmArgs a)
     if (NORM) {
 #pragma unroll
         for (int u = 0; u < SSQ_REGS; u++)
-            sv[u] = a.ssq_in[(int64_t)min(wv + u * KS, a.n_part - 1) * kSsqStride + lane];
+            sv[u] = a.ssq_in[(int64_t)min(wv + u * KS, a.n_part - 1) * kSsqStride + min(lane, 16 * MT - 1)];
     }
 
     // The residual rows and the next norm's gains that the epilogue of wave rt < RT will
@@ -393,7 +419,7 @@ __global__ __launch_bounds__(KS * 64) void skinny_gemm_kernel(GemmArgs a)
 #pragma unroll
             for (int u = 0; u < SSQ_REGS; u++) ss += (wv + u * KS < a.n_part) ? sv[u] : 0.f;
             for (int p = wv + SSQ_REGS * KS; p < a.n_part; p += KS)   // very wide models only
-                ss += a.ssq_in[(int64_t)p * kSsqStride + lane];
+                ss += a.ssq_in[(int64_t)p * kSsqStride + min(lane, 16 * MT - 1)];
             ssq_s[wv][lane] = ss;
         }
         // K-splits meet in LDS
