@@ -553,11 +553,13 @@ dk_status launch_gemm(const dk::GemmArgs &a, int Bp, hipStream_t st)
     const GemmPlan plan = gemm_plan(EPI, a.N, a.K, Bp, a.q4 != 0);
     if (plan.w) return launch_shared_gemm<EPI, NORM>(a, Bp, plan, st);
     const int tiles = (a.N + 15) / 16;
-    // A small matrix (at most one 16-row tile per compute unit) at 32..64 rows: the 16-row kernel
-    // over every group of 16 batch rows at once (blockIdx.y), instead of 64 blocks that each
-    // carry all the rows through one long epilogue (0.6B shape at 64 rows: O 14.3 -> 6 us).
+    // A small matrix at 32..64 rows whose row tiles times groups of 16 batch rows still make at
+    // most two blocks per compute unit: the 16-row kernel over every group at once (blockIdx.y),
+    // instead of a few blocks that each carry all the rows through one long epilogue (0.6B shape
+    // at 64 rows: O and down, 64 row tiles, 14.3 / 16.3 -> 7.6 us; q/k/v and gate/up, 256 / 192
+    // tiles, are slower that way - 8.5 -> 11.9, 10.9 -> 12.8 us - and keep the 64-row kernel).
     const int mt = Bp / 16;
-    const int col_groups = (mt >= 2 && tiles <= 256) ? mt : 1;
+    const int col_groups = (mt >= 2 && tiles * mt <= 512) ? mt : 1;
     switch (col_groups > 1 ? 1 : mt) {
         case 1:
             if constexpr (NM == 1) {
@@ -754,7 +756,7 @@ const char *dk_last_error(void) { return g_err; }
 
 // The kernel revisions change whenever a kernel's memory behaviour changes; the
 // benchmark quotes stored counter measurements only for a matching revision.
-const char *dk_version(void) { return "decodekit 0.8 (gfx950; gemv r3, gemm r10, attention r8, moe r4, fused r2, prefill r2, sample r1)"; }
+const char *dk_version(void) { return "decodekit 0.8 (gfx950; gemv r3, gemm r11, attention r8, moe r4, fused r2, prefill r2, sample r1)"; }
 
 // ------------------------------------------------------------------- pool --
 dk_status dk_kv_pool_bytes(const dk_model_config *cfg, int32_t num_blocks, int32_t block_size,
