@@ -170,7 +170,9 @@ dk_status dk_create_model(const dk_model_config *cfg, const dk_weight_ptrs *weig
  * benchmarks (evaluation setup: 4-bit quantised models): group-wise affine, a
  * group being 64 consecutive columns of a row with one bf16 scale and one bf16
  * bias, the weight being  scale * q + bias  for the code q in 0..15.
- * Dense models only; hidden, n_q_heads*head_dim and ffn multiples of 128.
+ * Dense and mixture-of-experts models (the expert stacks are 4-bit, the router
+ * stays bf16); hidden, n_q_heads*head_dim and ffn (expert_ffn) multiples of 128,
+ * and for expert layers hidden and expert_ffn of at least 512.
  *
  * Same structs as dk_create_model; g_* and embed stay bf16 as there, while
  * w_qkv, w_o, w_gate, w_up, w_down and lm_head each point to one packed matrix

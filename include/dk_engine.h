@@ -5,10 +5,11 @@
  *
  * What it implements (the serving method of the paper, section "Text Model
  * Inference"):
- *   - Algorithm 1 (continuous batching scheduler): a pending queue Q, an
- *     active batch B of at most M requests; every iteration admits requests
- *     while |B| < M, generates one token for every active request with one
- *     batched decode step, and removes completed requests at once.
+ *   - Algorithm 1 (continuous batching scheduler): a waiting queue and a
+ *     running batch of at most max_batch rows; a call to dk_engine_step first
+ *     refills free rows from the queue, then runs one batched decode step
+ *     that advances every running row by a token, then retires the rows that
+ *     finished, so their places are free for the next call.
  *   - Algorithm 2 (text prefix cache lookup): a new prompt is matched against
  *     cached prompts, the KV state of the longest cached prefix is reused and
  *     the forward pass resumes at the returned start position.  Here the cache
@@ -96,7 +97,7 @@ typedef struct dk_engine_stats {
     int64_t reused_tokens;       /* prompt tokens taken from the prefix cache               */
     int64_t evictions;           /* cached blocks dropped                                   */
     int32_t cached_blocks;       /* blocks the prefix cache holds now                       */
-    int32_t active, pending;     /* |B| and |Q| now                                         */
+    int32_t active, pending;     /* running rows and waiting requests now                   */
 } dk_engine_stats;
 
 /* Device bytes the engine needs in its arena (block tables, lengths, tokens and
@@ -125,7 +126,7 @@ dk_status dk_engine_submit(dk_engine *engine, const int32_t *h_prompt, int32_t n
  * one decode step for all active requests, removal of the completed ones.
  * A request for which no KV block can be found even after eviction ends with the
  * state DK_REQ_FAILED (only possible when the pool is too small for the batch).
- * *out_active (may be NULL) = |B| + |Q| afterwards: 0 means nothing is left to do. */
+ * *out_active (may be NULL) = running + waiting requests afterwards: 0 means nothing is left to do. */
 dk_status dk_engine_step(dk_engine *engine, void *hip_stream, int32_t *out_active);
 
 /* Sampling beyond greedy for every token generated from now on (dk_sampling and its exact

@@ -569,8 +569,10 @@ __global__ __launch_bounds__(256) void attention_kernel(AttnArgs a)
     if (a.defer_merge || nact == 1) return;
 
     // Last block of this (row, kv head) merges the chunk partials.  The partial
-    // stores above are device-coherent and complete (the barrier waits for
-    // them) before the ticket is taken.
+    // stores above are device-coherent; every thread waits for its own to complete,
+    // then the barrier, then one thread takes the ticket: whoever draws the last
+    // ticket reads finished partials (with device-coherent loads).
+    drain_stores();
     __syncthreads();
     if (tid == 0)
         sm_ticket = __hip_atomic_fetch_add(&a.tickets[b * a.nkv + j], 1, __ATOMIC_RELAXED,

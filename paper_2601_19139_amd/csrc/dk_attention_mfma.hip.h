@@ -422,6 +422,7 @@ __global__ __launch_bounds__(256, PREFETCH ? 2 : 3) void attention_mfma_kernel(A
         }
     }
     if (nact == 1) return;
+    drain_stores();   // the partials are complete before the ticket is taken (see attention_kernel)
     __syncthreads();
     if (tid == 0)
         sm_ticket = __hip_atomic_fetch_add(&a.tickets[b * a.nkv + j], 1, __ATOMIC_RELAXED,

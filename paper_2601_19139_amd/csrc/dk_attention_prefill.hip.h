@@ -188,7 +188,8 @@ __global__ __launch_bounds__(256, 3) void prefill_attention_kernel(AttnArgs a)
         }
     }
     if (nact == 1) return;
-    __syncthreads();   // the stores above are complete before the ticket is taken
+    drain_stores();    // every thread's partials are complete ...
+    __syncthreads();   // ... before one thread takes the ticket
     if (tid == 0)
         sm_ticket = __hip_atomic_fetch_add(&a.tickets[grp * a.nkv + j], 1, __ATOMIC_RELAXED,
                                            __HIP_MEMORY_SCOPE_AGENT);

@@ -88,6 +88,12 @@ __device__ __forceinline__ float max64(float v)
     return v;
 }
 
+// Waits until every store this wave has issued is complete.  A block that hands partial results
+// to "whichever block takes the last ticket" calls this in every storing thread before the barrier
+// that precedes the ticket: the barrier alone orders the waves of the block, not their outstanding
+// device-coherent stores against another wave's atomic.
+__device__ __forceinline__ void drain_stores() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
 __device__ __forceinline__ uint4 ld16(const void *p) { return *reinterpret_cast<const uint4 *>(p); }
 __device__ __forceinline__ float4 ldf4(const float *p) { return *reinterpret_cast<const float4 *>(p); }
 

@@ -296,8 +296,9 @@ bool engine_finished(const EngineRequest *r)
     return (int)r->out.size() >= r->max_new || (r->eos >= 0 && !r->out.empty() && r->out.back() == r->eos);
 }
 
-// Q.pop + B.add for one request: prefix lookup, blocks, prefill.  DK_E_POOL_EXHAUSTED
-// (with everything undone) means "not now".
+// Moves one request from the waiting queue into the running batch: prefix lookup, blocks,
+// prefill (Algorithm 1's admission, with Algorithm 2 inside).  DK_E_POOL_EXHAUSTED (with
+// everything undone) means "not now".
 dk_status engine_admit(dk_engine *e, EngineRequest *r, hipStream_t st)
 {
     const int bs = dk_prefix_index::kBlock;
@@ -368,7 +369,7 @@ dk_status engine_admit(dk_engine *e, EngineRequest *r, hipStream_t st)
     return DK_OK;
 }
 
-// B.remove: the last row moves into the hole
+// Takes a row out of the running batch: its blocks are released and the last row moves into the hole
 void engine_retire(dk_engine *e, size_t row, int state)
 {
     EngineRequest *r = e->active[row];
@@ -466,7 +467,7 @@ dk_status dk_engine_step(dk_engine *engine, void *hip_stream, int32_t *out_activ
     const int bs = dk_prefix_index::kBlock;
     bool worked = false;
 
-    // admit new requests at the token boundary, while |B| < M and Q is not empty
+    // admission happens only here, between two decode steps: fill free rows from the waiting queue
     while ((int)e->active.size() < e->cfg.max_batch && !e->queue.empty()) {
         EngineRequest *r = e->queue.front();
         const dk_status s = engine_admit(e, r, st);
@@ -483,7 +484,7 @@ dk_status dk_engine_step(dk_engine *engine, void *hip_stream, int32_t *out_activ
         if (engine_finished(r)) engine_retire(e, e->active.size() - 1, DK_REQ_DONE);
     }
 
-    // generate one token for every active request
+    // one batched decode step advances every running row by a token
     if (!e->active.empty()) {
         // a sequence whose next position starts a block needs that block first
         for (size_t row = 0; row < e->active.size();) {
@@ -527,7 +528,9 @@ dk_status dk_engine_step(dk_engine *engine, void *hip_stream, int32_t *out_activ
                 DK_HIP(hipMemcpyAsync(smp.data(), e->d_sampled, (size_t)B * 4, hipMemcpyDeviceToHost, st));
             }
             DK_HIP(hipStreamSynchronize(st));
-            if (nxt[0] >= 0) break;
+            bool valid = true;   // an invalid step marks every row with -1; check them all
+            for (int i = 0; i < B; i++) valid = valid && nxt[(size_t)i] >= 0;
+            if (valid) break;
             // the persistent kernel could not keep its blocks resident (its waits are bounded and it
             // says so with the token -1): the step left lengths and tokens alone, so it is simply
             // repeated, now and from here on as a chain of kernels
@@ -547,7 +550,7 @@ dk_status dk_engine_step(dk_engine *engine, void *hip_stream, int32_t *out_activ
             r->last = nxt[(size_t)i];
             r->T++;
         }
-        // remove completed requests immediately
+        // rows that reached their length or their stop token retire now, so the next call can refill them
         for (size_t row = 0; row < e->active.size();) {
             if (engine_finished(e->active[row])) engine_retire(e, row, DK_REQ_DONE);
             else row++;

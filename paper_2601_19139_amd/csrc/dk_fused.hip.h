@@ -854,29 +854,36 @@ __global__ __launch_bounds__(kFusedThreads) void fused_step_kernel(FusedArgs a)
             for (int ww = 1; ww < kFusedWaves; ww++)
                 if (sv[ww * NB + tid] > bv) { bv = sv[ww * NB + tid]; bi = si[ww * NB + tid]; }
             stc_f32(amax + 2 * ((long long)blk * NB + tid), bv);
-            // a block without rows reports index -1 (0x7fffffff would read as "not yet")
-            stc_f32(amax + 2 * ((long long)blk * NB + tid) + 1, __int_as_float(bi == 0x7fffffff ? -1 : bi));
+            // a block without rows reports index -1 (0x7fffffff would read as "not yet"); a block
+            // that gave up a wait (or saw another give up) reports -2: the verdict travels with the
+            // data block 0 waits for, so no ordering between this store and the abort word is needed
+            stc_f32(amax + 2 * ((long long)blk * NB + tid) + 1,
+                    __int_as_float(w.aborted ? -2 : (bi == 0x7fffffff ? -1 : bi)));
         }
         if (blk != 0) return;
         // block 0: all per-block maxima (blocks own ascending row ranges)
         for (int b = 0; b < NB; b++) {
             float bv = -INFINITY;
             int bi = 0x7fffffff;
+            bool some_gave_up = false;
             w.spins = 0;
             for (;;) {
                 bool ready = true;
                 bv = -INFINITY;
                 bi = 0x7fffffff;
+                some_gave_up = false;
                 for (int i = tid; i < nblk; i += kFusedThreads) {
                     const uint32_t uv = ldc_u32(amax + 2 * ((long long)i * NB + b));
                     const uint32_t ui = ldc_u32(amax + 2 * ((long long)i * NB + b) + 1);
                     ready = ready && uv != kNotYet && ui != kNotYet;
                     const float v = __uint_as_float(uv);
                     const int ix = (int)ui;
+                    some_gave_up = some_gave_up || ix == -2;
                     if (ix >= 0 && (v > bv || (v == bv && ix < bi))) { bv = v; bi = ix; }
                 }
                 if (w.done(ready)) break;
             }
+            some_gave_up = __syncthreads_or(some_gave_up);
 #pragma unroll
             for (int off = 1; off < 64; off <<= 1) {
                 const float ov = __shfl_xor(bv, off);
@@ -892,7 +899,7 @@ __global__ __launch_bounds__(kFusedThreads) void fused_step_kernel(FusedArgs a)
                 if (bi == 0x7fffffff) bi = 0;
                 // a step in which some block gave up a wait has no valid result: it says so
                 // with the token -1 and does not advance the sequence
-                const bool gave_up = w.aborted || ldc_u32(a.status) == a.serial;
+                const bool gave_up = w.aborted || some_gave_up || ldc_u32(a.status) == a.serial;
                 a.next[b] = gave_up ? -1 : bi;
                 if (a.advance && !gave_up) {
                     a.tokens[b] = bi;

@@ -227,7 +227,8 @@ __global__ __launch_bounds__(W * 64) void shared_gemm_kernel(GemmArgs a)
                     __hip_atomic_store(pp + (t * 4 + i) * 64 + lane, acc[m][t][i], __ATOMIC_RELAXED,
                                        __HIP_MEMORY_SCOPE_AGENT);
         }
-        __syncthreads();   // the stores above are complete before the ticket is taken
+        drain_stores();    // every wave's partial tiles are complete ...
+        __syncthreads();   // ... before one thread takes the ticket
         if (tid == 0)
             sm_last = __hip_atomic_fetch_add(&a.ktickets[blockIdx.x], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) ==
                       S - 1;

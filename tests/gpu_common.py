@@ -89,6 +89,41 @@ def check_parity(out, tol=1e-2, min_agree=0.99):
     return worst, agree / total
 
 
+def parity_stats(out):
+    """Count of compared tokens, worst and mean relative L2 of the logits and the
+    teacher-forced greedy agreement of a run_both / run_sampled result."""
+    errs = np.concatenate([rel_l2(g, o).reshape(-1) for g, o in zip(out["gpu_logits"], out["orc_logits"])])
+    same = sum(int((g == o).sum()) for g, o in zip(out["gpu_next"], out["orc_next"]))
+    return {"tokens": int(errs.size), "worst": float(errs.max()), "mean": float(errs.mean()),
+            "agree": same / errs.size}
+
+
+def free_running_report(free_next, orc_next, rows=None):
+    """The GPU decoding on its own tokens against the oracle decoding on its own:
+    fraction of equal tokens over the compared steps and the first step at which
+    any compared row differs (None: never).  Reported, not graded: one flipped
+    near-tie changes everything after it."""
+    n = min(len(free_next), len(orc_next))
+    g = np.stack([np.asarray(f)[list(rows)] if rows is not None else np.asarray(f) for f in free_next[:n]])
+    o = np.stack([np.asarray(x) for x in orc_next[:n]])
+    differs = np.nonzero((g != o).any(axis=1))[0]
+    return float((g == o).mean()), (int(differs[0]) if differs.size else None)
+
+
+def log_result(line):
+    """Prints a result line and, where the results folder of a GPU run exists or can be made,
+    appends it there (pytest shows captured output only for failing tests)."""
+    import os
+    print(line, flush=True)
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    try:
+        os.makedirs(os.path.join(root, "gpurun_out"), exist_ok=True)
+        with open(os.path.join(root, "gpurun_out", "parity_full_size.txt"), "a") as f:
+            f.write(line + "\n")
+    except OSError:
+        pass
+
+
 def check_pool(out, pool_before, shape, layout, steps):
     """Appends must land at exactly the oracle's offsets; values may differ by
     the bf16 rounding of nearly equal float32 numbers (<= 1 step, rarely)."""
@@ -102,14 +137,17 @@ def check_pool(out, pool_before, shape, layout, steps):
     assert (g[o_changed] != o[o_changed]).mean() < 0.02
 
 
-def run_sampled(orc, shape, weights, layout, pool_bits, tokens, steps, rows):
+def run_sampled(orc, shape, weights, layout, pool_bits, tokens, steps, rows, free_steps=0):
     """Full-size variant: the GPU runs the whole batch, the oracle only the
     sampled `rows` (rows of a batch do not interact, so a row's result does not
     depend on which other rows are computed).  Sampled rows are teacher-forced
     with the oracle's tokens; the others follow the GPU's own tokens.
 
     Returns per-step logits/tokens of the sampled rows from both sides, the GPU
-    pool, and the oracle pool (which holds only the sampled rows' appends)."""
+    pool, and the oracle pool (which holds only the sampled rows' appends).
+    free_steps > 0: the GPU also decodes that many steps from the same start on
+    its own tokens (the step advancing tokens and lengths on the device), all
+    rows, into a second copy of the pool: out["free_next"][step] = tokens [B]."""
     import torch
     import paper_2601_19139_amd as dk
     rows = list(rows)
@@ -139,8 +177,25 @@ def run_sampled(orc, shape, weights, layout, pool_bits, tokens, steps, rows):
     out["gpu_pool"] = dkv.bits().reshape(pool_bits.shape)
     out["orc_pool"] = opool
     dkv.close()
+    if free_steps:
+        out["free_next"] = free_run(dk, dm, layout, pool_bits, tokens, free_steps)
     dm.close()
     return out
+
+
+def free_run(dk, dm, layout, pool_bits, tokens, steps):
+    """`steps` decode steps on the GPU's own tokens (DK_STEP_ADVANCE): tokens per step [steps][B]."""
+    import torch
+    dkv = dk.DeviceKV(dm, layout, pool_bits)
+    dec = dk.Decoder(dm, dkv, layout.contexts, np.asarray(tokens, dtype=np.int32), want_logits=False)
+    got = []
+    for _ in range(steps):
+        dec.step(flags=dk.STEP_ADVANCE)
+        got.append(dec.next.clone())
+    torch.cuda.synchronize()
+    assert np.array_equal(dec.seq_lens.cpu().numpy(), layout.contexts + steps)
+    dkv.close()
+    return [g.cpu().numpy() for g in got]
 
 
 def check_pool_sampled(out, pool_before, shape, layout, steps, rows):

@@ -12,7 +12,8 @@ import pytest
 
 import workloads as W
 from workloads.blocktable import layout_for, build_block_tables
-from gpu_common import run_both, run_sampled, check_parity, check_pool, check_pool_sampled, rel_l2
+from gpu_common import (run_both, run_sampled, free_run, check_parity, parity_stats, free_running_report,
+                        log_result, check_pool, check_pool_sampled, rel_l2)
 
 pytestmark = pytest.mark.gpu
 
@@ -267,42 +268,72 @@ def test_logits_optional(dk, orc):
 
 
 def test_cfg1_full_size(dk, orc):
-    """The benchmark workload at full size (28 layers, vocabulary 151936,
-    context 512): every logit of the first steps, teacher-forced."""
+    """The benchmark workload at full size (28 layers, vocabulary 151936, context 512) for its
+    whole configured length: every logit of all 128 steps, teacher-forced, so the 99 % greedy
+    agreement bar is measured on 128 tokens; the context grows from 512 to 639 and crosses eight
+    block boundaries.  Also reported (not graded): the GPU decoding on its own tokens against the
+    oracle on its own."""
     wl = W.WORKLOADS["cfg1"]
     shape, lay = wl.cfg, layout_for(wl)
     weights = W.make_weights(shape, wl.seed_weights)
     pool = W.fill_kv_pool(shape, lay, wl.seed_kv)
     tokens = W.initial_tokens(shape, wl.batch, wl.seed_tokens)
-    steps = 6
+    steps = wl.steps
+    assert steps == 128
     out = run_both(orc, shape, weights, lay, pool, tokens, steps)
-    worst, agree = check_parity(out)
-    print(f"cfg1: worst rel-L2 {worst:.3e}, greedy agreement {agree:.3f}")
-    assert worst < TIGHT
+    check_parity(out)
+    st = parity_stats(out)
+    dm = dk.DeviceModel(shape, weights)
+    free = free_run(dk, dm, lay, pool, tokens, steps)
+    dm.close()
+    fr_agree, fr_first = free_running_report(free, out["orc_next"])
+    log_result(f"cfg1 full size: {st['tokens']} tokens teacher-forced, greedy agreement {st['agree']:.4f}, "
+               f"logits rel-L2 worst {st['worst']:.3e} mean {st['mean']:.3e}; free-running agreement "
+               f"{fr_agree:.3f}, first divergence at step {fr_first}")
+    assert st["tokens"] == 128 and st["agree"] >= 0.99
+    assert st["worst"] < TIGHT
     check_pool(out, pool, shape, lay, steps)
 
 
-@pytest.mark.parametrize("wname,rows,steps", [("cfg2", (0, 9, 15), 2), ("cfg3", (3, 12), 2),
-                                              ("cfg4_l4", (1, 8, 14), 2), ("cfg4", (2, 13), 1)])
+# rows: sharers of the prefix and non-sharers; rows x steps >= 128 compared tokens per workload
+FULL_SIZE = [("cfg2", (0, 2, 5, 7, 8, 10, 13, 15), 16), ("cfg3", (1, 6, 11, 14), 32),
+             ("cfg4_l4", (1, 8, 14), 2), ("cfg4", (0, 5, 9, 15), 32)]
+
+
+@pytest.mark.parametrize("wname,rows,steps", FULL_SIZE, ids=[c[0] for c in FULL_SIZE])
 def test_batch16_full_size_sampled_rows(dk, orc, wname, rows, steps):
-    """The batch-16 workloads at full size (Llama-3.2-3B shape with ragged
-    contexts and a shared 1024-token prefix; Qwen3-8B shape, context 4096):
-    the GPU decodes all 16 rows, the oracle the sampled rows; every logit of
-    those rows is compared, and append addressing is checked for all rows.
-    cfg4_l4 is the 30B-A3B mixture-of-experts shape (128 experts, top 8, expert
-    width 768, ragged contexts with a shared 2048-token prefix) cut to 4 layers
-    so that its weights are 5 GB instead of 61 GB; cfg4 is the same shape with all 48 layers."""
+    """The batch-16 workloads at full size (Llama-3.2-3B shape with ragged contexts and a shared
+    1024-token prefix; Qwen3-8B shape, context 4096; the Qwen3-30B-A3B mixture-of-experts shape
+    with all 48 layers, 128 experts, top 8, ragged contexts and a shared 2048-token prefix): the
+    GPU decodes all 16 rows, the oracle the sampled rows, teacher-forced, for enough steps that
+    rows x steps >= 128 tokens stand behind the 99 % greedy-agreement bar; every logit of those
+    rows is compared, and append addressing is checked for all rows.  The 8B rows start at a block
+    boundary (4096) and cross another at 4112.  cfg4_l4 is the mixture-of-experts shape cut to 4
+    layers (5 GB of weights instead of 61), kept as a quick check.  Reported, not graded: the GPU
+    decoding the configured number of steps on its own tokens against the oracle on its own."""
     wl = W.WORKLOADS[wname]
     shape, lay = wl.cfg, layout_for(wl)
     if wl.n_sharers:
-        assert rows[0] < wl.n_sharers <= rows[1]          # a sharer and a non-sharer are sampled
+        n_sh = sum(r < wl.n_sharers for r in rows)
+        assert 0 < n_sh < len(rows)                       # sharers and non-sharers are sampled
     weights = W.make_weights(shape, wl.seed_weights)
     pool = W.fill_kv_pool(shape, lay, wl.seed_kv)
     tokens = W.initial_tokens(shape, wl.batch, wl.seed_tokens)
-    out = run_sampled(orc, shape, weights, lay, pool, tokens, steps, rows)
-    worst, agree = check_parity(out)
-    print(f"{wname}: worst rel-L2 {worst:.3e}, greedy agreement {agree:.3f} on rows {rows}")
-    assert worst < TIGHT
+    out = run_sampled(orc, shape, weights, lay, pool, tokens, steps, rows, free_steps=wl.steps)
+    check_parity(out)
+    st = parity_stats(out)
+    fr_agree, fr_first = free_running_report(out["free_next"], out["orc_next"], rows)
+    boundary = sum(int((int(lay.contexts[r]) + s) % 16 == 0) for r in rows for s in range(steps))
+    log_result(f"{wname} full size: {st['tokens']} tokens teacher-forced (rows {rows} x {steps} steps, "
+               f"{boundary} of them opening a block), greedy agreement {st['agree']:.4f}, logits rel-L2 worst "
+               f"{st['worst']:.3e} mean {st['mean']:.3e}; free-running ({wl.steps} steps run, {steps} compared) "
+               f"agreement {fr_agree:.3f}, first divergence at step {fr_first}")
+    assert st["tokens"] == len(rows) * steps and st["agree"] >= 0.99
+    if wname != "cfg4_l4":
+        assert st["tokens"] >= 128 and boundary > 0
+    assert st["worst"] < TIGHT
+    for f in out["free_next"]:
+        assert ((f >= 0) & (f < shape.vocab)).all()
     check_pool_sampled(out, pool, shape, lay, steps, rows)
 
 

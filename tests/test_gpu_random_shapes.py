@@ -86,5 +86,5 @@ def test_random_shape(orc, seed):
         worst, agree = check_parity(out)
         check_pool(out, pool, shape, lay, steps)
     assert worst < TIGHT, (desc, worst)
-    # a router near-tie may legitimately pick another expert and move a greedy token; dense models must agree fully
-    assert agree == 1.0 or (shape.n_experts and agree >= 0.9), (desc, agree)
+    # check_parity has already held the contract's 99 %; with these seeds every token agrees
+    assert agree == 1.0, (desc, agree)
