@@ -279,10 +279,30 @@ static void swiglu(const uint16_t *wg, const uint16_t *wu, const uint16_t *wd,
     swiglu_any(wg, wu, wd, NULL, NULL, NULL, H, F, h, out);
 }
 
+/* Near-ties of the router.  The top-k choice is an integer decided by floating
+ * point: where the k-th and the (k+1)-th probability are closer than the arithmetic
+ * of the path under test resolves, another choice is as correct as this file's own,
+ * and everything after it (expert outputs, the cached k/v of later layers, the
+ * logits) follows that choice.  A test may therefore PROPOSE an expert set for a
+ * (layer, sequence).  route() adopts a proposal only if it is itself a valid top-k
+ * set up to the relative tolerance `tol`: k distinct experts, each with a
+ * probability of at least (1 - tol) times the largest probability left out.
+ * Anything else is ignored and this file's own choice stands.  With no proposal
+ * (every caller but that test) nothing changes. */
+typedef struct {
+    const int32_t *proposal;   /* [n_layers][B][top_k] or NULL */
+    double tol;
+    int32_t *adopted;          /* [n_layers][B] out: 1 where a differing proposal was adopted */
+    double *margin;            /* [n_layers][B] out: (largest left out - smallest proposed) / largest
+                                  left out, where the proposal differed from the own choice; else 0 */
+} orc_tie;
+
 /* Router: softmax over all experts, the top_k largest probabilities (ties to
- * the lower expert index), renormalised to sum to one. */
+ * the lower expert index), renormalised to sum to one.  proposal / tol /
+ * adopted / margin: see orc_tie (proposal NULL: the plain definition). */
 static void route(const orc_config *c, const uint16_t *w_router, const real *h,
-                  int32_t *idx, real *wts)
+                  int32_t *idx, real *wts, const int32_t *proposal, double tol,
+                  int32_t *adopted, double *margin)
 {
     int E = c->n_experts, K = c->top_k;
     real *logit = (real *)malloc(sizeof(real) * (size_t)E);
@@ -290,16 +310,51 @@ static void route(const orc_config *c, const uint16_t *w_router, const real *h,
     char *taken = (char *)calloc((size_t)E, 1);
     matvec(w_router, E, c->hidden, h, logit);
     softmax(logit, E, prob);
-    real sum = 0;
     for (int k = 0; k < K; k++) {
         int best = -1;
         for (int e = 0; e < E; e++)
             if (!taken[e] && (best < 0 || prob[e] > prob[best])) best = e;
         taken[best] = 1;
         idx[k] = best;
-        wts[k] = prob[best];
-        sum += prob[best];
     }
+    if (adopted) *adopted = 0;
+    if (margin) *margin = 0;
+    if (proposal) {
+        /* is the proposal a set of K distinct experts other than the own choice? */
+        char *in = (char *)calloc((size_t)E, 1);
+        int ok = 1, same = 1;
+        for (int k = 0; k < K; k++) {
+            int e = proposal[k];
+            if (e < 0 || e >= E || in[e]) { ok = 0; break; }
+            in[e] = 1;
+            if (!taken[e]) same = 0;
+        }
+        if (ok && !same) {
+            real pmin = 0, pout = 0;
+            int first = 1, any_out = 0;
+            for (int e = 0; e < E; e++) {
+                if (in[e]) { if (first || prob[e] < pmin) pmin = prob[e]; first = 0; }
+                else if (!any_out || prob[e] > pout) { pout = prob[e]; any_out = 1; }
+            }
+            double m = any_out && pout > 0 ? (double)(pout - pmin) / (double)pout : 0.0;
+            if (margin) *margin = m;
+            if (m <= tol) {
+                /* adopt: the proposed experts, largest probability first (ties to the lower index) */
+                memset(taken, 0, (size_t)E);
+                for (int k = 0; k < K; k++) {
+                    int best = -1;
+                    for (int e = 0; e < E; e++)
+                        if (in[e] && !taken[e] && (best < 0 || prob[e] > prob[best])) best = e;
+                    taken[best] = 1;
+                    idx[k] = best;
+                }
+                if (adopted) *adopted = 1;
+            }
+        }
+        free(in);
+    }
+    real sum = 0;
+    for (int k = 0; k < K; k++) { wts[k] = prob[idx[k]]; sum += wts[k]; }
     for (int k = 0; k < K; k++) wts[k] = wts[k] / sum;
     free(logit);
     free(prob);
@@ -309,13 +364,14 @@ static void route(const orc_config *c, const uint16_t *w_router, const real *h,
 /* qg / qu / qd: NULL, or the 4-bit gate / up / down matrices of ALL experts stacked by rows
  * (expert e owns rows e*Fe.. of gate and up, rows e*H.. of down); the router stays bf16. */
 static void moe_any(const orc_config *c, const orc_layer *L, const orc_q4 *qg, const orc_q4 *qu, const orc_q4 *qd,
-                    const real *h, real *out, int32_t *idx_out, real *wts_out)
+                    const real *h, real *out, int32_t *idx_out, real *wts_out,
+                    const int32_t *proposal, double tol, int32_t *adopted, double *margin)
 {
     int H = c->hidden, Fe = c->expert_ffn, K = c->top_k;
     int32_t *idx = (int32_t *)malloc(sizeof(int32_t) * (size_t)K);
     real *wts = (real *)malloc(sizeof(real) * (size_t)K);
     real *y = (real *)malloc(sizeof(real) * (size_t)H);
-    route(c, L->w_router, h, idx, wts);
+    route(c, L->w_router, h, idx, wts, proposal, tol, adopted, margin);
     for (int i = 0; i < H; i++) out[i] = 0;
     for (int k = 0; k < K; k++) {
         int64_t e = idx[k];
@@ -340,7 +396,7 @@ static void moe_any(const orc_config *c, const orc_layer *L, const orc_q4 *qg, c
 static void moe(const orc_config *c, const orc_layer *L, const real *h, real *out,
                 int32_t *idx_out, real *wts_out)
 {
-    moe_any(c, L, NULL, NULL, NULL, h, out, idx_out, wts_out);
+    moe_any(c, L, NULL, NULL, NULL, h, out, idx_out, wts_out, NULL, 0.0, NULL, NULL);
 }
 
 /* -------------------------------------------------------------- argmax -- */
@@ -454,7 +510,7 @@ static int decode_step_body(const orc_config *c, const orc_layer *layers, const 
                             const int32_t *block_tables, int32_t max_blocks_per_seq,
                             const int32_t *seq_lens, const int32_t *tokens, int32_t B,
                             float *logits, int32_t *next_tokens, float *trace_x,
-                            int32_t *trace_experts)
+                            int32_t *trace_experts, const orc_tie *tie)
 {
     int H = c->hidden, d = c->head_dim, nq = c->n_q_heads, nkv = c->n_kv_heads;
     int V = c->vocab;
@@ -512,7 +568,10 @@ static int decode_step_body(const orc_config *c, const orc_layer *layers, const 
             rmsnorm(x, H, L->g_mlp, (real)c->rms_eps, h);
             if (c->n_experts > 0)
                 moe_any(c, L, Q ? Q + Q4_GATE : NULL, Q ? Q + Q4_UP : NULL, Q ? Q + Q4_DOWN : NULL, h, y,
-                        trace_experts ? trace_experts + ((int64_t)l * B + b) * c->top_k : NULL, NULL);
+                        trace_experts ? trace_experts + ((int64_t)l * B + b) * c->top_k : NULL, NULL,
+                        tie && tie->proposal ? tie->proposal + ((int64_t)l * B + b) * c->top_k : NULL,
+                        tie ? tie->tol : 0.0, tie && tie->adopted ? tie->adopted + (int64_t)l * B + b : NULL,
+                        tie && tie->margin ? tie->margin + (int64_t)l * B + b : NULL);
             else
                 swiglu_any(L->w_gate, L->w_up, L->w_down, Q ? Q + Q4_GATE : NULL, Q ? Q + Q4_UP : NULL,
                            Q ? Q + Q4_DOWN : NULL, H, c->ffn, h, y);
@@ -541,7 +600,25 @@ int orc_decode_step(const orc_config *c, const orc_layer *layers,
 {
     return decode_step_body(c, layers, NULL, embed, g_final, lm_head, pool, num_blocks, block_size,
                             block_tables, max_blocks_per_seq, seq_lens, tokens, B, logits,
-                            next_tokens, trace_x, trace_experts);
+                            next_tokens, trace_x, trace_experts, NULL);
+}
+
+/* orc_decode_step of a mixture-of-experts model with proposed expert sets for the
+ * router's near-ties (see orc_tie): proposal int32 [n_layers][B][top_k]; a proposal
+ * is adopted only where it is a valid top-k set up to tie_tol; adopted int32
+ * [n_layers][B] and margin double [n_layers][B] report what happened. */
+int orc_decode_step_tie(const orc_config *c, const orc_layer *layers,
+                        const uint16_t *embed, const uint16_t *g_final, const uint16_t *lm_head,
+                        uint16_t *pool, int32_t num_blocks, int32_t block_size,
+                        const int32_t *block_tables, int32_t max_blocks_per_seq,
+                        const int32_t *seq_lens, const int32_t *tokens, int32_t B,
+                        float *logits, int32_t *next_tokens, int32_t *trace_experts,
+                        const int32_t *proposal, double tie_tol, int32_t *adopted, double *margin)
+{
+    const orc_tie tie = {proposal, tie_tol, adopted, margin};
+    return decode_step_body(c, layers, NULL, embed, g_final, lm_head, pool, num_blocks, block_size,
+                            block_tables, max_blocks_per_seq, seq_lens, tokens, B, logits,
+                            next_tokens, NULL, trace_experts, &tie);
 }
 
 /* The same step for a model with 4-bit projections.  q_ptrs / scale_ptrs /
@@ -569,12 +646,16 @@ int orc_decode_step_q4(const orc_config *c, const orc_layer *layers,
     }
     int rc = decode_step_body(c, layers, m, embed, g_final, NULL, pool, num_blocks, block_size,
                               block_tables, max_blocks_per_seq, seq_lens, tokens, B, logits,
-                              next_tokens, trace_x, trace_experts);
+                              next_tokens, trace_x, trace_experts, NULL);
     free(m);
     return rc;
 }
 
 /* ------------------------------------- stage entry points for the tests -- */
+/* route() alone, with an optional proposal: idx int32 [top_k], wts double [top_k]. */
+void orc_route(const orc_config *c, const uint16_t *w_router, const double *h, int32_t *idx, double *wts,
+               const int32_t *proposal, double tol, int32_t *adopted, double *margin);
+
 /* Thin wrappers taking float64 arrays so that each stage can be pinned alone. */
 
 static real *to_real(const double *a, int64_t n)
@@ -675,3 +756,15 @@ void orc_moe(const orc_config *c, const orc_layer *L, const double *h, double *o
 }
 
 double orc_silu(double z) { return (double)silu((real)z); }
+
+void orc_route(const orc_config *c, const uint16_t *w_router, const double *h, int32_t *idx, double *wts,
+               const int32_t *proposal, double tol, int32_t *adopted, double *margin)
+{
+    real *hr = (real *)malloc(sizeof(real) * (size_t)c->hidden);
+    real *w = (real *)malloc(sizeof(real) * (size_t)c->top_k);
+    for (int i = 0; i < c->hidden; i++) hr[i] = (real)h[i];
+    route(c, w_router, hr, idx, w, proposal, tol, adopted, margin);
+    for (int k = 0; k < c->top_k; k++) wts[k] = (double)w[k];
+    free(hr);
+    free(w);
+}

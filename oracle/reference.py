@@ -222,6 +222,53 @@ class Oracle:
         return float(self.lib.orc_sample_uniform(C.c_uint64(seed), C.c_uint64(step), C.c_uint32(row)))
 
     # -- whole step -------------------------------------------------------
+    def route(self, cfg, w_router_bits, h, proposal=None, tie_tol=0.0):
+        """The router alone: (experts int32 [k], weights [k], adopted, margin)."""
+        c = self.config(cfg)
+        h = _f64(h)
+        idx = np.empty(cfg.top_k, dtype=np.int32)
+        wts = np.empty(cfg.top_k, dtype=np.float64)
+        adopted = C.c_int32(0)
+        margin = C.c_double(0.0)
+        prop = None if proposal is None else _i32(proposal)
+        self.lib.orc_route.restype = None
+        self.lib.orc_route(C.byref(c), _p(_u16(w_router_bits)), _p(h), _p(idx), _p(wts), _p(prop),
+                           C.c_double(tie_tol), C.byref(adopted), C.byref(margin))
+        return idx, wts, bool(adopted.value), margin.value
+
+    def decode_step_tie(self, cfg, weights, pool, block_size, block_tables, seq_lens, tokens, proposal, tie_tol):
+        """decode_step of a mixture-of-experts model (bf16 weights) with expert sets proposed for
+        the router's near-ties: proposal int32 [L, B, top_k]; adopted only where it is a valid
+        top-k set up to tie_tol (see decode_oracle.c).  Adds 'adopted' int32 [L, B] and 'margin'
+        float64 [L, B] to the result."""
+        c = self.config(cfg)
+        assert pool.dtype == np.uint16 and pool.flags.c_contiguous and cfg.n_experts
+        L = cfg.n_layers
+        structs = (_Layer * L)()
+        keep = []
+        for i, lay in enumerate(weights["layers"]):
+            s = self.layer_struct(lay)
+            keep.append(s)
+            structs[i] = s
+        bt, sl, tk = _i32(block_tables), _i32(seq_lens), _i32(tokens)
+        B = tk.size
+        prop = _i32(proposal)
+        assert prop.shape == (L, B, cfg.top_k)
+        logits = np.empty((B, cfg.vocab), dtype=np.float32)
+        nxt = np.empty(B, dtype=np.int32)
+        experts = np.empty((L, B, cfg.top_k), dtype=np.int32)
+        adopted = np.zeros((L, B), dtype=np.int32)
+        margin = np.zeros((L, B), dtype=np.float64)
+        self.lib.orc_decode_step_tie.restype = C.c_int
+        rc = self.lib.orc_decode_step_tie(
+            C.byref(c), structs, _p(_u16(weights["embed"])), _p(_u16(weights["g_final"])),
+            _p(_u16(weights["lm_head"])), _p(pool), C.c_int32(pool.shape[1]), C.c_int32(block_size),
+            _p(bt), C.c_int32(bt.shape[1]), _p(sl), _p(tk), C.c_int32(B),
+            _p(logits), _p(nxt), _p(experts), _p(prop), C.c_double(tie_tol), _p(adopted), _p(margin))
+        if rc != 0:
+            raise ValueError(f"orc_decode_step_tie rejected its arguments (code {rc})")
+        return {"next": nxt, "logits": logits, "experts": experts, "adopted": adopted, "margin": margin}
+
     def decode_step(self, cfg, weights, pool, block_size, block_tables, seq_lens, tokens,
                     want_logits=True, want_trace=False):
         """One decode step for every row of the batch.  `pool` (uint16,

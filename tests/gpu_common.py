@@ -5,6 +5,16 @@ import numpy as np
 import workloads as W
 
 
+# Router near-ties.  An expert set of the kernel that differs from the oracle's own is accepted as
+# the oracle's choice for that (layer, row) only if it is a valid top-k set up to this relative
+# margin of the probabilities (oracle/decode_oracle.c, orc_tie).  Derivation: a router logit is a
+# dot product of the normalised residual (relative error of the float32 path up to ~1.5e-4 after
+# dozens of layers: the measured worst logits rel-L2) with a row of magnitude ~1, so two logits'
+# difference is off by ~2e-4 (one sigma); a probability ratio moves by the same amount.  1e-3 is
+# five sigma of that.  A wrong router (a dropped term, a wrong row) misses by orders of magnitude more.
+TIE_TOL = 1e-3
+
+
 def rel_l2(got, ref):
     got = got.astype(np.float64)
     ref = ref.astype(np.float64)
@@ -110,6 +120,19 @@ def free_running_report(free_next, orc_next, rows=None):
     return float((g == o).mean()), (int(differs[0]) if differs.size else None)
 
 
+def progress(line):
+    """A sign of life for long tests: appended to a file in the results folder of a GPU run (a
+    harness that watches for silence sees the file grow; pytest holds printed output back)."""
+    import os
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    try:
+        os.makedirs(os.path.join(root, "gpurun_out"), exist_ok=True)
+        with open(os.path.join(root, "gpurun_out", "test_progress.txt"), "a") as f:
+            f.write(line + "\n")
+    except OSError:
+        pass
+
+
 def log_result(line):
     """Prints a result line and, where the results folder of a GPU run exists or can be made,
     appends it there (pytest shows captured output only for failing tests)."""
@@ -124,9 +147,16 @@ def log_result(line):
         pass
 
 
-def check_pool(out, pool_before, shape, layout, steps):
+def check_pool(out, pool_before, shape, layout, steps, max_flips=0.02):
     """Appends must land at exactly the oracle's offsets; values may differ by
-    the bf16 rounding of nearly equal float32 numbers (<= 1 step, rarely)."""
+    the bf16 rounding of nearly equal float32 numbers (<= 1 step, rarely).
+
+    How rarely: two float32 computations of the same k or v element that differ
+    by a relative delta round to different bf16 neighbours with probability about
+    delta / 2^-8.  A short run has delta ~ 1e-5 (0.3 %: the default bound of 2 %
+    is generous); a run that has attended to more than a hundred of its own
+    appended tokens reaches delta ~ 1e-4, i.e. a few per cent, and passes its own
+    bound.  Returns the fraction that differed."""
     g, o = out["gpu_pool"], out["orc_pool"]
     g_changed = g != pool_before
     o_changed = o != pool_before
@@ -134,10 +164,12 @@ def check_pool(out, pool_before, shape, layout, steps):
     assert np.array_equal(g_changed, o_changed), "append addressing differs from the oracle"
     assert int(o_changed.sum()) == shape.n_layers * layout.tables.shape[0] * 2 * shape.kv_dim * steps
     assert bf16_close(g[o_changed], o[o_changed]).all(), "appended value differs by more than rounding"
-    assert (g[o_changed] != o[o_changed]).mean() < 0.02
+    flips = float((g[o_changed] != o[o_changed]).mean())
+    assert flips < max_flips, f"{flips:.4f} of the appended values differ by a rounding step"
+    return flips
 
 
-def run_sampled(orc, shape, weights, layout, pool_bits, tokens, steps, rows, free_steps=0):
+def run_sampled(orc, shape, weights, layout, pool_bits, tokens, steps, rows, free_steps=0, tie_tol=0.0):
     """Full-size variant: the GPU runs the whole batch, the oracle only the
     sampled `rows` (rows of a batch do not interact, so a row's result does not
     depend on which other rows are computed).  Sampled rows are teacher-forced
@@ -145,25 +177,40 @@ def run_sampled(orc, shape, weights, layout, pool_bits, tokens, steps, rows, fre
 
     Returns per-step logits/tokens of the sampled rows from both sides, the GPU
     pool, and the oracle pool (which holds only the sampled rows' appends).
+    tie_tol > 0 (mixture-of-experts models): see TIE_TOL.
     free_steps > 0: the GPU also decodes that many steps from the same start on
     its own tokens (the step advancing tokens and lengths on the device), all
     rows, into a second copy of the pool: out["free_next"][step] = tokens [B]."""
     import torch
     import paper_2601_19139_amd as dk
     rows = list(rows)
+    progress(f"{shape.name}: uploading weights")
     dm = dk.DeviceModel(shape, weights)
     dkv = dk.DeviceKV(dm, layout, pool_bits)
     opool = pool_bits.copy()
     sl = layout.contexts.copy().astype(np.int32)
     tok = np.asarray(tokens, dtype=np.int32).copy()
     dec = dk.Decoder(dm, dkv, sl, tok)
-    out = {"gpu_logits": [], "orc_logits": [], "gpu_next": [], "orc_next": []}
+    out = {"gpu_logits": [], "orc_logits": [], "gpu_next": [], "orc_next": [], "ties": [], "tie_refused": []}
+    q4 = isinstance(weights["lm_head"], dict)
     for s in range(steps):
         dk.kv_validate_tables(dkv.handle, layout.tables, sl)
-        step = orc.decode_step_q4 if isinstance(weights["lm_head"], dict) else orc.decode_step
-        r = step(shape, weights, opool, layout.block_size, layout.tables[rows], sl[rows], tok[rows])
         dec.step()
         torch.cuda.synchronize()
+        if tie_tol and shape.n_experts and not q4:
+            # the router's top-k is an integer decided by floating point: the kernel's expert sets go
+            # to the oracle as proposals, which it adopts only where they are valid up to tie_tol
+            prop = np.ascontiguousarray(dec.routing()[:, rows, :])
+            r = orc.decode_step_tie(shape, weights, opool, layout.block_size, layout.tables[rows], sl[rows],
+                                    tok[rows], prop, tie_tol)
+            for l, i in zip(*np.nonzero(r["adopted"])):
+                out["ties"].append((s, int(l), rows[i], float(r["margin"][l, i])))
+            for l, i in zip(*np.nonzero((r["margin"] > tie_tol))):
+                out["tie_refused"].append((s, int(l), rows[i], float(r["margin"][l, i])))
+        else:
+            step = orc.decode_step_q4 if q4 else orc.decode_step
+            r = step(shape, weights, opool, layout.block_size, layout.tables[rows], sl[rows], tok[rows])
+        progress(f"{shape.name}: oracle step {s + 1}/{steps} of rows {rows}")
         g_next = dec.next.cpu().numpy().copy()
         out["gpu_logits"].append(dec.logits[rows].cpu().numpy().copy())
         out["gpu_next"].append(g_next[rows])

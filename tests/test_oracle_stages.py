@@ -274,6 +274,101 @@ def test_moe_reductions(orc):
     assert list(idx_tie) == list(range(cfg.top_k)) and np.allclose(wts_tie, 1 / cfg.top_k)
 
 
+def test_router_adopts_only_valid_proposals(orc):
+    """A proposed expert set replaces the router's own top-k only where it is a valid top-k set up
+    to the tolerance (every proposed expert within (1 - tol) of the best one left out); pinned against
+    a numpy statement of that rule, an exact tie, and the whole step."""
+    cfg = W.CONFIGS["tiny_moe"]
+    lay = _moe_layer(cfg, 5)
+    h = RNG.standard_normal(cfg.hidden)
+    logits = vals(lay["w_router"]) @ h
+    p = np.exp(logits - logits.max())
+    p /= p.sum()
+    order = sorted(range(cfg.n_experts), key=lambda e: (-p[e], e))
+    own, runner = order[: cfg.top_k], order[cfg.top_k]
+    idx, wts, adopted, margin = orc.route(cfg, lay["w_router"], h)
+    assert list(idx) == own and not adopted and margin == 0.0
+    # the own set in another order: nothing to adopt, nothing changes
+    idx2, wts2, adopted, margin = orc.route(cfg, lay["w_router"], h, proposal=own[::-1], tie_tol=1.0)
+    assert list(idx2) == own and np.array_equal(wts2, wts) and not adopted
+    # the runner-up instead of the k-th: adopted exactly when the tolerance covers the margin
+    prop = own[:-1] + [runner]
+    want_margin = (p[own[-1]] - p[runner]) / p[own[-1]]
+    assert want_margin > 1e-6                       # random logits: no accidental tie
+    for tol, expect in ((want_margin * 0.99, False), (want_margin * 1.01, True)):
+        idx3, wts3, adopted, margin = orc.route(cfg, lay["w_router"], h, proposal=prop, tie_tol=tol)
+        assert adopted == expect and abs(margin - want_margin) < 1e-12
+        chosen = sorted(prop, key=lambda e: (-p[e], e)) if expect else own
+        assert list(idx3) == chosen
+        assert np.allclose(wts3, p[chosen] / p[chosen].sum(), rtol=1e-12)
+    # a proposal that leaves out the best expert for the worst: margin near 1, refused at any sane tolerance
+    bad = own[1:] + [order[-1]]
+    idx4, _, adopted, margin = orc.route(cfg, lay["w_router"], h, proposal=bad, tie_tol=1e-3)
+    assert list(idx4) == own and not adopted and margin > 0.1
+    # malformed proposals (repeated or out-of-range experts) are ignored
+    for junk in ([own[0]] * cfg.top_k, [cfg.n_experts] + own[1:], [-1] + own[1:]):
+        idx5, _, adopted, _ = orc.route(cfg, lay["w_router"], h, proposal=junk, tie_tol=1.0)
+        assert list(idx5) == own and not adopted
+    # an exact tie: two experts with the same router row; either set is valid at tolerance 0
+    tie = dict(lay)
+    wr = lay["w_router"].copy()
+    a, b = own[-1], runner
+    wr[b] = wr[a]
+    tie["w_router"] = wr
+    lo, hi = min(a, b), max(a, b)
+    idx6, _, adopted, _ = orc.route(cfg, wr, h)
+    assert lo in idx6 and hi not in idx6            # ties go to the lower index
+    swapped = [e for e in idx6 if e != lo] + [hi]
+    idx7, wts7, adopted, margin = orc.route(cfg, wr, h, proposal=swapped, tie_tol=0.0)
+    assert adopted and margin == 0.0 and hi in idx7 and lo not in idx7
+
+
+def test_step_with_adopted_proposal_equals_step_of_relabelled_model(orc):
+    """Whole step.  Two experts of layer 1 get the same router row, an exact tie; the plain step
+    takes the lower index.  Proposing the higher one (tolerance 0) must give, bit for bit, what the
+    plain step gives on the model with those two experts' weights exchanged: the same probabilities
+    in the same places, the other expert's matrices."""
+    from workloads.blocktable import layout_for
+    wl = W.WORKLOADS["cfg0_moe"]
+    shape, lay = wl.cfg, layout_for(wl)
+    weights = W.make_weights(shape, wl.seed_weights)
+    pool = W.fill_kv_pool(shape, lay, wl.seed_kv, poison=False)
+    tokens = W.initial_tokens(shape, wl.batch, wl.seed_tokens)
+
+    def step(w, **kw):
+        return orc.decode_step(shape, w, pool.copy(), 16, lay.tables, lay.contexts, tokens, want_trace=True, **kw)
+
+    own = list(step(weights)["experts"][1][0])          # row 0, layer 1: largest probability first
+    a = own[-1]
+    b = next(e for e in range(shape.n_experts) if e not in own)
+    lo, hi = min(a, b), max(a, b)
+    L1 = weights["layers"][1]
+    wr = L1["w_router"].copy()
+    wr[b] = wr[a]
+    tied = dict(weights, layers=[weights["layers"][0], dict(L1, w_router=wr)])
+    base = step(tied)
+    assert lo in base["experts"][1][0] and hi not in base["experts"][1][0]
+    proposal = base["experts"].copy()
+    proposal[1][0] = [hi if e == lo else e for e in base["experts"][1][0]]
+    got = orc.decode_step_tie(shape, tied, pool.copy(), 16, lay.tables, lay.contexts, tokens, proposal, 0.0)
+    assert got["adopted"].sum() == 1 and got["adopted"][1][0] == 1 and got["margin"][1][0] == 0.0
+    assert hi in got["experts"][1][0] and lo not in got["experts"][1][0]
+    swap = {k: L1[k].copy() for k in ("w_gate", "w_up", "w_down")}
+    for k in swap:
+        swap[k][[lo, hi]] = swap[k][[hi, lo]]
+    relabelled = dict(weights, layers=[weights["layers"][0], dict(L1, w_router=wr, **swap)])
+    want = step(relabelled)
+    assert np.array_equal(got["logits"][0], want["logits"][0]) and got["next"][0] == want["next"][0]
+    assert not np.array_equal(got["logits"][0], base["logits"][0])
+    # a proposal equal to the own choice everywhere is the plain step, whatever the tolerance
+    same = orc.decode_step_tie(shape, tied, pool.copy(), 16, lay.tables, lay.contexts, tokens, base["experts"], 1.0)
+    assert same["adopted"].sum() == 0 and np.array_equal(same["logits"], base["logits"])
+    # on the untied model the same proposal is no tie (margin above zero): refused at tolerance 0
+    far = orc.decode_step_tie(shape, weights, pool.copy(), 16, lay.tables, lay.contexts, tokens,
+                              step(weights)["experts"][:, :, ::-1].copy(), 0.0)
+    assert far["adopted"].sum() == 0 and np.array_equal(far["logits"], step(weights)["logits"])
+
+
 # ---------------------------------------------------------------- argmax --
 def test_argmax_planted_and_ties(orc):
     v = RNG.standard_normal(1000).astype(np.float32)
