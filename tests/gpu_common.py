@@ -21,14 +21,15 @@ def rel_l2(got, ref):
     return np.linalg.norm(got - ref, axis=-1) / np.linalg.norm(ref, axis=-1)
 
 
-def bf16_close(a_bits, b_bits):
+def bf16_close(a_bits, b_bits, drift=1e-4):
     """True where two stored bf16 values agree up to rounding: the float32
-    values they were rounded from differ by at most 1e-4 of the largest
-    magnitude (ten times the measured error of the path), and rounding adds at
-    most one bf16 step (2^-7 relative) on top of that."""
+    values they were rounded from differ by at most `drift` of the largest
+    magnitude (1e-4: ten times the measured error of a short run; a run whose
+    logits have drifted further from the oracle's passes a bound in proportion),
+    and rounding adds at most one bf16 step (2^-7 relative) on top of that."""
     a = W.f32_from_bf16_bits(a_bits).astype(np.float64)
     b = W.f32_from_bf16_bits(b_bits).astype(np.float64)
-    floor = 1e-4 * max(float(np.abs(b).max()), 1e-30)
+    floor = drift * max(float(np.abs(b).max()), 1e-30)
     return np.abs(a - b) <= 2.0 ** -7 * np.maximum(np.abs(a), np.abs(b)) + floor
 
 
@@ -245,7 +246,7 @@ def free_run(dk, dm, layout, pool_bits, tokens, steps):
     return [g.cpu().numpy() for g in got]
 
 
-def check_pool_sampled(out, pool_before, shape, layout, steps, rows):
+def check_pool_sampled(out, pool_before, shape, layout, steps, rows, drift=1e-4):
     """Addressing for every row against the closed-form slot list (block
     table entry T // 16, slot T % 16, every layer, K and V, every kv head);
     values of the sampled rows against the oracle's pool."""
@@ -268,4 +269,10 @@ def check_pool_sampled(out, pool_before, shape, layout, steps, rows):
                 # poisoned beforehand, so a written slot holds no NaN pattern any more
                 assert not np.any(g[l, blk, :, :, sl_, :] == W.BF16_NAN_BITS), "append slot not written"
                 if b in rows:
-                    assert bf16_close(g[l, blk, :, :, sl_, :], o[l, blk, :, :, sl_, :]).all()
+                    ga, oa = g[l, blk, :, :, sl_, :], o[l, blk, :, :, sl_, :]
+                    if not bf16_close(ga, oa, drift).all():
+                        a = W.f32_from_bf16_bits(ga).astype(np.float64)
+                        r = W.f32_from_bf16_bits(oa).astype(np.float64)
+                        excess = (np.abs(a - r) - 2.0 ** -7 * np.maximum(np.abs(a), np.abs(r))).max() / np.abs(r).max()
+                        raise AssertionError(f"layer {l} row {b} slot {sl_}: appended value off by a bf16 step plus "
+                                             f"{excess:.2e} of the largest magnitude (allowed {drift:.1e})")

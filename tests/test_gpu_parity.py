@@ -352,7 +352,9 @@ def test_batch16_full_size_sampled_rows(dk, orc, wname, rows, steps):
     assert st["worst"] < (5e-4 if wname == "cfg4" else TIGHT)
     for f in out["free_next"]:
         assert ((f >= 0) & (f < shape.vocab)).all()
-    check_pool_sampled(out, pool, shape, lay, steps, rows)
+    # appended values: one bf16 step plus ten times the drift of the float32 values behind them,
+    # which follows the logits' (1e-4 elsewhere, up to 2.7e-4 for the 48-layer mixture of experts)
+    check_pool_sampled(out, pool, shape, lay, steps, rows, drift=3e-3 if wname == "cfg4" else 1e-4)
 
 
 @pytest.mark.parametrize("batch", [16, 20, 40, 64])
