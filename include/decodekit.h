@@ -262,6 +262,32 @@ dk_status dk_decode_step(dk_model *model, dk_kv_pool *pool, const int32_t *d_blo
                          int32_t *d_next_tokens, uint32_t flags, void *hip_stream);
 
 /*
+ * dk_decode_step for callers that cannot allocate device memory (code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc): the same
+ * step with the workspace taken from a fixed device array inside the library
+ * instead of a caller buffer.  The call allocates nothing, on the device or
+ * through any allocating library routine.
+ *
+ * Same arguments, results and error behaviour as dk_decode_step without
+ * d_workspace / workspace_bytes.  Limits and rules of its own:
+ *   - the step's workspace (dk_workspace_bytes for this B and table width) must
+ *     fit DK_STATIC_SCRATCH_BYTES; otherwise DK_E_WORKSPACE_TOO_SMALL and nothing
+ *     is launched (every workload shape of this library at up to 64 rows fits);
+ *   - DK_STEP_PROFILE is refused (it creates events): DK_E_INVALID_ARG;
+ *   - every GPU the library runs on holds its own copy of the array until the
+ *     process ends, and every call on a GPU uses that GPU's copy: calls that
+ *     overlap on one GPU (two streams, two threads) race, so order them; a
+ *     call keeps no results in the array beyond what the persistent step kernel
+ *     prepares for the next step of the same model, and the library notices
+ *     when another model used the array in between and starts over by itself.
+ */
+#define DK_STATIC_SCRATCH_BYTES ((size_t)64 << 20)
+dk_status dk_decode_step_static(dk_model *model, dk_kv_pool *pool, const int32_t *d_block_tables,
+                                int32_t max_blocks_per_seq, int32_t *d_seq_lens, int32_t *d_tokens,
+                                int32_t B, float *d_logits, int32_t *d_next_tokens, uint32_t flags,
+                                void *hip_stream);
+
+/*
  * Chunked prefill of one sequence: what n decode steps of that sequence fed
  * with the prompt tokens d_tokens[0..n) would do, in one pass.  This is the step
  * that turns the part of a prompt behind the cached prefix into KV state

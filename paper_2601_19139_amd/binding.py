@@ -74,6 +74,8 @@ _SIGNATURES = {
     "dk_decode_step": (C.c_int32, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p,
                                    C.c_int32, C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p,
                                    C.c_uint32, C.c_void_p]),
+    "dk_decode_step_static": (C.c_int32, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p,
+                                          C.c_int32, C.c_void_p, C.c_void_p, C.c_uint32, C.c_void_p]),
     "dk_prefill_chunk": (C.c_int32, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p,
                                      C.c_int32, C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p, C.c_void_p]),
     "dk_workspace_reset": (C.c_int32, [C.c_void_p]),
@@ -280,6 +282,17 @@ def decode_step(model, pool, d_block_tables, d_seq_lens, d_tokens, d_workspace, 
     _check(lib().dk_decode_step(model, pool, _ptr(d_block_tables), mb, _ptr(d_seq_lens),
                                 _ptr(d_tokens), B, _ptr(d_workspace), nbytes, _ptr(d_logits),
                                 _ptr(d_next_tokens), flags, _stream(stream)))
+
+
+STATIC_SCRATCH_BYTES = 64 << 20
+
+
+def decode_step_static(model, pool, d_block_tables, d_seq_lens, d_tokens, d_logits, d_next_tokens,
+                       flags: int = 0, stream=None):
+    """dk_decode_step with the library's own fixed device scratch (allocates nothing)."""
+    B, mb = d_block_tables.shape
+    _check(lib().dk_decode_step_static(model, pool, _ptr(d_block_tables), mb, _ptr(d_seq_lens), _ptr(d_tokens), B,
+                                       _ptr(d_logits), _ptr(d_next_tokens), flags, _stream(stream)))
 
 
 def prefill_chunk(model, pool, d_block_table, start: int, d_tokens, d_workspace, workspace_bytes_: int,

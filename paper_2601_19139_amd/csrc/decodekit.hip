@@ -24,9 +24,22 @@
 #include "dk_moe.hip.h"
 #include "dk_sample.hip.h"
 
+#include <mutex>
+
+// Device scratch of dk_decode_step_static: one copy per GPU, held until the process ends.  In host
+// code this name is only a handle for hipGetSymbolAddress, never a device address.
+static __device__ __align__(256) unsigned char scratch[DK_STATIC_SCRATCH_BYTES];
+
 namespace {
 
 thread_local char g_err[512] = "";
+
+// Per GPU: the address of that GPU's copy of `scratch` (looked up on the entry point's first call
+// there) and the model whose step used it last (the persistent kernel keeps state in it).
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[kMaxDevices] = {};
+const void *g_scratch_owner[kMaxDevices] = {};
 
 dk_status fail(dk_status code, const char *fmt, ...)
 {
@@ -981,6 +994,12 @@ dk_status dk_create_model_q4(const dk_model_config *cfg, const dk_weight_ptrs *w
 
 dk_status dk_destroy_model(dk_model *model)
 {
+    if (model) {
+        // a later model at the same address must not pass for the last user of the static scratch
+        std::lock_guard<std::mutex> lock(g_scratch_mutex);
+        for (auto &o : g_scratch_owner)
+            if (o == model) o = nullptr;
+    }
     delete model;
     return DK_OK;
 }
@@ -1038,6 +1057,45 @@ dk_status dk_decode_step(dk_model *model, dk_kv_pool *pool, const int32_t *d_blo
     if (s != DK_OK) return s;
     if (e != hipSuccess) return fail(DK_E_HIP, "hipStreamSynchronize: %s", hipGetErrorString(e));
     return DK_OK;
+}
+
+dk_status dk_decode_step_static(dk_model *model, dk_kv_pool *pool, const int32_t *d_block_tables,
+                                int32_t max_blocks, int32_t *d_seq_lens, int32_t *d_tokens, int32_t B,
+                                float *d_logits, int32_t *d_next_tokens, uint32_t flags, void *hip_stream)
+{
+    if (!model) return fail(DK_E_INVALID_ARG, "NULL argument");
+    if (flags & DK_STEP_PROFILE)
+        return fail(DK_E_INVALID_ARG, "DK_STEP_PROFILE creates events; the entry point that allocates nothing refuses it");
+    if (B <= 0 || B > DK_MAX_BATCH) return fail(DK_E_INVALID_ARG, "B %d (1..%d)", B, DK_MAX_BATCH);
+    if (max_blocks <= 0) return fail(DK_E_INVALID_ARG, "max_blocks_per_seq %d", max_blocks);
+    const size_t need = carve(model->cfg, B, max_blocks, model->q4).total;
+    if (need > DK_STATIC_SCRATCH_BYTES)
+        return fail(DK_E_WORKSPACE_TOO_SMALL,
+                    "this step needs %zu bytes of workspace; the static scratch holds %zu (use dk_decode_step "
+                    "with a caller-owned workspace)", need, (size_t)DK_STATIC_SCRATCH_BYTES);
+    int dev = 0;
+    DK_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return fail(DK_E_INVALID_ARG, "device index %d (below %d)", dev, kMaxDevices);
+    void *ws = nullptr;
+    {
+        std::lock_guard<std::mutex> lock(g_scratch_mutex);
+        if (g_scratch_ptr[dev] == nullptr) {
+            // once per GPU, with that GPU current: the address of its copy of the array
+            void *p = nullptr;
+            DK_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+            if (p == nullptr || (uintptr_t)p % 256) return fail(DK_E_HIP, "static scratch has no usable device address");
+            g_scratch_ptr[dev] = p;
+        }
+        ws = g_scratch_ptr[dev];
+        if (g_scratch_owner[dev] != model) {
+            // someone else's step has been through the array since this model's last one (or this
+            // is its first): whatever the persistent kernel had prepared there is gone
+            if (model->fused_ws == ws) model->fused_ws = nullptr;
+            g_scratch_owner[dev] = model;
+        }
+    }
+    return decode_step_impl(model, pool, d_block_tables, max_blocks, d_seq_lens, d_tokens, B, ws,
+                            DK_STATIC_SCRATCH_BYTES, d_logits, d_next_tokens, flags, hip_stream);
 }
 
 dk_status dk_prefill_chunk(dk_model *model, dk_kv_pool *pool, const int32_t *d_block_table,
