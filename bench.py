@@ -9,7 +9,9 @@ and greedy argmax - one new token for each of the B sequences.  Inputs
 region.  Prints one JSON line: the contract fields, `roofline` (the dominant kernel
 class against the published HBM peak and against a read-only streaming kernel
 measured on the spot), `step_roofline` (the whole step), per-kernel times, the
-batch-16 figure of the same model (batch-1 workloads) and the CPU oracle's rate.
+batch-16 figure of the same model (batch-1 workloads), in the default run the
+batch-16 workloads `cfg2`, `cfg3` and `cfg4_l4` timed the same way (their own keys),
+and the CPU oracle's rate.
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg1]
 """
@@ -265,6 +267,135 @@ def bench_ttft(args, wl, dk, W, np, torch):
     dk.destroy_kv_pool(pool)
 
 
+def measure_decode(args, wl, dk, W, np, torch, steps, warmup, ceiling=None):
+    """Times `steps` decode steps of a workload (inputs resident in HBM beforehand; wall clock around
+    the timed steps with a device synchronisation on both sides, HIP events on the launch stream for
+    the device time), then profiles a few more steps kernel by kernel.  Returns everything the
+    report needs; the model stays alive in the result for follow-up measurements."""
+    from workloads.blocktable import layout_for
+    shape, lay = wl.cfg, layout_for(wl)
+    weights = make_model_weights(args, W, shape, wl.seed_weights)
+    router_bytes = shape.n_layers * shape.n_experts * shape.hidden * 2    # routers stay bf16
+    weight_bytes = shape.dense_weight_bytes()                             # attention, dense MLP, lm_head, routers
+    one_expert_bytes = shape.expert_bytes()
+    if args.weights == "q4":
+        def q4(b):                                                        # 4 bits + (scale, bias) per 64 weights
+            return b // 4 + b // 128 * 4
+        weight_bytes = q4(weight_bytes - router_bytes) + router_bytes
+        one_expert_bytes = q4(one_expert_bytes)
+    pool_bits = W.fill_kv_pool(shape, lay, wl.seed_kv, poison=False)
+    tokens0 = W.initial_tokens(shape, wl.batch, wl.seed_tokens)
+
+    dm = dk.DeviceModel(shape, weights)
+    dkv = dk.DeviceKV(dm, lay, pool_bits)
+    dec = dk.Decoder(dm, dkv, lay.contexts, tokens0, want_logits=True)
+    d_ctx0 = dec.seq_lens.clone()
+    d_tok0 = dec.tokens.clone()
+    span = wl.steps                              # tokens of growth the block tables have room for
+
+    path_flag = dk.STEP_NO_FUSED if args.kernel_per_stage else 0
+
+    def restart():
+        dec.seq_lens.copy_(d_ctx0)
+        dec.tokens.copy_(d_tok0)
+
+    def run(n):
+        for i in range(n):
+            if i % span == 0:
+                restart()                        # back to the initial context (tables are sized for `span` steps)
+            dec.step(flags=dk.STEP_ADVANCE | path_flag)   # greedy: the step feeds its token to the next one
+
+    run(warmup)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    run(steps)
+    e1.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    dev_ms = e0.elapsed_time(e1)
+
+    ms_per_step = wall * 1e3 / steps
+    tok_s = wl.batch * steps / wall
+
+    # per-kernel times: a few more steps with start/stop events on every launch
+    prof_steps = min(16, span)
+    dk.profile_read(dm.handle, reset=True)
+    restart()
+    for _ in range(prof_steps):
+        dec.step(flags=dk.STEP_ADVANCE | dk.STEP_PROFILE | path_flag)
+    prof = dk.profile_read(dm.handle, reset=True)
+
+    # algorithmic bytes of a step at the mean context of the timed steps
+    n_in_span = min(steps, span)
+    mean_ctx = (lay.contexts + (n_in_span - 1) // 2).astype(np.int32)
+    distinct = None
+    if shape.n_experts:
+        routing = dec.routing()                                  # last profiled step
+        distinct = np.array([len(np.unique(routing[l])) for l in range(shape.n_layers)], dtype=np.int32)
+    alg_bytes = dk.step_algorithmic_bytes(dm.handle, dkv.handle, lay.tables, mean_ctx, with_logits=True,
+                                          distinct_experts_per_layer=distinct)
+    kv_bytes = dk.step_algorithmic_bytes(dm.handle, dkv.handle, lay.tables, mean_ctx, with_logits=False,
+                                         distinct_experts_per_layer=distinct) \
+        - weight_bytes - wl.batch * shape.hidden * 2 \
+        - (int(distinct.sum()) * one_expert_bytes if distinct is not None else 0)
+    expert_bytes = int(distinct.sum()) * one_expert_bytes if distinct is not None else 0
+    class_bytes = {"gemv": weight_bytes - router_bytes, "gemm": weight_bytes - router_bytes,
+                   "attention": kv_bytes, "moe_expert": expert_bytes, "moe_router": router_bytes,
+                   "fused_step": alg_bytes}      # the persistent kernel is the whole step
+    step_dev_s = dev_ms * 1e-3 / steps
+    achieved_step = alg_bytes / step_dev_s / 1e9
+    if ceiling is None:
+        ceiling = read_ceiling(dk, torch)
+    kernels = {}
+    for k, (ms, cnt) in prof.items():
+        if cnt:
+            kernels[k] = {"launches_per_step": cnt // prof_steps, "avg_us": round(ms * 1e3 / cnt, 3),
+                          "us_per_step": round(ms * 1e3 / prof_steps, 2)}
+    dominant = max(kernels, key=lambda k: kernels[k]["us_per_step"])
+    dom = kernels[dominant]
+    dom_bytes_per_launch = class_bytes.get(dominant, 0) / dom["launches_per_step"]
+    achieved = dom_bytes_per_launch / (dom["avg_us"] * 1e-6) / 1e9
+    traffic = None
+    rev, measured = MEASURED_TRAFFIC.get((wl.name, dominant), (None, None))
+    if rev is not None and rev in dk.version() and args.weights == "bf16":   # counters were taken with bf16 weights
+        traffic = measured
+
+    return {"shape": shape, "lay": lay, "weights": weights, "pool_bits": pool_bits, "tokens0": tokens0, "dm": dm,
+            "dkv": dkv, "dec": dec, "span": span, "ms_per_step": ms_per_step, "tok_s": tok_s, "alg_bytes": alg_bytes,
+            "step_dev_s": step_dev_s, "achieved_step": achieved_step, "ceiling": ceiling, "kernels": kernels,
+            "dominant": dominant, "dom": dom, "dom_bytes_per_launch": dom_bytes_per_launch, "achieved": achieved,
+            "traffic": traffic, "distinct": distinct}
+
+
+def extra_workload(args, name, dk, W, np, torch, ceiling):
+    """A batch-16 workload of the task's list, timed like the headline one and reported compactly."""
+    import gc
+    wl = W.WORKLOADS[name]
+    steps = min(args.steps, wl.steps)
+    m = measure_decode(args, wl, dk, W, np, torch, steps, min(args.warmup, 8), ceiling)
+    out = {"workload": f"{wl.name}: {m['shape'].name} decode, batch {wl.batch}, context "
+                       f"{int(m['lay'].contexts.min())}..{int(m['lay'].contexts.max())} growing"
+                       + (f", {wl.n_sharers} rows sharing a {wl.shared_prefix}-token prefix" if wl.n_sharers else ""),
+           "value": round(m["tok_s"], 2), "unit": "tok/s", "steps": steps, "ms_per_step": round(m["ms_per_step"], 5),
+           "algorithmic_bytes_per_step": int(m["alg_bytes"]),
+           "step_frac": round(m["achieved_step"] / HBM_PEAK_GBS, 4), "step_achieved_GBs": round(m["achieved_step"], 1),
+           "dominant_kernel": m["dominant"], "dominant_avg_launch_us": m["dom"]["avg_us"],
+           "dominant_launches_per_step": m["dom"]["launches_per_step"],
+           "dominant_algorithmic_bytes_per_launch": int(m["dom_bytes_per_launch"]),
+           "dominant_frac": round(m["achieved"] / HBM_PEAK_GBS, 4),
+           "kernels_us_per_step": {k: v["us_per_step"] for k, v in m["kernels"].items()}}
+    if m["distinct"] is not None:
+        out["distinct_experts_per_layer_mean"] = round(float(m["distinct"].mean()), 2)
+    m["dkv"].close()
+    m["dm"].close()
+    m.clear()
+    gc.collect()
+    torch.cuda.empty_cache()
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -272,6 +403,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=16)
     ap.add_argument("--workload", default="cfg1")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extra", action="store_true",
+                    help="default run only: skip the batch-16 workloads cfg2 / cfg3 / cfg4_l4 reported beside cfg1")
     ap.add_argument("--prefill", type=int, default=0, metavar="P",
                     help="measure chunked prefill instead: a P-token prompt of the workload's model shape "
                          "into an empty cache, 64 tokens per chunk (one step = one whole prompt)")
@@ -308,93 +441,11 @@ def main():
         return bench_serve(args, wl, dk, W, np, torch)
     if args.ttft:
         return bench_ttft(args, wl, dk, W, np, torch)
-    shape, lay = wl.cfg, layout_for(wl)
-    weights = make_model_weights(args, W, shape, wl.seed_weights)
-    router_bytes = shape.n_layers * shape.n_experts * shape.hidden * 2    # routers stay bf16
-    weight_bytes = shape.dense_weight_bytes()                             # attention, dense MLP, lm_head, routers
-    one_expert_bytes = shape.expert_bytes()
-    if args.weights == "q4":
-        def q4(b):                                                        # 4 bits + (scale, bias) per 64 weights
-            return b // 4 + b // 128 * 4
-        weight_bytes = q4(weight_bytes - router_bytes) + router_bytes
-        one_expert_bytes = q4(one_expert_bytes)
-    pool_bits = W.fill_kv_pool(shape, lay, wl.seed_kv, poison=False)
-    tokens0 = W.initial_tokens(shape, wl.batch, wl.seed_tokens)
-
-    dm = dk.DeviceModel(shape, weights)
-    dkv = dk.DeviceKV(dm, lay, pool_bits)
-    dec = dk.Decoder(dm, dkv, lay.contexts, tokens0, want_logits=True)
-    d_ctx0 = dec.seq_lens.clone()
-    d_tok0 = dec.tokens.clone()
-    span = wl.steps                              # tokens of growth the block tables have room for
-
-    path_flag = dk.STEP_NO_FUSED if args.kernel_per_stage else 0
-
-    def restart():
-        dec.seq_lens.copy_(d_ctx0)
-        dec.tokens.copy_(d_tok0)
-
-    def run(n):
-        for i in range(n):
-            if i % span == 0:
-                restart()                        # back to the initial context (tables are sized for `span` steps)
-            dec.step(flags=dk.STEP_ADVANCE | path_flag)   # greedy: the step feeds its token to the next one
-
-    run(args.warmup)
-    torch.cuda.synchronize()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    t0 = time.perf_counter()
-    e0.record()
-    run(args.steps)
-    e1.record()
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
-    dev_ms = e0.elapsed_time(e1)
-
-    ms_per_step = wall * 1e3 / args.steps
-    tok_s = wl.batch * args.steps / wall
-
-    # per-kernel times: a few more steps with start/stop events on every launch
-    prof_steps = min(16, span)
-    dk.profile_read(dm.handle, reset=True)
-    restart()
-    for _ in range(prof_steps):
-        dec.step(flags=dk.STEP_ADVANCE | dk.STEP_PROFILE | path_flag)
-    prof = dk.profile_read(dm.handle, reset=True)
-
-    # algorithmic bytes of a step at the mean context of the timed steps
-    n_in_span = min(args.steps, span)
-    mean_ctx = (lay.contexts + (n_in_span - 1) // 2).astype(np.int32)
-    distinct = None
-    if shape.n_experts:
-        routing = dec.routing()                                  # last profiled step
-        distinct = np.array([len(np.unique(routing[l])) for l in range(shape.n_layers)], dtype=np.int32)
-    alg_bytes = dk.step_algorithmic_bytes(dm.handle, dkv.handle, lay.tables, mean_ctx, with_logits=True,
-                                          distinct_experts_per_layer=distinct)
-    kv_bytes = dk.step_algorithmic_bytes(dm.handle, dkv.handle, lay.tables, mean_ctx, with_logits=False,
-                                         distinct_experts_per_layer=distinct) \
-        - weight_bytes - wl.batch * shape.hidden * 2 \
-        - (int(distinct.sum()) * one_expert_bytes if distinct is not None else 0)
-    expert_bytes = int(distinct.sum()) * one_expert_bytes if distinct is not None else 0
-    class_bytes = {"gemv": weight_bytes - router_bytes, "gemm": weight_bytes - router_bytes,
-                   "attention": kv_bytes, "moe_expert": expert_bytes, "moe_router": router_bytes,
-                   "fused_step": alg_bytes}      # the persistent kernel is the whole step
-    step_dev_s = dev_ms * 1e-3 / args.steps
-    achieved_step = alg_bytes / step_dev_s / 1e9
-    ceiling = read_ceiling(dk, torch)
-    kernels = {}
-    for k, (ms, cnt) in prof.items():
-        if cnt:
-            kernels[k] = {"launches_per_step": cnt // prof_steps, "avg_us": round(ms * 1e3 / cnt, 3),
-                          "us_per_step": round(ms * 1e3 / prof_steps, 2)}
-    dominant = max(kernels, key=lambda k: kernels[k]["us_per_step"])
-    dom = kernels[dominant]
-    dom_bytes_per_launch = class_bytes.get(dominant, 0) / dom["launches_per_step"]
-    achieved = dom_bytes_per_launch / (dom["avg_us"] * 1e-6) / 1e9
-    traffic = None
-    rev, measured = MEASURED_TRAFFIC.get((wl.name, dominant), (None, None))
-    if rev is not None and rev in dk.version() and args.weights == "bf16":   # counters were taken with bf16 weights
-        traffic = measured
+    m = measure_decode(args, wl, dk, W, np, torch, args.steps, args.warmup)
+    shape, lay, weights, pool_bits, tokens0, dm = (m[k] for k in ("shape", "lay", "weights", "pool_bits", "tokens0", "dm"))
+    span, ms_per_step, tok_s, alg_bytes, step_dev_s = (m[k] for k in ("span", "ms_per_step", "tok_s", "alg_bytes", "step_dev_s"))
+    achieved_step, ceiling, kernels, dominant, dom = (m[k] for k in ("achieved_step", "ceiling", "kernels", "dominant", "dom"))
+    dom_bytes_per_launch, achieved, traffic, distinct = (m[k] for k in ("dom_bytes_per_launch", "achieved", "traffic", "distinct"))
 
     out = {
         "metric": "aggregate_decode_tok_per_s",
@@ -435,6 +486,16 @@ def main():
         out["distinct_experts_per_layer_mean"] = round(float(distinct.mean()), 2)
     if wl.batch == 1 and wl.contexts:
         out["batch16"] = batch16_line(args, wl, dk, W, np, torch, dm, tok_s)
+    if args.workload == "cfg1" and args.weights == "bf16" and not args.kernel_per_stage and not args.no_extra:
+        # the batch-16 half of the metric on the task's batch-16 workloads (cfg4_l4: the 30B-A3B
+        # mixture-of-experts shape cut to 4 layers, every kernel at its real size, 5 GB instead of 61)
+        import gc
+        m["dkv"].close()
+        del m["dec"], m["dkv"]
+        gc.collect()
+        torch.cuda.empty_cache()
+        for name in ("cfg2", "cfg3", "cfg4_l4"):
+            out[name] = extra_workload(args, name, dk, W, np, torch, ceiling)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(shape, weights, lay, pool_bits, tokens0,
                                            max_steps=min(64, span - 1))   # the tables have room for `span` tokens
