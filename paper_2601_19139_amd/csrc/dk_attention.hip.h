@@ -249,7 +249,9 @@ __device__ __forceinline__ void head_norm_rope(float (&h)[8], bool norm, const f
     }
 #pragma unroll
     for (int e = 0; e < 8; e++) {
-        const float other = __shfl_xor(h[e], TPR / 2);   // element dl+e +- D/2
+        // element dl+e +- D/2 sits TPR/2 lanes away: with 16 lanes per head that is a rotation of
+        // the 16-lane row by 8 (DPP row_ror:8), otherwise a shuffle
+        const float other = (TPR == 16) ? dpp_f<0x128>(h[e]) : __shfl_xor(h[e], TPR / 2);
         h[e] = upper ? h[e] * cs[e].x + other * cs[e].y : h[e] * cs[e].x - other * cs[e].y;
     }
 }

@@ -139,19 +139,19 @@ struct Waiter {
 
 // Loads x[NB][K] (device-coherent, re-reading until complete) into LDS as
 // x * gain (or x) and returns 1/rms per row when NORM.
-template <int NB, bool NORM>
+template <int NB, bool NORM, int MAXE /*elements per thread and row: K <= 256 * MAXE*/>
 __device__ __forceinline__ void stage_input(const float *src, int K, const uint16_t *gain, float eps,
                                             float *xs /*[NB][K]*/, float (&rinv)[NB], float *red /*[4][NB]*/,
                                             Waiter &w)
 {
     const int tid = threadIdx.x;
-    constexpr int MAXE = 16;   // elements per thread per row: K <= 4096
     uint32_t v[NB][MAXE];
     float gn[MAXE];
 #pragma unroll
     for (int e = 0; e < MAXE; e++) {
-        const int k = e * kFusedThreads + tid;
-        gn[e] = (NORM && k < K) ? bf16_to_f32(gain[k]) : 1.f;   // on its way during the wait
+        // on its way during the wait.  (Unconditional, from a clamped index: a load inside a
+        // condition is waited for on the spot, one after the other.)
+        gn[e] = NORM ? bf16_to_f32(gain[min(e * kFusedThreads + tid, K - 1)]) : 1.f;
     }
     w.spins = 0;
     for (;;) {
@@ -741,7 +741,7 @@ __global__ __launch_bounds__(kFusedThreads) void fused_step_kernel(FusedArgs a)
         // ---- x_mid = x + W_o attn -------------------------------------------------------------
         {
             float dummy[NB];
-            stage_input<NB, false>(b_attn, QD, nullptr, a.eps, xs, dummy, red, w);
+            stage_input<NB, false, 2 * KSQ>(b_attn, QD, nullptr, a.eps, xs, dummy, red, w);
             gemv_rows<NB, RW_Q, KSQ, Q4>(pre_q, Lw.w_o, H, QD, q0, q1, h_b0, xs, ones, sm_y, lane);
             publish_rows<NB>(b_xmid, H, h_b0, h_n, sm_y, rv_o);
         }
@@ -753,7 +753,7 @@ __global__ __launch_bounds__(kFusedThreads) void fused_step_kernel(FusedArgs a)
             load_rows<RW_GU, KSH, Q4>(pg, Lw.w_gate, F, H, f0, f1, lane);
             load_rows<RW_GU, KSH, Q4>(pu, Lw.w_up, F, H, f0, f1, lane);
             __syncthreads();   // xs is about to be overwritten
-            stage_input<NB, true>(b_xmid, H, Lw.g_mlp, a.eps, xs, rinv, red, w);
+            stage_input<NB, true, 2 * KSH>(b_xmid, H, Lw.g_mlp, a.eps, xs, rinv, red, w);
             for (int rb = f0; rb < f1; rb += RW_GU) {
                 if (rb != f0) {
                     load_rows<RW_GU, KSH, Q4>(pg, Lw.w_gate, F, H, rb, f1, lane);
@@ -789,7 +789,7 @@ __global__ __launch_bounds__(kFusedThreads) void fused_step_kernel(FusedArgs a)
             }
             __syncthreads();
             float dummy[NB];
-            stage_input<NB, false>(b_act, F, nullptr, a.eps, xs, dummy, red, w);
+            stage_input<NB, false, 2 * KSF>(b_act, F, nullptr, a.eps, xs, dummy, red, w);
             gemv_rows<NB, RW_F, KSF, Q4>(pd, Lw.w_down, H, F, d0, d1, h_b0, xs, ones, sm_y, lane);
             publish_rows<NB>(b_xout, H, h_b0, h_n, sm_y, rv_d);
         }
@@ -797,7 +797,7 @@ __global__ __launch_bounds__(kFusedThreads) void fused_step_kernel(FusedArgs a)
         if (l + 1 < a.L) {
             load_rows<RW_H, KSH, Q4>(pre_h, a.layers[l + 1].w_qkv, QKV, H, r0, r1, lane);
             __syncthreads();
-            stage_input<NB, true>(b_xout, H, a.layers[l + 1].g_attn, a.eps, xs, rinv, red, w);
+            stage_input<NB, true, 2 * KSH>(b_xout, H, a.layers[l + 1].g_attn, a.eps, xs, rinv, red, w);
         }
     }
 
@@ -813,7 +813,7 @@ __global__ __launch_bounds__(kFusedThreads) void fused_step_kernel(FusedArgs a)
         for (int p = 0; p < PF; p++) load_rows<RW_H, KSH, Q4>(ring[p], a.lm_head, V, H, v0 + p * RW_H, v1, lane);
         __syncthreads();
         const float *x_last = a.set + lay.per_layer * (a.L - 1) + lay.xout;
-        stage_input<NB, true>(x_last, H, a.g_final, a.eps, xs, rinv, red, w);
+        stage_input<NB, true, 2 * KSH>(x_last, H, a.g_final, a.eps, xs, rinv, red, w);
         float best[NB];
         int best_i[NB];
 #pragma unroll
