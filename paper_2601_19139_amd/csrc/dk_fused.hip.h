@@ -460,6 +460,22 @@ __global__ __launch_bounds__(kFusedThreads) void fused_step_kernel(FusedArgs a)
     const int items = NB * a.nkv * a.nchunks;
     float2 cs[8];
     int cs_row = -1;
+    // The block's first attention item is the same in every layer, and where its tiles sit in a
+    // layer's slab of the pool does not depend on the layer: the block-table entries are looked
+    // up once, so that a layer's tile requests (and the q|k|v polls queued behind them) do not
+    // wait for a table load first.
+    int first_phys[kFusedWaveTiles], first_phys_new = 0;
+#pragma unroll
+    for (int u = 0; u < kFusedWaveTiles; u++) first_phys[u] = 0;
+    if (blk < items) {
+        const int c = blk % a.nchunks, j = (blk / a.nchunks) % a.nkv, b = blk / (a.nchunks * a.nkv);
+        const int *table = a.block_tables + (long long)b * a.max_blocks;
+#pragma unroll
+        for (int u = 0; u < kFusedWaveTiles; u++)
+            first_phys[u] = min(max(table[min(c * kFusedChunk / BS + wv + u * kFusedWaves, a.max_blocks - 1)], 0), a.num_blocks - 1);
+        first_phys_new = min(max(table[T[b] / BS], 0), a.num_blocks - 1);
+        (void)j;
+    }
 
     for (int l = 0; l < a.L; l++) {
         const FusedLayer &Lw = a.layers[l];
@@ -495,20 +511,19 @@ __global__ __launch_bounds__(kFusedThreads) void fused_step_kernel(FusedArgs a)
             const int t0 = c * kFusedChunk, t1 = min(T[b], t0 + kFusedChunk);
             const bool owns_new = (c == nact[b] - 1);
             const bool norm = Lw.g_q != nullptr;
-            float gq[8], gk[8];
-            if (norm) {
-                unpack8(ld16(Lw.g_q + dl), gq);
-                unpack8(ld16(Lw.g_k + dl), gk);
-            } else {
-#pragma unroll
-                for (int e = 0; e < 8; e++) gq[e] = gk[e] = 1.f;
-            }
+            // the head-norm gains are only requested here and unpacked once q has arrived (used on
+            // the spot they would hold up the tile requests below for a round trip)
+            const uint4 gq_raw = ld16((norm ? Lw.g_q : Lw.g_attn) + dl), gk_raw = ld16((norm ? Lw.g_k : Lw.g_attn) + dl);
+            const bool first_item = item == blk;
             // this wave's tiles: t0/16 + wv (+ 4, + 8 ... when a chunk has more tiles than waves)
             uint4 kw[kFusedWaveTiles][NI], vw[kFusedWaveTiles][NI];
 #pragma unroll
             for (int u = 0; u < kFusedWaveTiles; u++) {
-                const int tb = min(t0 / BS + wv + u * kFusedWaves, a.max_blocks - 1);
-                const int phys = min(max(table[tb], 0), a.num_blocks - 1);
+                int phys = first_phys[u];
+                if (!first_item) {
+                    const int tb = min(t0 / BS + wv + u * kFusedWaves, a.max_blocks - 1);
+                    phys = min(max(table[tb], 0), a.num_blocks - 1);
+                }
                 const uint16_t *kt = a.pool + kv_tile_offset(l, a.num_blocks, phys, 0, a.nkv, j, BS, D);
                 const uint16_t *vt = kt + (long long)a.nkv * BS * D;
 #pragma unroll
@@ -555,6 +570,13 @@ __global__ __launch_bounds__(kFusedThreads) void fused_step_kernel(FusedArgs a)
                     if (src[e]) sm_qkv[e * kFusedThreads + tid] = __uint_as_float(got[e]);
                 __syncthreads();
             }
+            float gq[8], gk[8];
+            unpack8(gq_raw, gq);
+            unpack8(gk_raw, gk);
+            if (!norm) {
+#pragma unroll
+                for (int e = 0; e < 8; e++) gq[e] = gk[e] = 1.f;
+            }
             float q[G][8], kn[8], vn[8];
 #pragma unroll
             for (int e = 0; e < 8; e++) {
@@ -590,7 +612,8 @@ __global__ __launch_bounds__(kFusedThreads) void fused_step_kernel(FusedArgs a)
                     vn[2 * e] = __uint_as_float(v0 << 16); vn[2 * e + 1] = __uint_as_float(v1 << 16);
                 }
                 if (sub == 0) {
-                    const int phys = min(max(table[T[b] / BS], 0), a.num_blocks - 1);
+                    int phys = first_phys_new;
+                    if (!first_item) phys = min(max(table[T[b] / BS], 0), a.num_blocks - 1);
                     uint16_t *kt = a.pool + kv_tile_offset(l, a.num_blocks, phys, 0, a.nkv, j, BS, D) +
                                    (T[b] % BS) * D + dl;
                     uint16_t *vt = kt + (long long)a.nkv * BS * D;
@@ -709,22 +732,22 @@ __global__ __launch_bounds__(kFusedThreads) void fused_step_kernel(FusedArgs a)
                     w.spins = 0;
                     for (;;) {
                         bool ready = true;
+                        // every request is unconditional (chunks past the last repeat it, threads
+                        // without an element read element 0): a load inside a condition is waited
+                        // for on the spot, and a round of polls would be a chain of round trips
 #pragma unroll
                         for (int u = 0; u < kFusedMergeRound; u++) {
-                            um[u] = ul[u] = uo[u] = 0u;
-                            if (has && c0 + u < nact[b]) {
-                                const float *pp = pg + (long long)(c0 + u) * (G * (D + 2));
-                                um[u] = ldc_u32(pp + D);
-                                ul[u] = ldc_u32(pp + D + 1);
-                                uo[u] = ldc_u32(pp + dim);
-                                ready = ready && um[u] != kNotYet && ul[u] != kNotYet && uo[u] != kNotYet;
-                            }
+                            const float *pp = pg + (long long)min(c0 + u, nact[b] - 1) * (G * (D + 2));
+                            um[u] = ldc_u32(pp + D);
+                            ul[u] = ldc_u32(pp + D + 1);
+                            uo[u] = ldc_u32(pp + dim);
+                            ready = ready && um[u] != kNotYet && ul[u] != kNotYet && uo[u] != kNotYet;
                         }
                         if (w.done(ready)) break;
                     }
 #pragma unroll
                     for (int u = 0; u < kFusedMergeRound; u++)
-                        if (has && c0 + u < nact[b]) {
+                        if (c0 + u < nact[b]) {
                             const float mc = __uint_as_float(um[u]), lc = __uint_as_float(ul[u]);
                             const float oc = __uint_as_float(uo[u]);
                             const float m2 = fmaxf(mn, mc);
