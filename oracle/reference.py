@@ -8,7 +8,10 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "decode_oracle.c")
-_BUILD = os.path.join(_HERE, "_build")
+# ORACLE_SANITIZE=1 selects a build under AddressSanitizer and UndefinedBehaviorSanitizer (kept in a
+# folder of its own; the process must then start with gcc's libasan preloaded - the tests do that)
+_SANITIZE = os.environ.get("ORACLE_SANITIZE") == "1"
+_BUILD = os.path.join(_HERE, "_build", "san") if _SANITIZE else os.path.join(_HERE, "_build")
 _LOCK = threading.Lock()
 
 
@@ -27,7 +30,9 @@ def build(force: bool = False) -> None:
                 and os.path.getmtime(out) >= os.path.getmtime(_SRC)):
             continue
         tmp = out + f".tmp{os.getpid()}"
-        cmd = ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-fopenmp",
+        opt = ["-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined",
+               "-fno-omit-frame-pointer"] if _SANITIZE else ["-O2"]
+        cmd = ["gcc", *opt, "-std=c11", "-fPIC", "-shared", "-fopenmp",
                "-fno-fast-math", "-ffp-contract=off", *flag, _SRC, "-o", tmp, "-lm"]
         subprocess.run(cmd, check=True)
         os.replace(tmp, out)

@@ -6,7 +6,8 @@ import os
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libdecodekit.so")
+# DECODEKIT_LIBRARY names another build of the same library (the host-sanitizer build of the tests)
+LIB_PATH = os.environ.get("DECODEKIT_LIBRARY") or os.path.join(_HERE, "libdecodekit.so")
 
 STATUS = {0: "DK_OK", -1: "DK_E_INVALID_ARG", -2: "DK_E_POOL_EXHAUSTED", -3: "DK_E_BAD_BLOCK",
           -4: "DK_E_WORKSPACE_TOO_SMALL", -5: "DK_E_UNSUPPORTED_SHAPE", -6: "DK_E_HIP"}
