@@ -404,6 +404,20 @@ dk_status dk_step_algorithmic_bytes(const dk_model *model, const dk_kv_pool *poo
  * ceiling the decode kernels are compared with beside the published peak. */
 dk_status dk_read_stream(const void *d_buf, size_t bytes, void *d_sink, void *hip_stream);
 
+/* Introspection (host only, launches nothing): which kernel a batched weight-streaming GEMM of the decode
+ * step takes for a matrix of N rows and K columns at B batch rows (5..64), on a device with
+ * `compute_units` compute units (0: the current device's count, 256 if none answers).  The choice is the
+ * candidate with the smallest estimated duration of a latency/occupancy model of the weight stream.
+ * epilogue: 0 plain store (q | k | v, lm_head), 1 residual projection (attention output, down), 2 the
+ * gate/up pair with SwiGLU (N = rows of each of the two matrices).  four_bit: 1 for 4-bit weights.
+ * out_waves: 0 = the kernel whose waves split K (then out_slices = 1); otherwise the waves per block of
+ * the kernel whose waves share the activation tile, with K cut into out_slices slices across blocks.
+ * out_estimate_us: the model's estimate for the choice (0 where no estimate is made: 4-bit weights, K
+ * not a multiple of 128).  DK_E_INVALID_ARG for NULL outputs, B outside 5..64 or non-positive sizes. */
+dk_status dk_gemm_plan_query(int32_t epilogue, int32_t N, int32_t K, int32_t B, int32_t four_bit,
+                             int32_t compute_units, int32_t *out_waves, int32_t *out_slices,
+                             double *out_estimate_us);
+
 #ifdef __cplusplus
 }
 #endif

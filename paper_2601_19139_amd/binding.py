@@ -107,6 +107,7 @@ _SIGNATURES.update({
     "dk_sample_scratch_bytes": (C.c_int32, [C.c_int32, C.c_int32, C.POINTER(C.c_size_t)]),
     "dk_sample_tokens": (C.c_int32, [C.c_void_p, C.c_int32, C.c_int32, C.POINTER(Sampling), C.c_uint64, C.c_void_p,
                                      C.c_size_t, C.c_void_p, C.c_void_p]),
+    "dk_gemm_plan_query": (C.c_int32, [C.c_int32] * 6 + [C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.POINTER(C.c_double)]),
     "dk_prefix_index_create": (C.c_int32, [C.c_int32, C.POINTER(C.c_void_p)]),
     "dk_prefix_index_destroy": (C.c_int32, [C.c_void_p, C.c_void_p]),
     "dk_prefix_index_match": (C.c_int32, [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p,
@@ -268,6 +269,13 @@ def destroy_model(model):
 def read_stream(d_buf, d_sink, stream=None):
     """Enqueues the read-only streaming kernel over the whole of d_buf (measurement aid)."""
     _check(lib().dk_read_stream(_ptr(d_buf), d_buf.numel() * d_buf.element_size(), _ptr(d_sink), _stream(stream)))
+
+
+def gemm_plan_query(epilogue: int, N: int, K: int, B: int, four_bit: bool = False, compute_units: int = 0):
+    """(waves per block or 0, K slices, estimated microseconds) of the batched GEMM the step would launch."""
+    w, s, us = C.c_int32(), C.c_int32(), C.c_double()
+    _check(lib().dk_gemm_plan_query(epilogue, N, K, B, int(four_bit), compute_units, C.byref(w), C.byref(s), C.byref(us)))
+    return w.value, s.value, us.value
 
 
 def workspace_bytes(model, max_B: int, max_blocks_per_seq: int) -> int:

@@ -20,6 +20,7 @@
 #include "dk_fused.hip.h"
 #include "dk_gemm.hip.h"
 #include "dk_gemm_shared.hip.h"
+#include "dk_gemm_plan.h"
 #include "dk_gemv.hip.h"
 #include "dk_moe.hip.h"
 #include "dk_sample.hip.h"
@@ -109,8 +110,8 @@ dk_status check_config(const dk_model_config *c)
         return fail(DK_E_UNSUPPORTED_SHAPE, "n_q_heads %d is not a multiple of n_kv_heads %d",
                     c->n_q_heads, c->n_kv_heads);
     const int G = c->n_q_heads / c->n_kv_heads;
-    if (!(G == 1 || G == 2 || G == 3 || G == 4 || G == 6 || G == 8))
-        return fail(DK_E_UNSUPPORTED_SHAPE, "query group size %d (1,2,3,4,6,8 supported)", G);
+    if (G < 1 || G > 8)
+        return fail(DK_E_UNSUPPORTED_SHAPE, "query group size %d (1..8 supported)", G);
     if (c->hidden % 8) return fail(DK_E_UNSUPPORTED_SHAPE, "hidden %d not a multiple of 8", c->hidden);
     if (c->n_experts < 0 || c->n_experts > DK_MAX_EXPERTS)
         return fail(DK_E_UNSUPPORTED_SHAPE, "n_experts %d (at most %d)", c->n_experts, DK_MAX_EXPERTS);
@@ -186,13 +187,35 @@ constexpr int kLmTiles = 1;  // tiles per block of the lm_head GEMV
 // The persistent step kernel is compiled for a few shape classes: (head_dim,
 // query group, 512-element pieces of hidden / nq*d / ffn).  Returns the index of
 // the smallest class that fits, or -1.
-constexpr int kFusedBlocks = 256;   // one per compute unit of an MI355X
+// Compute units of the current device, asked once per process (256 when no device answers: sizing
+// calls on a machine without a GPU).  Every plan of the process uses the same number, so the workspace
+// a sizing call reports always fits the launches that follow.
+int device_cus()
+{
+    static int cus = 0;
+    if (cus == 0) {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) {
+            (void)hipGetLastError();
+            n = 256;
+        }
+        cus = n;
+    }
+    return cus;
+}
+
+// The persistent kernel runs one block per compute unit of the device (256 on an MI355X).
+int fused_blocks() { return device_cus(); }
 struct FusedClass { int d, g, ksh, ksq, ksf; };
 constexpr FusedClass kFusedClasses[] = {{64, 2, 1, 1, 2}, {128, 2, 2, 4, 6}};
 int fused_variant(const dk_model_config &c, int B)
 {
     if (B > 2 || c.n_experts > 0 || c.n_layers > dk::kFusedMaxLayers) return -1;
     const int g = c.n_q_heads / c.n_kv_heads;
+    // a block hands at most kFusedMaxBlockRows rows of a stage over
+    const int widest = std::max(std::max((c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim, c.ffn), c.hidden);
+    if ((widest + fused_blocks() - 1) / fused_blocks() > dk::kFusedMaxBlockRows) return -1;
     for (int i = 0; i < (int)(sizeof kFusedClasses / sizeof kFusedClasses[0]); i++) {
         const FusedClass &k = kFusedClasses[i];
         if (k.d == c.head_dim && k.g == g && c.hidden <= 512 * k.ksh &&
@@ -202,56 +225,11 @@ int fused_variant(const dk_model_config &c, int B)
     return -1;
 }
 
-// Which kernel a batched GEMM takes: w == 0 the K-split-per-wave kernel (skinny_gemm_kernel),
-// otherwise shared_gemm_kernel with w waves per block and K cut into `slices` across blocks.
-// From a sweep (16..64 batch rows; waves 4 / 8; slices 1..8) over the layer matrices of the 0.6B, 3B,
-// 8B and 30B-A3B shapes, HBM-cold: four K slices win wherever the matrix is large enough to hide the
-// hand-over of the partial tiles - 1.05-1.25x at 16 rows, 1.2-2.2x at 32..64 rows - and lose
-// (0.75-0.9x) on the few-MB matrices of the 0.6B shape, which stay with the other kernel.
-struct GemmPlan { int w, slices; };
-GemmPlan gemm_plan(int epi, int N, int K, int Bp, bool q4)
-{
-    const int mt = Bp / 16;
-    const long long elems = (long long)N * K;
-    if (K % 128) return {0, 1};
-    if (q4) {
-        // 4-bit weights (the same sweep): the lm_head at every batch size; q | k | v from 32 rows on;
-        // the gate/up pair and the down projection of the 3B / 8B shapes; never the output projection
-        if (epi == dk::GEPI_STORE) {
-            if ((N + 15) / 16 >= 4096) return {8, 1};
-            if (mt >= 2 && elems >= (8ll << 20)) return {8, 4};
-        } else if (epi == dk::GEPI_SWIGLU) {
-            if (elems >= (40ll << 20)) return {8, 2};
-            if (elems >= (20ll << 20)) return {8, 4};
-        } else {
-            if (elems >= (mt >= 2 ? (20ll << 20) : (40ll << 20))) return {4, 8};
-        }
-        return {0, 1};
-    }
-    // K slices of a bf16 layer matrix handled by blocks of w waves: as many as still give one round of
-    // blocks on the 256 compute units (a second, partly filled round costs more than the slices save;
-    // 3B down projection at 16 rows: 4 slices / 192 blocks 16.4 us, 5 / 240 14.5, 6 / 288 19.9), at
-    // least four K-steps per slice; matrices with many row blocks take four slices.
-    auto slices = [&](int w) {
-        const int row_blocks = ((N + 15) / 16 + w - 1) / w;
-        if (row_blocks > 128) return 4;
-        int s = std::min(std::min(256 / row_blocks, 8), K / 512);
-        return std::max(s, 1);
-    };
-    if (epi == dk::GEPI_STORE) {
-        // lm_head: one slice (thousands of row blocks).  At 16 rows only while K is short (measured:
-        // 106 -> 67 us at K = 1024, 181 -> 150 us at K = 3072, 250 -> 276 us at K = 4096)
-        if ((N + 15) / 16 >= 4096) return (mt >= 2 || K <= 3072) ? GemmPlan{8, 1} : GemmPlan{0, 1};
-        if (elems >= (mt >= 2 ? (8ll << 20) : (20ll << 20))) return {8, slices(8)};   // q | k | v
-    } else if (epi == dk::GEPI_SWIGLU) {
-        if (elems >= (20ll << 20)) return (mt == 1 && elems >= (40ll << 20)) ? GemmPlan{4, slices(4)} : GemmPlan{8, slices(8)};
-    } else {
-        // output projection, down.  At 16 rows only the down projections: the square-ish output
-        // projections are as fast or faster with two-wave blocks of the other kernel (3B: 8.8 vs 9.6 us)
-        if (elems >= (mt >= 2 ? (8ll << 20) : (20ll << 20))) return {4, slices(4)};
-    }
-    return {0, 1};
-}
+// Which kernel a batched GEMM takes (dk_gemm_plan.h: the candidate with the smallest estimated duration).
+using dkplan::GemmPlan;
+static_assert(dkplan::EPI_STORE == dk::GEPI_STORE && dkplan::EPI_RESID == dk::GEPI_RESID && dkplan::EPI_SWIGLU == dk::GEPI_SWIGLU,
+              "the plan's epilogue codes are the kernels'");
+GemmPlan gemm_plan(int epi, int N, int K, int Bp, bool q4) { return dkplan::gemm_plan(epi, N, K, Bp, q4, device_cus()); }
 // Row blocks (= tickets) and partial-tile floats of that plan.
 void gemm_plan_needs(int epi, int N, int K, int Bp, bool q4, size_t &tickets, size_t &part_floats)
 {
@@ -388,7 +366,7 @@ Workspace carve(const dk_model_config &c, int B, int max_blocks, bool q4)
     if (w.fused) {
         w.fused_chunks = (ctx_max + dk::kFusedChunk - 1) / dk::kFusedChunk;
         w.fused_set_floats = dk::fused_layout(c.n_layers, B, c.hidden, c.n_q_heads, c.n_kv_heads, d, c.ffn,
-                                              w.fused_chunks, kFusedBlocks).total;
+                                              w.fused_chunks, fused_blocks()).total;
         w.fused_sets = take((size_t)2 * w.fused_set_floats * 4);
         w.fused_status = take(64);
     }
@@ -565,33 +543,22 @@ dk_status launch_gemm(const dk::GemmArgs &a, int Bp, hipStream_t st)
     constexpr int NM = (EPI == dk::GEPI_SWIGLU) ? 2 : 1;
     const GemmPlan plan = gemm_plan(EPI, a.N, a.K, Bp, a.q4 != 0);
     if (plan.w) return launch_shared_gemm<EPI, NORM>(a, Bp, plan, st);
-    const int tiles = (a.N + 15) / 16;
-    // A small matrix at 32..64 rows whose row tiles times groups of 16 batch rows still make at
-    // most two blocks per compute unit: the 16-row kernel over every group at once (blockIdx.y),
-    // instead of a few blocks that each carry all the rows through one long epilogue (0.6B shape
-    // at 64 rows: O and down, 64 row tiles, 14.3 / 16.3 -> 7.6 us; q/k/v and gate/up, 256 / 192
-    // tiles, are slower that way - 8.5 -> 11.9, 10.9 -> 12.8 us - and keep the 64-row kernel).
-    const int mt = Bp / 16;
-    const int col_groups = (mt >= 2 && tiles * mt <= 512) ? mt : 1;
-    switch (col_groups > 1 ? 1 : mt) {
-        case 1:
-            if constexpr (NM == 1) {
-                if (tiles >= 4096) return launch_gemm_cfg<1, 8, 4, EPI, NORM>(a, st);
-                if (tiles >= 320) return launch_gemm_cfg<1, 8, 2, EPI, NORM>(a, st);
-                // residual projections with at most one block per compute unit: two waves per block,
-                // less to add up across waves (0.6B shape: O 5.9 -> 5.1 us, down 8.8 -> 8.2 us)
-                if (tiles <= 256 && EPI == dk::GEPI_RESID && !a.q4) return launch_gemm_cfg<1, 2, 1, EPI, NORM>(a, st, col_groups);
-            }
-            return launch_gemm_cfg<1, 8, 1, EPI, NORM>(a, st, col_groups);
-        case 2:
-            if constexpr (NM == 1) {
-                if (tiles >= 1024) return launch_gemm_cfg<2, 8, 2, EPI, NORM>(a, st);
-            }
-            return launch_gemm_cfg<2, 8, 1, EPI, NORM>(a, st);
-        case 3: return launch_gemm_cfg<3, 4, 1, EPI, NORM>(a, st);
-        case 4: return launch_gemm_cfg<4, 4, 1, EPI, NORM>(a, st);
-        default: return fail(DK_E_INVALID_ARG, "batch %d exceeds %d", Bp, DK_MAX_BATCH);
+    // the variant of the K-split-per-wave kernel (dk_gemm_plan.h)
+    const dkplan::SkinnyVariant v = dkplan::skinny_variant(EPI, a.N, Bp, a.q4 != 0, device_cus());
+#define DK_SKINNY_CASE(MT_, KS_, RT_)                                                     \
+    if (v.mt == MT_ && v.ks == KS_ && v.rt == RT_) return launch_gemm_cfg<MT_, KS_, RT_, EPI, NORM>(a, st, v.groups)
+    if constexpr (NM == 1) {
+        DK_SKINNY_CASE(1, 8, 4);
+        DK_SKINNY_CASE(1, 8, 2);
+        DK_SKINNY_CASE(1, 2, 1);
+        DK_SKINNY_CASE(2, 8, 2);
     }
+    DK_SKINNY_CASE(1, 8, 1);
+    DK_SKINNY_CASE(2, 8, 1);
+    DK_SKINNY_CASE(3, 4, 1);
+    DK_SKINNY_CASE(4, 4, 1);
+#undef DK_SKINNY_CASE
+    return fail(DK_E_INVALID_ARG, "no GEMM kernel for %d rows (at most %d)", Bp, DK_MAX_BATCH);
 }
 
 // light: without the register double buffer (short chunks, query groups of up to 4: the host's choice)
@@ -621,7 +588,9 @@ dk_status launch_attention_d(const dk::AttnArgs &a, int G, dim3 grid, bool mfma,
         DK_ATTN_CASE(2)
         DK_ATTN_CASE(3)
         DK_ATTN_CASE(4)
+        DK_ATTN_CASE(5)
         DK_ATTN_CASE(6)
+        DK_ATTN_CASE(7)
         DK_ATTN_CASE(8)
         default: return fail(DK_E_UNSUPPORTED_SHAPE, "query group size %d", G);
     }
@@ -642,7 +611,9 @@ dk_status launch_prefill_attention_d(const dk::AttnArgs &a, int G, dim3 grid, hi
         DK_PF_ATTN_CASE(2)
         DK_PF_ATTN_CASE(3)
         DK_PF_ATTN_CASE(4)
+        DK_PF_ATTN_CASE(5)
         DK_PF_ATTN_CASE(6)
+        DK_PF_ATTN_CASE(7)
         DK_PF_ATTN_CASE(8)
         default: return fail(DK_E_UNSUPPORTED_SHAPE, "query group size %d", G);
     }
@@ -655,10 +626,10 @@ template <int NB, int D, int G, int KSH, int KSQ, int KSF>
 dk_status launch_fused_inst(const dk::FusedArgs &a, bool q4, hipStream_t st)
 {
     if (q4) {
-        DK_LAUNCH(DK_K_FUSED_STEP, (dk::fused_step_kernel<NB, D, G, KSH, KSQ, KSF, true>), dim3(kFusedBlocks),
+        DK_LAUNCH(DK_K_FUSED_STEP, (dk::fused_step_kernel<NB, D, G, KSH, KSQ, KSF, true>), dim3(fused_blocks()),
                   dim3(dk::kFusedThreads), 0, st, a);
     } else {
-        DK_LAUNCH(DK_K_FUSED_STEP, (dk::fused_step_kernel<NB, D, G, KSH, KSQ, KSF, false>), dim3(kFusedBlocks),
+        DK_LAUNCH(DK_K_FUSED_STEP, (dk::fused_step_kernel<NB, D, G, KSH, KSQ, KSF, false>), dim3(fused_blocks()),
                   dim3(dk::kFusedThreads), 0, st, a);
     }
     DK_HIP(hipGetLastError());
@@ -680,7 +651,7 @@ dk_status launch_fused(dk_model *model, dk_kv_pool *pool, const Workspace &w, ch
         DK_HIP(hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev));
         model->n_cus = n;
     }
-    if (model->n_cus < kFusedBlocks) return DK_E_UNSUPPORTED_SHAPE;   // blocks could not all be resident
+    if (model->n_cus < fused_blocks()) return DK_E_UNSUPPORTED_SHAPE;   // (another device than the one asked first) blocks could not all be resident
     float *sets = reinterpret_cast<float *>(ws + w.fused_sets);
     unsigned *status = reinterpret_cast<unsigned *>(ws + w.fused_status);
     if (model->fused_ws != ws || model->fused_ws_bytes != w.total) {
@@ -1753,6 +1724,21 @@ dk_status dk_read_stream(const void *d_buf, size_t bytes, void *d_sink, void *hi
     hipLaunchKernelGGL(read_stream_kernel, dim3(cus > 0 ? cus : 256), dim3(256), 0, static_cast<hipStream_t>(hip_stream),
                        static_cast<const uint4 *>(d_buf), bytes / 16, static_cast<uint32_t *>(d_sink));
     DK_HIP(hipGetLastError());
+    return DK_OK;
+}
+
+dk_status dk_gemm_plan_query(int32_t epilogue, int32_t N, int32_t K, int32_t B, int32_t four_bit,
+                             int32_t compute_units, int32_t *out_waves, int32_t *out_slices,
+                             double *out_estimate_us)
+{
+    if (!out_waves || !out_slices || !out_estimate_us) return fail(DK_E_INVALID_ARG, "NULL argument");
+    if (epilogue < 0 || epilogue > 2 || N < 1 || K < 1 || B <= kMaxGemvBatch || B > DK_MAX_BATCH || compute_units < 0)
+        return fail(DK_E_INVALID_ARG, "epilogue %d, N %d, K %d, B %d, compute units %d", epilogue, N, K, B, compute_units);
+    const int Bp = (B + 15) / 16 * 16;
+    const GemmPlan p = dkplan::gemm_plan(epilogue, N, K, Bp, four_bit != 0, compute_units ? compute_units : device_cus(),
+                                         out_estimate_us);
+    *out_waves = p.w;
+    *out_slices = p.slices;
     return DK_OK;
 }
 

@@ -273,3 +273,44 @@ def test_shared_prefix_counts_once_in_algorithmic_bytes():
     logical = int(sum(int(t) + 1 for t in lay.contexts))
     unique = logical - 7 * 1024
     assert got == wl.cfg.dense_weight_bytes() + unique * wl.cfg.kv_bytes_per_token() + 16 * wl.cfg.hidden * 2
+
+
+def test_gemm_plan_follows_the_cost_model():
+    """The batched-GEMM dispatch is the argmin of a cost estimate, not a table of shapes: properties
+    that any shape must meet, checked on layer matrices of model shapes the calibration never saw
+    (hidden 2560 / ffn 9728, hidden 5120 / ffn 17408) beside the ones it did."""
+    STORE, RESID, SWIGLU = 0, 1, 2
+    shapes = []
+    for H, nq, nkv, F, V in ((1024, 16, 8, 3072, 151936), (3072, 24, 8, 8192, 128256), (4096, 32, 8, 12288, 151936),
+                             (2560, 32, 8, 9728, 151936), (5120, 40, 8, 17408, 152064), (1536, 12, 2, 8960, 151936)):
+        qkv, qd = (nq + 2 * nkv) * 128, nq * 128
+        shapes += [(STORE, qkv, H), (RESID, H, qd), (SWIGLU, F, H), (RESID, H, F), (STORE, V, H)]
+    for cus in (256, 128, 304):
+        for epi, N, K in shapes:
+            for B in (5, 16, 17, 32, 48, 64):
+                w, s, us = dk.gemm_plan_query(epi, N, K, B, False, cus)
+                tiles = (N + 15) // 16
+                assert w in (0, 4, 8) and 1 <= s <= 8 and us > 0
+                if w == 0:
+                    assert s == 1
+                    continue
+                # instantiated block widths: 4 waves for residual projections (and the gate/up pair at 16 rows)
+                assert (w == 4) == (epi == RESID or (epi == SWIGLU and B <= 16 and w == 4))
+                row_blocks = (tiles + w - 1) // w
+                assert s <= max(1, K // 512)                     # at least four K-steps per slice
+                if row_blocks <= cus // 2:
+                    assert row_blocks * s <= cus                  # one round of blocks
+                if row_blocks >= 2 * cus:
+                    assert s == 1                                 # many rounds already: no slices (the lm_head)
+                # the estimate grows with the batch rows
+                assert dk.gemm_plan_query(epi, N, K, 64, False, cus)[2] >= dk.gemm_plan_query(epi, N, K, 16, False, cus)[2] or w == 0
+    # small matrices stay with the kernel whose waves split K; K off the 128 grid always does
+    assert dk.gemm_plan_query(STORE, 4096, 1024, 16)[0] == 0
+    assert dk.gemm_plan_query(RESID, 1024, 3072, 16)[0] == 0
+    assert dk.gemm_plan_query(STORE, 6144, 4000, 32)[:2] == (0, 1)
+    # the large ones do not
+    assert dk.gemm_plan_query(SWIGLU, 12288, 4096, 16)[0] in (4, 8)
+    assert dk.gemm_plan_query(RESID, 4096, 12288, 16)[0] == 4
+    for bad in ((3, 64, 128, 16), (0, 0, 128, 16), (0, 64, 128, 4), (0, 64, 128, 65)):
+        with pytest.raises(dk.DecodeKitError):
+            dk.gemm_plan_query(*bad)

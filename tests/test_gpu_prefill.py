@@ -97,6 +97,8 @@ CASES = [
     ("g8", variant("tiny", n_q_heads=8, n_kv_heads=1, qk_norm=True), 290, 64, 1),
     ("g1", variant("tiny", n_q_heads=2), 280, 50, 1),
     ("g6", variant("tiny", n_q_heads=6, n_kv_heads=1), 100, 9, 1),
+    ("g5", variant("tiny", head_dim=128, n_q_heads=5, n_kv_heads=1, qk_norm=True), 270, 40, 1),
+    ("g7", variant("tiny", n_q_heads=7, n_kv_heads=1), 120, 11, 1),
 ]
 
 
