@@ -208,7 +208,9 @@ int device_cus()
 // The persistent kernel runs one block per compute unit of the device (256 on an MI355X).
 int fused_blocks() { return device_cus(); }
 struct FusedClass { int d, g, ksh, ksq, ksf; };
-constexpr FusedClass kFusedClasses[] = {{64, 2, 1, 1, 2}, {128, 2, 2, 4, 6}};
+// (0.6B-class shapes with two batch rows as well; the wide classes - 3B- and 8B-class shapes - one row)
+constexpr FusedClass kFusedClasses[] = {{64, 2, 1, 1, 2}, {128, 2, 2, 4, 6}, {128, 3, 6, 6, 16}, {128, 4, 8, 8, 24}};
+constexpr int kFusedTwoRowClasses = 2;
 int fused_variant(const dk_model_config &c, int B)
 {
     if (B > 2 || c.n_experts > 0 || c.n_layers > dk::kFusedMaxLayers) return -1;
@@ -219,7 +221,7 @@ int fused_variant(const dk_model_config &c, int B)
     for (int i = 0; i < (int)(sizeof kFusedClasses / sizeof kFusedClasses[0]); i++) {
         const FusedClass &k = kFusedClasses[i];
         if (k.d == c.head_dim && k.g == g && c.hidden <= 512 * k.ksh &&
-            c.n_q_heads * c.head_dim <= 512 * k.ksq && c.ffn <= 512 * k.ksf)
+            c.n_q_heads * c.head_dim <= 512 * k.ksq && c.ffn <= 512 * k.ksf && (B == 1 || i < kFusedTwoRowClasses))
             return i;
     }
     return -1;
@@ -362,7 +364,10 @@ Workspace carve(const dk_model_config &c, int B, int max_blocks, bool q4)
     }
     w.pmax_val = take((size_t)B * w.lm_blocks * 4);
     w.pmax_idx = take((size_t)B * w.lm_blocks * 4);
-    w.fused = fused_variant(c, B) >= 0;
+    // (the block of a sequence's first chunk waits for the blocks of its other chunks while every block
+    // works through its items in ascending order: free of cycles as long as a sequence has no more
+    // chunks than there are blocks)
+    w.fused = fused_variant(c, B) >= 0 && (ctx_max + dk::kFusedChunk - 1) / dk::kFusedChunk <= fused_blocks();
     if (w.fused) {
         w.fused_chunks = (ctx_max + dk::kFusedChunk - 1) / dk::kFusedChunk;
         w.fused_set_floats = dk::fused_layout(c.n_layers, B, c.hidden, c.n_q_heads, c.n_kv_heads, d, c.ffn,
@@ -622,18 +627,27 @@ dk_status launch_prefill_attention_d(const dk::AttnArgs &a, int G, dim3 grid, hi
     return DK_OK;
 }
 
+template <int NB, int D, int G, int KSH, int KSQ, int KSF, bool Q4>
+dk_status launch_fused_q(const dk::FusedArgs &a, hipStream_t st)
+{
+    constexpr size_t lds = dk::fused_xs_bytes(NB, KSH, KSQ, KSF);
+    auto kernel = dk::fused_step_kernel<NB, D, G, KSH, KSQ, KSF, Q4>;
+    static bool lds_allowed = false;   // with the kernel's static LDS this can exceed 64 KB: ask once
+    if (!lds_allowed) {
+        DK_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                   (int)lds));
+        lds_allowed = true;
+    }
+    DK_LAUNCH(DK_K_FUSED_STEP, kernel, dim3(fused_blocks()), dim3(dk::kFusedThreads), lds, st, a);
+    DK_HIP(hipGetLastError());
+    return DK_OK;
+}
+
 template <int NB, int D, int G, int KSH, int KSQ, int KSF>
 dk_status launch_fused_inst(const dk::FusedArgs &a, bool q4, hipStream_t st)
 {
-    if (q4) {
-        DK_LAUNCH(DK_K_FUSED_STEP, (dk::fused_step_kernel<NB, D, G, KSH, KSQ, KSF, true>), dim3(fused_blocks()),
-                  dim3(dk::kFusedThreads), 0, st, a);
-    } else {
-        DK_LAUNCH(DK_K_FUSED_STEP, (dk::fused_step_kernel<NB, D, G, KSH, KSQ, KSF, false>), dim3(fused_blocks()),
-                  dim3(dk::kFusedThreads), 0, st, a);
-    }
-    DK_HIP(hipGetLastError());
-    return DK_OK;
+    if (q4) return launch_fused_q<NB, D, G, KSH, KSQ, KSF, true>(a, st);
+    return launch_fused_q<NB, D, G, KSH, KSQ, KSF, false>(a, st);
 }
 
 // The whole step as one persistent kernel (see dk_fused.hip.h).  Returns
@@ -708,6 +722,8 @@ dk_status launch_fused(dk_model *model, dk_kv_pool *pool, const Workspace &w, ch
     else if (v == 0 && B == 2) s = launch_fused_inst<2, 64, 2, 1, 1, 2>(a, model->q4, st);
     else if (v == 1 && B == 1) s = launch_fused_inst<1, 128, 2, 2, 4, 6>(a, model->q4, st);
     else if (v == 1 && B == 2) s = launch_fused_inst<2, 128, 2, 2, 4, 6>(a, model->q4, st);
+    else if (v == 2 && B == 1) s = launch_fused_inst<1, 128, 3, 6, 6, 16>(a, model->q4, st);
+    else if (v == 3 && B == 1) s = launch_fused_inst<1, 128, 4, 8, 8, 24>(a, model->q4, st);
     return s;
 }
 

@@ -314,6 +314,8 @@ __device__ __forceinline__ void dot_rows(const RowRegs<RW, KS, Q4> &r, const flo
 #pragma unroll
         for (int s = 0; s < KS; s++) {
             const int k = s * 512 + lane * 8;
+            // long rows: the LDS reads of all pieces, hoisted to the top, would not fit the registers
+            if (KS > 8 && (s & 3) == 0) __builtin_amdgcn_sched_barrier(0);
             if (k < K) {
                 float xv[NB][8];
 #pragma unroll
@@ -380,25 +382,29 @@ __device__ __forceinline__ void publish_rows(float *out, int N, int b0, int n, c
     }
 }
 
+// Dynamic LDS of an instance: the stage input xs[NB][512 * max(KSH, KSQ, KSF)].
+constexpr size_t fused_xs_bytes(int NB, int KSH, int KSQ, int KSF)
+{
+    return (size_t)NB * 512 * (KSF > KSQ ? (KSF > KSH ? KSF : KSH) : (KSQ > KSH ? KSQ : KSH)) * 4;
+}
+
 template <int NB, int D, int G, int KSH, int KSQ, int KSF, bool Q4 = false>
 __global__ __launch_bounds__(kFusedThreads) void fused_step_kernel(FusedArgs a)
 {
     constexpr int BS = 16, TPR = D / 8, TPW = 64 / TPR, NI = BS / TPW;
-    constexpr int RW_H = (KSH <= 2) ? 4 : 2;      // rows per wave in flight, K = H
-    constexpr int RW_GU = (KSH <= 2) ? 3 : 1;     // gate and up: two matrices
-    // the output projection and the down projection have `hidden` rows: at most one per wave
-    // (hidden <= 512 * KSH <= 1024 = blocks * waves for every shape class)
-    constexpr int RW_Q = 1, RW_F = 1;
-    static_assert(KSH <= 2, "a wave owns at most one row of a hidden-sized output");
-    constexpr int MAXK = 512 * (KSF > KSQ ? (KSF > KSH ? KSF : KSH) : (KSQ > KSH ? KSQ : KSH));
-    __shared__ float xs[NB * MAXK];
+    // rows per wave in flight (registers: a row of K = 512 * KS columns is KS 16-byte pieces per lane)
+    constexpr int RW_H = (KSH <= 2) ? 4 : (KSH <= 4 ? 2 : 1);   // K = hidden
+    constexpr int RW_GU = (KSH <= 2) ? 3 : 1;                   // gate and up: two matrices
+    constexpr int RW_Q = 1, RW_F = 1;                           // output and down projection
+    constexpr int EP = (G * D + kFusedThreads - 1) / kFusedThreads;   // elements of a query group's output per thread
+    constexpr int MERGE_ROUND = kFusedMergeRound / EP > 0 ? kFusedMergeRound / EP : 1;
+    extern __shared__ __attribute__((aligned(16))) float xs[];   // [NB][512 * max(KSH, KSQ, KSF)]: the stage's input (fused_xs_bytes)
     __shared__ float red[kFusedWaves * NB];
     __shared__ float sm_o[kFusedWaves][G][D];
     __shared__ float sm_ml[kFusedWaves][G][2];
     __shared__ float sm_qkv[(G + 2) * D];
     __shared__ unsigned wslots[2 * kFusedWaves];
     __shared__ float sm_y[NB * kFusedMaxBlockRows];
-    static_assert(G * D <= kFusedThreads, "one thread per element of a kv head's query group");
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -703,32 +709,44 @@ __global__ __launch_bounds__(kFusedThreads) void fused_step_kernel(FusedArgs a)
                 }
             }
             __syncthreads();
-            // thread (g, dim) owns one element of the chunk's result
-            const bool has = tid < G * D;
-            const int g_ = has ? tid / D : 0, dim = has ? tid - g_ * D : 0;
-            float mn = sm_ml[0][g_][0];
+            // thread tid owns the elements tid, tid + 256, ... (g, dim) of the chunk's result
+            bool has[EP];
+            int g_[EP], dim[EP];
+            float mn[EP], ls[EP], os[EP];
+            const float *pg[EP];
 #pragma unroll
-            for (int ww = 1; ww < kFusedWaves; ww++) mn = fmaxf(mn, sm_ml[ww][g_][0]);
-            float ls = 0.f, os = 0.f;
+            for (int x = 0; x < EP; x++) {
+                const int idx = x * kFusedThreads + tid;
+                has[x] = idx < G * D;
+                g_[x] = has[x] ? idx / D : 0;
+                dim[x] = has[x] ? idx - g_[x] * D : 0;
+                mn[x] = sm_ml[0][g_[x]][0];
 #pragma unroll
-            for (int ww = 0; ww < kFusedWaves; ww++) {
-                const float sc = __expf(sm_ml[ww][g_][0] - mn);
-                ls += sm_ml[ww][g_][1] * sc;
-                os += sm_o[ww][g_][dim] * sc;
+                for (int ww = 1; ww < kFusedWaves; ww++) mn[x] = fmaxf(mn[x], sm_ml[ww][g_[x]][0]);
+                ls[x] = 0.f;
+                os[x] = 0.f;
+#pragma unroll
+                for (int ww = 0; ww < kFusedWaves; ww++) {
+                    const float sc = __expf(sm_ml[ww][g_[x]][0] - mn[x]);
+                    ls[x] += sm_ml[ww][g_[x]][1] * sc;
+                    os[x] += sm_o[ww][g_[x]][dim[x]] * sc;
+                }
+                pg[x] = b_part + (((long long)b * a.nkv + j) * a.nchunks) * (G * (D + 2)) + g_[x] * (D + 2);
             }
-            float *pg = b_part + (((long long)b * a.nkv + j) * a.nchunks) * (G * (D + 2)) + g_ * (D + 2);
             if (c != 0) {
                 // a later chunk: hand the partial to the block of chunk 0
-                if (has) {
-                    float *pp = pg + (long long)c * (G * (D + 2));
-                    stc_f32(pp + dim, os);
-                    if (dim == 0) { stc_f32(pp + D, mn); stc_f32(pp + D + 1, ls); }
-                }
+#pragma unroll
+                for (int x = 0; x < EP; x++)
+                    if (has[x]) {
+                        float *pp = const_cast<float *>(pg[x]) + (long long)c * (G * (D + 2));
+                        stc_f32(pp + dim[x], os[x]);
+                        if (dim[x] == 0) { stc_f32(pp + D, mn[x]); stc_f32(pp + D + 1, ls[x]); }
+                    }
             } else {
                 // chunk 0 collects the other chunks of its (row, kv head) in order and
                 // publishes the finished attention output
-                for (int c0 = 1; c0 < nact[b]; c0 += kFusedMergeRound) {
-                    uint32_t um[kFusedMergeRound], ul[kFusedMergeRound], uo[kFusedMergeRound];
+                for (int c0 = 1; c0 < nact[b]; c0 += MERGE_ROUND) {
+                    uint32_t um[EP][MERGE_ROUND], ul[EP][MERGE_ROUND], uo[EP][MERGE_ROUND];
                     w.spins = 0;
                     for (;;) {
                         bool ready = true;
@@ -736,28 +754,34 @@ __global__ __launch_bounds__(kFusedThreads) void fused_step_kernel(FusedArgs a)
                         // without an element read element 0): a load inside a condition is waited
                         // for on the spot, and a round of polls would be a chain of round trips
 #pragma unroll
-                        for (int u = 0; u < kFusedMergeRound; u++) {
-                            const float *pp = pg + (long long)min(c0 + u, nact[b] - 1) * (G * (D + 2));
-                            um[u] = ldc_u32(pp + D);
-                            ul[u] = ldc_u32(pp + D + 1);
-                            uo[u] = ldc_u32(pp + dim);
-                            ready = ready && um[u] != kNotYet && ul[u] != kNotYet && uo[u] != kNotYet;
-                        }
+                        for (int x = 0; x < EP; x++)
+#pragma unroll
+                            for (int u = 0; u < MERGE_ROUND; u++) {
+                                const float *pp = pg[x] + (long long)min(c0 + u, nact[b] - 1) * (G * (D + 2));
+                                um[x][u] = ldc_u32(pp + D);
+                                ul[x][u] = ldc_u32(pp + D + 1);
+                                uo[x][u] = ldc_u32(pp + dim[x]);
+                                ready = ready && um[x][u] != kNotYet && ul[x][u] != kNotYet && uo[x][u] != kNotYet;
+                            }
                         if (w.done(ready)) break;
                     }
 #pragma unroll
-                    for (int u = 0; u < kFusedMergeRound; u++)
-                        if (c0 + u < nact[b]) {
-                            const float mc = __uint_as_float(um[u]), lc = __uint_as_float(ul[u]);
-                            const float oc = __uint_as_float(uo[u]);
-                            const float m2 = fmaxf(mn, mc);
-                            const float sa = __expf(mn - m2), sb = __expf(mc - m2);
-                            ls = ls * sa + lc * sb;
-                            os = os * sa + oc * sb;
-                            mn = m2;
-                        }
+                    for (int x = 0; x < EP; x++)
+#pragma unroll
+                        for (int u = 0; u < MERGE_ROUND; u++)
+                            if (c0 + u < nact[b]) {
+                                const float mc = __uint_as_float(um[x][u]), lc = __uint_as_float(ul[x][u]);
+                                const float oc = __uint_as_float(uo[x][u]);
+                                const float m2 = fmaxf(mn[x], mc);
+                                const float sa = __expf(mn[x] - m2), sb = __expf(mc - m2);
+                                ls[x] = ls[x] * sa + lc * sb;
+                                os[x] = os[x] * sa + oc * sb;
+                                mn[x] = m2;
+                            }
                 }
-                if (has) stc_f32(b_attn + (long long)b * QD + (long long)(j * G + g_) * D + dim, os / ls);
+#pragma unroll
+                for (int x = 0; x < EP; x++)
+                    if (has[x]) stc_f32(b_attn + (long long)b * QD + (long long)(j * G + g_[x]) * D + dim[x], os[x] / ls[x]);
             }
             __syncthreads();   // sm_o / sm_ml / sm_qkv are rewritten by the block's next item
         }
@@ -803,8 +827,11 @@ __global__ __launch_bounds__(kFusedThreads) void fused_step_kernel(FusedArgs a)
         {
             int d0, d1;
             wave_rows(H, wv, d0, d1);
+            // (a row of more than 8192 columns and the polled activations do not fit the registers
+            // together: such a row is requested after the wait instead of before it)
+            constexpr bool ROW_AHEAD = KSF <= 16;
             RowRegs<RW_F, KSF, Q4> pd;
-            load_rows<RW_F, KSF, Q4>(pd, Lw.w_down, H, F, d0, d1, lane);
+            if (ROW_AHEAD) load_rows<RW_F, KSF, Q4>(pd, Lw.w_down, H, F, d0, d1, lane);
             float rv_d = 0.f;
             if (tid < h_n * NB) {
                 const int b = tid / h_n, r = tid - b * h_n;
@@ -813,6 +840,7 @@ __global__ __launch_bounds__(kFusedThreads) void fused_step_kernel(FusedArgs a)
             __syncthreads();
             float dummy[NB];
             stage_input<NB, false, 2 * KSF>(b_act, F, nullptr, a.eps, xs, dummy, red, w);
+            if (!ROW_AHEAD) load_rows<RW_F, KSF, Q4>(pd, Lw.w_down, H, F, d0, d1, lane);
             gemv_rows<NB, RW_F, KSF, Q4>(pd, Lw.w_down, H, F, d0, d1, h_b0, xs, ones, sm_y, lane);
             publish_rows<NB>(b_xout, H, h_b0, h_n, sm_y, rv_d);
         }

@@ -183,6 +183,17 @@ FUSED_CASES = [
     ("d128_one_row", variant("tiny", head_dim=128, n_q_heads=4, n_kv_heads=2), [129], 2),
     ("d128_wide", variant("tiny", head_dim=128, n_q_heads=16, n_kv_heads=8, hidden=1024, ffn=3072, vocab=2000,
                           qk_norm=True), [1, 513], 2),
+    # the wide classes (one row): query groups of 3 and 4 - two result elements per thread in the chunk
+    # merge -, hidden up to 4096, rows of up to 12288 columns; contexts over several chunks, and one
+    # long enough that a block takes more than one attention item (8 kv heads x 40 chunks > 256 blocks)
+    ("g3_3b_layer", variant("tiny", n_layers=2, head_dim=128, n_q_heads=24, n_kv_heads=8, hidden=3072, ffn=8192,
+                            vocab=3001, rope_theta=5e5), [333], 2),
+    ("g3_narrow", variant("tiny", head_dim=128, n_q_heads=6, n_kv_heads=2, hidden=1536, ffn=4000, vocab=1500,
+                          qk_norm=True), [64], 3),
+    ("g4_8b_layer", variant("tiny", n_layers=2, head_dim=128, n_q_heads=32, n_kv_heads=8, hidden=4096, ffn=12288,
+                            vocab=3001, qk_norm=True, rope_theta=1e6), [130], 2),
+    ("g4_many_items", variant("tiny", head_dim=128, n_q_heads=32, n_kv_heads=8, hidden=2048, ffn=4096, vocab=1000,
+                              qk_norm=True), [2555], 2),
 ]
 
 

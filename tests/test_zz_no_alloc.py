@@ -119,9 +119,14 @@ def test_static_scratch_refusals(dk):
         dk.decode_step_static(c.dm.handle, c.dkv.handle, c.dkv.block_tables, c.seq, c.tok, c.logits, c.next,
                               dk.STEP_PROFILE)
     assert e.value.status == "DK_E_INVALID_ARG"
-    # a table so wide (2 M tokens) that the persistent kernel's attention partials alone exceed the
-    # array: refused before any launch
-    wide = torch.zeros((2, 1 << 17), dtype=torch.int32, device="cuda")
+    c.dkv.close()
+    c.close()
+    # 40 layers, two rows and a table of 16 320 tokens (255 attention chunks per sequence): the two sets of
+    # hand-over buffers of the persistent kernel (attention partials of every layer) exceed the array -
+    # refused before any launch
+    c = Case(dk, variant("tiny", n_layers=40, n_q_heads=8, n_kv_heads=4), [5, 9], 1, seed=92)
+    c.start_static()
+    wide = torch.zeros((2, 1020), dtype=torch.int32, device="cuda")
     seq = torch.zeros(2, dtype=torch.int32, device="cuda")
     with pytest.raises(dk.DecodeKitError) as e:
         dk.decode_step_static(c.dm.handle, c.dkv.handle, wide, seq, seq, None, seq, 0)

@@ -124,6 +124,9 @@ WORKLOADS = {
                      shared_prefix=2048, n_sharers=8),
     "cfg4_l4": Workload("cfg4_l4", "qwen3_30b_a3b_l4", 16, 16, 32, context_range=(256, 4096),
                         shared_prefix=2048, n_sharers=8),
+    # one request alone on the larger dense shapes (the persistent kernel's wide classes)
+    "b1_3b": Workload("b1_3b", "llama32_3b", 1, 16, 64, contexts=(512,)),
+    "b1_8b": Workload("b1_8b", "qwen3_8b", 1, 16, 64, contexts=(512,)),
     "cfg0_q4": Workload("cfg0_q4", "tiny_q4", 5, 16, 6, contexts=(40, 16, 3, 0, 65)),
     "cfg0_moe": Workload("cfg0_moe", "tiny_moe", 3, 16, 4, contexts=(33, 16, 5)),
 }
