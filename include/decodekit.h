@@ -270,9 +270,11 @@ dk_status dk_decode_step(dk_model *model, dk_kv_pool *pool, const int32_t *d_blo
  *
  * Same arguments, results and error behaviour as dk_decode_step without
  * d_workspace / workspace_bytes.  Limits and rules of its own:
- *   - the step's workspace (dk_workspace_bytes for this B and table width) must
- *     fit DK_STATIC_SCRATCH_BYTES; otherwise DK_E_WORKSPACE_TOO_SMALL and nothing
- *     is launched (every workload shape of this library at up to 64 rows fits);
+ *   - the step's workspace must fit DK_STATIC_SCRATCH_BYTES.  Where only the
+ *     persistent step kernel's hand-over buffers outgrow it (long tables of the
+ *     3B- / 8B-class shapes at batch 1) the step runs one kernel per stage, as with
+ *     DK_STEP_NO_FUSED; if that does not fit either, DK_E_WORKSPACE_TOO_SMALL and
+ *     nothing is launched (every workload shape of this library at up to 64 rows fits);
  *   - DK_STEP_PROFILE is refused (it creates events): DK_E_INVALID_ARG;
  *   - every GPU the library runs on holds its own copy of the array until the
  *     process ends, and every call on a GPU uses that GPU's copy: calls that

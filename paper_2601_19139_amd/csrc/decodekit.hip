@@ -243,7 +243,8 @@ void gemm_plan_needs(int epi, int N, int K, int Bp, bool q4, size_t &tickets, si
 }
 
 // q4: the model's matrices are 4-bit; every batch size then takes the matrix-core kernels
-Workspace carve(const dk_model_config &c, int B, int max_blocks, bool q4)
+// allow_fused false: without the persistent kernel's hand-over buffers (they come last: everything else keeps its place)
+Workspace carve(const dk_model_config &c, int B, int max_blocks, bool q4, bool allow_fused = true)
 {
     Workspace w{};
     const int d = c.head_dim, G = c.n_q_heads / c.n_kv_heads;
@@ -367,7 +368,7 @@ Workspace carve(const dk_model_config &c, int B, int max_blocks, bool q4)
     // (the block of a sequence's first chunk waits for the blocks of its other chunks while every block
     // works through its items in ascending order: free of cycles as long as a sequence has no more
     // chunks than there are blocks)
-    w.fused = fused_variant(c, B) >= 0 && (ctx_max + dk::kFusedChunk - 1) / dk::kFusedChunk <= fused_blocks();
+    w.fused = allow_fused && fused_variant(c, B) >= 0 && (ctx_max + dk::kFusedChunk - 1) / dk::kFusedChunk <= fused_blocks();
     if (w.fused) {
         w.fused_chunks = (ctx_max + dk::kFusedChunk - 1) / dk::kFusedChunk;
         w.fused_set_floats = dk::fused_layout(c.n_layers, B, c.hidden, c.n_q_heads, c.n_kv_heads, d, c.ffn,
@@ -1055,7 +1056,13 @@ dk_status dk_decode_step_static(dk_model *model, dk_kv_pool *pool, const int32_t
         return fail(DK_E_INVALID_ARG, "DK_STEP_PROFILE creates events; the entry point that allocates nothing refuses it");
     if (B <= 0 || B > DK_MAX_BATCH) return fail(DK_E_INVALID_ARG, "B %d (1..%d)", B, DK_MAX_BATCH);
     if (max_blocks <= 0) return fail(DK_E_INVALID_ARG, "max_blocks_per_seq %d", max_blocks);
-    const size_t need = carve(model->cfg, B, max_blocks, model->q4).total;
+    size_t need = carve(model->cfg, B, max_blocks, model->q4, !(flags & DK_STEP_NO_FUSED)).total;
+    if (need > DK_STATIC_SCRATCH_BYTES && !(flags & DK_STEP_NO_FUSED)) {
+        // the persistent kernel's hand-over buffers (two sets, every layer's attention partials) outgrow the
+        // array for long tables of the wide shapes: such a step runs one kernel per stage instead
+        flags |= DK_STEP_NO_FUSED;
+        need = carve(model->cfg, B, max_blocks, model->q4, false).total;
+    }
     if (need > DK_STATIC_SCRATCH_BYTES)
         return fail(DK_E_WORKSPACE_TOO_SMALL,
                     "this step needs %zu bytes of workspace; the static scratch holds %zu (use dk_decode_step "
@@ -1239,13 +1246,13 @@ static dk_status decode_step_impl(dk_model *model, dk_kv_pool *pool, const int32
     if (pc.n_layers != c.n_layers || pc.n_kv_heads != c.n_kv_heads || pc.head_dim != c.head_dim)
         return fail(DK_E_INVALID_ARG, "pool was created for a different model shape");
     if ((uintptr_t)d_workspace % 256) return fail(DK_E_INVALID_ARG, "workspace must be 256-byte aligned");
-    const Workspace w = carve(c, B, max_blocks, model->q4);
+    const Workspace w = carve(c, B, max_blocks, model->q4, !(flags & DK_STEP_NO_FUSED));
     if (workspace_bytes < w.total)
         return fail(DK_E_WORKSPACE_TOO_SMALL, "workspace %zu bytes, %zu needed", workspace_bytes, w.total);
 
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     char *ws = static_cast<char *>(d_workspace);
-    if (w.fused && !(flags & DK_STEP_NO_FUSED)) {
+    if (w.fused) {
         const dk_status fs = launch_fused(model, pool, w, ws, d_block_tables, max_blocks, d_seq_lens, d_tokens,
                                           B, d_logits, d_next_tokens, (flags & DK_STEP_ADVANCE) != 0, st);
         if (fs != DK_E_UNSUPPORTED_SHAPE) return fs;   // otherwise: the ordinary path below

@@ -139,7 +139,8 @@ def test_model_shape_checks_and_workspace():
     m = dk.create_model(cfg, ptrs)
     small = dk.workspace_bytes(m, 1, 40)
     big = dk.workspace_bytes(m, 16, 260)
-    assert 0 < small < big < 64 << 20
+    # (the largest part: the persistent kernel's two sets of hand-over buffers at batch 1, 78 MB for 4160 tokens)
+    assert 0 < small < big < 128 << 20
     with pytest.raises(dk.DecodeKitError) as e:
         dk.workspace_bytes(m, 65, 40)
     assert e.value.status == "DK_E_INVALID_ARG"

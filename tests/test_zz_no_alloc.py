@@ -119,18 +119,31 @@ def test_static_scratch_refusals(dk):
         dk.decode_step_static(c.dm.handle, c.dkv.handle, c.dkv.block_tables, c.seq, c.tok, c.logits, c.next,
                               dk.STEP_PROFILE)
     assert e.value.status == "DK_E_INVALID_ARG"
-    c.dkv.close()
-    c.close()
     # 40 layers, two rows and a table of 16 320 tokens (255 attention chunks per sequence): the two sets of
-    # hand-over buffers of the persistent kernel (attention partials of every layer) exceed the array -
-    # refused before any launch
-    c = Case(dk, variant("tiny", n_layers=40, n_q_heads=8, n_kv_heads=4), [5, 9], 1, seed=92)
-    c.start_static()
+    # hand-over buffers of the persistent kernel (attention partials of every layer) exceed the array, so the
+    # step runs one kernel per stage - and gives what dk_decode_step gives with DK_STEP_NO_FUSED
+    deep = Case(dk, variant("tiny", n_layers=40, n_q_heads=8, n_kv_heads=4), [5, 9], 1, seed=92)
+    deep.start_static()
     wide = torch.zeros((2, 1020), dtype=torch.int32, device="cuda")
-    seq = torch.zeros(2, dtype=torch.int32, device="cuda")
-    with pytest.raises(dk.DecodeKitError) as e:
-        dk.decode_step_static(c.dm.handle, c.dkv.handle, wide, seq, seq, None, seq, 0)
-    assert e.value.status == "DK_E_WORKSPACE_TOO_SMALL"
+    wide[:, :deep.dkv.block_tables.shape[1]] = deep.dkv.block_tables
+    assert dk.workspace_bytes(deep.dm.handle, 2, 1020) > dk.STATIC_SCRATCH_BYTES
+    # the reference: the same step (same table width) with a caller-owned workspace and DK_STEP_NO_FUSED,
+    # on a second copy of the cache
+    ref_kv = dk.DeviceKV(deep.dm, deep.lay, deep.pool)
+    nbytes = dk.workspace_bytes(deep.dm.handle, 2, 1020)
+    ws = torch.empty(nbytes + 256, dtype=torch.uint8, device="cuda")
+    ws_ptr = (ws.data_ptr() + 255) // 256 * 256
+    r_next, r_logits = torch.empty_like(deep.next), torch.empty_like(deep.logits)
+    dk.decode_step(deep.dm.handle, ref_kv.handle, wide, deep.seq.clone(), deep.tok.clone(), ws_ptr, r_logits, r_next,
+                   dk.STEP_NO_FUSED, None, workspace_bytes_=nbytes)
+    dk.decode_step_static(deep.dm.handle, deep.dkv.handle, wide, deep.seq, deep.tok, deep.logits, deep.next, 0)
+    torch.cuda.synchronize()
+    same((deep.next.cpu().numpy(), deep.logits.cpu().numpy()), (r_next.cpu().numpy(), r_logits.cpu().numpy()),
+         "deep model, wide table")
+    assert np.array_equal(deep.dkv.bits(), ref_kv.bits())
+    ref_kv.close()
+    deep.dkv.close()
+    deep.close()
     torch.cuda.synchronize()
     c.dkv.close()
     c.close()
