@@ -396,6 +396,59 @@ def extra_workload(args, name, dk, W, np, torch, ceiling):
     return out
 
 
+STAMP_NAMES = ("layer begins", "q|k|v rows handed over", "q|k|v of the attention item arrived", "chunk attention done",
+               "merged attention output handed over (collecting blocks)", "attention output arrived",
+               "x_mid rows handed over", "x_mid arrived", "activations handed over", "activations arrived",
+               "x_out rows handed over", "next layer's input arrived")
+
+
+def bench_stage_stamps(args, wl, dk, W, np, torch):
+    """Where a layer of the persistent step kernel spends its time: every block stamps the device's
+    100 MHz clock at the stage boundaries of one layer (dk_debug_set_stage_stamps); reported per
+    boundary as microseconds since the earliest block began the layer - median, earliest and latest
+    block - averaged over the timed steps."""
+    from workloads.blocktable import layout_for
+    shape, lay = wl.cfg, layout_for(wl)
+    weights = make_model_weights(args, W, shape, wl.seed_weights)
+    pool_bits = W.fill_kv_pool(shape, lay, wl.seed_kv, poison=False)
+    tokens0 = W.initial_tokens(shape, wl.batch, wl.seed_tokens)
+    dm = dk.DeviceModel(shape, weights)
+    dkv = dk.DeviceKV(dm, lay, pool_bits)
+    dec = dk.Decoder(dm, dkv, lay.contexts, tokens0, want_logits=True)
+    ctx0, tok0 = dec.seq_lens.clone(), dec.tokens.clone()
+    n_blocks = torch.cuda.get_device_properties(0).multi_processor_count
+    stamps = torch.zeros((n_blocks, dk.STAGE_STAMPS), dtype=torch.int64, device="cuda")
+    layer = args.stamps
+    for _ in range(args.warmup):
+        dec.step(flags=dk.STEP_ADVANCE)
+    torch.cuda.synchronize()
+    if dec.fused_status() is None:
+        print("bench.py --stamps: this workload does not run as the persistent kernel", file=sys.stderr)
+        sys.exit(2)
+    dk.debug_set_stage_stamps(dm.handle, layer, stamps)
+    n = len(STAMP_NAMES)
+    acc = np.zeros((3, n))
+    steps = min(args.steps, wl.steps - 1)
+    dec.seq_lens.copy_(ctx0)
+    dec.tokens.copy_(tok0)
+    for _ in range(steps):
+        stamps.zero_()
+        dec.step(flags=dk.STEP_ADVANCE)
+        torch.cuda.synchronize()
+        t = stamps.cpu().numpy()[:, :n].astype(np.float64)
+        t0 = t[:, 0].min()
+        for i in range(n):
+            col = t[:, i][t[:, i] > 0]                        # blocks that reached the boundary
+            acc[:, i] += ((np.median(col) - t0) / 100.0, (col.min() - t0) / 100.0, (col.max() - t0) / 100.0)
+    dk.debug_set_stage_stamps(dm.handle, 0, None)
+    acc /= steps
+    out = {"metric": "persistent_kernel_stage_stamps_us", "workload": wl.name, "layer": layer, "steps": steps,
+           "blocks": int(n_blocks), "unit": "us since the first block began the layer",
+           "boundaries": [{"boundary": STAMP_NAMES[i], "median": round(acc[0, i], 2), "earliest": round(acc[1, i], 2),
+                           "latest": round(acc[2, i], 2)} for i in range(n)]}
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -417,6 +470,9 @@ def main():
     ap.add_argument("--weights", choices=("bf16", "q4"), default="bf16",
                     help="q4: the projections and the lm_head as 4-bit group-wise affine codes (groups of 64 "
                          "columns, bf16 scale and bias), the precision the paper benchmarks; dense workloads")
+    ap.add_argument("--stamps", type=int, default=-1, metavar="L",
+                    help="instead of timing steps: where layer L of the persistent step kernel spends its time "
+                         "(device clock stamps of every block at the stage boundaries)")
     ap.add_argument("--kernel-per-stage", action="store_true",
                     help="never take the single persistent kernel (small batches of small dense models)")
     args = ap.parse_args()
@@ -441,6 +497,8 @@ def main():
         return bench_serve(args, wl, dk, W, np, torch)
     if args.ttft:
         return bench_ttft(args, wl, dk, W, np, torch)
+    if args.stamps >= 0:
+        return bench_stage_stamps(args, wl, dk, W, np, torch)
     m = measure_decode(args, wl, dk, W, np, torch, args.steps, args.warmup)
     shape, lay, weights, pool_bits, tokens0, dm = (m[k] for k in ("shape", "lay", "weights", "pool_bits", "tokens0", "dm"))
     span, ms_per_step, tok_s, alg_bytes, step_dev_s = (m[k] for k in ("span", "ms_per_step", "tok_s", "alg_bytes", "step_dev_s"))

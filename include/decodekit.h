@@ -380,6 +380,20 @@ dk_status dk_fused_status(const dk_model *model, const void *d_workspace, uint32
  * and dk_fused_status reports the step.  Host only. */
 dk_status dk_debug_set_wait_limit(dk_model *model, int32_t polls);
 
+/* Measurement aid for the persistent step kernel: from the next step on, every block records the device's
+ * constant 100 MHz clock at the stage boundaries of layer `layer` into d_stamps[block][DK_STAGE_STAMPS]
+ * (int64, device memory of at least blocks x DK_STAGE_STAMPS x 8 bytes with blocks = compute units of the
+ * device; owned by the caller, must outlive the steps; entries a block does not reach keep their old value).
+ * Boundaries: 0 layer begins, 1 q|k|v rows handed over, 2 q|k|v of the block's attention item arrived,
+ * 3 chunk attention done, 4 merged attention output handed over (collecting blocks only), 5 attention output
+ * arrived, 6 x_mid handed over, 7 x_mid arrived, 8 activations handed over, 9 activations arrived, 10 x_out
+ * handed over, 11 next layer's input arrived.  Only the instance for batch 1 of the 0.6B-class shapes with
+ * bf16 weights (head_dim 128, query groups of 2) has a stamping twin; other steps ignore the setting.
+ * d_stamps NULL switches the stamps off (the default: the ordinary kernel, which has no trace of them).
+ * Host only. */
+#define DK_STAGE_STAMPS 16
+dk_status dk_debug_set_stage_stamps(dk_model *model, int32_t layer, void *d_stamps, size_t stamps_bytes);
+
 /* Experts chosen in the most recent decode step that used `d_workspace` with
  * the same B and max_blocks_per_seq (mixture-of-experts models only): copies
  * int32 [n_layers][B][top_k], each row in order of decreasing router

@@ -10,7 +10,7 @@ from .binding import (  # noqa: F401
     kv_pool_bytes, create_kv_pool, destroy_kv_pool,
     kv_alloc_block, kv_alloc_block_id, kv_retain_block, kv_release_block, kv_refcount,
     kv_free_blocks, kv_offset, kv_validate_tables, append_kv,
-    create_model, create_model_q4, destroy_model, read_stream, gemm_plan_query, workspace_bytes, decode_step, decode_step_static, STATIC_SCRATCH_BYTES, step_routing, step_algorithmic_bytes, profile_read, fused_status, workspace_reset, prefill_chunk, debug_set_wait_limit, sample_tokens, sample_scratch_bytes,
+    create_model, create_model_q4, destroy_model, read_stream, gemm_plan_query, workspace_bytes, decode_step, decode_step_static, STATIC_SCRATCH_BYTES, step_routing, step_algorithmic_bytes, profile_read, fused_status, workspace_reset, prefill_chunk, debug_set_wait_limit, debug_set_stage_stamps, STAGE_STAMPS, sample_tokens, sample_scratch_bytes,
     STEP_ADVANCE, STEP_PROFILE, STEP_NO_FUSED, KERNEL_CLASSES, STATUS,
     EngineConfig, prefix_index_create, prefix_index_destroy, prefix_index_match, prefix_index_insert,
     prefix_index_evict_lru, prefix_index_size, engine_device_bytes, engine_create, engine_destroy,

@@ -81,6 +81,7 @@ _SIGNATURES = {
                                      C.c_int32, C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p, C.c_void_p]),
     "dk_workspace_reset": (C.c_int32, [C.c_void_p]),
     "dk_debug_set_wait_limit": (C.c_int32, [C.c_void_p, C.c_int32]),
+    "dk_debug_set_stage_stamps": (C.c_int32, [C.c_void_p, C.c_int32, C.c_void_p, C.c_size_t]),
     "dk_fused_status": (C.c_int32, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
     "dk_profile_read": (C.c_int32, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32]),
     "dk_step_routing": (C.c_int32, [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]),
@@ -310,6 +311,17 @@ def prefill_chunk(model, pool, d_block_table, start: int, d_tokens, d_workspace,
     _check(lib().dk_prefill_chunk(model, pool, _ptr(d_block_table), int(d_block_table.numel()), int(start),
                                   _ptr(d_tokens), int(d_tokens.numel()), _ptr(d_workspace), workspace_bytes_,
                                   _ptr(d_logits), _ptr(d_next_tokens), _stream(stream)))
+
+
+STAGE_STAMPS = 16
+
+
+def debug_set_stage_stamps(model, layer: int, d_stamps):
+    """d_stamps: an int64 device tensor [blocks][STAGE_STAMPS], or None to switch the stamps off."""
+    if d_stamps is None:
+        _check(lib().dk_debug_set_stage_stamps(model, 0, None, 0))
+    else:
+        _check(lib().dk_debug_set_stage_stamps(model, layer, _ptr(d_stamps), d_stamps.numel() * d_stamps.element_size()))
 
 
 def debug_set_wait_limit(model, polls: int):

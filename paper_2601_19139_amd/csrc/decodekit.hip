@@ -153,6 +153,8 @@ struct dk_model {
     int fused_parity = 0;
     unsigned fused_serial = 0;
     int fused_spin_limit = dk::kFusedSpinLimit;
+    long long *fused_stamps = nullptr;   // measurement aid (dk_debug_set_stage_stamps)
+    int fused_stamp_layer = 0;
     int n_cus = 0;
 };
 
@@ -628,11 +630,11 @@ dk_status launch_prefill_attention_d(const dk::AttnArgs &a, int G, dim3 grid, hi
     return DK_OK;
 }
 
-template <int NB, int D, int G, int KSH, int KSQ, int KSF, bool Q4>
+template <int NB, int D, int G, int KSH, int KSQ, int KSF, bool Q4, bool STAMPS = false>
 dk_status launch_fused_q(const dk::FusedArgs &a, hipStream_t st)
 {
     constexpr size_t lds = dk::fused_xs_bytes(NB, KSH, KSQ, KSF);
-    auto kernel = dk::fused_step_kernel<NB, D, G, KSH, KSQ, KSF, Q4>;
+    auto kernel = dk::fused_step_kernel<NB, D, G, KSH, KSQ, KSF, Q4, STAMPS>;
     static bool lds_allowed = false;   // with the kernel's static LDS this can exceed 64 KB: ask once
     if (!lds_allowed) {
         DK_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -708,6 +710,8 @@ dk_status launch_fused(dk_model *model, dk_kv_pool *pool, const Workspace &w, ch
     model->fused_serial = model->fused_serial + 1 == 0 ? 1 : model->fused_serial + 1;
     a.serial = model->fused_serial;
     a.spin_limit = model->fused_spin_limit;
+    a.stamps = model->fused_stamps;
+    a.stamp_layer = model->fused_stamp_layer;
     std::memcpy(a.inv_freq, model->inv_freq, sizeof a.inv_freq);
     for (int l = 0; l < c.n_layers; l++) {
         const dk_layer_weights &L = model->layers[(size_t)l];
@@ -721,6 +725,8 @@ dk_status launch_fused(dk_model *model, dk_kv_pool *pool, const Workspace &w, ch
     dk_status s = DK_E_UNSUPPORTED_SHAPE;
     if (v == 0 && B == 1) s = launch_fused_inst<1, 64, 2, 1, 1, 2>(a, model->q4, st);
     else if (v == 0 && B == 2) s = launch_fused_inst<2, 64, 2, 1, 1, 2>(a, model->q4, st);
+    else if (v == 1 && B == 1 && a.stamps != nullptr && !model->q4)
+        s = launch_fused_q<1, 128, 2, 2, 4, 6, false, true>(a, st);   // the one instance with stage stamps
     else if (v == 1 && B == 1) s = launch_fused_inst<1, 128, 2, 2, 4, 6>(a, model->q4, st);
     else if (v == 1 && B == 2) s = launch_fused_inst<2, 128, 2, 2, 4, 6>(a, model->q4, st);
     else if (v == 2 && B == 1) s = launch_fused_inst<1, 128, 3, 6, 6, 16>(a, model->q4, st);
@@ -1646,6 +1652,22 @@ dk_status dk_debug_set_wait_limit(dk_model *model, int32_t polls)
     if (!model) return fail(DK_E_INVALID_ARG, "model is NULL");
     if (polls < 0) return fail(DK_E_INVALID_ARG, "polls %d", polls);
     model->fused_spin_limit = polls > 0 ? polls : dk::kFusedSpinLimit;
+    return DK_OK;
+}
+
+dk_status dk_debug_set_stage_stamps(dk_model *model, int32_t layer, void *d_stamps, size_t stamps_bytes)
+{
+    if (!model) return fail(DK_E_INVALID_ARG, "model is NULL");
+    if (d_stamps == nullptr) {
+        model->fused_stamps = nullptr;
+        return DK_OK;
+    }
+    if (layer < 0 || layer >= model->cfg.n_layers) return fail(DK_E_INVALID_ARG, "layer %d of %d", layer, model->cfg.n_layers);
+    const size_t need = (size_t)fused_blocks() * dk::kFusedStamps * sizeof(long long);
+    if (stamps_bytes < need || (uintptr_t)d_stamps % 8)
+        return fail(DK_E_INVALID_ARG, "stamp buffer of %zu bytes (%zu needed, 8-byte aligned)", stamps_bytes, need);
+    model->fused_stamps = static_cast<long long *>(d_stamps);
+    model->fused_stamp_layer = layer;
     return DK_OK;
 }
 

@@ -41,6 +41,7 @@ constexpr int kFusedMaxLayers = 40;
 constexpr int kFusedChunk = 64;             // tokens per attention work item
 constexpr int kFusedMergeRound = 12;        // chunk partials the collecting block awaits at a time
 constexpr int kFusedWaveTiles = kFusedChunk / (16 * kFusedWaves);   // 16-token K/V tiles per wave
+constexpr int kFusedStamps = 16;            // stage boundaries a block can stamp per layer (see FusedArgs::stamps)
 constexpr int kFusedSpinLimit = 1 << 16;    // polls before a block gives up (each ~1 us)
 
 struct FusedLayer {
@@ -65,6 +66,8 @@ struct FusedArgs {
     unsigned *status;      // [0] abort tag, [1] number of timeouts ever
     unsigned serial;       // this step's tag (never 0)
     int spin_limit;        // polls before a block gives up a wait
+    long long *stamps;     // measurement aid, normally null: [blocks][kFusedStamps] device clock readings of layer stamp_layer
+    int stamp_layer;
     double inv_freq[64];
     FusedLayer layers[kFusedMaxLayers];
 };
@@ -388,7 +391,8 @@ constexpr size_t fused_xs_bytes(int NB, int KSH, int KSQ, int KSF)
     return (size_t)NB * 512 * (KSF > KSQ ? (KSF > KSH ? KSF : KSH) : (KSQ > KSH ? KSQ : KSH)) * 4;
 }
 
-template <int NB, int D, int G, int KSH, int KSQ, int KSF, bool Q4 = false>
+// STAMPS: the instance that records stage stamps (FusedArgs::stamps); the ordinary one has no trace of them
+template <int NB, int D, int G, int KSH, int KSQ, int KSF, bool Q4 = false, bool STAMPS = false>
 __global__ __launch_bounds__(kFusedThreads) void fused_step_kernel(FusedArgs a)
 {
     constexpr int BS = 16, TPR = D / 8, TPW = 64 / TPR, NI = BS / TPW;
@@ -412,6 +416,15 @@ __global__ __launch_bounds__(kFusedThreads) void fused_step_kernel(FusedArgs a)
     const int H = a.H, F = a.F, V = a.V, QD = a.nq * D, QKV = (a.nq + 2 * a.nkv) * D;
     const FusedLayout lay = fused_layout(a.L, NB, H, a.nq, a.nkv, D, F, a.nchunks, nblk);
     Waiter w{a.status, a.serial, 0, false, a.spin_limit, wslots, 0};
+    // stage stamps of one layer (100 MHz device clock), when the host asked for them: one flag per
+    // layer, tested at every boundary
+    long long *const stamp_to = a.stamps != nullptr ? a.stamps + (long long)blk * kFusedStamps : nullptr;
+    bool stamp_on = false;
+    auto stamp = [&](int i) {
+        if constexpr (STAMPS) {
+            if (stamp_on) stamp_to[i] = wall_clock64();
+        }
+    };
 
     // refill the other buffer set for the next step
     {
@@ -485,6 +498,8 @@ __global__ __launch_bounds__(kFusedThreads) void fused_step_kernel(FusedArgs a)
 
     for (int l = 0; l < a.L; l++) {
         const FusedLayer &Lw = a.layers[l];
+        if constexpr (STAMPS) stamp_on = stamp_to != nullptr && l == a.stamp_layer && tid == 0;
+        stamp(0);    // layer begins (input staged, q|k|v rows requested)
         float *base = a.set + lay.per_layer * l;
         float *b_qkv = base + lay.qkv, *b_part = base + lay.part, *b_attn = base + lay.attn, *b_xmid = base + lay.xmid;
         float *b_act = base + lay.act, *b_xout = base + lay.xout;
@@ -493,6 +508,7 @@ __global__ __launch_bounds__(kFusedThreads) void fused_step_kernel(FusedArgs a)
         // ---- q|k|v = W_qkv rmsnorm(x) ------------------------------------------------
         gemv_rows<NB, RW_H, KSH, Q4>(pre_h, Lw.w_qkv, QKV, H, r0, r1, qkv_b0, xs, rinv, sm_y, lane);
         publish_rows<NB>(b_qkv, QKV, qkv_b0, qkv_n, sm_y, 0.f);
+        stamp(1);    // q|k|v rows handed over
         // ---- attention: request the K/V tiles, then wait for q|k|v --------------------
         RowRegs<RW_Q, KSQ, Q4> pre_q;
         int q0, q1;
@@ -571,6 +587,7 @@ __global__ __launch_bounds__(kFusedThreads) void fused_step_kernel(FusedArgs a)
                     }
                     if (w.done(ready)) break;
                 }
+                stamp(2);    // q|k|v of the block's attention item arrived
 #pragma unroll
                 for (int e = 0; e < PE; e++)
                     if (src[e]) sm_qkv[e * kFusedThreads + tid] = __uint_as_float(got[e]);
@@ -709,6 +726,7 @@ __global__ __launch_bounds__(kFusedThreads) void fused_step_kernel(FusedArgs a)
                 }
             }
             __syncthreads();
+            stamp(3);    // the chunk's scores, softmax and weighted values done
             // thread tid owns the elements tid, tid + 256, ... (g, dim) of the chunk's result
             bool has[EP];
             int g_[EP], dim[EP];
@@ -782,6 +800,7 @@ __global__ __launch_bounds__(kFusedThreads) void fused_step_kernel(FusedArgs a)
 #pragma unroll
                 for (int x = 0; x < EP; x++)
                     if (has[x]) stc_f32(b_attn + (long long)b * QD + (long long)(j * G + g_[x]) * D + dim[x], os[x] / ls[x]);
+                stamp(4);    // (collecting blocks) merged attention output handed over
             }
             __syncthreads();   // sm_o / sm_ml / sm_qkv are rewritten by the block's next item
         }
@@ -789,8 +808,10 @@ __global__ __launch_bounds__(kFusedThreads) void fused_step_kernel(FusedArgs a)
         {
             float dummy[NB];
             stage_input<NB, false, 2 * KSQ>(b_attn, QD, nullptr, a.eps, xs, dummy, red, w);
+            stamp(5);    // attention output arrived
             gemv_rows<NB, RW_Q, KSQ, Q4>(pre_q, Lw.w_o, H, QD, q0, q1, h_b0, xs, ones, sm_y, lane);
             publish_rows<NB>(b_xmid, H, h_b0, h_n, sm_y, rv_o);
+            stamp(6);    // x_mid rows handed over
         }
         // ---- act = silu(W_g h) * (W_u h), h = rmsnorm(x_mid) ----------------------------
         {
@@ -801,6 +822,7 @@ __global__ __launch_bounds__(kFusedThreads) void fused_step_kernel(FusedArgs a)
             load_rows<RW_GU, KSH, Q4>(pu, Lw.w_up, F, H, f0, f1, lane);
             __syncthreads();   // xs is about to be overwritten
             stage_input<NB, true, 2 * KSH>(b_xmid, H, Lw.g_mlp, a.eps, xs, rinv, red, w);
+            stamp(7);    // x_mid arrived
             for (int rb = f0; rb < f1; rb += RW_GU) {
                 if (rb != f0) {
                     load_rows<RW_GU, KSH, Q4>(pg, Lw.w_gate, F, H, rb, f1, lane);
@@ -822,6 +844,7 @@ __global__ __launch_bounds__(kFusedThreads) void fused_step_kernel(FusedArgs a)
                 if (lane < RW_GU * NB && rb + li < f1) sm_y[lb * kFusedMaxBlockRows + rb + li - f_b0] = v;
             }
             publish_rows<NB>(b_act, F, f_b0, f_n, sm_y, 0.f);
+            stamp(8);    // activations handed over
         }
         // ---- x_out = x_mid + W_d act ------------------------------------------------------
         {
@@ -840,15 +863,18 @@ __global__ __launch_bounds__(kFusedThreads) void fused_step_kernel(FusedArgs a)
             __syncthreads();
             float dummy[NB];
             stage_input<NB, false, 2 * KSF>(b_act, F, nullptr, a.eps, xs, dummy, red, w);
+            stamp(9);    // activations arrived
             if (!ROW_AHEAD) load_rows<RW_F, KSF, Q4>(pd, Lw.w_down, H, F, d0, d1, lane);
             gemv_rows<NB, RW_F, KSF, Q4>(pd, Lw.w_down, H, F, d0, d1, h_b0, xs, ones, sm_y, lane);
             publish_rows<NB>(b_xout, H, h_b0, h_n, sm_y, rv_d);
+            stamp(10);   // x_out rows handed over
         }
         // ---- next layer's q|k|v weights ahead, then its input --------------------------------
         if (l + 1 < a.L) {
             load_rows<RW_H, KSH, Q4>(pre_h, a.layers[l + 1].w_qkv, QKV, H, r0, r1, lane);
             __syncthreads();
             stage_input<NB, true, 2 * KSH>(b_xout, H, a.layers[l + 1].g_attn, a.eps, xs, rinv, red, w);
+            stamp(11);   // next layer's input arrived
         }
     }
 
