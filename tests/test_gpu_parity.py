@@ -312,6 +312,31 @@ def test_cfg1_full_size(dk, orc):
     assert st["worst"] < TIGHT
 
 
+@pytest.mark.parametrize("wname", ["b1_3b", "b1_8b"])
+def test_single_request_on_the_larger_shapes_full_size(dk, orc, wname):
+    """One request alone on the 3B and 8B shapes at full size (28 / 36 layers, context 512): the wide
+    classes of the persistent kernel (query groups of 3 and 4, two result elements per thread in the
+    chunk merge, rows of 8192 / 12288 columns), 12 steps teacher-forced across a block boundary, every
+    logit against the oracle; the kernel-per-stage path must give the same tokens."""
+    wl = W.WORKLOADS[wname]
+    shape, lay = wl.cfg, layout_for(wl)
+    weights = W.make_weights(shape, wl.seed_weights)
+    pool = W.fill_kv_pool(shape, lay, wl.seed_kv)
+    tokens = W.initial_tokens(shape, wl.batch, wl.seed_tokens)
+    steps = 12
+    out = run_both(orc, shape, weights, lay, pool, tokens, steps)
+    assert out["fused_status"] == (0, 0), "the persistent kernel did not run (or gave up a wait)"
+    check_parity(out)
+    st = parity_stats(out)
+    check_pool(out, pool, shape, lay, steps)
+    log_result(f"{wname} full size (persistent kernel): {st['tokens']} tokens teacher-forced, greedy agreement "
+               f"{st['agree']:.4f}, logits rel-L2 worst {st['worst']:.3e} mean {st['mean']:.3e}")
+    assert st["tokens"] == steps and st["agree"] == 1.0 and st["worst"] < TIGHT
+    staged = run_both(orc, shape, weights, lay, pool, tokens, 2, gpu_flags=dk.STEP_NO_FUSED)
+    for a, b in zip(staged["gpu_next"], out["gpu_next"][:2]):
+        assert np.array_equal(a, b)
+
+
 # rows: sharers of the prefix and non-sharers; rows x steps >= 128 compared tokens per workload
 FULL_SIZE = [("cfg2", (0, 2, 5, 7, 8, 10, 13, 15), 16), ("cfg3", (1, 6, 11, 14), 32),
              ("cfg4_l4", (1, 8, 14), 2), ("cfg4", (0, 5, 9, 15), 32)]
