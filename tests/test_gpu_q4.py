@@ -82,6 +82,23 @@ def test_q4_shapes_and_edges(dk, orc, name, shape, contexts, steps):
     check_pool(out, pool, shape, lay, steps)
 
 
+@pytest.mark.parametrize("heads,hidden,ffn", [((6, 2), 1536, 4096), ((8, 2), 2048, 8192)], ids=["g3", "g4"])
+def test_q4_persistent_kernel_wide_classes(dk, orc, heads, hidden, ffn):
+    """One row of a 4-bit model with query groups of 3 and 4: the wide classes of the persistent kernel
+    with packed codes (must run as the persistent kernel, and meet the oracle)."""
+    shape = variant("tiny_q4", hidden=hidden, ffn=ffn, vocab=2000, n_q_heads=heads[0], n_kv_heads=heads[1],
+                    head_dim=128, qk_norm=True, n_layers=2)
+    lay = build_block_tables([150], 16, 3, seed=31)
+    weights = quantize_weights(W.make_weights(shape, 14))
+    pool = W.fill_kv_pool(shape, lay, 15)
+    tokens = W.initial_tokens(shape, 1, 16)
+    out = run_both(orc, shape, weights, lay, pool, tokens, 3)
+    assert out["fused_status"] == (0, 0), "the persistent kernel did not run (or gave up a wait)"
+    worst, agree = check_parity(out)
+    assert worst < TIGHT and agree == 1.0, (worst, agree)
+    check_pool(out, pool, shape, lay, 3)
+
+
 @pytest.mark.parametrize("contexts", [[37], [64, 5]], ids=["batch1", "batch2"])
 def test_q4_both_paths_for_small_batches(dk, orc, contexts):
     """Batches of 1-2 rows take the single persistent kernel (vector-ALU dot products over the
