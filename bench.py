@@ -428,6 +428,8 @@ def bench_stage_stamps(args, wl, dk, W, np, torch):
     dk.debug_set_stage_stamps(dm.handle, layer, stamps)
     n = len(STAMP_NAMES)
     acc = np.zeros((3, n))
+    step_names = ("kernel entry", "first layer begins", "lm_head begins", "lm_head rows streamed")
+    acc_step = np.zeros((3, 4))
     steps = min(args.steps, wl.steps - 1)
     dec.seq_lens.copy_(ctx0)
     dec.tokens.copy_(tok0)
@@ -435,17 +437,25 @@ def bench_stage_stamps(args, wl, dk, W, np, torch):
         stamps.zero_()
         dec.step(flags=dk.STEP_ADVANCE)
         torch.cuda.synchronize()
-        t = stamps.cpu().numpy()[:, :n].astype(np.float64)
+        raw = stamps.cpu().numpy().astype(np.float64)
+        t = raw[:, :n]
         t0 = t[:, 0].min()
+        ts = raw[:, 12:16]
+        ts0 = ts[:, 0].min()
+        for i in range(4):
+            acc_step[:, i] += ((np.median(ts[:, i]) - ts0) / 100.0, (ts[:, i].min() - ts0) / 100.0, (ts[:, i].max() - ts0) / 100.0)
         for i in range(n):
             col = t[:, i][t[:, i] > 0]                        # blocks that reached the boundary
             acc[:, i] += ((np.median(col) - t0) / 100.0, (col.min() - t0) / 100.0, (col.max() - t0) / 100.0)
     dk.debug_set_stage_stamps(dm.handle, 0, None)
     acc /= steps
+    acc_step /= steps
     out = {"metric": "persistent_kernel_stage_stamps_us", "workload": wl.name, "layer": layer, "steps": steps,
            "blocks": int(n_blocks), "unit": "us since the first block began the layer",
            "boundaries": [{"boundary": STAMP_NAMES[i], "median": round(acc[0, i], 2), "earliest": round(acc[1, i], 2),
-                           "latest": round(acc[2, i], 2)} for i in range(n)]}
+                           "latest": round(acc[2, i], 2)} for i in range(n)],
+           "step": [{"boundary": step_names[i], "median": round(acc_step[0, i], 2), "earliest": round(acc_step[1, i], 2),
+                     "latest": round(acc_step[2, i], 2)} for i in range(4)]}
     print(json.dumps(out))
 
 

@@ -387,7 +387,8 @@ dk_status dk_debug_set_wait_limit(dk_model *model, int32_t polls);
  * Boundaries: 0 layer begins, 1 q|k|v rows handed over, 2 q|k|v of the block's attention item arrived,
  * 3 chunk attention done, 4 merged attention output handed over (collecting blocks only), 5 attention output
  * arrived, 6 x_mid handed over, 7 x_mid arrived, 8 activations handed over, 9 activations arrived, 10 x_out
- * handed over, 11 next layer's input arrived.  Only the instance for batch 1 of the 0.6B-class shapes with
+ * handed over, 11 next layer's input arrived; and of the step itself 12 kernel entry, 13 first layer begins,
+ * 14 lm_head begins (last layer done), 15 the block's lm_head rows streamed.  Only the instance for batch 1 of the 0.6B-class shapes with
  * bf16 weights (head_dim 128, query groups of 2) has a stamping twin; other steps ignore the setting.
  * d_stamps NULL switches the stamps off (the default: the ordinary kernel, which has no trace of them).
  * Host only. */

@@ -425,6 +425,13 @@ __global__ __launch_bounds__(kFusedThreads) void fused_step_kernel(FusedArgs a)
             if (stamp_on) stamp_to[i] = wall_clock64();
         }
     };
+    // (12..15: the step itself - kernel entry, first layer begins, lm_head begins, lm_head streamed)
+    auto stamp_step = [&](int i) {
+        if constexpr (STAMPS) {
+            if (stamp_to != nullptr && tid == 0) stamp_to[i] = wall_clock64();
+        }
+    };
+    stamp_step(12);
 
     // refill the other buffer set for the next step
     {
@@ -499,6 +506,7 @@ __global__ __launch_bounds__(kFusedThreads) void fused_step_kernel(FusedArgs a)
     for (int l = 0; l < a.L; l++) {
         const FusedLayer &Lw = a.layers[l];
         if constexpr (STAMPS) stamp_on = stamp_to != nullptr && l == a.stamp_layer && tid == 0;
+        if (l == 0) stamp_step(13);
         stamp(0);    // layer begins (input staged, q|k|v rows requested)
         float *base = a.set + lay.per_layer * l;
         float *b_qkv = base + lay.qkv, *b_part = base + lay.part, *b_attn = base + lay.attn, *b_xmid = base + lay.xmid;
@@ -879,6 +887,7 @@ __global__ __launch_bounds__(kFusedThreads) void fused_step_kernel(FusedArgs a)
     }
 
     // ---- logits = W_lm rmsnorm(x); per-block maxima; block 0 picks the tokens ------------------
+    stamp_step(14);
     {
         int v0, v1;
         wave_rows(V, wv, v0, v1);
@@ -915,6 +924,7 @@ __global__ __launch_bounds__(kFusedThreads) void fused_step_kernel(FusedArgs a)
                     }
             }
         }
+        stamp_step(15);
         // block maximum per row of the batch: waves own ascending row ranges
         __syncthreads();
         float *sv = xs;                       // reuse LDS: [wave][b] values and indices
