@@ -77,25 +77,6 @@ __device__ __forceinline__ float sum64(float v)
     v += __shfl_xor(v, 32);
     return v;
 }
-// The same sum and maximum without a trip through the LDS crossbar: rows of 16 by DPP, then the
-// four row results read from their lanes.  Same order of additions as sum64, wave-uniform result.
-__device__ __forceinline__ float lane_value(float v, int lane)
-{
-    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), lane));
-}
-__device__ __forceinline__ float sum64_uniform(float v)
-{
-    v = sum16(v);
-    return (lane_value(v, 0) + lane_value(v, 16)) + (lane_value(v, 32) + lane_value(v, 48));
-}
-__device__ __forceinline__ float max64_uniform(float v)
-{
-    v = fmaxf(v, dpp_f<0xB1>(v));
-    v = fmaxf(v, dpp_f<0x4E>(v));
-    v = fmaxf(v, dpp_f<0x141>(v));
-    v = fmaxf(v, dpp_f<0x140>(v));
-    return fmaxf(fmaxf(lane_value(v, 0), lane_value(v, 16)), fmaxf(lane_value(v, 32), lane_value(v, 48)));
-}
 __device__ __forceinline__ float max64(float v)
 {
     v = fmaxf(v, dpp_f<0xB1>(v));
