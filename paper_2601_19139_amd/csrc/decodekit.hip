@@ -763,7 +763,7 @@ const char *dk_last_error(void) { return g_err; }
 
 // The kernel revisions change whenever a kernel's memory behaviour changes; the
 // benchmark quotes stored counter measurements only for a matching revision.
-const char *dk_version(void) { return "decodekit 0.9 (gfx950; gemv r3, gemm r12, attention r9, moe r4, fused r3, prefill r2, sample r1)"; }
+const char *dk_version(void) { return "decodekit 0.9 (gfx950; gemv r3, gemm r12, attention r9, moe r4, fused r3, prefill r2, sample r2)"; }
 
 // ------------------------------------------------------------------- pool --
 dk_status dk_kv_pool_bytes(const dk_model_config *cfg, int32_t num_blocks, int32_t block_size,
@@ -1125,7 +1125,7 @@ dk_status dk_prefill_chunk(dk_model *model, dk_kv_pool *pool, const int32_t *d_b
 }
 
 namespace {
-struct SampleScratch { size_t p, pmax, part_a, part_b, st_a, st_b, total; };
+struct SampleScratch { size_t p, pmax, part_a, part_b, st_a, st_b, item_val, item_cnt, total; };
 SampleScratch sample_scratch(int B, int V)
 {
     SampleScratch L{};
@@ -1137,6 +1137,8 @@ SampleScratch sample_scratch(int B, int V)
     L.part_b = take((size_t)B * dk::kSampleBlocks * 16 * 4);
     L.st_a = take((size_t)B * sizeof(dk::SampleState));
     L.st_b = take((size_t)B * sizeof(dk::SampleState));
+    L.item_val = take((size_t)B * dk::kSampleItems * 4);
+    L.item_cnt = take((size_t)B * dk::kSampleItems * 4);
     L.total = off;
     return L;
 }
@@ -1193,6 +1195,28 @@ dk_status dk_sample_tokens(const float *d_logits, int32_t B, int32_t V, const dk
     };
     const bool use_k = params->top_k > 0 && params->top_k < V, use_p = params->top_p < 1.f;
     launch(dk::SAMPLE_MAX, dk::kSampleBlocks);
+    if (use_k && params->top_k <= dk::kSampleFastK && V <= dk::kSampleBlocks * dk::kSampleSliceMax) {
+        // few candidates: the weights and the slices' top k, then one block per row for thresholds and draw
+        dk::SampleSelectArgs s{};
+        s.logits = d_logits;
+        s.p = a.p;
+        s.pmax = a.pmax;
+        s.item_val = reinterpret_cast<float *>(base + L.item_val);
+        s.item_cnt = reinterpret_cast<uint32_t *>(base + L.item_cnt);
+        s.out = d_out;
+        s.V = V;
+        s.top_k = params->top_k;
+        s.temperature = params->temperature;
+        s.top_p = params->top_p;
+        s.seed_lo = a.seed_lo;
+        s.seed_hi = a.seed_hi;
+        s.step_lo = a.step_lo;
+        s.step_hi = a.step_hi;
+        hipLaunchKernelGGL(dk::sample_exp_topk_kernel, dim3(dk::kSampleBlocks, B), dim3(dk::kSampleThreads), 0, st, s);
+        hipLaunchKernelGGL(dk::sample_merge_draw_kernel, dim3(1, B), dim3(dk::kSampleThreads), 0, st, s);
+        DK_HIP(hipGetLastError());
+        return DK_OK;
+    }
     launch(dk::SAMPLE_EXP, dk::kSampleBlocks);
     if (use_k) {
         a.count = 1;
@@ -1217,7 +1241,8 @@ dk_status dk_sample_tokens(const float *d_logits, int32_t B, int32_t V, const dk
     } else {
         a.settle = 0;
     }
-    launch(dk::SAMPLE_KEEP, dk::kSampleBlocks);
+    // with neither threshold every weight is kept: the slices' totals are already there
+    if (use_k || use_p) launch(dk::SAMPLE_KEEP, dk::kSampleBlocks);
     launch(dk::SAMPLE_DRAW, 1);
     DK_HIP(hipGetLastError());
     return DK_OK;

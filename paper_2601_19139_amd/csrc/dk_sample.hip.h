@@ -12,13 +12,15 @@
 //                                                      key = (seed_lo, seed_hi))
 //
 // A vocabulary of 150 000 entries is too much for one compute unit per row, so a row is
-// spread over kSampleBlocks blocks and the work is a short chain of launches of one
-// kernel (its `stage` argument says which step).  Thresholds are found by a radix search
-// on the bit pattern of the (non-negative) float threshold: count / mass above a
-// threshold is monotone, so a pass tries the 15 next-digit candidates at once and settles
-// four bits; eight passes settle all of them.  A pass leaves per-block partial totals;
-// the next launch adds them in block order (every block does, redundantly) and decides
-// the digit.  No atomics and a fixed summation order everywhere: a call is repeatable
+// spread over kSampleBlocks blocks (slice g of the row belongs to block g).  In general the
+// work is a chain of launches of one kernel (its `stage` argument says which step):
+// thresholds are found by a radix search on the bit pattern of the (non-negative) float
+// threshold - count / mass above a threshold is monotone, so a pass tries the 15 next-digit
+// candidates at once and settles four bits; eight passes settle all of them.  A pass leaves
+// per-block partial totals; the next launch adds them in block order (every block does,
+// redundantly) and decides the digit.  With a small top_k (the usual serving setting) the
+// candidates are selected slice by slice instead and a call is three launches (below).
+// Float sums have a fixed order everywhere and counts are integers: a call is repeatable
 // bit for bit.
 #pragma once
 #include "dk_common.hip.h"
@@ -107,12 +109,447 @@ __device__ __forceinline__ float sample_block_sum(float v, float *sm /*[4]*/)
     return sm[0] + sm[1] + sm[2] + sm[3];
 }
 
+// ---- small top_k: candidates by selection instead of a search over the whole row -------------
+// With 0 < top_k <= kSampleFastK a call is three launches (maximum; weights and the slices' top k;
+// thresholds and draw) instead of up to 21.  The block that computes a slice's weights also selects
+// the k-th largest of them (tau_g) and hands on the weights above it (fewer than k values, in index
+// order) plus (tau_g, how many equal it): an element of the row's top k is in its slice's top k, so
+// the row's k-th largest weight - and every weight at or above it - is among those items, ties
+// counted.  One block per row then selects the k-th largest of that multiset (tau_k), gathers the
+// candidates (items >= tau_k; a few dozen unless many weights are equal), finds the nucleus
+// threshold among them (a candidate per thread adds up the mass at or above its own value; beyond a
+// block's worth of candidates, the four-bit search of the general path), adds up each slice's kept
+// mass from its items and draws: the slice that holds r by those masses, then the index inside it
+// from the weights themselves.  Selections are radix selections on the bit pattern (weights are
+// non-negative floats), eight bits per pass through an integer LDS histogram, on items held in
+// registers.  Integer counts and fixed summation orders: repeatable bit for bit.
+constexpr int kSampleFastK = 64;
+constexpr int kSampleSlot = kSampleFastK + 1;                 // a slice's values, then its (tau_g, ties) entry
+constexpr int kSampleItems = kSampleBlocks * kSampleSlot;
+constexpr int kSampleSliceMax = 4096;                         // weights of a slice staged in LDS
+
+struct SampleSelectArgs {
+    const float *logits;   // [B][V]
+    float *p;              // [B][V]
+    const float *pmax;     // [B][kSampleBlocks]
+    float *item_val;       // [B][kSampleItems]
+    uint32_t *item_cnt;    // [B][kSampleItems]: how many weights of the row an item stands for (0: unused)
+    int *out;              // [B]
+    int V, top_k;
+    float temperature, top_p;
+    uint32_t seed_lo, seed_hi, step_lo, step_hi;
+};
+
+// Sum of v over the block (every thread gets it) and, in *before, over the threads below this one.
+__device__ __forceinline__ uint32_t sample_block_scan(uint32_t v, uint32_t *sm_w /*[4]*/, uint32_t *before)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    uint32_t inc = v;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const uint32_t o = (uint32_t)__shfl_up((int)inc, d, 64);
+        inc += (lane >= d) ? o : 0u;
+    }
+    __syncthreads();
+    if (lane == 63) sm_w[wave] = inc;
+    __syncthreads();
+    uint32_t below = 0, total = 0;
+#pragma unroll
+    for (int w = 0; w < 4; w++) {
+        below += (w < wave) ? sm_w[w] : 0u;
+        total += sm_w[w];
+    }
+    *before = below + inc - v;
+    return total;
+}
+
+// The k-th largest, counting multiplicities, of the block's items: every thread brings N of them in
+// registers, item j with bit pattern bits[j], standing for cnt[j] weights (0: no item).  Returns the bit
+// pattern.  Needs k <= the total count.  hist: LDS [256]; sm_u: LDS [2].  Called by all threads of the block.
+template <int N>
+__device__ __forceinline__ uint32_t sample_select_kth(const uint32_t (&bits)[N], const uint32_t (&cnt)[N], uint32_t k,
+                                                      uint32_t *hist, uint32_t *sm_u)
+{
+    const int tid = threadIdx.x;
+    uint32_t prefix = 0, need = k;
+    for (int shift = 24; shift >= 0; shift -= 8) {
+        __syncthreads();
+        hist[tid] = 0u;
+        if (tid == 0) { sm_u[0] = 0u; sm_u[1] = 0u; }
+        __syncthreads();
+        const uint32_t mask = shift == 24 ? 0u : (0xffffffffu << (shift + 8));
+#pragma unroll
+        for (int j = 0; j < N; j++)
+            if (cnt[j] && (bits[j] & mask) == prefix) atomicAdd(&hist[(bits[j] >> shift) & 255u], cnt[j]);
+        __syncthreads();
+        // digits from the top: the first whose count, added to those above it, reaches `need`.  Lane l of
+        // the first wave holds digits 4l..4l+3; a suffix sum over the lanes says what is above a lane's.
+        if (tid < 64) {
+            const uint32_t h0 = hist[4 * tid], h1 = hist[4 * tid + 1], h2 = hist[4 * tid + 2], h3 = hist[4 * tid + 3];
+            const uint32_t own = h0 + h1 + h2 + h3;
+            uint32_t inc = own;
+#pragma unroll
+            for (int d = 1; d < 64; d <<= 1) {
+                const uint32_t o = (uint32_t)__shfl_down((int)inc, d, 64);
+                inc += (tid + d < 64) ? o : 0u;
+            }
+            const uint32_t over = inc - own;          // counts of the digits above this lane's four
+            if (over < need && inc >= need) {         // exactly one lane (the counts reach `need` in all)
+                uint32_t run = over;
+                int d = 3;
+                if (run + h3 >= need) d = 3;
+                else if (run + h3 + h2 >= need) { d = 2; run += h3; }
+                else if (run + h3 + h2 + h1 >= need) { d = 1; run += h3 + h2; }
+                else { d = 0; run += h3 + h2 + h1; }
+                sm_u[0] = (uint32_t)(4 * tid + d);
+                sm_u[1] = run;
+            }
+        }
+        __syncthreads();
+        prefix |= sm_u[0] << shift;
+        need -= sm_u[1];
+    }
+    return prefix;
+}
+
+// Inclusive prefix sums over the lanes of a wave, in a fixed order (a doubling scan).
+__device__ __forceinline__ float sample_wave_scan(float v)
+{
+    const int lane = threadIdx.x & 63;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const float o = __shfl_up(v, d, 64);
+        v += (lane >= d) ? o : 0.f;
+    }
+    return v;
+}
+
+// The draw for row b: r = u * (sum of mass[k * stride], k in slice order); the slice that holds r, then
+// the index inside it by a running sum of the kept weights (p >= tau) in index order.  Two levels of
+// prefix sums (the slices' masses across a wave; inside the slice a contiguous piece per thread, the
+// pieces' sums across the block) name the thread whose piece holds r; that thread walks its piece.  Where
+// rounding leaves r beyond the last prefix, the last kept weight is taken.  Called by all threads of a
+// block; sm: LDS [8], sm_i: LDS [12].
+constexpr int kSampleDrawPiece = 16;     // weights of a piece held in registers (slices up to 4096)
+__device__ __forceinline__ void sample_draw_row(const float *p, const float *mass, int stride, float tau, int V, int b,
+                                                uint32_t seed_lo, uint32_t seed_hi, uint32_t step_lo, uint32_t step_hi,
+                                                int *out, float *sm, int *sm_i)
+{
+    static_assert(kSampleBlocks == 64, "one slice per lane of the first wave");
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int slice = (V + kSampleBlocks - 1) / kSampleBlocks;
+    __syncthreads();
+    if (wave == 0) {
+        const float m = mass[lane * stride];
+        const float inc = sample_wave_scan(m);
+        const float total = __shfl(inc, 63, 64);
+        const uint32_t x0 = philox4x32_10_first(step_lo, step_hi, (uint32_t)b, 0u, seed_lo, seed_hi);
+        const float r = (float)(x0 >> 8) * (1.0f / 16777216.0f) * total;
+        const uint64_t hit = __ballot(inc > r), any = __ballot(m > 0.f);
+        const int owner = hit ? __ffsll((unsigned long long)hit) - 1 : (any ? 63 - __clzll((long long)any) : 0);
+        const float before = __shfl(inc - m, owner, 64);
+        if (lane == 0) {
+            sm_i[0] = owner;
+            sm[0] = before;
+            sm[1] = r;
+        }
+    }
+    __syncthreads();
+    const float r = sm[1];
+    const int k0 = min(sm_i[0] * slice, V), k1 = min(k0 + slice, V);
+    // thread t owns a contiguous piece of the slice; pieces in thread order = index order
+    const int piece = (slice + kSampleThreads - 1) / kSampleThreads;
+    const int j0 = min(k0 + tid * piece, k1), j1 = min(j0 + piece, k1);
+    const bool in_regs = piece <= kSampleDrawPiece;
+    float pv[kSampleDrawPiece];
+    uint32_t kept = 0;
+    float mine = 0.f;
+    if (in_regs) {
+        // loads from clamped addresses, all in flight together; what is outside the piece is dropped afterwards
+#pragma unroll
+        for (int j = 0; j < kSampleDrawPiece; j++) pv[j] = p[min(j0 + j, V - 1)];
+#pragma unroll
+        for (int j = 0; j < kSampleDrawPiece; j++) {
+            const bool k = j0 + j < j1 && pv[j] >= tau;
+            kept |= k ? (1u << j) : 0u;
+            mine += k ? pv[j] : 0.f;
+        }
+    } else {
+        for (int i = j0; i < j1; i++) mine += (p[i] >= tau) ? p[i] : 0.f;
+    }
+    const float incw = sample_wave_scan(mine);
+    if (lane == 63) sm[4 + wave] = incw;
+    __syncthreads();
+    float off = sm[0];
+    for (int w = 0; w < wave; w++) off += sm[4 + w];
+    const float inc = off + incw;
+    {
+        const uint64_t hit = __ballot(inc > r), any = __ballot(mine > 0.f);
+        if (lane == 0) {
+            sm_i[2 + wave] = hit ? __ffsll((unsigned long long)hit) - 1 : 64;
+            sm_i[6 + wave] = any ? 63 - __clzll((long long)any) : -1;
+        }
+    }
+    __syncthreads();
+    int owner_t = -1;
+#pragma unroll
+    for (int w = 0; w < 4; w++)
+        if (owner_t < 0 && sm_i[2 + w] < 64) owner_t = w * 64 + sm_i[2 + w];
+    if (owner_t < 0) {
+#pragma unroll
+        for (int w = 0; w < 4; w++)
+            if (sm_i[6 + w] >= 0) owner_t = w * 64 + sm_i[6 + w];     // the last piece that keeps anything
+    }
+    if (owner_t < 0) owner_t = 0;
+    if (tid == owner_t) {
+        float run = inc - mine;
+        int pick = -1, last = j0;
+        if (in_regs) {
+#pragma unroll
+            for (int j = 0; j < kSampleDrawPiece; j++)
+                if (kept & (1u << j)) {
+                    last = j0 + j;
+                    run += pv[j];
+                    if (pick < 0 && run > r) pick = j0 + j;
+                }
+        } else {
+            for (int i = j0; i < j1; i++)
+                if (p[i] >= tau) {
+                    last = i;
+                    run += p[i];
+                    if (run > r) { pick = i; break; }
+                }
+        }
+        out[b] = pick >= 0 ? pick : last;
+    }
+}
+
+// grid (kSampleBlocks, B): the slice's weights and its top k.  Needs a slice of at most kSampleSliceMax.
+__global__ __launch_bounds__(kSampleThreads) void sample_exp_topk_kernel(SampleSelectArgs a)
+{
+    constexpr int N = kSampleSliceMax / kSampleThreads;
+    __shared__ float sl[kSampleSliceMax];
+    __shared__ uint32_t hist[256];
+    __shared__ uint32_t sm_u[2];
+    __shared__ uint32_t sm_w[4];
+    const int g = blockIdx.x, b = blockIdx.y, tid = threadIdx.x, V = a.V;
+    const int slice = (V + kSampleBlocks - 1) / kSampleBlocks;
+    const int i0 = min(g * slice, V), i1 = min(i0 + slice, V), n = i1 - i0;
+    float *val = a.item_val + ((int64_t)b * kSampleBlocks + g) * kSampleSlot;
+    uint32_t *cnt = a.item_cnt + ((int64_t)b * kSampleBlocks + g) * kSampleSlot;
+    if (n <= 0) {     // a slice beyond the end of a short row
+        for (int i = tid; i < kSampleSlot; i += kSampleThreads) {
+            val[i] = 0.f;
+            cnt[i] = 0u;
+        }
+        return;
+    }
+    const float *l = a.logits + (int64_t)b * V + i0;
+    float *p = a.p + (int64_t)b * V + i0;
+    const float mx = max64(a.pmax[b * kSampleBlocks + (tid & 63)]);
+    // the weights: element tid + 256 j in register j (loads from clamped addresses, all in flight together)
+    float x[N];
+    uint32_t bits[N], one[N];
+#pragma unroll
+    for (int j = 0; j < N; j++) x[j] = l[min(tid + kSampleThreads * j, n - 1)];
+#pragma unroll
+    for (int j = 0; j < N; j++) {
+        const int i = tid + kSampleThreads * j;
+        const float v = expf(x[j] / a.temperature - mx);
+        bits[j] = __float_as_uint(v);
+        one[j] = i < n ? 1u : 0u;
+        if (i < n) {
+            p[i] = v;
+            sl[i] = v;
+        }
+    }
+    // a slice with fewer than k weights hands on all of them ("the k-th largest" is below everything)
+    const bool all = n < a.top_k;
+    uint32_t tau = 0;
+    if (!all) tau = sample_select_kth(bits, one, (uint32_t)a.top_k, hist, sm_u);
+    else __syncthreads();
+    // the weights above tau in index order: thread t owns a contiguous piece of the slice
+    const int piece = (n + kSampleThreads - 1) / kSampleThreads;
+    const int j0 = min(tid * piece, n), j1 = min(j0 + piece, n);
+    uint32_t above = 0, mine = 0;     // bit j: element j0 + j is listed; counts: listed | equal to tau << 16
+#pragma unroll
+    for (int j = 0; j < N; j++) {
+        x[j] = sl[min(j0 + j, n - 1)];
+        const uint32_t w = __float_as_uint(x[j]);
+        const bool in = j0 + j < j1;
+        const bool up = in && (all || w > tau);
+        above |= up ? (1u << j) : 0u;
+        mine += (up ? 1u : 0u) + ((in && !all && w == tau) ? 0x10000u : 0u);
+    }
+    uint32_t pos;
+    const uint32_t total = sample_block_scan(mine, sm_w, &pos);
+    const uint32_t listed = total & 0xffffu, ties = total >> 16;        // listed < k by construction
+    pos &= 0xffffu;
+#pragma unroll
+    for (int j = 0; j < N; j++)
+        if ((above >> j) & 1u) {
+            if (pos < (uint32_t)kSampleFastK) {
+                val[pos] = x[j];
+                cnt[pos] = 1u;
+            }
+            pos++;
+        }
+    for (uint32_t i = listed + tid; i < (uint32_t)kSampleFastK; i += kSampleThreads) {
+        val[i] = 0.f;
+        cnt[i] = 0u;
+    }
+    if (tid == 0) {
+        val[kSampleFastK] = __uint_as_float(tau);
+        cnt[kSampleFastK] = ties;
+    }
+}
+
+// Largest value of v over the block; every thread gets it.
+__device__ __forceinline__ uint32_t sample_block_max(uint32_t v, uint32_t *sm_w /*[4]*/)
+{
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) v = max(v, (uint32_t)__shfl_xor((int)v, d, 64));
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) sm_w[threadIdx.x >> 6] = v;
+    __syncthreads();
+    return max(max(sm_w[0], sm_w[1]), max(sm_w[2], sm_w[3]));
+}
+
+// grid (1, B): both thresholds from the slices' items, the slices' kept masses, the draw
+__global__ __launch_bounds__(kSampleThreads) void sample_merge_draw_kernel(SampleSelectArgs a)
+{
+    __shared__ float val[kSampleItems];      // items; from the gathering on: the candidates' values
+    __shared__ uint32_t cnt[kSampleItems];   // how many weights an item stands for; then: float value x count
+    __shared__ uint32_t hist[256];
+    __shared__ uint32_t per_slice[kSampleBlocks];
+    __shared__ float mass[kSampleBlocks];
+    __shared__ uint32_t sm_u[2];
+    __shared__ uint32_t sm_w[4];
+    __shared__ float sm[8];
+    __shared__ int sm_i[12];
+    __shared__ float red[4 * 15];
+    const int b = blockIdx.y, tid = threadIdx.x;
+    constexpr int PIECE = (kSampleItems + kSampleThreads - 1) / kSampleThreads;
+    // the items into LDS (loads from clamped addresses, all in flight together), then a contiguous piece of
+    // them - item order: slice by slice, index order inside a slice, its ties entry last - into registers
+    {
+        float lv[PIECE];
+        uint32_t lc[PIECE];
+#pragma unroll
+        for (int j = 0; j < PIECE; j++) {
+            const int i = min(tid + kSampleThreads * j, kSampleItems - 1);
+            lv[j] = a.item_val[(int64_t)b * kSampleItems + i];
+            lc[j] = a.item_cnt[(int64_t)b * kSampleItems + i];
+        }
+#pragma unroll
+        for (int j = 0; j < PIECE; j++)
+            if (tid + kSampleThreads * j < kSampleItems) {
+                val[tid + kSampleThreads * j] = lv[j];
+                cnt[tid + kSampleThreads * j] = lc[j];
+            }
+    }
+    if (tid < kSampleBlocks) per_slice[tid] = 0u;
+    __syncthreads();
+    float pv[PIECE];
+    uint32_t pb[PIECE], pc[PIECE];
+#pragma unroll
+    for (int j = 0; j < PIECE; j++) {
+        const int i = min(tid * PIECE + j, kSampleItems - 1);
+        pv[j] = val[i];
+        pb[j] = __float_as_uint(pv[j]);
+        pc[j] = tid * PIECE + j < kSampleItems ? cnt[i] : 0u;
+    }
+    const uint32_t tau_k = sample_select_kth(pb, pc, (uint32_t)a.top_k, hist, sm_u);
+    const float tau_kf = __uint_as_float(tau_k);
+    // gather the candidates (items at or above tau_k) in item order
+    uint32_t mine = 0;
+#pragma unroll
+    for (int j = 0; j < PIECE; j++) {
+        pc[j] = pv[j] >= tau_kf ? pc[j] : 0u;
+        mine += pc[j] ? 1u : 0u;
+    }
+    uint32_t pos;
+    const int nc = (int)sample_block_scan(mine, sm_w, &pos);     // its barriers separate the reads from the writes
+    float *wgt = reinterpret_cast<float *>(cnt);
+#pragma unroll
+    for (int j = 0; j < PIECE; j++)
+        if (pc[j]) {
+            val[pos] = pv[j];
+            wgt[pos] = pv[j] * (float)pc[j];
+            atomicAdd(&per_slice[(tid * PIECE + j) / kSampleSlot], 1u);
+            pos++;
+        }
+    __syncthreads();
+    uint32_t tau = tau_k;
+    if (a.top_p < 1.f && nc <= kSampleThreads) {
+        // a candidate per thread: the mass at or above its value, every thread adding in candidate order; the
+        // nucleus threshold is the largest value whose mass reaches top_p of the total
+        const float vi = tid < nc ? val[tid] : INFINITY;
+        float z = 0.f, ge = 0.f;
+        for (int j = 0; j < nc; j++) {
+            const float w = wgt[j];
+            z += w;
+            ge += (val[j] >= vi) ? w : 0.f;
+        }
+        tau = max(tau_k, sample_block_max((tid < nc && ge >= a.top_p * z) ? __float_as_uint(vi) : 0u, sm_w));
+    } else if (a.top_p < 1.f) {
+        // many equal weights: the search of the general path (four bits per pass; the 15 candidates of a digit
+        // in registers, added over the block in a fixed order) on the candidates' values
+        float z = 0.f;
+        for (int i = tid; i < nc; i += kSampleThreads) z += wgt[i];
+        z = sample_block_sum(z, sm);
+        const float need = a.top_p * z;
+        uint32_t prefix = 0;
+        for (int shift = 28; shift >= 0; shift -= 4) {
+            float acc[15];
+#pragma unroll
+            for (int d = 0; d < 15; d++) acc[d] = 0.f;
+            for (int i = tid; i < nc; i += kSampleThreads) {
+                const float w = wgt[i];
+                const uint32_t bits = __float_as_uint(val[i]);
+#pragma unroll
+                for (int d = 0; d < 15; d++) acc[d] += (bits >= (prefix | ((uint32_t)(d + 1) << shift))) ? w : 0.f;
+            }
+#pragma unroll
+            for (int d = 0; d < 15; d++) acc[d] = sum64(acc[d]);
+            __syncthreads();
+            if ((tid & 63) == 0) {
+#pragma unroll
+                for (int d = 0; d < 15; d++) red[(tid >> 6) * 15 + d] = acc[d];
+            }
+            __syncthreads();
+            uint32_t digit = 0;
+#pragma unroll
+            for (int d = 0; d < 15; d++)
+                if (red[d] + red[15 + d] + red[30 + d] + red[45 + d] >= need) digit = (uint32_t)(d + 1);
+            prefix |= digit << shift;
+        }
+        tau = max(tau_k, prefix);
+    }
+    const float tau_f = __uint_as_float(tau);
+    // every slice's kept mass from its candidates (the gathering kept a slice's together and in order)
+    if (tid < kSampleBlocks) {
+        const uint32_t c = per_slice[tid];
+        uint32_t inc = c;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const uint32_t o = (uint32_t)__shfl_up((int)inc, d, 64);
+            inc += (tid >= d) ? o : 0u;
+        }
+        float m = 0.f;
+        for (uint32_t i = inc - c; i < inc; i++) m += (val[i] >= tau_f) ? wgt[i] : 0.f;
+        mass[tid] = m;
+    }
+    sample_draw_row(a.p + (int64_t)b * a.V, mass, 1, tau_f, a.V, b, a.seed_lo, a.seed_hi, a.step_lo, a.step_hi, a.out, sm,
+                    sm_i);
+}
+
 __global__ __launch_bounds__(kSampleThreads) void sample_kernel(SampleArgs a)
 {
     __shared__ float sm[16];
     __shared__ float red[4 * 15];
     __shared__ float scan[kSampleThreads];
-    __shared__ int sm_i[2];
+    __shared__ int sm_i[12];
     const int g = blockIdx.x, b = blockIdx.y, tid = threadIdx.x, V = a.V;
     const int slice = (V + kSampleBlocks - 1) / kSampleBlocks;
     const int i0 = min(g * slice, V), i1 = min(i0 + slice, V);
@@ -122,8 +559,13 @@ __global__ __launch_bounds__(kSampleThreads) void sample_kernel(SampleArgs a)
     const float *part_in = a.part_in + (int64_t)b * kSampleBlocks * 16;
 
     if (a.stage == SAMPLE_MAX) {
+        // four loads in flight; an address past the slice is clamped (a value twice does not change a maximum)
         float mx = -INFINITY;
-        for (int i = i0 + tid; i < i1; i += kSampleThreads) mx = fmaxf(mx, l[i] / a.temperature);
+        for (int i = i0 + tid; i < i1; i += 4 * kSampleThreads) {
+            const float x0 = l[i], x1 = l[min(i + kSampleThreads, i1 - 1)], x2 = l[min(i + 2 * kSampleThreads, i1 - 1)],
+                        x3 = l[min(i + 3 * kSampleThreads, i1 - 1)];
+            mx = fmaxf(fmaxf(fmaxf(mx, x0 / a.temperature), fmaxf(x1 / a.temperature, x2 / a.temperature)), x3 / a.temperature);
+        }
         mx = max64(mx);
         if ((tid & 63) == 0) sm[tid >> 6] = mx;
         __syncthreads();
@@ -131,13 +573,19 @@ __global__ __launch_bounds__(kSampleThreads) void sample_kernel(SampleArgs a)
         return;
     }
     if (a.stage == SAMPLE_EXP) {
-        float mx = -INFINITY;
-        for (int k = 0; k < kSampleBlocks; k++) mx = fmaxf(mx, a.pmax[b * kSampleBlocks + k]);
+        const float mx = max64(a.pmax[b * kSampleBlocks + (tid & 63)]);
         float z = 0.f;
-        for (int i = i0 + tid; i < i1; i += kSampleThreads) {
-            const float v = expf(l[i] / a.temperature - mx);
-            p[i] = v;
-            z += v;
+        for (int i = i0 + tid; i < i1; i += 4 * kSampleThreads) {     // four loads in flight
+            float x[4];
+#pragma unroll
+            for (int j = 0; j < 4; j++) x[j] = l[min(i + j * kSampleThreads, i1 - 1)];
+#pragma unroll
+            for (int j = 0; j < 4; j++)
+                if (i + j * kSampleThreads < i1) {
+                    const float v = expf(x[j] / a.temperature - mx);
+                    p[i + j * kSampleThreads] = v;
+                    z += v;
+                }
         }
         z = sample_block_sum(z, sm);
         if (tid == 0) part_out[0] = z;
@@ -145,60 +593,9 @@ __global__ __launch_bounds__(kSampleThreads) void sample_kernel(SampleArgs a)
         return;
     }
     if (a.stage == SAMPLE_DRAW) {
-        // g == 0 only (grid.x = 1): the block that holds r, then the index inside its slice
-        const SampleState st = a.st_in[b];
-        const float tau = __uint_as_float(st.prefix);
-        if (tid == 0) {
-            float total = 0.f;
-            for (int k = 0; k < kSampleBlocks; k++) total += part_in[k * 16];
-            const uint32_t x0 = philox4x32_10_first(a.step_lo, a.step_hi, (uint32_t)b, 0u, a.seed_lo, a.seed_hi);
-            const float r = (float)(x0 >> 8) * (1.0f / 16777216.0f) * total;
-            float run = 0.f;
-            int owner = -1, last = 0;
-            for (int k = 0; k < kSampleBlocks; k++) {
-                const float m = part_in[k * 16];
-                if (m > 0.f) last = k;
-                if (owner < 0 && run + m > r) owner = k;
-                if (owner < 0) run += m;
-            }
-            if (owner < 0) { owner = last; run -= part_in[last * 16]; }   // rounding left r beyond the end
-            sm_i[0] = owner;
-            sm[0] = run;
-            sm[1] = r;
-        }
-        __syncthreads();
-        const int k0 = min(sm_i[0] * slice, V), k1 = min(k0 + slice, V);
-        // thread t owns a contiguous piece of the slice; pieces in thread order = index order
-        const int piece = (slice + kSampleThreads - 1) / kSampleThreads;
-        const int j0 = min(k0 + tid * piece, k1), j1 = min(j0 + piece, k1);
-        float mine = 0.f;
-        for (int i = j0; i < j1; i++) mine += (p[i] >= tau) ? p[i] : 0.f;
-        scan[tid] = mine;
-        __syncthreads();
-        if (tid == 0) {
-            float run = sm[0];
-            int owner = -1, last = 0;
-            for (int t = 0; t < kSampleThreads; t++) {
-                if (scan[t] > 0.f) last = t;
-                if (owner < 0 && run + scan[t] > sm[1]) owner = t;
-                if (owner < 0) run += scan[t];
-            }
-            if (owner < 0) { owner = last; run -= scan[last]; }
-            sm_i[1] = owner;
-            sm[0] = run;
-        }
-        __syncthreads();
-        if (tid == sm_i[1]) {
-            float run = sm[0];
-            int pick = -1, last = j0;
-            for (int i = j0; i < j1; i++)
-                if (p[i] >= tau) {
-                    last = i;
-                    run += p[i];
-                    if (run > sm[1]) { pick = i; break; }
-                }
-            a.out[b] = pick >= 0 ? pick : last;
-        }
+        // g == 0 only (grid.x = 1)
+        sample_draw_row(p, part_in, 16, __uint_as_float(a.st_in[b].prefix), V, b, a.seed_lo, a.seed_hi, a.step_lo,
+                        a.step_hi, a.out, sm, sm_i);
         return;
     }
 

@@ -50,6 +50,12 @@ CASES = [
     (151936, 2, 0.8, 0, 0.95),       # the vocabulary of the 0.6B / 8B shapes
     (151936, 1, 1.0, 20, 1.0),
     (64, 5, 1.0, 1, 1.0),            # top_k = 1: the argmax
+    (151936, 16, 0.8, 50, 0.9),      # a serving batch: few candidates out of a large vocabulary
+    (5000, 3, 1.0, 64, 0.5),         # the largest top_k that is found by selection
+    (5000, 2, 1.0, 65, 0.9),         # ... and the smallest that is not
+    (5000, 2, 1.2, 10, 1.0),         # the 10th largest weight is one of 20 equal ones in two slices
+    (5000, 2, 1.2, 10, 0.57),
+    (5000, 2, 1.0, 64, 0.5001),      # 63 copies of the largest weight in every 1/64 of the row: ~4000 candidates
     (300, 3, 1e-3, 0, 1.0),          # tiny temperature: the argmax
 ]
 
@@ -61,6 +67,11 @@ def test_sampler_matches_oracle(dk, orc, V, B, T, top_k, top_p):
     logits = (rng.normal(size=(B, V)) * 2.5).astype(np.float32)
     if V == 1003:
         logits[0, 10:40] = logits[0, 10]                      # a run of equal values
+    if V == 5000 and top_p == 0.5001:
+        for start in range(0, V, -(-V // 64)):
+            logits[1, start:start + 63] = 9.0
+    if V == 5000 and top_k == 10:
+        logits[0, 70:90] = logits[0].max() + 0.5              # 20 equal largest values: all of them stay
     d_logits = torch.from_numpy(logits).cuda()
     scratch = torch.empty(dk.sample_scratch_bytes(B, V), dtype=torch.uint8, device="cuda")
     out = torch.empty(B, dtype=torch.int32, device="cuda")
