@@ -42,6 +42,7 @@ constexpr int kFusedChunk = 64;             // tokens per attention work item
 constexpr int kFusedMergeRound = 12;        // chunk partials the collecting block awaits at a time
 constexpr int kFusedWaveTiles = kFusedChunk / (16 * kFusedWaves);   // 16-token K/V tiles per wave
 constexpr int kFusedStamps = 16;            // stage boundaries a block can stamp per layer (see FusedArgs::stamps)
+constexpr int kFusedReplicas = 2;           // copies of a vector that every block awaits (block blk polls copy blk % kFusedReplicas)
 constexpr int kFusedSpinLimit = 1 << 16;    // polls before a block gives up (each ~1 us)
 
 struct FusedLayer {
@@ -83,11 +84,13 @@ __host__ __device__ inline FusedLayout fused_layout(int L, int B, int H, int nq,
     const long long qkv_dim = (long long)(nq + 2 * nkv) * d;
     o.qkv = 0;
     o.part = o.qkv + B * qkv_dim;
+    // the vectors that all blocks await at once come in kFusedReplicas copies ([copy][B][N]): the more blocks
+    // poll the lines that 8 producers at a time are writing, the later the last word is seen
     o.attn = o.part + (long long)B * nq * nchunks * (d + 2);
-    o.xmid = o.attn + (long long)B * nq * d;
-    o.act = o.xmid + (long long)B * H;
-    o.xout = o.act + (long long)B * F;
-    o.per_layer = o.xout + (long long)B * H;
+    o.xmid = o.attn + (long long)kFusedReplicas * B * nq * d;
+    o.act = o.xmid + (long long)kFusedReplicas * B * H;
+    o.xout = o.act + (long long)kFusedReplicas * B * F;
+    o.per_layer = o.xout + (long long)kFusedReplicas * B * H;
     o.amax = o.per_layer * L;
     o.total = o.amax + 2LL * nblocks * B;
     return o;
@@ -163,8 +166,8 @@ __device__ __forceinline__ void stage_input(const float *src, int K, const uint1
         for (int b = 0; b < NB; b++)
 #pragma unroll
             for (int e = 0; e < MAXE; e++) {
-                const int k = e * kFusedThreads + tid;
-                v[b][e] = k < K ? ldc_u32(src + (long long)b * K + k) : 0u;
+                const int k = min(e * kFusedThreads + tid, K - 1);     // past the end: the last word again
+                v[b][e] = ldc_u32(src + (long long)b * K + k);
                 ready = ready && v[b][e] != kNotYet;
             }
         if (w.done(ready)) break;
@@ -373,15 +376,17 @@ __device__ __forceinline__ void gemv_rows(RowRegs<RW, KS, Q4> &pre, const uint16
     }
 }
 
-// The block's n rows starting at b0, for every batch row: out[b][b0 + r] = sm_y[b][r] + rv.
-template <int NB>
+// The block's n rows starting at b0, for every batch row: out[copy][b][b0 + r] = sm_y[b][r] + rv, COPIES copies.
+template <int NB, int COPIES = kFusedReplicas>
 __device__ __forceinline__ void publish_rows(float *out, int N, int b0, int n, const float *sm_y, float rv)
 {
     __syncthreads();
     const int tid = threadIdx.x;
     if (tid < n * NB) {
         const int b = tid / n, r = tid - b * n;
-        stc_f32(out + (long long)b * N + b0 + r, sm_y[b * kFusedMaxBlockRows + r] + rv);
+        const float y = sm_y[b * kFusedMaxBlockRows + r] + rv;
+#pragma unroll
+        for (int c = 0; c < COPIES; c++) stc_f32(out + ((long long)c * NB + b) * N + b0 + r, y);
     }
 }
 
@@ -416,6 +421,7 @@ __global__ __launch_bounds__(kFusedThreads) void fused_step_kernel(FusedArgs a)
     const int H = a.H, F = a.F, V = a.V, QD = a.nq * D, QKV = (a.nq + 2 * a.nkv) * D;
     const FusedLayout lay = fused_layout(a.L, NB, H, a.nq, a.nkv, D, F, a.nchunks, nblk);
     Waiter w{a.status, a.serial, 0, false, a.spin_limit, wslots, 0};
+    const int copy = blk % kFusedReplicas;
     // stage stamps of one layer (100 MHz device clock), when the host asked for them: one flag per
     // layer, tested at every boundary
     long long *const stamp_to = a.stamps != nullptr ? a.stamps + (long long)blk * kFusedStamps : nullptr;
@@ -511,11 +517,14 @@ __global__ __launch_bounds__(kFusedThreads) void fused_step_kernel(FusedArgs a)
         float *base = a.set + lay.per_layer * l;
         float *b_qkv = base + lay.qkv, *b_part = base + lay.part, *b_attn = base + lay.attn, *b_xmid = base + lay.xmid;
         float *b_act = base + lay.act, *b_xout = base + lay.xout;
-        const float *x_in = l ? a.set + lay.per_layer * (l - 1) + lay.xout : nullptr;   // layer 0: embedding
+        // this block's copy of the replicated vectors
+        const float *my_attn = b_attn + (long long)copy * NB * QD, *my_xmid = b_xmid + (long long)copy * NB * H;
+        const float *my_act = b_act + (long long)copy * NB * F, *my_xout = b_xout + (long long)copy * NB * H;
+        const float *x_in = l ? a.set + lay.per_layer * (l - 1) + lay.xout + (long long)copy * NB * H : nullptr;   // layer 0: embedding
 
         // ---- q|k|v = W_qkv rmsnorm(x) ------------------------------------------------
         gemv_rows<NB, RW_H, KSH, Q4>(pre_h, Lw.w_qkv, QKV, H, r0, r1, qkv_b0, xs, rinv, sm_y, lane);
-        publish_rows<NB>(b_qkv, QKV, qkv_b0, qkv_n, sm_y, 0.f);
+        publish_rows<NB, 1>(b_qkv, QKV, qkv_b0, qkv_n, sm_y, 0.f);
         stamp(1);    // q|k|v rows handed over
         // ---- attention: request the K/V tiles, then wait for q|k|v --------------------
         RowRegs<RW_Q, KSQ, Q4> pre_q;
@@ -583,14 +592,14 @@ __global__ __launch_bounds__(kFusedThreads) void fused_step_kernel(FusedArgs a)
                     const int idx = e * kFusedThreads + tid;
                     const int part = idx / D, dim = idx - part * D;   // part: G query heads, then k, then v
                     const int head = part < G ? j * G + part : (part == G ? a.nq + j : a.nq + a.nkv + j);
-                    src[e] = idx < NW ? rowp + (long long)head * D + dim : nullptr;
+                    src[e] = rowp + (long long)head * D + dim;     // threads past the last word repeat a word of v
                 }
                 w.spins = 0;
                 for (;;) {
                     bool ready = true;
 #pragma unroll
                     for (int e = 0; e < PE; e++) {
-                        got[e] = src[e] ? ldc_u32(src[e]) : 0u;
+                        got[e] = ldc_u32(src[e]);
                         ready = ready && got[e] != kNotYet;
                     }
                     if (w.done(ready)) break;
@@ -598,7 +607,7 @@ __global__ __launch_bounds__(kFusedThreads) void fused_step_kernel(FusedArgs a)
                 stamp(2);    // q|k|v of the block's attention item arrived
 #pragma unroll
                 for (int e = 0; e < PE; e++)
-                    if (src[e]) sm_qkv[e * kFusedThreads + tid] = __uint_as_float(got[e]);
+                    if (e * kFusedThreads + tid < NW) sm_qkv[e * kFusedThreads + tid] = __uint_as_float(got[e]);
                 __syncthreads();
             }
             float gq[8], gk[8];
@@ -807,7 +816,12 @@ __global__ __launch_bounds__(kFusedThreads) void fused_step_kernel(FusedArgs a)
                 }
 #pragma unroll
                 for (int x = 0; x < EP; x++)
-                    if (has[x]) stc_f32(b_attn + (long long)b * QD + (long long)(j * G + g_[x]) * D + dim[x], os[x] / ls[x]);
+                    if (has[x]) {
+                        const float y = os[x] / ls[x];
+#pragma unroll
+                        for (int cp = 0; cp < kFusedReplicas; cp++)
+                            stc_f32(b_attn + ((long long)cp * NB + b) * QD + (long long)(j * G + g_[x]) * D + dim[x], y);
+                    }
                 stamp(4);    // (collecting blocks) merged attention output handed over
             }
             __syncthreads();   // sm_o / sm_ml / sm_qkv are rewritten by the block's next item
@@ -815,7 +829,7 @@ __global__ __launch_bounds__(kFusedThreads) void fused_step_kernel(FusedArgs a)
         // ---- x_mid = x + W_o attn -------------------------------------------------------------
         {
             float dummy[NB];
-            stage_input<NB, false, 2 * KSQ>(b_attn, QD, nullptr, a.eps, xs, dummy, red, w);
+            stage_input<NB, false, 2 * KSQ>(my_attn, QD, nullptr, a.eps, xs, dummy, red, w);
             stamp(5);    // attention output arrived
             gemv_rows<NB, RW_Q, KSQ, Q4>(pre_q, Lw.w_o, H, QD, q0, q1, h_b0, xs, ones, sm_y, lane);
             publish_rows<NB>(b_xmid, H, h_b0, h_n, sm_y, rv_o);
@@ -829,7 +843,7 @@ __global__ __launch_bounds__(kFusedThreads) void fused_step_kernel(FusedArgs a)
             load_rows<RW_GU, KSH, Q4>(pg, Lw.w_gate, F, H, f0, f1, lane);
             load_rows<RW_GU, KSH, Q4>(pu, Lw.w_up, F, H, f0, f1, lane);
             __syncthreads();   // xs is about to be overwritten
-            stage_input<NB, true, 2 * KSH>(b_xmid, H, Lw.g_mlp, a.eps, xs, rinv, red, w);
+            stage_input<NB, true, 2 * KSH>(my_xmid, H, Lw.g_mlp, a.eps, xs, rinv, red, w);
             stamp(7);    // x_mid arrived
             for (int rb = f0; rb < f1; rb += RW_GU) {
                 if (rb != f0) {
@@ -866,11 +880,11 @@ __global__ __launch_bounds__(kFusedThreads) void fused_step_kernel(FusedArgs a)
             float rv_d = 0.f;
             if (tid < h_n * NB) {
                 const int b = tid / h_n, r = tid - b * h_n;
-                rv_d = __uint_as_float(ldc_u32(b_xmid + (long long)b * H + h_b0 + r));
+                rv_d = __uint_as_float(ldc_u32(my_xmid + (long long)b * H + h_b0 + r));
             }
             __syncthreads();
             float dummy[NB];
-            stage_input<NB, false, 2 * KSF>(b_act, F, nullptr, a.eps, xs, dummy, red, w);
+            stage_input<NB, false, 2 * KSF>(my_act, F, nullptr, a.eps, xs, dummy, red, w);
             stamp(9);    // activations arrived
             if (!ROW_AHEAD) load_rows<RW_F, KSF, Q4>(pd, Lw.w_down, H, F, d0, d1, lane);
             gemv_rows<NB, RW_F, KSF, Q4>(pd, Lw.w_down, H, F, d0, d1, h_b0, xs, ones, sm_y, lane);
@@ -881,7 +895,7 @@ __global__ __launch_bounds__(kFusedThreads) void fused_step_kernel(FusedArgs a)
         if (l + 1 < a.L) {
             load_rows<RW_H, KSH, Q4>(pre_h, a.layers[l + 1].w_qkv, QKV, H, r0, r1, lane);
             __syncthreads();
-            stage_input<NB, true, 2 * KSH>(b_xout, H, a.layers[l + 1].g_attn, a.eps, xs, rinv, red, w);
+            stage_input<NB, true, 2 * KSH>(my_xout, H, a.layers[l + 1].g_attn, a.eps, xs, rinv, red, w);
             stamp(11);   // next layer's input arrived
         }
     }
@@ -898,7 +912,7 @@ __global__ __launch_bounds__(kFusedThreads) void fused_step_kernel(FusedArgs a)
 #pragma unroll
         for (int p = 0; p < PF; p++) load_rows<RW_H, KSH, Q4>(ring[p], a.lm_head, V, H, v0 + p * RW_H, v1, lane);
         __syncthreads();
-        const float *x_last = a.set + lay.per_layer * (a.L - 1) + lay.xout;
+        const float *x_last = a.set + lay.per_layer * (a.L - 1) + lay.xout + (long long)copy * NB * H;
         stage_input<NB, true, 2 * KSH>(x_last, H, a.g_final, a.eps, xs, rinv, red, w);
         float best[NB];
         int best_i[NB];
