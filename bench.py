@@ -29,7 +29,7 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
 # HBM bytes per launch from rocprofv3 FETCH_SIZE + WRITE_SIZE (scaled by a plain copy
 # kernel: x2.0 and x1.0 to KiB), see profiles/decode_step_cfg1_hbm_counters.md.
 # Quoted only while the library reports the kernel revision they were taken on.
-MEASURED_TRAFFIC = {("cfg1", "fused_step"): ("fused r3", 1283567661),      # the whole step, one launch
+MEASURED_TRAFFIC = {("cfg1", "fused_step"): ("fused r4", 1285025009),      # the whole step, one launch
                     ("cfg1", "gemv"): ("gemv r3", 10805373)}             # --kernel-per-stage
 
 
@@ -459,6 +459,31 @@ def bench_stage_stamps(args, wl, dk, W, np, torch):
     print(json.dumps(out))
 
 
+def bench_sample(args, wl, dk, W, np, torch):
+    """The sampler on synthetic logits (seeded normal, standard deviation 2.5) of the workload's vocabulary:
+    microseconds per call of dk_sample_tokens on `--sample` rows, for four settings."""
+    shape = wl.cfg
+    B, V = args.sample, shape.vocab
+    rng = np.random.default_rng(1)
+    logits = torch.from_numpy((rng.normal(size=(B, V)) * 2.5).astype(np.float32)).cuda()
+    scratch = torch.empty(dk.sample_scratch_bytes(B, V), dtype=torch.uint8, device="cuda")
+    out = torch.empty(B, dtype=torch.int32, device="cuda")
+    settings = []
+    for top_k, top_p in ((0, 1.0), (50, 1.0), (0, 0.9), (50, 0.9)):
+        for i in range(args.warmup):
+            dk.sample_tokens(logits, 0.8, top_k, top_p, 7, i, scratch, out)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(args.steps):
+            dk.sample_tokens(logits, 0.8, top_k, top_p, 7, i, scratch, out)
+        e1.record()
+        torch.cuda.synchronize()
+        settings.append({"top_k": top_k, "top_p": top_p, "us_per_call": round(e0.elapsed_time(e1) * 1e3 / args.steps, 2)})
+    print(json.dumps({"metric": "sampler_us_per_call", "unit": "us", "rows": B, "vocab": V, "temperature": 0.8,
+                      "steps": args.steps, "warmup": args.warmup, "higher_is_better": False, "settings": settings}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -483,6 +508,9 @@ def main():
     ap.add_argument("--stamps", type=int, default=-1, metavar="L",
                     help="instead of timing steps: where layer L of the persistent step kernel spends its time "
                          "(device clock stamps of every block at the stage boundaries)")
+    ap.add_argument("--sample", type=int, default=0, metavar="B",
+                    help="measure the sampler (dk_sample_tokens) instead: B rows of logits over the workload's "
+                         "vocabulary, temperature 0.8, with and without top-k 50 and top-p 0.9")
     ap.add_argument("--kernel-per-stage", action="store_true",
                     help="never take the single persistent kernel (small batches of small dense models)")
     args = ap.parse_args()
@@ -509,6 +537,8 @@ def main():
         return bench_ttft(args, wl, dk, W, np, torch)
     if args.stamps >= 0:
         return bench_stage_stamps(args, wl, dk, W, np, torch)
+    if args.sample:
+        return bench_sample(args, wl, dk, W, np, torch)
     m = measure_decode(args, wl, dk, W, np, torch, args.steps, args.warmup)
     shape, lay, weights, pool_bits, tokens0, dm = (m[k] for k in ("shape", "lay", "weights", "pool_bits", "tokens0", "dm"))
     span, ms_per_step, tok_s, alg_bytes, step_dev_s = (m[k] for k in ("span", "ms_per_step", "tok_s", "alg_bytes", "step_dev_s"))
