@@ -195,6 +195,8 @@ def bench_serve(args, wl, dk, W, np, torch):
 
     def run():
         eng = dk.engine_create(dm.handle, pool, cfg, (arena.data_ptr() + 255) // 256 * 256, need)
+        if args.sampled:
+            dk.engine_set_sampling(eng, 0.8, 50, 0.9, seed=7)
         ids = [dk.engine_submit(eng, p, NEW) for p in prompts]
         t0 = time.perf_counter()
         dk.engine_step(eng)                      # admission: prefix lookup + prefill of all C prompts, first decode step
@@ -214,7 +216,8 @@ def bench_serve(args, wl, dk, W, np, torch):
         "metric": "engine_aggregate_decode_tok_per_s", "value": round(gen_tokens / gen_s, 1), "unit": "tok/s",
         "n_gpus": 1, "higher_is_better": True, "dtype": dtype_name(args), "data": "synthetic (seeded random-init weights)",
         "config": {"workload": f"{shape.name}: {C} concurrent requests, {P}-token prompts sharing a {STEM}-token "
-                               f"stem, {NEW} new tokens each, continuous batching with prefix cache",
+                               f"stem, {NEW} new tokens each, continuous batching with prefix cache"
+                               + (", sampled (temperature 0.8, top-k 50, top-p 0.9)" if args.sampled else ", greedy"),
                    "concurrency": C},
         "ms_per_decode_iteration": round(gen_s * 1e3 / max(1, st["decode_steps"] - 1), 4),
         "admission_ms": round(admit_s * 1e3, 2),
@@ -499,6 +502,8 @@ def main():
     ap.add_argument("--serve", type=int, default=0, metavar="C",
                     help="measure the continuous-batching engine instead: C concurrent requests of the "
                          "workload's model shape (512-token prompts with a shared 256-token stem, 128 new tokens)")
+    ap.add_argument("--sampled", action="store_true",
+                    help="with --serve: tokens drawn by the sampler (temperature 0.8, top-k 50, top-p 0.9) instead of greedy")
     ap.add_argument("--ttft", action="store_true",
                     help="measure time to first token through the engine with and without a prefix-cache hit "
                          "(512-token shared prefix + 32 own tokens, the shape of the paper's text prefix-cache table)")
