@@ -507,17 +507,22 @@ dk_status dk_engine_step(dk_engine *engine, void *hip_stream, int32_t *out_activ
         for (int i = 0; i < B; i++) { seq[(size_t)i] = e->active[(size_t)i]->T; tok[(size_t)i] = e->active[(size_t)i]->last; }
         dk_status s = engine_upload_rows(e, st);
         if (s != DK_OK) return s;
-        if (e->state_dirty || e->sampling) {
+        auto upload_state = [&]() -> dk_status {
             DK_HIP(hipMemcpyAsync(e->d_seq, seq.data(), (size_t)B * 4, hipMemcpyHostToDevice, st));
             DK_HIP(hipMemcpyAsync(e->d_tok, tok.data(), (size_t)B * 4, hipMemcpyHostToDevice, st));
+            return DK_OK;
+        };
+        if (e->state_dirty) {
+            s = upload_state();
+            if (s != DK_OK) return s;
             e->state_dirty = false;
         }
-        // greedy: the step feeds its own tokens and lengths to the next one (an invalid step advances nothing)
-        const uint32_t advance = e->sampling ? 0u : DK_STEP_ADVANCE;
+        // the step feeds its own (greedy) tokens and lengths to the next one (an invalid step advances
+        // nothing); with sampling the drawn tokens then replace the greedy ones on the device
         for (int attempt = 0; attempt < 2; attempt++) {
             s = dk_decode_step(e->model, e->pool, e->d_tables, e->cfg.max_blocks_per_seq, e->d_seq, e->d_tok, B,
                                e->d_ws, e->ws_bytes, e->sampling ? e->d_logits : nullptr, e->d_next,
-                               advance | (e->no_fused ? DK_STEP_NO_FUSED : 0u), st);
+                               DK_STEP_ADVANCE | (e->no_fused ? DK_STEP_NO_FUSED : 0u), st);
             if (s != DK_OK) return s;
             DK_HIP(hipMemcpyAsync(nxt.data(), e->d_next, (size_t)B * 4, hipMemcpyDeviceToHost, st));
             if (e->sampling) {
@@ -526,11 +531,16 @@ dk_status dk_engine_step(dk_engine *engine, void *hip_stream, int32_t *out_activ
                                      e->sample_ws_bytes, e->d_sampled, st);
                 if (s != DK_OK) return s;
                 DK_HIP(hipMemcpyAsync(smp.data(), e->d_sampled, (size_t)B * 4, hipMemcpyDeviceToHost, st));
+                DK_HIP(hipMemcpyAsync(e->d_tok, e->d_sampled, (size_t)B * 4, hipMemcpyDeviceToDevice, st));
             }
             DK_HIP(hipStreamSynchronize(st));
             bool valid = true;   // an invalid step marks every row with -1; check them all
             for (int i = 0; i < B; i++) valid = valid && nxt[(size_t)i] >= 0;
             if (valid) break;
+            if (e->sampling) {   // tokens drawn from an invalid step's logits went to the device: restore
+                s = upload_state();
+                if (s != DK_OK) return s;
+            }
             // the persistent kernel could not keep its blocks resident (its waits are bounded and it
             // says so with the token -1): the step left lengths and tokens alone, so it is simply
             // repeated, now and from here on as a chain of kernels
