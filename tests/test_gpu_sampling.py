@@ -50,6 +50,7 @@ CASES = [
     (151936, 2, 0.8, 0, 0.95),       # the vocabulary of the 0.6B / 8B shapes
     (151936, 1, 1.0, 20, 1.0),
     (64, 5, 1.0, 1, 1.0),            # top_k = 1: the argmax
+    (70, 64, 1.0, 5, 0.8),           # slices of one or two entries, the engine's largest batch
     (151936, 16, 0.8, 50, 0.9),      # a serving batch: few candidates out of a large vocabulary
     (5000, 3, 1.0, 64, 0.5),         # the largest top_k that is found by selection
     (5000, 2, 1.0, 65, 0.9),         # ... and the smallest that is not
