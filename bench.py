@@ -163,6 +163,10 @@ def bench_prefill(args, wl, dk, W, np, torch):
     head = shape.vocab * shape.hidden * 2
     alg = sum(shape.dense_weight_bytes() - (0 if o + chunk >= P else head) + min(o + chunk, P) * kv_tok
               for o in range(0, P, chunk))
+    # the method's own arithmetic: two flops per weight of the projections and token (the lm_head for the last
+    # token only), and per layer and token 4 * n_q_heads * head_dim flops per cached position it attends to
+    flops = 2.0 * ((shape.dense_weight_bytes() - head) / 2) * P + 2.0 * (head / 2) \
+        + 4.0 * shape.n_layers * shape.n_q_heads * shape.head_dim * (P * (P + 1) / 2)
     print(json.dumps({
         "metric": "prefill_tok_per_s", "value": round(P / wall, 1), "unit": "tok/s", "n_gpus": 1,
         "steps": reps, "ms_per_step": round(wall * 1e3, 4), "higher_is_better": True, "dtype": dtype_name(args),
@@ -172,7 +176,10 @@ def bench_prefill(args, wl, dk, W, np, torch):
         "roofline": {"bound": "hbm", "achieved": round(alg / wall / 1e9, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(alg / wall / 1e9 / HBM_PEAK_GBS, 4), "traffic": None,
                      "note": "weights are streamed once per 64-token chunk (the decode kernels with the rows "
-                             "of one sequence); a compute-bound large-tile prefill is not built"}}))
+                             "of one sequence); a compute-bound large-tile prefill is not built"},
+        # the same run against the matrix cores' dense bf16 peak (what a compute-bound prefill would be held to)
+        "mfma_roofline": {"bound": "mfma", "achieved": round(flops / wall / 1e12, 2), "peak": 2500.0, "unit": "TFLOP/s",
+                          "frac": round(flops / wall / 1e12 / 2500.0, 4), "flops_per_prompt": int(flops)}}))
 
 
 def bench_serve(args, wl, dk, W, np, torch):
