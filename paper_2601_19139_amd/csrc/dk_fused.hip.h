@@ -30,6 +30,7 @@
 // the block of a sequence's first chunk collects the other chunks' partials and
 // publishes the finished attention output, which the output projection awaits.
 #pragma once
+#include <type_traits>
 #include "dk_attention.hip.h"
 
 namespace dk {
@@ -104,7 +105,6 @@ __device__ __forceinline__ void stc_f32(float *p, float v)
 {
     __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
-
 // Bounded wait shared by every hand-over: `ready` is this thread's verdict on
 // the elements it just loaded.  Returns true when the whole block may stop
 // polling (everything arrived, or the step was aborted).
@@ -407,6 +407,7 @@ __global__ __launch_bounds__(kFusedThreads) void fused_step_kernel(FusedArgs a)
     constexpr int RW_Q = 1, RW_F = 1;                           // output and down projection
     constexpr int EP = (G * D + kFusedThreads - 1) / kFusedThreads;   // elements of a query group's output per thread
     constexpr int MERGE_ROUND = kFusedMergeRound / EP > 0 ? kFusedMergeRound / EP : 1;
+    static_assert(D % 64 == 0, "a query head's elements fill whole waves (the collecting block fetches a chunk's maximum and sum once per wave)");
     extern __shared__ __attribute__((aligned(16))) float xs[];   // [NB][512 * max(KSH, KSQ, KSF)]: the stage's input (fused_xs_bytes)
     __shared__ float red[kFusedWaves * NB];
     __shared__ float sm_o[kFusedWaves][G][D];
@@ -780,40 +781,59 @@ __global__ __launch_bounds__(kFusedThreads) void fused_step_kernel(FusedArgs a)
             } else {
                 // chunk 0 collects the other chunks of its (row, kv head) in order and
                 // publishes the finished attention output
-                for (int c0 = 1; c0 < nact[b]; c0 += MERGE_ROUND) {
-                    uint32_t um[EP][MERGE_ROUND], ul[EP][MERGE_ROUND], uo[EP][MERGE_ROUND];
-                    w.spins = 0;
-                    for (;;) {
-                        bool ready = true;
-                        // every request is unconditional (chunks past the last repeat it, threads
-                        // without an element read element 0): a load inside a condition is waited
-                        // for on the spot, and a round of polls would be a chain of round trips
+                // a round awaits ROUND chunks at once; its size follows the number of chunks, so that a short
+                // context does not poll (and wait for) repeats of its last chunk
+                auto merge_rounds = [&](auto round_tag) {
+                    constexpr int ROUND = decltype(round_tag)::value;
+                    for (int c0 = 1; c0 < nact[b]; c0 += ROUND) {
+                        uint32_t uml[EP][ROUND], uo[EP][ROUND];
+                        w.spins = 0;
+                        for (;;) {
+                            bool ready = true;
+                            // every request is unconditional (chunks past the last repeat it, threads
+                            // without an element read element 0): a load inside a condition is waited
+                            // for on the spot, and a round of polls would be a chain of round trips
+#pragma unroll
+                            for (int x = 0; x < EP; x++)
+#pragma unroll
+                                for (int u = 0; u < ROUND; u++) {
+                                    const float *pp = pg[x] + (long long)min(c0 + u, nact[b] - 1) * (G * (D + 2));
+                                    // (maximum, sum) of the chunk: even lanes fetch the one, odd lanes the other -
+                                    // a query head's elements fill whole waves, so one request serves a wave
+                                    uml[x][u] = ldc_u32(pp + D + (lane & 1));
+                                    uo[x][u] = ldc_u32(pp + dim[x]);
+                                    ready = ready && uml[x][u] != kNotYet && uo[x][u] != kNotYet;
+                                }
+                            if (w.done(ready)) break;
+                        }
 #pragma unroll
                         for (int x = 0; x < EP; x++)
 #pragma unroll
-                            for (int u = 0; u < MERGE_ROUND; u++) {
-                                const float *pp = pg[x] + (long long)min(c0 + u, nact[b] - 1) * (G * (D + 2));
-                                um[x][u] = ldc_u32(pp + D);
-                                ul[x][u] = ldc_u32(pp + D + 1);
-                                uo[x][u] = ldc_u32(pp + dim[x]);
-                                ready = ready && um[x][u] != kNotYet && ul[x][u] != kNotYet && uo[x][u] != kNotYet;
-                            }
-                        if (w.done(ready)) break;
+                            for (int u = 0; u < ROUND; u++)
+                                if (c0 + u < nact[b]) {
+                                    const float mc = __uint_as_float((uint32_t)__builtin_amdgcn_readlane((int)uml[x][u], 0));
+                                    const float lc = __uint_as_float((uint32_t)__builtin_amdgcn_readlane((int)uml[x][u], 1));
+                                    const float oc = __uint_as_float(uo[x][u]);
+                                    const float m2 = fmaxf(mn[x], mc);
+                                    const float sa = __expf(mn[x] - m2), sb = __expf(mc - m2);
+                                    ls[x] = ls[x] * sa + lc * sb;
+                                    os[x] = os[x] * sa + oc * sb;
+                                    mn[x] = m2;
+                                }
                     }
-#pragma unroll
-                    for (int x = 0; x < EP; x++)
-#pragma unroll
-                        for (int u = 0; u < MERGE_ROUND; u++)
-                            if (c0 + u < nact[b]) {
-                                const float mc = __uint_as_float(um[x][u]), lc = __uint_as_float(ul[x][u]);
-                                const float oc = __uint_as_float(uo[x][u]);
-                                const float m2 = fmaxf(mn[x], mc);
-                                const float sa = __expf(mn[x] - m2), sb = __expf(mc - m2);
-                                ls[x] = ls[x] * sa + lc * sb;
-                                os[x] = os[x] * sa + oc * sb;
-                                mn[x] = m2;
-                            }
-                }
+                };
+                // the smallest of the instantiated round sizes (multiples of ROUND_STEP) that takes all chunks at once
+                constexpr int ROUND_STEP = MERGE_ROUND >= 6 ? MERGE_ROUND / 6 : 1;
+                auto pick_round = [&](auto self, auto round_tag) -> void {
+                    constexpr int ROUND = decltype(round_tag)::value;
+                    if constexpr (ROUND + ROUND_STEP > MERGE_ROUND) {
+                        merge_rounds(std::integral_constant<int, MERGE_ROUND>{});
+                    } else {
+                        if (nact[b] - 1 <= ROUND) merge_rounds(round_tag);
+                        else self(self, std::integral_constant<int, ROUND + ROUND_STEP>{});
+                    }
+                };
+                pick_round(pick_round, std::integral_constant<int, ROUND_STEP>{});
 #pragma unroll
                 for (int x = 0; x < EP; x++)
                     if (has[x]) {
