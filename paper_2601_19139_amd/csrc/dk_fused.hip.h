@@ -44,6 +44,7 @@ constexpr int kFusedMergeRound = 12;        // chunk partials the collecting blo
 constexpr int kFusedWaveTiles = kFusedChunk / (16 * kFusedWaves);   // 16-token K/V tiles per wave
 constexpr int kFusedStamps = 16;            // stage boundaries a block can stamp per layer (see FusedArgs::stamps)
 constexpr int kFusedReplicas = 2;           // copies of a vector that every block awaits (block blk polls copy blk % kFusedReplicas)
+constexpr int kFusedWarmDelay = 80;         // x 64 clocks between a layer's start and an idle block's L2 warming
 constexpr int kFusedSpinLimit = 1 << 16;    // polls before a block gives up (each ~1 us)
 
 struct FusedLayer {
@@ -105,6 +106,22 @@ __device__ __forceinline__ void stc_f32(float *p, float v)
 {
     __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
+// Warming the die's L2: one word of every 128-byte line of [p, p + bytes) is requested, LINES lines per thread
+// (bytes <= LINES * 32 KB; lines past the end repeat the last).  The words are returned so that nothing waits
+// for them here: the caller folds them into a sink once the loads have long returned.
+template <int LINES>
+struct WarmWords { uint32_t w[LINES]; };
+template <int LINES>
+__device__ __forceinline__ WarmWords<LINES> warm_l2(const void *p, int bytes)
+{
+    WarmWords<LINES> r;
+    const uint32_t *q = static_cast<const uint32_t *>(p);
+    const int lines = (bytes + 127) >> 7;
+#pragma unroll
+    for (int i = 0; i < LINES; i++) r.w[i] = q[(long long)min(i * kFusedThreads + (int)threadIdx.x, lines - 1) * 32];
+    return r;
+}
+
 // Bounded wait shared by every hand-over: `ready` is this thread's verdict on
 // the elements it just loaded.  Returns true when the whole block may stop
 // polling (everything arrived, or the step was aborted).
@@ -510,6 +527,13 @@ __global__ __launch_bounds__(kFusedThreads) void fused_step_kernel(FusedArgs a)
         (void)j;
     }
 
+    // The MLP's weights are requested a first time while attention runs - most blocks have nothing to do then
+    // and HBM is idle - so that the requests in front of the MLP's hand-overs find them in the die's L2: those
+    // hand-overs are then as long as the hand-over takes, not as long as the burst of weight requests in front of
+    // the polls.  (The narrow classes only: the wide ones stream more per block than the L2 can hold for them.)
+    constexpr bool WARM = !Q4 && KSH <= 2 && KSF <= 8;
+    uint32_t sink = 0;
+    WarmWords<1> wg{}, wu{}, wd{}, wg2{}, wu2{}, wd2{};
     for (int l = 0; l < a.L; l++) {
         const FusedLayer &Lw = a.layers[l];
         if constexpr (STAMPS) stamp_on = stamp_to != nullptr && l == a.stamp_layer && tid == 0;
@@ -542,6 +566,28 @@ __global__ __launch_bounds__(kFusedThreads) void fused_step_kernel(FusedArgs a)
                 rv_o = bf16_to_f32(a.embed[(long long)tok * H + h_b0 + r]);
             } else {
                 rv_o = __uint_as_float(ldc_u32(x_in + (long long)b * H + h_b0 + r));
+            }
+        }
+        if constexpr (WARM) {
+            // Only blocks without work in this layer's attention warm, and not at once: the attention blocks' K/V
+            // tiles and the q|k|v hand-over come first.  A block with an attention item has a partner among the
+            // idle blocks of its die - `pair` blocks further on, a multiple of 8 - that warms its rows for it.
+            auto attends = [&](int who) {
+                const int c = who % a.nchunks, b = who / (a.nchunks * a.nkv);
+                return who < items && c < nact[min(b, NB - 1)];
+            };
+            auto warm_rows_of = [&](int who, WarmWords<1> &g, WarmWords<1> &u, WarmWords<1> &d) {
+                const int fb = (int)((long long)F * who / nblk), fn = (int)((long long)F * (who + 1) / nblk) - fb;
+                const int hb = (int)((long long)H * who / nblk), hn = (int)((long long)H * (who + 1) / nblk) - hb;
+                g = warm_l2<1>(Lw.w_gate + (long long)fb * H, fn * H * 2);
+                u = warm_l2<1>(Lw.w_up + (long long)fb * H, fn * H * 2);
+                d = warm_l2<1>(Lw.w_down + (long long)hb * F, hn * F * 2);
+            };
+            if (!attends(blk)) {
+                const int pair = (min(items, nblk) + 7) & ~7;
+                __builtin_amdgcn_s_sleep(kFusedWarmDelay);
+                warm_rows_of(blk, wg, wu, wd);
+                if (blk >= pair && attends(blk - pair)) warm_rows_of(blk - pair, wg2, wu2, wd2);
             }
         }
         for (int item = blk; item < items; item += nblk) {
@@ -865,6 +911,7 @@ __global__ __launch_bounds__(kFusedThreads) void fused_step_kernel(FusedArgs a)
             __syncthreads();   // xs is about to be overwritten
             stage_input<NB, true, 2 * KSH>(my_xmid, H, Lw.g_mlp, a.eps, xs, rinv, red, w);
             stamp(7);    // x_mid arrived
+            if constexpr (WARM) sink ^= wg.w[0] ^ wu.w[0] ^ wd.w[0] ^ wg2.w[0] ^ wu2.w[0] ^ wd2.w[0];
             for (int rb = f0; rb < f1; rb += RW_GU) {
                 if (rb != f0) {
                     load_rows<RW_GU, KSH, Q4>(pg, Lw.w_gate, F, H, rb, f1, lane);
@@ -932,6 +979,8 @@ __global__ __launch_bounds__(kFusedThreads) void fused_step_kernel(FusedArgs a)
 #pragma unroll
         for (int p = 0; p < PF; p++) load_rows<RW_H, KSH, Q4>(ring[p], a.lm_head, V, H, v0 + p * RW_H, v1, lane);
         __syncthreads();
+        // (the warmed words have to end somewhere: a store that never happens - the wait limit is positive)
+        if (WARM && a.spin_limit < 0 && sink == 0x5bd1e995u) a.status[1] = sink;
         const float *x_last = a.set + lay.per_layer * (a.L - 1) + lay.xout + (long long)copy * NB * H;
         stage_input<NB, true, 2 * KSH>(x_last, H, a.g_final, a.eps, xs, rinv, red, w);
         float best[NB];
