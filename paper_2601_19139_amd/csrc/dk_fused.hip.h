@@ -43,8 +43,8 @@ constexpr int kFusedChunk = 64;             // tokens per attention work item
 constexpr int kFusedMergeRound = 12;        // chunk partials the collecting block awaits at a time
 constexpr int kFusedWaveTiles = kFusedChunk / (16 * kFusedWaves);   // 16-token K/V tiles per wave
 constexpr int kFusedStamps = 16;            // stage boundaries a block can stamp per layer (see FusedArgs::stamps)
-constexpr int kFusedReplicas = 2;           // copies of a vector that every block awaits (block blk polls copy blk % kFusedReplicas)
-constexpr int kFusedWarmDelay = 80;         // x 64 clocks between a layer's start and an idle block's L2 warming
+constexpr int kFusedReplicas = 4;           // copies of a vector that every block awaits (block blk polls copy blk % kFusedReplicas)
+constexpr int kFusedWarmDelay = 64;         // x 64 clocks between a layer's start and an idle block's L2 warming
 constexpr int kFusedSpinLimit = 1 << 16;    // polls before a block gives up (each ~1 us)
 
 struct FusedLayer {
