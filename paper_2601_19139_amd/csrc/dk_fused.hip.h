@@ -279,7 +279,11 @@ __device__ __forceinline__ void load_rows(RowRegs<RW, KS, Q4> &r, const uint16_t
                 const int k = s * 512 + lane * 8;
                 // rows / pieces outside the matrix read a valid address and are not used
                 const int row = min(row0 + i, row_end - 1);
-                r.w[i][s] = ld16(W + (long long)max(row, 0) * K + min(k, K - 8));
+                // used once per step: a streaming (non-temporal) request, so that the row does not push the rows
+                // that were warmed for the coming stages out of the L2
+                typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+                const u32x4 t = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(W + (long long)max(row, 0) * K + min(k, K - 8)));
+                r.w[i][s] = make_uint4(t.x, t.y, t.z, t.w);
             }
     }
 }
