@@ -463,10 +463,14 @@ __global__ __launch_bounds__(kFusedThreads) void fused_step_kernel(FusedArgs a)
 
     // refill the other buffer set for the next step
     {
+        // (16 bytes per store; the set is 256-byte aligned, a block's share starts at a multiple of four words)
         uint32_t *o = reinterpret_cast<uint32_t *>(a.other_set);
-        const long long per = (a.set_floats + nblk - 1) / nblk;
+        const long long per = ((a.set_floats + nblk - 1) / nblk + 3) & ~3LL;
         const long long lo = per * blk, hi = min(a.set_floats, lo + per);
-        for (long long i = lo + tid; i < hi; i += kFusedThreads) o[i] = kNotYet;
+        const long long hi4 = lo + ((hi - lo) & ~3LL);
+        for (long long i = lo + 4 * tid; i < hi4; i += 4 * kFusedThreads)
+            *reinterpret_cast<uint4 *>(o + i) = make_uint4(kNotYet, kNotYet, kNotYet, kNotYet);
+        for (long long i = hi4 + tid; i < hi; i += kFusedThreads) o[i] = kNotYet;
     }
 
     // sequence state of the step (constant until the very end)
