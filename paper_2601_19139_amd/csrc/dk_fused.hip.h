@@ -267,7 +267,9 @@ __device__ __forceinline__ void load_rows(RowRegs<RW, KS, Q4> &r, const uint16_t
 #pragma unroll
             for (int s = 0; s < RowRegs<RW, KS, true>::KQ; s++) {
                 const int c = min(s * 64 + lane, units - 1);   // units past the row: a valid address, not used
-                r.w[i][s] = *reinterpret_cast<const uint2 *>(codes + c * 8);
+                typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+                const u32x2 t = __builtin_nontemporal_load(reinterpret_cast<const u32x2 *>(codes + c * 8));   // used once per step
+                r.w[i][s] = make_uint2(t.x, t.y);
                 r.sb[i][s] = *reinterpret_cast<const uint32_t *>(sbase + tile_off + (c >> 3) * 128 + (c & 1) * 16);
             }
         }
@@ -539,7 +541,7 @@ __global__ __launch_bounds__(kFusedThreads) void fused_step_kernel(FusedArgs a)
     // and HBM is idle - so that the requests in front of the MLP's hand-overs find them in the die's L2: those
     // hand-overs are then as long as the hand-over takes, not as long as the burst of weight requests in front of
     // the polls.  (The narrow classes only: the wide ones stream more per block than the L2 can hold for them.)
-    constexpr bool WARM = !Q4 && KSH <= 2 && KSF <= 8;
+    constexpr bool WARM = KSH <= 2 && KSF <= 8;
     uint32_t sink = 0;
     WarmWords<1> wg{}, wu{}, wd{}, wg2{}, wu2{}, wd2{};
     for (int l = 0; l < a.L; l++) {
@@ -587,9 +589,15 @@ __global__ __launch_bounds__(kFusedThreads) void fused_step_kernel(FusedArgs a)
             auto warm_rows_of = [&](int who, WarmWords<1> &g, WarmWords<1> &u, WarmWords<1> &d) {
                 const int fb = (int)((long long)F * who / nblk), fn = (int)((long long)F * (who + 1) / nblk) - fb;
                 const int hb = (int)((long long)H * who / nblk), hn = (int)((long long)H * (who + 1) / nblk) - hb;
-                g = warm_l2<1>(Lw.w_gate + (long long)fb * H, fn * H * 2);
-                u = warm_l2<1>(Lw.w_up + (long long)fb * H, fn * H * 2);
-                d = warm_l2<1>(Lw.w_down + (long long)hb * F, hn * F * 2);
+                if constexpr (Q4) {   // the rows' 4-bit codes (half a byte per column; the scales, an eighth of that, are left)
+                    g = warm_l2<1>(reinterpret_cast<const uint8_t *>(Lw.w_gate) + (long long)fb * (H >> 1), fn * (H >> 1));
+                    u = warm_l2<1>(reinterpret_cast<const uint8_t *>(Lw.w_up) + (long long)fb * (H >> 1), fn * (H >> 1));
+                    d = warm_l2<1>(reinterpret_cast<const uint8_t *>(Lw.w_down) + (long long)hb * (F >> 1), hn * (F >> 1));
+                } else {
+                    g = warm_l2<1>(Lw.w_gate + (long long)fb * H, fn * H * 2);
+                    u = warm_l2<1>(Lw.w_up + (long long)fb * H, fn * H * 2);
+                    d = warm_l2<1>(Lw.w_down + (long long)hb * F, hn * F * 2);
+                }
             };
             if (!attends(blk)) {
                 const int pair = (min(items, nblk) + 7) & ~7;
