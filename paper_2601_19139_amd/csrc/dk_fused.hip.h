@@ -16,7 +16,19 @@
 //     device-coherent loads and simply re-read until no element is the pattern
 //     (the 8 compute dies do not share an L2, so ordinary loads could be stale);
 //   * there are two sets; a step uses one and refills the other with the
-//     pattern for the next step (the kernel boundary between steps orders that).
+//     pattern for the next step (the kernel boundary between steps orders that);
+//   * the vectors that every block awaits (attention output, the two residual
+//     vectors, the MLP activations) are written in kFusedReplicas copies and a
+//     block polls copy blockIdx % kFusedReplicas: fewer blocks poll the same lines.
+//
+// Requests return in order, so whatever a wave has requested before it polls
+// delays the poll's answer: a stage's weight rows are requested ahead of its
+// wait on purpose (they stream during the hand-over), but a burst of such requests
+// from all blocks at once makes the hand-over as long as the burst.  While
+// attention runs most blocks are idle and HBM is too: those blocks request a word
+// of every line of the MLP's rows then (their own and those of a partner block of
+// their die that is busy), which brings the rows into the die's L2 before the
+// MLP's stages ask for them.  Weight rows are requested as streaming loads.
 //
 // Every wait is bounded: after a spin limit a block raises an abort word tagged
 // with the step's serial number, and every waiter that sees it stops waiting, so
