@@ -118,6 +118,16 @@ __device__ __forceinline__ void stc_f32(float *p, float v)
 {
     __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
+// Four consecutive words at base + byte_off by one device-scope load (a raw buffer load with the sc1 bit: the
+// 16-byte form of ldc_u32; the words may come from different moments, which data-as-flag does not mind).
+// base: uniform over the wave, 16-byte aligned; bytes: the extent that may be read from base.
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ u32x4 ldc_u32x4(const void *base, uint32_t bytes, uint32_t byte_off)
+{
+    const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, (int)bytes, 0x00020000);
+    return __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)byte_off, 0, 16);
+}
+
 // Warming the die's L2: one word of every 128-byte line of [p, p + bytes) is requested, LINES lines per thread
 // (bytes <= LINES * 32 KB; lines past the end repeat the last).  The words are returned so that nothing waits
 // for them here: the caller folds them into a sink once the loads have long returned.
@@ -175,7 +185,7 @@ struct Waiter {
 // Loads x[NB][K] (device-coherent, re-reading until complete) into LDS as
 // x * gain (or x) and returns 1/rms per row when NORM.
 template <int NB, bool NORM, int MAXE /*elements per thread and row: K <= 256 * MAXE*/>
-__device__ __forceinline__ void stage_input(const float *src, int K, const uint16_t *gain, float eps,
+__device__ __forceinline__ void stage_input_words(const float *src, int K, const uint16_t *gain, float eps,
                                             float *xs /*[NB][K]*/, float (&rinv)[NB], float *red /*[4][NB]*/,
                                             Waiter &w)
 {
@@ -228,6 +238,78 @@ __device__ __forceinline__ void stage_input(const float *src, int K, const uint1
         for (int b = 0; b < NB; b++)
             rinv[b] = rsqrtf((red[b] + red[NB + b] + red[2 * NB + b] + red[3 * NB + b]) / (float)K + eps);
     }
+}
+
+// The same with 16-byte requests (four consecutive words per thread): a quarter of the poll instructions.  For
+// the long vectors of the wide classes (16 and more words per thread and row), where a poll round is as long as
+// the compute unit's memory pipeline needs for its requests; K a multiple of 4.
+template <int NB, bool NORM, int MAXE>
+__device__ __forceinline__ void stage_input_quads(const float *src, int K, const uint16_t *gain, float eps,
+                                                  float *xs /*[NB][K]*/, float (&rinv)[NB], float *red /*[4][NB]*/,
+                                                  Waiter &w)
+{
+    constexpr int GROUPS = (MAXE + 3) / 4;
+    const int tid = threadIdx.x;
+    u32x4 v[NB][GROUPS];
+    uint2 gn[GROUPS];
+#pragma unroll
+    for (int e = 0; e < GROUPS; e++)
+        gn[e] = NORM ? *reinterpret_cast<const uint2 *>(gain + min((e * kFusedThreads + tid) * 4, K - 4)) : make_uint2(0u, 0u);
+    w.spins = 0;
+    for (;;) {
+        bool ready = true;
+#pragma unroll
+        for (int b = 0; b < NB; b++)
+#pragma unroll
+            for (int e = 0; e < GROUPS; e++) {
+                const int k = min((e * kFusedThreads + tid) * 4, K - 4);     // past the end: the last four words again
+                v[b][e] = ldc_u32x4(src, (uint32_t)(NB * K) * 4u, (uint32_t)(b * K + k) * 4u);
+                ready = ready && v[b][e].x != kNotYet && v[b][e].y != kNotYet && v[b][e].z != kNotYet && v[b][e].w != kNotYet;
+            }
+        if (w.done(ready)) break;
+    }
+    float ss[NB];
+#pragma unroll
+    for (int b = 0; b < NB; b++) {
+        ss[b] = 0.f;
+#pragma unroll
+        for (int e = 0; e < GROUPS; e++) {
+            const int k = (e * kFusedThreads + tid) * 4;
+            if (k < K) {
+                float4 x = make_float4(__uint_as_float(v[b][e].x), __uint_as_float(v[b][e].y), __uint_as_float(v[b][e].z),
+                                       __uint_as_float(v[b][e].w));
+                ss[b] += x.x * x.x + x.y * x.y + x.z * x.z + x.w * x.w;
+                if (NORM) {
+                    x.x *= bf16lo(gn[e].x); x.y *= bf16hi(gn[e].x);
+                    x.z *= bf16lo(gn[e].y); x.w *= bf16hi(gn[e].y);
+                }
+                *reinterpret_cast<float4 *>(xs + b * K + k) = x;
+            }
+        }
+    }
+    if (NORM) {
+#pragma unroll
+        for (int b = 0; b < NB; b++) {
+            const float s = sum64(ss[b]);
+            if ((tid & 63) == 0) red[(tid >> 6) * NB + b] = s;
+        }
+    }
+    __syncthreads();
+    if (NORM) {
+#pragma unroll
+        for (int b = 0; b < NB; b++)
+            rinv[b] = rsqrtf((red[b] + red[NB + b] + red[2 * NB + b] + red[3 * NB + b]) / (float)K + eps);
+    }
+}
+
+template <int NB, bool NORM, int MAXE>
+__device__ __forceinline__ void stage_input(const float *src, int K, const uint16_t *gain, float eps, float *xs,
+                                            float (&rinv)[NB], float *red, Waiter &w)
+{
+    if constexpr (MAXE >= 16) {
+        if ((K & 3) == 0) return stage_input_quads<NB, NORM, MAXE>(src, K, gain, eps, xs, rinv, red, w);
+    }
+    stage_input_words<NB, NORM, MAXE>(src, K, gain, eps, xs, rinv, red, w);
 }
 
 // The rows [r0, r1) of a matrix that a wave owns: rows of the block split over
