@@ -763,7 +763,7 @@ const char *dk_last_error(void) { return g_err; }
 
 // The kernel revisions change whenever a kernel's memory behaviour changes; the
 // benchmark quotes stored counter measurements only for a matching revision.
-const char *dk_version(void) { return "decodekit 0.9 (gfx950; gemv r3, gemm r12, attention r9, moe r4, fused r8, prefill r2, sample r2)"; }
+const char *dk_version(void) { return "decodekit 0.9 (gfx950; gemv r3, gemm r12, attention r9, moe r4, fused r9, prefill r2, sample r2)"; }
 
 // ------------------------------------------------------------------- pool --
 dk_status dk_kv_pool_bytes(const dk_model_config *cfg, int32_t num_blocks, int32_t block_size,

@@ -583,6 +583,17 @@ __global__ __launch_bounds__(kFusedThreads) void fused_step_kernel(FusedArgs a)
     block_rows(QKV, qkv_b0, qkv_n);
     block_rows(H, h_b0, h_n);
     block_rows(F, f_b0, f_n);
+    // The embedding rows are requested before the first weight rows (requests return in order: behind the 8 MB
+    // that all blocks ask for at once they would arrive microseconds later), all of a thread's elements together.
+    constexpr int EM = 2 * KSH;                    // H <= 256 * EM
+    uint16_t ex[NB][EM], eg[EM];
+#pragma unroll
+    for (int e = 0; e < EM; e++) {
+        const int k = min(e * kFusedThreads + tid, H - 1);
+        eg[e] = a.layers[0].g_attn[k];
+#pragma unroll
+        for (int b = 0; b < NB; b++) ex[b][e] = a.embed[(long long)min(max(a.tokens[b], 0), V - 1) * H + k];
+    }
     RowRegs<RW_H, KSH, Q4> pre_h;
     load_rows<RW_H, KSH, Q4>(pre_h, a.layers[0].w_qkv, QKV, H, r0, r1, lane);
     float rinv[NB], ones[NB];
@@ -593,11 +604,14 @@ __global__ __launch_bounds__(kFusedThreads) void fused_step_kernel(FusedArgs a)
 #pragma unroll
         for (int b = 0; b < NB; b++) {
             ss[b] = 0.f;
-            const int tok = min(max(a.tokens[b], 0), V - 1);
-            for (int k = tid; k < H; k += kFusedThreads) {
-                const float x = bf16_to_f32(a.embed[(long long)tok * H + k]);
-                ss[b] += x * x;
-                xs[b * H + k] = x * bf16_to_f32(a.layers[0].g_attn[k]);
+#pragma unroll
+            for (int e = 0; e < EM; e++) {
+                const int k = e * kFusedThreads + tid;
+                if (k < H) {
+                    const float x = bf16_to_f32(ex[b][e]);
+                    ss[b] += x * x;
+                    xs[b * H + k] = x * bf16_to_f32(eg[e]);
+                }
             }
             const float s = sum64(ss[b]);
             if (lane == 0) red[wv * NB + b] = s;
