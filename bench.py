@@ -29,7 +29,7 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
 # HBM bytes per launch from rocprofv3 FETCH_SIZE + WRITE_SIZE (scaled by a plain copy
 # kernel: x2.0 and x1.0 to KiB), see profiles/decode_step_cfg1_hbm_counters.md.
 # Quoted only while the library reports the kernel revision they were taken on.
-MEASURED_TRAFFIC = {("cfg1", "fused_step"): ("fused r8", 1291010929),      # the whole step, one launch
+MEASURED_TRAFFIC = {("cfg1", "fused_step"): ("fused r9", 1290928457),      # the whole step, one launch
                     ("cfg1", "gemv"): ("gemv r3", 10805373)}             # --kernel-per-stage
 
 
